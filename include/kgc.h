@@ -1,0 +1,132 @@
+/*
+ * kgc -- TransE knowledge-graph completion as a threshold similarity join, on one AMD MI355X (gfx950).
+ *
+ * Given entity embeddings E (N x d) and relation vectors Rv (R x d), the join returns every triple
+ * (h, r, t) in E x R x E with
+ *
+ *        dist_3(h, r, t) = || E[h] + Rv[r] - E[t] ||_p  <=  delta,        p in {1, 2}.
+ *
+ * This is the completion problem of Definition 1 (Section 3.1) for the TransE distance, after the
+ * transformation of Section 4.3: connector_1(h, r) = h + r, connector_2(t, r) = t,
+ * dist(a, b) = ||a - b||_p.  The threshold is inclusive (Section 3.1: "less than or equal"), self
+ * pairs h == t are included and nothing is filtered against an existing graph.  The paper calls the
+ * distance threshold epsilon; it is named delta here because the paper also uses epsilon for the score.
+ *
+ * C ABI, plain pointers and sizes.  Unless marked "host", a pointer is a DEVICE pointer owned by the
+ * caller: the library reads E / Rv, writes out_triples, and never frees or reallocates them.
+ * Scratch memory is owned by the handle and released by kgc_destroy.  All work of a handle is
+ * enqueued on the HIP stream given at creation.  A handle must not be used from two threads at once.
+ */
+#ifndef KGC_H
+#define KGC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kgc_handle kgc_handle;          /* opaque */
+
+/* One result record (16 bytes).  h, r, t are 0-based row numbers in the caller's E / Rv (any
+ * internal reordering is undone).  dist is the norm itself (not its square), rounded to float from
+ * the double-precision value the hit decision was taken on. */
+typedef struct { int32_t h, r, t; float dist; } kgc_triple;
+
+/* storage type of E and Rv */
+#define KGC_F32  0      /* IEEE float32 */
+#define KGC_BF16 1      /* bfloat16 (upper 16 bits of a float32) */
+
+/* pruning */
+#define KGC_PRUNE_AUTO 0   /* = KGC_PRUNE_ON */
+#define KGC_PRUNE_OFF  1   /* dense: every tile pair goes through the join kernel (Section 5.1's naive mode) */
+#define KGC_PRUNE_ON   2   /* tile pairs are skipped when the pivot bound of Lemma 1 (Section 4.4) exceeds delta */
+
+/* return codes */
+#define KGC_OK            0
+#define KGC_OVERFLOW      1    /* more hits than cap: *count is the true total, out_triples holds cap of them */
+#define KGC_E_INVALID    -1    /* bad argument; nothing was launched */
+#define KGC_E_NOMEM      -2    /* device or host allocation failed */
+#define KGC_E_HIP        -3    /* a HIP call failed; see kgc_last_error */
+
+/* Configuration of a handle.  A zero-filled struct selects the defaults. */
+typedef struct {
+    int32_t dtype;            /* KGC_F32 (default) or KGC_BF16: element type of E and Rv */
+    int32_t max_d;            /* largest d this handle accepts; 0 = 1024 (the compiled limit) */
+    int32_t prune;            /* KGC_PRUNE_* */
+    int32_t tile_cfg;         /* 0 = automatic choice of the join kernel's tile shape; >0 selects a variant */
+    int64_t workspace_bytes;  /* cap on scratch held for staged operands; 0 = 16 GiB.  Larger joins run in relation batches */
+    void*   stream;           /* hipStream_t to enqueue on; NULL = the default stream */
+    float   group_radius;     /* pruning only: radius of entity groups as a multiple of delta; 0 = 2.0 */
+    int32_t reserved[5];      /* must be zero */
+} kgc_config;
+
+/* Counters and timings of the last kgc_join on a handle. */
+typedef struct {
+    uint64_t triples_total;     /* N * N * R */
+    uint64_t tiles_total;       /* tile triples (r, head tile, tail tile) of the dense problem */
+    uint64_t tiles_evaluated;   /* tile triples that went through the join kernel */
+    uint64_t tiles_pruned;      /* tiles_total - tiles_evaluated */
+    uint64_t pairs_evaluated;   /* (h, r, t) scored by the join kernel, padding rows excluded */
+    uint64_t candidates;        /* triples that passed the low-precision stage and were re-scored in double */
+    uint64_t emitted;           /* hits found (= *count) */
+    uint64_t join_launches;     /* launches of the join kernel */
+    uint64_t groups;            /* entity groups formed for pruning (0 when pruning is off) */
+    float    ms_total;          /* whole call on the stream, from HIP events */
+    float    ms_precompute;     /* norm / operand staging kernels (a1) */
+    float    ms_prune;          /* grouping + tile bound kernels (a2) */
+    float    ms_join;           /* join kernel launches only (a3 or a4, with the compaction a5 inside) */
+    int32_t  tile_m, tile_n;    /* tile shape used (heads x tails) */
+    int32_t  k_padded;          /* contraction length after appending the norm columns and padding (L2) */
+    int32_t  relation_batches;
+} kgc_stats;
+
+/* Create a handle.  cfg may be NULL (defaults).  Returns KGC_OK and stores the handle in *out (host),
+ * or a negative code and stores NULL. */
+int kgc_create(const kgc_config* cfg, kgc_handle** out);
+
+/* The join (Definition 1, Section 3.1; distance of Section 4.3).
+ *   E           N x d row-major, contiguous, of the handle's dtype           (device)
+ *   Rvecs       R x d row-major, contiguous, same dtype                      (device)
+ *   p           1 or 2
+ *   delta       threshold on the norm; negative => empty result
+ *   out_triples room for cap records, 16-byte aligned                        (device; may be NULL iff cap == 0)
+ *   count       receives the number of qualifying triples, which may exceed cap (host)
+ * On KGC_OK the first *count records are the result, in unspecified order, each triple once.
+ * On KGC_OVERFLOW the buffer holds an arbitrary cap-subset of the result and *count is the true total.
+ * N == 0 or R == 0 is valid and yields *count == 0.  Non-finite values in E, Rvecs: undefined result.
+ * KGC_E_INVALID: p not in {1,2}; d < 1 or d > max_d; N > 2^31 - 64 or R > 2^31 - 1; delta NaN;
+ * a NULL pointer where data is required.  The call synchronises the stream once, to read the count.
+ *
+ * How the set is found: the L2 join scores tile pairs with a bf16 MFMA contraction whose result is a
+ * conservative filter; the L1 join uses float32 vector arithmetic as the filter.  Every triple that
+ * passes the filter is re-scored from the caller's E / Rv in double precision in the order
+ * (E[h] + Rv[r]) - E[t], dimensions summed by a wave-level tree, and the <= delta decision is taken
+ * on that double value. */
+int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R,
+             int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
+
+/* Kernel 1 on its own, for testing: squared L2 norms the pivot bound and the contraction use.
+ *   nB[t]        = || bf16(E[t]) ||^2                 N floats      (device)
+ *   nA[r*N + h]  = || bf16(E[h] + Rv[r]) ||^2         R*N floats    (device)
+ * With the zero vector as pivot (Section 4.5) these are the squares of distB and distA, taken on the
+ * bf16-rounded operands the contraction sees.  Either output may be NULL. */
+int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R,
+              float* nB, float* nA);
+
+/* Copy the statistics of the last kgc_join into *out (host). */
+int kgc_get_stats(const kgc_handle* hd, kgc_stats* out);
+
+/* Message of the last failure on this handle ("" if none).  The string lives as long as the handle. */
+const char* kgc_last_error(const kgc_handle* hd);
+
+/* Release the handle and its scratch memory.  NULL is allowed. */
+void kgc_destroy(kgc_handle* hd);
+
+/* Library version, "major.minor.patch". */
+const char* kgc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KGC_H */

@@ -1,0 +1,207 @@
+"""Python binding of the kgc C ABI (include/kgc.h): argument marshalling only.
+
+Every step of the join runs in the HIP library ``libkgc.so`` built from
+``csrc/``; PyTorch is used for device memory and the stream.  There is no CPU
+fallback: importing works without a GPU (so the exported symbols can be
+checked), but any compute call fails loudly if the library or a device is
+missing.
+
+Names follow the C ABI: ``kgc_create``, ``kgc_join``, ``kgc_norms``,
+``kgc_get_stats``, ``kgc_last_error``, ``kgc_destroy``, ``kgc_version``.  The
+class ``Join`` is a thin convenience wrapper around them.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+from . import build as _build
+
+KGC_F32, KGC_BF16 = 0, 1
+KGC_PRUNE_AUTO, KGC_PRUNE_OFF, KGC_PRUNE_ON = 0, 1, 2
+KGC_OK, KGC_OVERFLOW = 0, 1
+KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
+
+EXPORTS = ["kgc_create", "kgc_join", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy", "kgc_version"]
+
+
+class kgc_triple(ctypes.Structure):
+    _fields_ = [("h", ctypes.c_int32), ("r", ctypes.c_int32), ("t", ctypes.c_int32), ("dist", ctypes.c_float)]
+
+
+class kgc_config(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("max_d", ctypes.c_int32), ("prune", ctypes.c_int32),
+                ("tile_cfg", ctypes.c_int32), ("workspace_bytes", ctypes.c_int64), ("stream", ctypes.c_void_p),
+                ("group_radius", ctypes.c_float), ("reserved", ctypes.c_int32 * 5)]
+
+
+class kgc_stats(ctypes.Structure):
+    _fields_ = [("triples_total", ctypes.c_uint64), ("tiles_total", ctypes.c_uint64),
+                ("tiles_evaluated", ctypes.c_uint64), ("tiles_pruned", ctypes.c_uint64),
+                ("pairs_evaluated", ctypes.c_uint64), ("candidates", ctypes.c_uint64),
+                ("emitted", ctypes.c_uint64), ("join_launches", ctypes.c_uint64), ("groups", ctypes.c_uint64),
+                ("ms_total", ctypes.c_float), ("ms_precompute", ctypes.c_float), ("ms_prune", ctypes.c_float),
+                ("ms_join", ctypes.c_float), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
+                ("k_padded", ctypes.c_int32), ("relation_batches", ctypes.c_int32)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load_library():
+    """Load libkgc.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB)
+    vp = ctypes.c_void_p
+    lib.kgc_create.restype = ctypes.c_int
+    lib.kgc_create.argtypes = [ctypes.POINTER(kgc_config), ctypes.POINTER(vp)]
+    lib.kgc_join.restype = ctypes.c_int
+    lib.kgc_join.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
+                             ctypes.c_float, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64)]
+    lib.kgc_norms.restype = ctypes.c_int
+    lib.kgc_norms.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
+    lib.kgc_get_stats.restype = ctypes.c_int
+    lib.kgc_get_stats.argtypes = [vp, ctypes.POINTER(kgc_stats)]
+    lib.kgc_last_error.restype = ctypes.c_char_p
+    lib.kgc_last_error.argtypes = [vp]
+    lib.kgc_destroy.restype = None
+    lib.kgc_destroy.argtypes = [vp]
+    lib.kgc_version.restype = ctypes.c_char_p
+    lib.kgc_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+# ---- the C ABI, one Python function per entry point ----
+def kgc_version() -> str:
+    return load_library().kgc_version().decode()
+
+
+def kgc_create(cfg: Optional[kgc_config] = None):
+    """Returns (code, handle); handle is an opaque integer (None on failure)."""
+    out = ctypes.c_void_p()
+    rc = load_library().kgc_create(ctypes.byref(cfg) if cfg is not None else None, ctypes.byref(out))
+    return rc, (out.value if rc == KGC_OK else None)
+
+
+def kgc_destroy(handle) -> None:
+    if handle:
+        load_library().kgc_destroy(ctypes.c_void_p(handle))
+
+
+def kgc_last_error(handle) -> str:
+    return load_library().kgc_last_error(ctypes.c_void_p(handle)).decode()
+
+
+def kgc_get_stats(handle) -> dict:
+    st = kgc_stats()
+    rc = load_library().kgc_get_stats(ctypes.c_void_p(handle), ctypes.byref(st))
+    if rc != KGC_OK:
+        raise RuntimeError("kgc_get_stats failed")
+    return st.as_dict()
+
+
+def kgc_join(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, delta: float, out_ptr: int, cap: int):
+    """Raw call on device addresses.  Returns (code, count)."""
+    count = ctypes.c_uint64(0)
+    rc = load_library().kgc_join(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
+                                 ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap, ctypes.byref(count))
+    return rc, int(count.value)
+
+
+def kgc_norms(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, nB_ptr: int, nA_ptr: int) -> int:
+    return load_library().kgc_norms(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R,
+                                    ctypes.c_void_p(nB_ptr), ctypes.c_void_p(nA_ptr))
+
+
+# ---- convenience wrapper over torch tensors ----
+class Join:
+    """Owns one kgc handle bound to the current torch stream.
+
+    ``E`` and ``Rv`` are CUDA tensors, float32 or bfloat16 (matching ``dtype``),
+    contiguous.  ``join`` returns a dict of numpy arrays ``h, r, t, dist``
+    (the first min(count, cap) records), ``count``, ``code`` and ``stats``.
+    """
+
+    def __init__(self, dtype: str = "f32", prune: int = KGC_PRUNE_AUTO, tile_cfg: int = 0, max_d: int = 0,
+                 workspace_bytes: int = 0, group_radius: float = 0.0):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise RuntimeError("kgc needs a GPU: torch.cuda.is_available() is False and there is no CPU fallback")
+        cfg = kgc_config()
+        cfg.dtype = {"f32": KGC_F32, "bf16": KGC_BF16}[dtype]
+        cfg.prune = prune
+        cfg.tile_cfg = tile_cfg
+        cfg.max_d = max_d
+        cfg.workspace_bytes = workspace_bytes
+        cfg.group_radius = group_radius
+        cfg.stream = torch.cuda.current_stream().cuda_stream
+        rc, h = kgc_create(cfg)
+        if rc != KGC_OK:
+            raise RuntimeError(f"kgc_create failed with code {rc}")
+        self.handle = h
+        self.dtype = dtype
+        self._torch = torch
+
+    def close(self):
+        if getattr(self, "handle", None):
+            kgc_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, E, Rv):
+        torch = self._torch
+        want = torch.float32 if self.dtype == "f32" else torch.bfloat16
+        for x in (E, Rv):
+            if not (x.is_cuda and x.is_contiguous() and x.dtype == want and x.dim() == 2):
+                raise ValueError("E and Rv must be contiguous 2-D CUDA tensors of the handle's dtype")
+        if E.shape[0] and Rv.shape[0] and E.shape[1] != Rv.shape[1]:
+            raise ValueError("E and Rv must share d")
+
+    def join(self, E, Rv, p: int, delta: float, cap: int, out=None, fetch: bool = True) -> dict:
+        torch = self._torch
+        self._check(E, Rv)
+        N, d = E.shape[0], (E.shape[1] if E.shape[0] else Rv.shape[1])
+        R = Rv.shape[0]
+        if out is None:
+            out = torch.empty((max(cap, 1), 4), dtype=torch.int32, device=E.device)
+        rc, count = kgc_join(self.handle, E.data_ptr(), N, d, Rv.data_ptr(), R, p, float(delta), out.data_ptr(), cap)
+        if rc < 0:
+            raise RuntimeError(f"kgc_join failed with code {rc}: {kgc_last_error(self.handle)}")
+        res = {"code": rc, "count": count, "stats": kgc_get_stats(self.handle), "out": out}
+        if fetch:
+            n = min(count, cap)
+            host = out[:n].cpu().numpy()
+            res.update({"h": host[:, 0].copy(), "r": host[:, 1].copy(), "t": host[:, 2].copy(),
+                        "dist": host[:, 3].copy().view("float32")})
+        return res
+
+    def norms(self, E, Rv, want_nA: bool = True):
+        torch = self._torch
+        self._check(E, Rv)
+        N, d, R = E.shape[0], E.shape[1], Rv.shape[0]
+        nB = torch.empty(N, dtype=torch.float32, device=E.device)
+        nA = torch.empty((R, N), dtype=torch.float32, device=E.device) if want_nA else None
+        rc = kgc_norms(self.handle, E.data_ptr(), N, d, Rv.data_ptr(), R, nB.data_ptr(),
+                       nA.data_ptr() if nA is not None else 0)
+        if rc < 0:
+            raise RuntimeError(f"kgc_norms failed with code {rc}: {kgc_last_error(self.handle)}")
+        return nB, nA

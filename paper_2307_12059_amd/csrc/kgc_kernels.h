@@ -1,0 +1,428 @@
+// Kernels of the TransE completion join for gfx950 (CDNA4, wave64).
+//
+//   stage_operands   kernel 1: norms of the connector outputs (Section 4.3: a = h + r, b = t) with the zero
+//                    vector as pivot (Section 4.5), and the bf16 operands of the contraction
+//   join_l2          kernel 2: ||a - b||^2 for a tile of heads x tails by bf16 MFMA, filter, exact re-score
+//   join_l1          kernel 3: sum |a - b| for a tile by float32 vector arithmetic, filter, exact re-score
+// Both join kernels end in recheck_and_emit / wave_append (kgc_device.h).
+#pragma once
+#include "kgc_device.h"
+
+namespace kgc {
+
+// Number of extra contraction columns that carry the norms (three bf16 pieces of each float32 norm).
+constexpr int kNormCols = 6;
+// Operands are stored K-slice-major: X[ks][slot][32] bf16, so one tile's slice is contiguous.
+constexpr int kSliceK = 32;
+// Row stride (elements) of a slice in LDS: 32 + 8 padding = 80 bytes, which spreads eight consecutive
+// rows' 16-byte fragments over all banks.
+constexpr int kLdsRow = 40;
+
+// device-side scalars of one join
+struct JoinParams {
+  float thr;            // filter threshold: on the squared distance (L2) or on the float32 sum (L1)
+  float pad[3];
+};
+
+struct DevCounters {
+  unsigned long long hits;        // true number of qualifying triples
+  unsigned long long candidates;  // triples re-scored in double
+  unsigned int max_a_bits;        // max ||bf16(h + r)||^2 (L2) or max ||e||_1 (L1), as float bits
+  unsigned int max_b_bits;        // max ||bf16(t)||^2 (L2) or max ||r||_1 (L1), as float bits
+};
+
+__global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// slot -> entity for the dense order: identity, -1 on the padding rows
+__global__ void k_identity_slots(int32_t* slot_ent, int64_t N, int64_t Nslots) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < Nslots) slot_ent[i] = i < N ? (int32_t)i : -1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 1.  One 32-lane half wave per output row (IS_A: rows are (relation, slot) pairs and the row
+// is a = h + r; otherwise rows are slots and the row is b = t).  The row is rounded to bf16, its
+// squared norm ||.||^2 is summed in float32 from the rounded values, and the staged row is
+//     A:  [ a~ (d) | nA_hi nA_mid nA_lo | 1 1 1 | 0 ... ]
+//     B:  [ -2 b~ (d) | 1 1 1 | nB_hi nB_mid nB_lo | 0 ... ]
+// so that the dot product of an A row and a B row is nA + nB - 2 a~.b~ = ||a~ - b~||^2.  The three
+// pieces are the float32 norm cut into 8-bit mantissa chunks, exact in bf16.  Padding rows get a norm
+// of 1e30 so they never pass the filter.  The squared norms are also written out plainly; with the
+// zero pivot they are distA^2 and distB^2 of Section 4.5.
+template <bool IS_A>
+__global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__ E, const void* __restrict__ Rv,
+                                                        int dtype, int d, int r0, int RB,
+                                                        const int32_t* __restrict__ slot_ent, int64_t Nslots, int KS,
+                                                        uint16_t* __restrict__ out, float* __restrict__ norms,
+                                                        unsigned int* __restrict__ max_bits) {
+  const int j = threadIdx.x & 31;
+  const int64_t hw = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 5;
+  const int64_t nhw = ((int64_t)gridDim.x * blockDim.x) >> 5;
+  const int64_t rows = (int64_t)RB * Nslots;
+  float vmax = 0.f;
+  for (int64_t row = hw; row < rows; row += nhw) {
+    const int rl = (int)(row / Nslots);
+    const int64_t slot = row - (int64_t)rl * Nslots;
+    const int ent = slot_ent[slot];
+    const int64_t eo = (int64_t)(ent < 0 ? 0 : ent) * d;
+    const int64_t ro = (int64_t)(r0 + rl) * d;
+    float sq = 0.f;
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks * kSliceK + j;
+      if (ent >= 0 && c < d) {
+        float v = ld_elem(E, eo + c, dtype);
+        if (IS_A) v += ld_elem(Rv, ro + c, dtype);
+        v = bf16_to_f32(f32_to_bf16_rne(v));
+        sq += v * v;
+      }
+    }
+    sq += __shfl_xor(sq, 16, 32);
+    sq += __shfl_xor(sq, 8, 32);
+    sq += __shfl_xor(sq, 4, 32);
+    sq += __shfl_xor(sq, 2, 32);
+    sq += __shfl_xor(sq, 1, 32);
+    const float nrm = ent >= 0 ? sq : 1e30f;
+    uint16_t piece[3];
+    float rem = nrm;
+    for (int q = 0; q < 3; ++q) {
+      piece[q] = f32_to_bf16_trunc(rem);
+      rem -= bf16_to_f32(piece[q]);
+    }
+    const uint16_t one = 0x3F80u;
+    uint16_t* orow = out + ((int64_t)rl * KS * Nslots + slot) * kSliceK + j;
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks * kSliceK + j;
+      uint16_t o = 0;
+      if (c < d) {
+        if (ent >= 0) {
+          float v = ld_elem(E, eo + c, dtype);
+          if (IS_A) v += ld_elem(Rv, ro + c, dtype);
+          v = bf16_to_f32(f32_to_bf16_rne(v));
+          o = f32_to_bf16_rne(IS_A ? v : -2.f * v);
+        }
+      } else {
+        const int q = c - d;
+        if (q < 3) o = IS_A ? piece[q] : one;
+        else if (q < kNormCols) o = IS_A ? one : piece[q - 3];
+      }
+      orow[(int64_t)ks * Nslots * kSliceK] = o;
+    }
+    if (j == 0) {
+      if (norms) norms[row] = nrm;
+      if (ent >= 0) vmax = fmaxf(vmax, nrm);
+    }
+  }
+  if (j == 0 && max_bits) atomicMax(max_bits, __float_as_uint(vmax));   // non-negative floats order like their bits
+}
+
+// squared norms scattered back to entity order (kgc_norms)
+__global__ void k_scatter_norms(const float* __restrict__ norms, const int32_t* __restrict__ slot_ent, int64_t Nslots,
+                                int64_t N, int RB, float* __restrict__ outp) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)RB * Nslots) return;
+  const int rl = (int)(i / Nslots);
+  const int ent = slot_ent[i - (int64_t)rl * Nslots];
+  if (ent >= 0) outp[(int64_t)rl * N + ent] = norms[i];
+}
+
+// max over rows of the L1 norm (used for the float32 error bound of the L1 filter)
+__global__ __launch_bounds__(256) void k_row_l1_max(const void* __restrict__ X, int64_t rows, int d, int dtype,
+                                                    unsigned int* __restrict__ max_bits) {
+  const int j = threadIdx.x & 31;
+  const int64_t hw = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 5;
+  const int64_t nhw = ((int64_t)gridDim.x * blockDim.x) >> 5;
+  float vmax = 0.f;
+  for (int64_t row = hw; row < rows; row += nhw) {
+    float s = 0.f;
+    for (int c = j; c < d; c += 32) s += fabsf(ld_elem(X, row * d + c, dtype));
+    s += __shfl_xor(s, 16, 32);
+    s += __shfl_xor(s, 8, 32);
+    s += __shfl_xor(s, 4, 32);
+    s += __shfl_xor(s, 2, 32);
+    s += __shfl_xor(s, 1, 32);
+    vmax = fmaxf(vmax, s);
+  }
+  if (j == 0) atomicMax(max_bits, __float_as_uint(vmax));
+}
+
+// Filter thresholds, computed on the device so that no host round trip sits between kernel 1 and the join.
+//
+// L2.  a~, b~ are a, b rounded to bf16 (unit roundoff 2^-8), so ||a~ - a|| <= 2^-8 ||a|| and likewise b.
+// By the triangle inequality (the argument of Lemma 1, Section 4.4) a true hit ||a - b|| <= delta has
+// ||a~ - b~|| <= delta + m with m = u (max||a|| + max||b||), u slightly above 2^-8.  The contraction
+// returns ||a~ - b~||^2 with an accumulated float32 error of at most e_acc, so the filter keeps
+// D <= (delta + m)^2 + e_acc and loses no hit.  With bf16 storage b~ = b and drops out of m.
+// L1.  The float32 sum of |fl(fl(h + r) - t)| differs from the exact sum by at most
+// 2^-23 (max||h||_1 + max||r||_1) + (d + 2) 2^-23 (delta + that); the filter keeps sums below delta + margin.
+__global__ void k_join_params(DevCounters* cnt, JoinParams* prm, float delta, int p, int dtype, int d, int kp) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const float ma = __uint_as_float(cnt->max_a_bits), mb = __uint_as_float(cnt->max_b_bits);
+  float thr;
+  if (delta < 0.f) {
+    thr = -1.f;                                   // squared distances and sums are >= 0: nothing passes
+  } else if (p == 2) {
+    const float u = 1.01f / 256.f;
+    const float na = sqrtf(ma) * 1.01f, nb = sqrtf(mb) * 1.01f;
+    const float m = u * (na + (dtype == KGC_BF16 ? 0.f : nb));
+    const float eacc = (float)(kp + 16) * 1.2e-7f * 2.f * (ma + mb);
+    const float dm = delta + m;
+    thr = (dm * dm + eacc) * (1.f + 1e-6f);
+  } else {
+    const float base = 1.2e-7f * (ma + mb);
+    thr = (delta + base + (float)(d + 2) * 1.2e-7f * (delta + base)) * (1.f + 1e-6f);
+  }
+  prm->thr = thr;
+}
+
+// ---------------------------------------------------------------------------------------------
+struct JoinArgs {
+  const uint16_t* A;        // staged A operands of this relation batch: [RB][KS][Nslots][32]   (L2)
+  const uint16_t* B;        // staged B operands: [KS][Nslots][32]                              (L2)
+  const JoinParams* prm;
+  int64_t Nslots;
+  int KS;                   // 32-wide slices
+  int k16;                  // 16-wide MFMA steps that hold data (the last slice may be half empty)
+  int nH, nT;               // tiles along heads / tails
+  int r0, RB;               // first relation and number of relations of this batch
+  const uint32_t* worklist; // NULL: dense grid; else packed (r_local, tile_h, tile_t) triples, 3 words each
+  RecheckCtx cx;
+};
+
+// Kernel 2.  One block scores one (relation, head tile, tail tile): D = A_tile * B_tile^T over the
+// augmented K (Section 4.3's dist for p = 2, squared, on bf16-rounded operands), with bf16 MFMA
+// 32x32x16 and float32 accumulation.  K slices go global -> registers -> LDS, double buffered.
+// WGM x WGN waves; each wave owns a (BM/WGM) x (BN/WGN) sub-tile as TM x TN MFMA tiles.
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(WGM* WGN * 64) void k_join_l2(const JoinArgs a) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int LA = (BM * 4) / NT, LB = (BN * 4) / NT;   // 16-byte chunks per thread per slice
+  static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
+  static_assert(TM >= 1 && TN >= 1, "wave tile too small");
+
+  __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * kLdsRow];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * kLdsRow];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  int tH, tT, rl;
+  if (a.worklist) {
+    const uint32_t* w = a.worklist + (int64_t)blockIdx.x * 3;
+    rl = (int)w[0]; tH = (int)w[1]; tT = (int)w[2];
+  } else {
+    const int64_t bid = blockIdx.x;
+    tT = (int)(bid % a.nT);
+    const int64_t q = bid / a.nT;
+    tH = (int)(q % a.nH);
+    rl = (int)(q / a.nH);
+  }
+
+  const int64_t slice_elems = a.Nslots * kSliceK;
+  const uint16_t* Ab = a.A + (int64_t)rl * a.KS * slice_elems + (int64_t)tH * BM * kSliceK;
+  const uint16_t* Bb = a.B + (int64_t)tT * BN * kSliceK;
+
+  uint4 ra[LA], rb[LB];
+  auto gload = [&](int ks) {
+    const uint4* ga = (const uint4*)(Ab + (int64_t)ks * slice_elems);
+    const uint4* gb = (const uint4*)(Bb + (int64_t)ks * slice_elems);
+#pragma unroll
+    for (int i = 0; i < LA; ++i) ra[i] = ga[tid + i * NT];
+#pragma unroll
+    for (int i = 0; i < LB; ++i) rb[i] = gb[tid + i * NT];
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      const int c = tid + i * NT;
+      *(uint4*)(&As[buf][(c >> 2) * kLdsRow + (c & 3) * 8]) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      const int c = tid + i * NT;
+      *(uint4*)(&Bs[buf][(c >> 2) * kLdsRow + (c & 3) * 8]) = rb[i];
+    }
+  };
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+
+  const int arow = wm * WTM + (lane & 31);
+  const int brow = wn * WTN + (lane & 31);
+  const int koff = (lane >> 5) * 8;
+
+  for (int ks = 0; ks < a.KS; ++ks) {
+    const int buf = ks & 1;
+    if (ks + 1 < a.KS) gload(ks + 1);
+    const int steps = (a.k16 - ks * 2) >= 2 ? 2 : 1;
+    for (int s = 0; s < steps; ++s) {
+      bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        fa[i] = *(const bf16x8_t*)(&As[buf][(arow + i * 32) * kLdsRow + s * 16 + koff]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        fb[j] = *(const bf16x8_t*)(&Bs[buf][(brow + j * 32) * kLdsRow + s * 16 + koff]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (ks + 1 < a.KS) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: filter on the squared distance, then the rare exact path ----
+  const float thr = a.prm->thr;
+  float mn = acc[0][0][0];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);
+  if (__builtin_amdgcn_ballot_w64(mn <= thr) == 0ull) return;
+
+  // MFMA 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
+  const int64_t hbase = (int64_t)tH * BM + wm * WTM;
+  const int64_t tbase = (int64_t)tT * BN + wn * WTN;
+  constexpr int NW = (TM * TN + 3) / 4;      // 64-element words of the candidate mask
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    unsigned long long cm = 0ull;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int tile = w * 4 + q;
+      if (tile < TM * TN) {
+        const int i = tile / TN, j = tile % TN;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (acc[i][j][v] <= thr) cm |= 1ull << (q * 16 + v);
+      }
+    }
+    if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;
+    recheck_and_emit(cm, a.r0 + rl, a.cx, [&](int e, int src, int64_t& hslot, int64_t& tslot) {
+      const int tile = w * 4 + (e >> 4), v = e & 15;
+      const int i = tile / TN, j = tile % TN;
+      hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);
+      tslot = tbase + j * 32 + (src & 31);
+    });
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+struct JoinL1Args {
+  const JoinParams* prm;
+  int64_t Nslots;
+  int nH, nT;
+  int r0, RB;
+  const uint32_t* worklist;
+  RecheckCtx cx;
+};
+
+// Kernel 3.  One block of 256 threads scores a 128 x 128 tile of (heads, tails) for one relation in
+// float32 vector arithmetic only: acc += |(h_k + r_k) - t_k| (Section 4.3's dist for p = 1).  The
+// tile is staged through LDS in 16-dimension slices, dimension-major, a = h + r formed while staging;
+// each thread keeps an 8 x 8 block of sums in registers (two 4-row groups x two 4-column groups).
+constexpr int kL1Tile = 128;
+constexpr int kL1K = 16;
+__global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
+  constexpr int BM = kL1Tile, BN = kL1Tile, BK = kL1K;
+  __shared__ __attribute__((aligned(16))) float As[BK][BM];
+  __shared__ __attribute__((aligned(16))) float Bs[BK][BN];
+  __shared__ int32_t hent[BM], tent[BN];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int tH, tT, rl;
+  if (a.worklist) {
+    const uint32_t* w = a.worklist + (int64_t)blockIdx.x * 3;
+    rl = (int)w[0]; tH = (int)w[1]; tT = (int)w[2];
+  } else {
+    const int64_t bid = blockIdx.x;
+    tT = (int)(bid % a.nT);
+    const int64_t q = bid / a.nT;
+    tH = (int)(q % a.nH);
+    rl = (int)(q / a.nH);
+  }
+  const int r = a.r0 + rl;
+  const int d = a.cx.d, dtype = a.cx.dtype;
+  if (tid < BM) hent[tid] = a.cx.slot_ent[(int64_t)tH * BM + tid];
+  else tent[tid - BM] = a.cx.slot_ent[(int64_t)tT * BN + (tid - BM)];
+  __syncthreads();
+
+  const int tx = tid & 15, ty = tid >> 4;
+  float acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+
+  // staging assignment: thread -> (row = tid / 2, eight dimensions starting at (tid % 2) * 8)
+  const int srow = tid >> 1, sk0 = (tid & 1) * 8;
+  const int he = hent[srow], te = tent[srow];
+  const int64_t ho = (int64_t)(he < 0 ? 0 : he) * d, to = (int64_t)(te < 0 ? 0 : te) * d, ro = (int64_t)r * d;
+
+  for (int k0 = 0; k0 < d; k0 += BK) {
+    float va[8], vb[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int k = k0 + sk0 + q;
+      const bool in = k < d;
+      va[q] = in ? ld_elem(a.cx.E, ho + k, dtype) + ld_elem(a.cx.Rv, ro + k, dtype) : 0.f;
+      vb[q] = in ? ld_elem(a.cx.E, to + k, dtype) : 0.f;
+    }
+    __syncthreads();                        // previous slice fully consumed
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      As[sk0 + q][srow] = va[q];
+      Bs[sk0 + q][srow] = vb[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < BK; ++k) {
+      const float4 a0 = *(const float4*)(&As[k][ty * 4]);
+      const float4 a1 = *(const float4*)(&As[k][64 + ty * 4]);
+      const float4 b0 = *(const float4*)(&Bs[k][tx * 4]);
+      const float4 b1 = *(const float4*)(&Bs[k][64 + tx * 4]);
+      const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+      const float bv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] += fabsf(av[i] - bv[j]);
+    }
+  }
+
+  const float thr = a.prm->thr;
+  unsigned long long cm = 0ull;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (acc[i][j] <= thr) cm |= 1ull << (i * 8 + j);
+  if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) return;
+  const int64_t hbase = (int64_t)tH * BM, tbase = (int64_t)tT * BN;
+  recheck_and_emit(cm, r, a.cx, [&](int e, int src, int64_t& hslot, int64_t& tslot) {
+    const int stid = wave * 64 + src;
+    const int sx = stid & 15, sy = stid >> 4;
+    const int i = e >> 3, j = e & 7;
+    hslot = hbase + (i >> 2) * 64 + sy * 4 + (i & 3);
+    tslot = tbase + (j >> 2) * 64 + sx * 4 + (j & 3);
+  });
+}
+
+}  // namespace kgc

@@ -1,0 +1,167 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dev(x, dtype="f32"):
+    torch = _torch()
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16).contiguous() if dtype == "bf16" else t
+
+
+def _run(E, Rv, p, delta, cap=None, dtype="f32", **kw):
+    import paper_2307_12059_amd as kgc
+    j = kgc.Join(dtype=dtype, **kw)
+    try:
+        Ed, Rd = _dev(E, dtype), _dev(Rv, dtype)
+        if cap is None:
+            cap = 1 << 20
+        return j.join(Ed, Rd, p, delta, cap)
+    finally:
+        j.close()
+
+
+def _check(E, Rv, p, delta, dtype="f32", **kw):
+    """E, Rv: float32 arrays holding the values the device sees."""
+    ref = oracle.join(E, Rv, p, delta, mode="abandon")
+    got = _run(E, Rv, p, delta, cap=max(1024, 2 * ref["count"]), dtype=dtype, **kw)
+    assert got["code"] == 0
+    rep = parity.compare(got, ref, E, Rv, p, delta, E.shape[0])
+    assert got["count"] == rep["gpu_count"]
+    return got, ref, rep
+
+
+E3 = np.array([[0.0, 0.0], [3.0, 4.0], [1.0, 0.0]], np.float32)
+R2 = np.array([[3.0, 4.0], [0.0, 0.0]], np.float32)
+
+
+@pytest.mark.parametrize("p,delta,count", [(2, 1.0, 7), (2, 5.0, 15), (1, 5.0, 7)])
+def test_hand_case(p, delta, count):
+    got, ref, rep = _check(E3, R2, p, delta)
+    assert got["count"] == count == ref["count"]
+
+
+@pytest.mark.parametrize("tile_cfg", [0, 2, 3, 4, 5])
+def test_c1_l2_full_parity(tile_cfg):
+    wl = workloads.generate("c1_tiny_l2")
+    got, ref, rep = _check(wl.E, wl.Rv, 2, wl.delta, tile_cfg=tile_cfg)
+    assert ref["count"] == 3640 and rep["boundary_band"] <= 40
+    # the hit decision is taken in double on both sides, so even the boundary band agrees here
+    assert rep["only_gpu_in_band"] == 0 and rep["only_oracle_in_band"] == 0
+    st = got["stats"]
+    assert st["triples_total"] == 2000 * 2000 * 8 and st["emitted"] == got["count"] and st["candidates"] >= got["count"]
+
+
+def test_c1_l1_full_parity():
+    wl = workloads.generate("c1_tiny_l2")
+    h, r, t = workloads.sample_uniform_triples(wl, 200_000, 77)
+    delta = float(np.float32(np.sort(oracle.dist_triples(wl.E, wl.Rv, 1, h, r, t))[40]))
+    got, ref, rep = _check(wl.E, wl.Rv, 1, delta)
+    assert ref["count"] > 1000
+
+
+@pytest.mark.parametrize("p", [1, 2])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,R,d", [(300, 3, 37), (257, 2, 200), (129, 1, 7), (1, 1, 1), (700, 5, 122)])
+def test_ragged_shapes(p, dtype, N, R, d):
+    g = np.random.default_rng(N * 1000 + d)
+    cent = g.standard_normal((4, d))
+    E = (cent[g.integers(0, 4, N)] + 0.1 * g.standard_normal((N, d))).astype(np.float32)
+    Rv = (cent[g.integers(0, 4, R)] - cent[g.integers(0, 4, R)] + 0.02 * g.standard_normal((R, d))).astype(np.float32)
+    if dtype == "bf16":
+        E = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(E))
+        Rv = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(Rv))
+    n = min(20000, N * N * R)
+    hh, rr, tt = g.integers(0, N, n), g.integers(0, R, n), g.integers(0, N, n)
+    delta = float(np.float32(np.quantile(oracle.dist_triples(E, Rv, p, hh, rr, tt), 0.02)))
+    got, ref, rep = _check(E, Rv, p, delta, dtype=dtype)
+    assert ref["count"] > 0
+
+
+@pytest.mark.parametrize("p", [1, 2])
+def test_edge_cases(p):
+    import paper_2307_12059_amd as kgc
+    torch = _torch()
+    wl = workloads.generate("c1_tiny_l2", N=400, R=3)
+    E, Rv = wl.E, wl.Rv
+    # negative threshold and empty inputs: valid, empty
+    assert _run(E, Rv, p, -1.0)["count"] == 0
+    assert _run(E[:0], Rv, p, 1.0)["count"] == 0
+    assert _run(E, Rv[:0], p, 1.0)["count"] == 0
+    # infinite threshold: every triple, each once
+    got = _run(E[:70], Rv[:2], p, float("inf"), cap=70 * 70 * 2)
+    assert got["count"] == 70 * 70 * 2
+    assert np.unique((got["r"].astype(np.int64) * 70 + got["h"]) * 70 + got["t"]).size == 70 * 70 * 2
+    np.testing.assert_allclose(got["dist"], oracle.dist_triples(E[:70], Rv[:2], p, got["h"], got["r"], got["t"]),
+                               rtol=1e-6)
+    # overflow: true count reported, cap valid records, all of them real hits
+    ref = oracle.join(E, Rv, p, 3.0 if p == 2 else 14.0)
+    assert ref["count"] > 50
+    got = _run(E, Rv, p, 3.0 if p == 2 else 14.0, cap=17)
+    assert got["code"] == kgc.KGC_OVERFLOW and got["count"] == ref["count"] and got["h"].size == 17
+    refset = set(zip(ref["r"].tolist(), ref["h"].tolist(), ref["t"].tolist()))
+    assert all(k in refset for k in zip(got["r"].tolist(), got["h"].tolist(), got["t"].tolist()))
+    # cap == 0 with a NULL buffer only counts
+    j = kgc.Join()
+    rc, cnt = kgc.kgc_join(j.handle, _dev(E).data_ptr(), 400, 32, _dev(Rv).data_ptr(), 3, p,
+                           3.0 if p == 2 else 14.0, 0, 0)
+    assert rc == kgc.KGC_OVERFLOW and cnt == ref["count"]
+    # invalid arguments
+    Ed, Rd = _dev(E), _dev(Rv)
+    out = torch.empty((16, 4), dtype=torch.int32, device="cuda")
+    assert kgc.kgc_join(j.handle, Ed.data_ptr(), 400, 32, Rd.data_ptr(), 3, 3, 1.0, out.data_ptr(), 16)[0] == kgc.KGC_E_INVALID
+    assert "p must be" in kgc.kgc_last_error(j.handle)
+    assert kgc.kgc_join(j.handle, Ed.data_ptr(), 400, 0, Rd.data_ptr(), 3, p, 1.0, out.data_ptr(), 16)[0] == kgc.KGC_E_INVALID
+    assert kgc.kgc_join(j.handle, Ed.data_ptr(), 400, 5000, Rd.data_ptr(), 3, p, 1.0, out.data_ptr(), 16)[0] == kgc.KGC_E_INVALID
+    assert kgc.kgc_join(j.handle, 0, 400, 32, Rd.data_ptr(), 3, p, 1.0, out.data_ptr(), 16)[0] == kgc.KGC_E_INVALID
+    assert kgc.kgc_join(j.handle, Ed.data_ptr(), 400, 32, Rd.data_ptr(), 3, p, float("nan"), out.data_ptr(), 16)[0] == kgc.KGC_E_INVALID
+    assert kgc.kgc_join(j.handle, Ed.data_ptr(), 400, 32, Rd.data_ptr(), 3, p, 1.0, 0, 16)[0] == kgc.KGC_E_INVALID
+    assert kgc.kgc_join(j.handle, Ed.data_ptr(), 400, 32, Rd.data_ptr(), 3, p, 1.0, out.data_ptr() + 4, 8)[0] == kgc.KGC_E_INVALID
+    j.close()
+
+
+def test_zero_relation_symmetry():
+    wl = workloads.generate("c1_tiny_l2", N=500, R=1)
+    got = _run(wl.E, np.zeros_like(wl.Rv), 2, 0.8)
+    S = set(zip(got["h"].tolist(), got["t"].tolist()))
+    assert all((t, h) in S for (h, t) in S) and all((i, i) in S for i in range(500))
+
+
+def test_repeatable_and_tile_independent():
+    wl = workloads.generate("c1_tiny_l2", N=1500, R=4)
+    ref = None
+    for tile_cfg in (1, 1, 2, 3):
+        got = _run(wl.E, wl.Rv, 2, 0.7, tile_cfg=tile_cfg)
+        key = np.sort((got["r"].astype(np.int64) * 1500 + got["h"]) * 1500 + got["t"])
+        assert ref is None or np.array_equal(ref, key)
+        ref = key
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_kernel1_norms(dtype):
+    import paper_2307_12059_amd as kgc
+    wl = workloads.generate("c1_tiny_l2", N=333, R=3, d=45)
+    E, Rv = wl.E, wl.Rv
+    if dtype == "bf16":
+        E = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(E)); Rv = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(Rv))
+    j = kgc.Join(dtype=dtype)
+    nB, nA = j.norms(_dev(E, dtype), _dev(Rv, dtype))
+    j.close()
+    rb = lambda x: workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(x.astype(np.float32))).astype(np.float64)
+    refB = (rb(E) ** 2).sum(1)
+    refA = np.stack([(rb(E + Rv[r]) ** 2).sum(1) for r in range(3)])
+    np.testing.assert_allclose(nB.cpu().numpy(), refB, rtol=2e-6)
+    np.testing.assert_allclose(nA.cpu().numpy(), refA, rtol=2e-6)
+    # zero pivot (Section 4.5): sqrt(nB) is distB up to the bf16 rounding of the operand
+    np.testing.assert_allclose(np.sqrt(nB.cpu().numpy()), np.linalg.norm(E.astype(np.float64), axis=1), rtol=5e-3)
