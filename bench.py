@@ -1,0 +1,149 @@
+"""Benchmark of the TransE completion join on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_mid_l2] [--prune on|off]
+
+A step is one whole kgc_join (operand staging, pruning, join kernel, compaction, count read-back) on
+synthetic inputs already resident in HBM.  Prints ONE JSON line: effective triple-scores/s
+(N*N*R / time), the roofline of the dominant kernel (the join kernel, timed with HIP events on the
+library's stream), and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA
+PEAK_VALU_TLANEOPS = 39.3          # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz, plain (unpacked) float32 lane-ops
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(wl, target_seconds=12.0):
+    """The oracle as it stands (brute-force mode, all host threads) on a bounded sample of the workload."""
+    import numpy as np
+
+    import oracle
+    spec = wl.spec
+    d = wl.E.shape[1]
+    threads = oracle.num_threads()
+    n0 = min(wl.E.shape[0], 1500)
+    r0 = min(wl.Rv.shape[0], 4)
+    t0 = time.perf_counter()
+    oracle.join(wl.E[:n0], wl.Rv[:r0], spec.p, wl.delta, mode="brute")
+    rate0 = n0 * n0 * r0 / max(time.perf_counter() - t0, 1e-6)
+    ns = min(wl.E.shape[0], 4000)
+    rs = int(max(1, min(wl.Rv.shape[0], round(rate0 * target_seconds / (ns * ns)))))
+    t0 = time.perf_counter()
+    res = oracle.join(wl.E[:ns], wl.Rv[:rs], spec.p, wl.delta, mode="brute")
+    dt = time.perf_counter() - t0
+    return {"value": ns * ns * rs / dt, "unit": "triple-scores/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {ns} entities x first {rs} relations of {spec.name} (d={d}, p={spec.p}), "
+                      f"brute-force fp64, {dt:.1f} s, {res['count']} hits"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c2_mid_l2")
+    ap.add_argument("--prune", choices=["on", "off"], default="on")
+    ap.add_argument("--tile", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--also-dense", type=int, default=3, help="extra dense (prune off) steps reported beside a pruned run")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2307_12059_amd as kgc
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    wl = workloads.generate(args.workload)
+    spec = wl.spec
+    N, R, d, p = spec.N, spec.R, spec.d, spec.p
+    if spec.storage == "bf16":
+        E = torch.from_numpy(wl.E_bits.view(np.int16)).cuda().view(torch.bfloat16)
+        Rv = torch.from_numpy(wl.Rv_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        E = torch.from_numpy(wl.E).cuda()
+        Rv = torch.from_numpy(wl.Rv).cuda()
+    cap = int(4 * spec.selectivity * spec.n_triples) + 4096
+    out = torch.empty((cap, 4), dtype=torch.int32, device="cuda")
+
+    def run(prune, steps, warmup):
+        j = kgc.Join(dtype=spec.storage, prune=kgc.KGC_PRUNE_ON if prune else kgc.KGC_PRUNE_OFF, tile_cfg=args.tile)
+        res = None
+        for _ in range(warmup):
+            res = j.join(E, Rv, p, wl.delta, cap, out=out, fetch=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        acc = {"ms_join": 0.0, "ms_precompute": 0.0, "ms_prune": 0.0, "ms_total": 0.0}
+        for _ in range(steps):
+            res = j.join(E, Rv, p, wl.delta, cap, out=out, fetch=False)
+            for k in acc:
+                acc[k] += res["stats"][k]
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        j.close()
+        st = res["stats"]
+        launches = max(1, st["join_launches"])
+        ms_join = acc["ms_join"] / steps
+        work = 2.0 * d * st["pairs_evaluated"]                 # flop (L2) or lane-ops (L1) of the join kernel per step
+        if p == 2:
+            roof = {"bound": "mfma", "achieved": work / (ms_join * 1e-3) / 1e12 if ms_join > 0 else 0.0,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+        else:
+            roof = {"bound": "alu", "achieved": work / (ms_join * 1e-3) / 1e12 if ms_join > 0 else 0.0,
+                    "peak": PEAK_VALU_TLANEOPS, "unit": "Tlane-op/s"}
+        roof["frac"] = roof["achieved"] / roof["peak"]
+        roof["traffic"] = None
+        roof["kernel"] = "k_join_l2" if p == 2 else "k_join_l1"
+        roof["launches_per_step"] = launches
+        roof["avg_launch_ms"] = ms_join / launches
+        return {"ms_per_step": dt * 1e3 / steps, "count": res["count"], "code": res["code"], "stats": st,
+                "phase_ms": {k: v / steps for k, v in acc.items()}, "roofline": roof}
+
+    main_run = run(args.prune == "on", args.steps, args.warmup)
+    line = {
+        "metric": "triple_scores_per_sec_effective",
+        "value": N * N * R / (main_run["ms_per_step"] * 1e-3),
+        "unit": "triple-scores/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_run["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if p == 2 else "f32", "data": "synthetic",
+        "config": {"workload": f"{spec.name}: N={N} R={R} d={d} L{p} {spec.storage} storage, delta={wl.delta:.6g}, "
+                               f"selectivity {spec.selectivity:g}",
+                   "prune": args.prune, "tile": [main_run["stats"]["tile_m"], main_run["stats"]["tile_n"]]},
+        "hits": main_run["count"],
+        "evaluated_triple_scores_per_sec": main_run["stats"]["pairs_evaluated"] / (main_run["ms_per_step"] * 1e-3),
+        "tiles": {"total": main_run["stats"]["tiles_total"], "pruned": main_run["stats"]["tiles_pruned"],
+                  "pruned_frac": main_run["stats"]["tiles_pruned"] / max(1, main_run["stats"]["tiles_total"])},
+        "candidates": main_run["stats"]["candidates"],
+        "phase_ms": main_run["phase_ms"],
+        "roofline": main_run["roofline"],
+    }
+    if args.prune == "on" and args.also_dense > 0:
+        dense = run(False, args.also_dense, 1)
+        line["dense"] = {"ms_per_step": dense["ms_per_step"], "value": N * N * R / (dense["ms_per_step"] * 1e-3),
+                         "hits": dense["count"], "phase_ms": dense["phase_ms"], "roofline": dense["roofline"],
+                         "speedup_prune_on_vs_off": dense["ms_per_step"] / main_run["ms_per_step"]}
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -52,7 +52,7 @@ typedef struct { int32_t h, r, t; float dist; } kgc_triple;
 /* Configuration of a handle.  A zero-filled struct selects the defaults. */
 typedef struct {
     int32_t dtype;            /* KGC_F32 (default) or KGC_BF16: element type of E and Rv */
-    int32_t max_d;            /* largest d this handle accepts; 0 = 1024 (the compiled limit) */
+    int32_t max_d;            /* largest d this handle accepts; 0 = 960 (the compiled limit) */
     int32_t prune;            /* KGC_PRUNE_* */
     int32_t tile_cfg;         /* 0 = automatic choice of the join kernel's tile shape; >0 selects a variant */
     int64_t workspace_bytes;  /* cap on scratch held for staged operands; 0 = 16 GiB.  Larger joins run in relation batches */

@@ -15,7 +15,7 @@ using namespace kgc;
 
 namespace {
 
-constexpr int kMaxD = 1024;
+constexpr int kMaxD = 960;                      // keeps kernel 1's LDS tile under 64 KiB
 constexpr int64_t kSlotAlign = 256;            // rows are padded to a multiple of the largest tile
 constexpr int64_t kDefaultWorkspace = 16ll << 30;
 
@@ -177,16 +177,17 @@ int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* R
       (rc = ensure(hd, hd->opA, op_bytes)) || (rc = ensure(hd, hd->normsB, Nslots * 4)))
     return rc;
   k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
-  const int g = grid_for(Nslots * 32, 256);
+  const int g = grid_for(Nslots / kStageRows, 1);
+  const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
   if (nB) {
-    k_stage_operands<false><<<g, 256, 0, st>>>(E, Rvecs, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Nslots, KS,
+    k_stage_operands<false><<<g, 256, stage_lds, st>>>(E, Rvecs, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Nslots, KS,
                                                (uint16_t*)hd->opB.p, (float*)hd->normsB.p, nullptr);
     k_scatter_norms<<<grid_for(Nslots, 256), 256, 0, st>>>((const float*)hd->normsB.p, (const int32_t*)hd->slot_ent.p,
                                                            Nslots, N, 1, nB);
   }
   if (nA) {
     for (int r = 0; r < R; ++r) {
-      k_stage_operands<true><<<g, 256, 0, st>>>(E, Rvecs, dtype, d, r, 1, (const int32_t*)hd->slot_ent.p, Nslots, KS,
+      k_stage_operands<true><<<g, 256, stage_lds, st>>>(E, Rvecs, dtype, d, r, 1, (const int32_t*)hd->slot_ent.p, Nslots, KS,
                                                 (uint16_t*)hd->opA.p, (float*)hd->normsB.p, nullptr);
       k_scatter_norms<<<grid_for(Nslots, 256), 256, 0, st>>>((const float*)hd->normsB.p,
                                                              (const int32_t*)hd->slot_ent.p, Nslots, N, 1,
@@ -231,9 +232,10 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   const size_t opA_per_rel = (p == 2) ? (size_t)KS * Nslots * kSliceK * 2 : 0;
   int64_t RBmax = R;
   if (p == 2) RBmax = std::max<int64_t>(1, std::min<int64_t>(R, ws / (int64_t)(opA_per_rel + Nslots * 4)));
+  // dense launches use a (tail tile, head tile, relation) grid; y and z are limited to 65535 blocks
   const int64_t tiles_per_rel = (int64_t)nH * nT;
-  RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, ((int64_t)1 << 31) / tiles_per_rel - 1));
-  if (tiles_per_rel >= ((int64_t)1 << 31) - 1) return fail(hd, KGC_E_INVALID, "N too large for one launch grid");
+  RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, 65535));
+  if (nH > 65535) return fail(hd, KGC_E_INVALID, "N too large for one launch grid");
 
   if ((rc = ensure(hd, hd->slot_ent, Nslots * 4)) || (rc = ensure(hd, hd->counters, sizeof(DevCounters))) ||
       (rc = ensure(hd, hd->params, sizeof(JoinParams))))
@@ -256,7 +258,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   const int32_t* slot_ent = (const int32_t*)hd->slot_ent.p;
 
   KGC_HIP(hd, hipEventRecord(hd->ev[0], st));
-  k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
+  k_fill_u32<<<grid_for(sizeof(DevCounters) / 4, 256), 256, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
   k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
 
   RecheckCtx cx;
@@ -265,12 +267,13 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates;
 
   float ms_pre_extra = 0.f;
+  const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
   if (p == 2) {
-    k_stage_operands<false><<<grid_for(Nslots * 32, 256), 256, 0, st>>>(
-        E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, &cnt->max_b_bits);
+    k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
+        E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b);
   } else {
-    k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(E, N, d, dtype, &cnt->max_a_bits);
-    k_row_l1_max<<<grid_for((int64_t)R * 32, 256), 256, 0, st>>>(Rvecs, R, d, dtype, &cnt->max_b_bits);
+    k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(E, N, d, dtype, cnt->max_a);
+    k_row_l1_max<<<grid_for((int64_t)R * 32, 256), 256, 0, st>>>(Rvecs, R, d, dtype, cnt->max_b);
     k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, 0);
   }
   KGC_HIP(hd, hipEventRecord(hd->ev[1], st));
@@ -278,31 +281,30 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   int b = 0;
   for (int64_t r0 = 0; r0 < R; r0 += RBmax, ++b) {
     const int RB = (int)std::min<int64_t>(RBmax, R - r0);
-    const int64_t nblocks = tiles_per_rel * RB;
     if (p == 2) {
-      k_stage_operands<true><<<grid_for((int64_t)RB * Nslots * 32, 256 * 4), 256, 0, st>>>(
+      k_stage_operands<true><<<grid_for((int64_t)RB * (Nslots / kStageRows), 1), 256, stage_lds, st>>>(
           E, Rvecs, dtype, d, (int)r0, RB, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p,
-          &cnt->max_a_bits);
+          cnt->max_a);
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
       JoinArgs ja;
       ja.A = (const uint16_t*)hd->opA.p; ja.B = (const uint16_t*)hd->opB.p; ja.prm = prm;
       ja.Nslots = Nslots; ja.KS = KS; ja.k16 = k16; ja.nH = nH; ja.nT = nT; ja.r0 = (int)r0; ja.RB = RB;
       ja.worklist = nullptr; ja.cx = cx;
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
-      hipLaunchKernelGGL(tc.kernel, dim3((unsigned)nblocks), dim3(tc.threads), 0, st, ja);
+      hipLaunchKernelGGL(tc.kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else {
       JoinL1Args la;
       la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = (int)r0; la.RB = RB;
       la.worklist = nullptr; la.cx = cx;
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
-      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)nblocks), dim3(256), 0, st, la);
+      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(256), 0, st, la);
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     }
     hd->stats.join_launches++;
   }
   KGC_HIP(hd, hipGetLastError());
-  KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, sizeof(DevCounters), hipMemcpyDeviceToHost, st));
+  KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 16, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
   KGC_HIP(hd, hipStreamSynchronize(st));
 

@@ -17,6 +17,8 @@ constexpr int kSliceK = 32;
 // Row stride (elements) of a slice in LDS: 32 + 8 padding = 80 bytes, which spreads eight consecutive
 // rows' 16-byte fragments over all banks.
 constexpr int kLdsRow = 40;
+// Running maxima are kept in this many slots so that the atomics of kernel 1 do not pile on one address.
+constexpr int kMaxSlots = 1024;
 
 // device-side scalars of one join
 struct JoinParams {
@@ -27,8 +29,8 @@ struct JoinParams {
 struct DevCounters {
   unsigned long long hits;        // true number of qualifying triples
   unsigned long long candidates;  // triples re-scored in double
-  unsigned int max_a_bits;        // max ||bf16(h + r)||^2 (L2) or max ||e||_1 (L1), as float bits
-  unsigned int max_b_bits;        // max ||bf16(t)||^2 (L2) or max ||r||_1 (L1), as float bits
+  unsigned int max_a[1024];       // running maxima of ||bf16(h + r)||^2 (L2) or ||e||_1 (L1), float bits, spread over slots
+  unsigned int max_b[1024];       // running maxima of ||bf16(t)||^2 (L2) or ||r||_1 (L1)
 };
 
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
@@ -43,79 +45,108 @@ __global__ void k_identity_slots(int32_t* slot_ent, int64_t N, int64_t Nslots) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Kernel 1.  One 32-lane half wave per output row (IS_A: rows are (relation, slot) pairs and the row
-// is a = h + r; otherwise rows are slots and the row is b = t).  The row is rounded to bf16, its
-// squared norm ||.||^2 is summed in float32 from the rounded values, and the staged row is
+// Kernel 1.  One block stages kStageRows consecutive slots of one relation (IS_A: the row is
+// a = h + r; otherwise the row is b = t and there is a single "relation").  The rows are read with
+// consecutive threads on consecutive dimensions, rounded to bf16 into an LDS tile, their squared
+// norms ||.||^2 are summed in float32 from the rounded values, and the staged rows
 //     A:  [ a~ (d) | nA_hi nA_mid nA_lo | 1 1 1 | 0 ... ]
 //     B:  [ -2 b~ (d) | 1 1 1 | nB_hi nB_mid nB_lo | 0 ... ]
-// so that the dot product of an A row and a B row is nA + nB - 2 a~.b~ = ||a~ - b~||^2.  The three
-// pieces are the float32 norm cut into 8-bit mantissa chunks, exact in bf16.  Padding rows get a norm
-// of 1e30 so they never pass the filter.  The squared norms are also written out plainly; with the
-// zero pivot they are distA^2 and distB^2 of Section 4.5.
+// are written slice by slice, 16 bytes per thread, so that the dot product of an A row and a B row is
+// nA + nB - 2 a~.b~ = ||a~ - b~||^2.  The three pieces are the float32 norm cut into 8-bit mantissa
+// chunks, exact in bf16.  Padding rows get a norm of 1e30 so they never pass the filter.  The squared
+// norms are also written out plainly; with the zero pivot they are distA^2 and distB^2 of Section 4.5.
+constexpr int kStageRows = 32;
 template <bool IS_A>
 __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__ E, const void* __restrict__ Rv,
                                                         int dtype, int d, int r0, int RB,
                                                         const int32_t* __restrict__ slot_ent, int64_t Nslots, int KS,
                                                         uint16_t* __restrict__ out, float* __restrict__ norms,
-                                                        unsigned int* __restrict__ max_bits) {
-  const int j = threadIdx.x & 31;
-  const int64_t hw = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 5;
-  const int64_t nhw = ((int64_t)gridDim.x * blockDim.x) >> 5;
-  const int64_t rows = (int64_t)RB * Nslots;
+                                                        unsigned int* __restrict__ max_slots) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [kStageRows][KS * 32 + 8]
+  __shared__ int32_t ents[kStageRows];
+  __shared__ float wmax[4];
+  const int tid = threadIdx.x;
+  const int W = KS * kSliceK + 8;
+  const int64_t groups_per_rel = Nslots / kStageRows;
+  const int64_t ngroups = groups_per_rel * RB;
   float vmax = 0.f;
-  for (int64_t row = hw; row < rows; row += nhw) {
-    const int rl = (int)(row / Nslots);
-    const int64_t slot = row - (int64_t)rl * Nslots;
-    const int ent = slot_ent[slot];
-    const int64_t eo = (int64_t)(ent < 0 ? 0 : ent) * d;
+  for (int64_t g = blockIdx.x; g < ngroups; g += gridDim.x) {
+    const int rl = (int)(g / groups_per_rel);
+    const int64_t slot0 = (g - (int64_t)rl * groups_per_rel) * kStageRows;
+    __syncthreads();                                   // previous group fully written out
+    if (tid < kStageRows) ents[tid] = slot_ent[slot0 + tid];
+    __syncthreads();
     const int64_t ro = (int64_t)(r0 + rl) * d;
-    float sq = 0.f;
-    for (int ks = 0; ks < KS; ++ks) {
-      const int c = ks * kSliceK + j;
-      if (ent >= 0 && c < d) {
-        float v = ld_elem(E, eo + c, dtype);
+    for (int e = tid; e < kStageRows * d; e += 256) {
+      const int row = e / d, c = e - row * d;
+      const int ent = ents[row];
+      uint16_t o = 0;
+      if (ent >= 0) {
+        float v = ld_elem(E, (int64_t)ent * d + c, dtype);
         if (IS_A) v += ld_elem(Rv, ro + c, dtype);
-        v = bf16_to_f32(f32_to_bf16_rne(v));
+        o = f32_to_bf16_rne(v);
+      }
+      tile[row * W + c] = o;
+    }
+    __syncthreads();
+    {   // eight threads per row: norm of the rounded row, then the norm columns and the zero padding
+      const int row = tid >> 3, sub = tid & 7;
+      float sq = 0.f;
+      for (int c = sub; c < d; c += 8) {
+        const float v = bf16_to_f32(tile[row * W + c]);
         sq += v * v;
       }
-    }
-    sq += __shfl_xor(sq, 16, 32);
-    sq += __shfl_xor(sq, 8, 32);
-    sq += __shfl_xor(sq, 4, 32);
-    sq += __shfl_xor(sq, 2, 32);
-    sq += __shfl_xor(sq, 1, 32);
-    const float nrm = ent >= 0 ? sq : 1e30f;
-    uint16_t piece[3];
-    float rem = nrm;
-    for (int q = 0; q < 3; ++q) {
-      piece[q] = f32_to_bf16_trunc(rem);
-      rem -= bf16_to_f32(piece[q]);
-    }
-    const uint16_t one = 0x3F80u;
-    uint16_t* orow = out + ((int64_t)rl * KS * Nslots + slot) * kSliceK + j;
-    for (int ks = 0; ks < KS; ++ks) {
-      const int c = ks * kSliceK + j;
-      uint16_t o = 0;
-      if (c < d) {
-        if (ent >= 0) {
-          float v = ld_elem(E, eo + c, dtype);
-          if (IS_A) v += ld_elem(Rv, ro + c, dtype);
-          v = bf16_to_f32(f32_to_bf16_rne(v));
-          o = f32_to_bf16_rne(IS_A ? v : -2.f * v);
-        }
-      } else {
-        const int q = c - d;
-        if (q < 3) o = IS_A ? piece[q] : one;
-        else if (q < kNormCols) o = IS_A ? one : piece[q - 3];
+      sq += __shfl_xor(sq, 4, 8);
+      sq += __shfl_xor(sq, 2, 8);
+      sq += __shfl_xor(sq, 1, 8);
+      const float nrm = ents[row] >= 0 ? sq : 1e30f;
+      uint16_t piece[3];
+      float rem = nrm;
+#pragma unroll
+      for (int q = 0; q < 3; ++q) {
+        piece[q] = f32_to_bf16_trunc(rem);
+        rem -= bf16_to_f32(piece[q]);
       }
-      orow[(int64_t)ks * Nslots * kSliceK] = o;
+      const uint16_t one = 0x3F80u;
+      for (int c = d + sub; c < KS * kSliceK; c += 8) {
+        const int q = c - d;
+        uint16_t o = 0;
+        if (q < 3) o = IS_A ? (q == 0 ? piece[0] : q == 1 ? piece[1] : piece[2]) : one;
+        else if (q < kNormCols) o = IS_A ? one : (q == 3 ? piece[0] : q == 4 ? piece[1] : piece[2]);
+        tile[row * W + c] = o;
+      }
+      if (sub == 0) {
+        if (norms) norms[(int64_t)rl * Nslots + slot0 + row] = nrm;
+        if (ents[row] >= 0) vmax = fmaxf(vmax, nrm);
+      }
     }
-    if (j == 0) {
-      if (norms) norms[row] = nrm;
-      if (ent >= 0) vmax = fmaxf(vmax, nrm);
+    __syncthreads();
+    if (!IS_A) {   // B rows carry -2 b~ (exact: a sign flip and an exponent step)
+      for (int e = tid; e < kStageRows * d; e += 256) {
+        const int row = e / d, c = e - row * d;
+        tile[row * W + c] = f32_to_bf16_rne(-2.f * bf16_to_f32(tile[row * W + c]));
+      }
+      __syncthreads();
+    }
+    // write out: slice ks of these rows is kStageRows * 64 contiguous bytes
+    if (tid < kStageRows * 4) {
+      const int row = tid >> 2, part = tid & 3;
+      uint16_t* obase = out + ((int64_t)rl * KS * Nslots + slot0) * kSliceK + tid * 8;
+      for (int ks = 0; ks < KS; ++ks) {
+        const uint4 v = *(const uint4*)(&tile[row * W + ks * kSliceK + part * 8]);
+        *(uint4*)(obase + (int64_t)ks * Nslots * kSliceK) = v;
+      }
     }
   }
-  if (j == 0 && max_bits) atomicMax(max_bits, __float_as_uint(vmax));   // non-negative floats order like their bits
+  if (max_slots) {   // one atomic per block, spread over kMaxSlots addresses
+    for (int off = 32; off > 0; off >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, off, 64));
+    if ((tid & 63) == 0) wmax[tid >> 6] = vmax;
+    __syncthreads();
+    if (tid == 0) {
+      const float m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+      atomicMax(&max_slots[blockIdx.x % kMaxSlots], __float_as_uint(m));   // non-negative floats order like their bits
+    }
+  }
 }
 
 // squared norms scattered back to entity order (kgc_norms)
@@ -145,7 +176,7 @@ __global__ __launch_bounds__(256) void k_row_l1_max(const void* __restrict__ X, 
     s += __shfl_xor(s, 1, 32);
     vmax = fmaxf(vmax, s);
   }
-  if (j == 0) atomicMax(max_bits, __float_as_uint(vmax));
+  if (j == 0) atomicMax(&max_bits[blockIdx.x % kMaxSlots], __float_as_uint(vmax));
 }
 
 // Filter thresholds, computed on the device so that no host round trip sits between kernel 1 and the join.
@@ -157,9 +188,18 @@ __global__ __launch_bounds__(256) void k_row_l1_max(const void* __restrict__ X, 
 // D <= (delta + m)^2 + e_acc and loses no hit.  With bf16 storage b~ = b and drops out of m.
 // L1.  The float32 sum of |fl(fl(h + r) - t)| differs from the exact sum by at most
 // 2^-23 (max||h||_1 + max||r||_1) + (d + 2) 2^-23 (delta + that); the filter keeps sums below delta + margin.
-__global__ void k_join_params(DevCounters* cnt, JoinParams* prm, float delta, int p, int dtype, int d, int kp) {
+__global__ __launch_bounds__(64) void k_join_params(DevCounters* cnt, JoinParams* prm, float delta, int p, int dtype,
+                                                    int d, int kp) {
+  float ma = 0.f, mb = 0.f;
+  for (int i = threadIdx.x; i < 1024; i += 64) {
+    ma = fmaxf(ma, __uint_as_float(cnt->max_a[i]));
+    mb = fmaxf(mb, __uint_as_float(cnt->max_b[i]));
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    ma = fmaxf(ma, __shfl_xor(ma, off, 64));
+    mb = fmaxf(mb, __shfl_xor(mb, off, 64));
+  }
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  const float ma = __uint_as_float(cnt->max_a_bits), mb = __uint_as_float(cnt->max_b_bits);
   float thr;
   if (delta < 0.f) {
     thr = -1.f;                                   // squared distances and sums are >= 0: nothing passes
@@ -215,11 +255,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_join_l2(const JoinArgs a) {
     const uint32_t* w = a.worklist + (int64_t)blockIdx.x * 3;
     rl = (int)w[0]; tH = (int)w[1]; tT = (int)w[2];
   } else {
-    const int64_t bid = blockIdx.x;
-    tT = (int)(bid % a.nT);
-    const int64_t q = bid / a.nT;
-    tH = (int)(q % a.nH);
-    rl = (int)(q / a.nH);
+    tT = (int)blockIdx.x; tH = (int)blockIdx.y; rl = (int)blockIdx.z;
   }
 
   const int64_t slice_elems = a.Nslots * kSliceK;
@@ -346,17 +382,13 @@ __global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
   __shared__ __attribute__((aligned(16))) float Bs[BK][BN];
   __shared__ int32_t hent[BM], tent[BN];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, wave = tid >> 6;
   int tH, tT, rl;
   if (a.worklist) {
     const uint32_t* w = a.worklist + (int64_t)blockIdx.x * 3;
     rl = (int)w[0]; tH = (int)w[1]; tT = (int)w[2];
   } else {
-    const int64_t bid = blockIdx.x;
-    tT = (int)(bid % a.nT);
-    const int64_t q = bid / a.nT;
-    tH = (int)(q % a.nH);
-    rl = (int)(q / a.nH);
+    tT = (int)blockIdx.x; tH = (int)blockIdx.y; rl = (int)blockIdx.z;
   }
   const int r = a.r0 + rl;
   const int d = a.cx.d, dtype = a.cx.dtype;
