@@ -79,17 +79,24 @@ void release(DevBuf& b) {
 
 struct TileCfg {
   int bm, bn, threads;
-  void (*kernel)(const JoinArgs);
+  void (*tile_kernel)(const JoinArgs);            // one block per tile pair
+  void (*stream_kernel)(const JoinStreamArgs);    // one block per (relation, head tile), streaming over tail tiles
 };
 
-// Tile variants of kernel 2.  Variant 1 is the default.
+// Tile variants of kernel 2 (tile_cfg = index + 1).
 const TileCfg kL2Tiles[] = {
-    {128, 128, 256, k_join_l2<128, 128, 2, 2>},
-    {256, 128, 256, k_join_l2<256, 128, 2, 2>},
-    {256, 256, 256, k_join_l2<256, 256, 2, 2>},
-    {128, 128, 512, k_join_l2<128, 128, 4, 2>},
-    {256, 256, 512, k_join_l2<256, 256, 4, 2>},
+    {128, 128, 256, k_join_l2<128, 128, 2, 2>, nullptr},
+    {256, 128, 256, k_join_l2<256, 128, 2, 2>, nullptr},
+    {256, 256, 256, k_join_l2<256, 256, 2, 2>, nullptr},
+    {128, 128, 512, k_join_l2<128, 128, 4, 2>, nullptr},
+    {256, 256, 512, k_join_l2<256, 256, 4, 2>, nullptr},
+    {256, 256, 256, nullptr, k_join_l2_stream<256, 256, 2, 2, 1>},
+    {256, 128, 256, nullptr, k_join_l2_stream<256, 128, 2, 2, 2>},
+    {128, 128, 256, nullptr, k_join_l2_stream<128, 128, 2, 2, 2>},
+    {256, 256, 512, nullptr, k_join_l2_stream<256, 256, 4, 2, 1>},
+    {128, 256, 256, nullptr, k_join_l2_stream<128, 256, 2, 2, 2>},
 };
+constexpr int kDefaultL2Tile = 9;                 // index into kL2Tiles
 constexpr int kNumL2Tiles = (int)(sizeof(kL2Tiles) / sizeof(kL2Tiles[0]));
 
 int check_common(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R) {
@@ -219,7 +226,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   const int dtype = hd->cfg.dtype;
 
   // tile shape
-  int tile_id = hd->cfg.tile_cfg > 0 ? hd->cfg.tile_cfg - 1 : 0;
+  int tile_id = hd->cfg.tile_cfg > 0 ? hd->cfg.tile_cfg - 1 : kDefaultL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
   const int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
@@ -291,7 +298,18 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
       ja.Nslots = Nslots; ja.KS = KS; ja.k16 = k16; ja.nH = nH; ja.nT = nT; ja.r0 = (int)r0; ja.RB = RB;
       ja.worklist = nullptr; ja.cx = cx;
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
-      hipLaunchKernelGGL(tc.kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);
+      if (tc.stream_kernel) {
+        JoinStreamArgs sa;
+        sa.A = ja.A; sa.B = ja.B; sa.prm = prm; sa.Nslots = Nslots; sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT;
+        sa.r0 = (int)r0; sa.RB = RB; sa.row_ptr = nullptr; sa.row_key = nullptr; sa.cols = nullptr; sa.cx = cx;
+        // enough blocks to fill the chip several times over; otherwise one block walks all tail tiles
+        int64_t nsplit = (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB);
+        nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, nT));
+        hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nsplit, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st,
+                           sa);
+      } else {
+        hipLaunchKernelGGL(tc.tile_kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);
+      }
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else {
       JoinL1Args la;

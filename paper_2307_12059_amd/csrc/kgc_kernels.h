@@ -361,6 +361,212 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_join_l2(const JoinArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Kernel 2, streaming form.  One block owns one (relation, head tile) and walks over a range of tail
+// tiles; the K slices of all those tiles form one continuous stream that is prefetched two slices
+// ahead through registers into a double-buffered LDS stage, so the global-memory latency of a slice
+// is covered by the MFMA work of the two slices before it, also across tile boundaries.
+// Tail-tile range: dense mode splits [0, nT) evenly over gridDim.x; worklist mode reads a row list
+// (row_ptr / col lists keyed by (relation, head tile)).
+struct JoinStreamArgs {
+  const uint16_t* A;
+  const uint16_t* B;
+  const JoinParams* prm;
+  int64_t Nslots;
+  int KS, k16;
+  int nH, nT;
+  int r0, RB;
+  const uint32_t* row_ptr;   // NULL: dense.  Else row_ptr[row], row_ptr[row + 1] delimit this block's tail tiles
+  const uint32_t* row_key;   // row -> (r_local << 16 | head tile) when row_ptr is given
+  const uint32_t* cols;      // tail tile numbers
+  RecheckCtx cx;
+};
+
+template <int BM, int BN, int WGM, int WGN, int MINB>
+__global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const JoinStreamArgs a) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int LA = (BM * 4) / NT, LB = (BN * 4) / NT;
+  constexpr int ASZ = BM * kLdsRow, BSZ = BN * kLdsRow;      // elements per LDS buffer
+  static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
+
+  __shared__ __attribute__((aligned(16))) uint16_t As[2 * ASZ];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[2 * BSZ];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  int tH, rl, t_begin, t_end;
+  const uint32_t* cols = nullptr;
+  if (a.row_ptr) {
+    const uint32_t key = a.row_key[blockIdx.x];
+    rl = (int)(key >> 16); tH = (int)(key & 0xffffu);
+    t_begin = (int)a.row_ptr[blockIdx.x]; t_end = (int)a.row_ptr[blockIdx.x + 1];
+    cols = a.cols;
+  } else {
+    tH = (int)blockIdx.y; rl = (int)blockIdx.z;
+    t_begin = (int)(((int64_t)a.nT * blockIdx.x) / gridDim.x);
+    t_end = (int)(((int64_t)a.nT * (blockIdx.x + 1)) / gridDim.x);
+  }
+  const int ntiles = t_end - t_begin;
+  if (ntiles <= 0) return;
+  const int KS = a.KS;
+  const int64_t slice_bytes = a.Nslots * kSliceK * 2;
+
+  // per-thread byte offset inside a tile slice; uniform bases are kept apart so they can live in SGPRs
+  const uint32_t voff = (uint32_t)tid * 16u;
+  const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * (kSliceK * 2);
+  const char* Bbase = (const char*)a.B;
+  int tcol = cols ? (int)cols[t_begin] : t_begin;
+  const char* pA = Abase;                                            // slice being prefetched
+  const char* pB = Bbase + (int64_t)tcol * BN * (kSliceK * 2);
+
+  // LDS addresses (elements): where this thread stores its chunks (chunk i sits NT / 4 rows below chunk 0),
+  // and where it reads its fragments
+  const int st0 = (tid >> 2) * kLdsRow + (tid & 3) * 8;
+  constexpr int st_step = (NT / 4) * kLdsRow;
+  const int rd_a = (wm * WTM + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+  const int rd_b = (wn * WTN + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+
+  // staging registers as vectors (not arrays), so they are plain SSA values for the compiler
+  typedef uint32_t rega_t __attribute__((ext_vector_type(4 * LA)));
+  typedef uint32_t regb_t __attribute__((ext_vector_type(4 * LB)));
+  rega_t ra;
+  regb_t rb;
+  // prologue: first slice -> registers -> LDS buffer 0
+#pragma unroll
+  for (int i = 0; i < LA; ++i) {
+    const uint4 t = *(const uint4*)(pA + voff + (uint32_t)(i * NT * 16));
+    ra[4 * i] = t.x; ra[4 * i + 1] = t.y; ra[4 * i + 2] = t.z; ra[4 * i + 3] = t.w;
+  }
+#pragma unroll
+  for (int i = 0; i < LB; ++i) {
+    const uint4 t = *(const uint4*)(pB + voff + (uint32_t)(i * NT * 16));
+    rb[4 * i] = t.x; rb[4 * i + 1] = t.y; rb[4 * i + 2] = t.z; rb[4 * i + 3] = t.w;
+  }
+#pragma unroll
+  for (int i = 0; i < LA; ++i) *(uint4*)(&As[st0 + i * st_step]) = make_uint4(ra[4 * i], ra[4 * i + 1], ra[4 * i + 2], ra[4 * i + 3]);
+#pragma unroll
+  for (int i = 0; i < LB; ++i) *(uint4*)(&Bs[st0 + i * st_step]) = make_uint4(rb[4 * i], rb[4 * i + 1], rb[4 * i + 2], rb[4 * i + 3]);
+  __syncthreads();
+
+  const float thr = a.prm->thr;
+  const int last_two = (a.k16 - (KS - 1) * 2) >= 2;   // does the last slice of a tile hold two MFMA steps of data?
+  int buf = 0;
+
+  for (int ti = 0; ti < ntiles; ++ti) {
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    const int tcol_cur = tcol;
+
+    for (int ks = 0; ks < KS; ++ks) {
+      // ---- issue the loads of the next slice of the stream (next K slice, or slice 0 of the next tile) ----
+      const bool last_slice = (ks == KS - 1);
+      const bool has_next = !(last_slice && ti == ntiles - 1);
+      if (has_next) {
+        if (last_slice) {
+          tcol = cols ? (int)cols[t_begin + ti + 1] : t_begin + ti + 1;
+          pA = Abase;
+          pB = Bbase + (int64_t)tcol * BN * (kSliceK * 2);
+        } else {
+          pA += slice_bytes;
+          pB += slice_bytes;
+        }
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+          const uint4 t = *(const uint4*)(pA + voff + (uint32_t)(i * NT * 16));
+          ra[4 * i] = t.x; ra[4 * i + 1] = t.y; ra[4 * i + 2] = t.z; ra[4 * i + 3] = t.w;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+          const uint4 t = *(const uint4*)(pB + voff + (uint32_t)(i * NT * 16));
+          rb[4 * i] = t.x; rb[4 * i + 1] = t.y; rb[4 * i + 2] = t.z; rb[4 * i + 3] = t.w;
+        }
+      }
+      // ---- MFMA on the current slice ----
+      const uint16_t* Ac = As + buf * ASZ + rd_a;
+      const uint16_t* Bc = Bs + buf * BSZ + rd_b;
+      {
+        bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kLdsRow);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kLdsRow);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+      if (!last_slice || last_two) {
+        bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kLdsRow + 16);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kLdsRow + 16);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+      // ---- stage the prefetched slice into the other buffer ----
+      if (has_next) {
+        uint16_t* Aw = As + (buf ^ 1) * ASZ;
+        uint16_t* Bw = Bs + (buf ^ 1) * BSZ;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) *(uint4*)(&Aw[st0 + i * st_step]) = make_uint4(ra[4 * i], ra[4 * i + 1], ra[4 * i + 2], ra[4 * i + 3]);
+#pragma unroll
+        for (int i = 0; i < LB; ++i) *(uint4*)(&Bw[st0 + i * st_step]) = make_uint4(rb[4 * i], rb[4 * i + 1], rb[4 * i + 2], rb[4 * i + 3]);
+      }
+      __syncthreads();
+      buf ^= 1;
+    }
+
+    // ---- end of a tile: filter on the squared distance, then the rare exact path ----
+    float mn = acc[0][0][0];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);
+    if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {
+      // MFMA 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
+      const int64_t hbase = (int64_t)tH * BM + wm * WTM;
+      const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;
+      constexpr int NW = (TM * TN + 3) / 4;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        unsigned long long cm = 0ull;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int tile = w * 4 + q;
+          if (tile < TM * TN) {
+            const int i = tile / TN, j = tile % TN;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              if (acc[i][j][v] <= thr) cm |= 1ull << (q * 16 + v);
+          }
+        }
+        if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;
+        recheck_and_emit(cm, a.r0 + rl, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
+          const int tile = w * 4 + (e >> 4), v = e & 15;
+          const int i = tile / TN, j = tile % TN;
+          hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);
+          tslot = tbase + j * 32 + (src & 31);
+        });
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 struct JoinL1Args {
   const JoinParams* prm;
   int64_t Nslots;
