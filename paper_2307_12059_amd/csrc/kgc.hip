@@ -18,6 +18,7 @@ namespace {
 constexpr int kMaxD = 960;                      // keeps kernel 1's LDS tile under 64 KiB
 constexpr int64_t kSlotAlign = 256;            // rows are padded to a multiple of the largest tile
 constexpr int64_t kDefaultWorkspace = 16ll << 30;
+constexpr int64_t kL2RangeBytes = 1ll << 20;
 
 struct DevBuf {
   void* p = nullptr;
@@ -302,10 +303,14 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         JoinStreamArgs sa;
         sa.A = ja.A; sa.B = ja.B; sa.prm = prm; sa.Nslots = Nslots; sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT;
         sa.r0 = (int)r0; sa.RB = RB; sa.row_ptr = nullptr; sa.row_key = nullptr; sa.cols = nullptr; sa.cx = cx;
-        // enough blocks to fill the chip several times over; otherwise one block walks all tail tiles
-        int64_t nsplit = (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB);
-        nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, nT));
-        hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nsplit, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st,
+        // Tail tiles are cut into ranges of about kL2RangeBytes of staged B rows, so that the blocks running at
+        // the same time (consecutive head tiles of one range) keep their B rows in the 4 MiB L2 of their XCD;
+        // small problems are cut further to fill the chip.
+        const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
+        int64_t nsplit = (nT * tile_bytes + kL2RangeBytes - 1) / kL2RangeBytes;
+        nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
+        nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
+        hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB), dim3(tc.threads), 0, st,
                            sa);
       } else {
         hipLaunchKernelGGL(tc.tile_kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);

@@ -17,6 +17,12 @@ constexpr int kSliceK = 32;
 // Row stride (elements) of a slice in LDS: 32 + 8 padding = 80 bytes, which spreads eight consecutive
 // rows' 16-byte fragments over all banks.
 constexpr int kLdsRow = 40;
+// Swizzle of the streaming kernel's LDS slices: rows are 64 bytes (four 16-byte chunks) without padding, and
+// chunk c of row r is stored at position c ^ lds_swizzle(r).  With r = ...b3 b2 b1 b0 the swizzle is
+// (b2 << 1) | (b1 ^ b3): eight or sixteen consecutive rows reading the same logical chunk, and four
+// consecutive rows writing all their chunks, then fall on distinct banks whether the LDS serves 128 or
+// 256 bytes per cycle.
+__device__ __forceinline__ int lds_swizzle(int row) { return (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1); }
 // Running maxima are kept in this many slots so that the atomics of kernel 1 do not pile on one address.
 constexpr int kMaxSlots = 1024;
 
@@ -365,7 +371,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_join_l2(const JoinArgs a) {
 // tiles; the K slices of all those tiles form one continuous stream that is prefetched two slices
 // ahead through registers into a double-buffered LDS stage, so the global-memory latency of a slice
 // is covered by the MFMA work of the two slices before it, also across tile boundaries.
-// Tail-tile range: dense mode splits [0, nT) evenly over gridDim.x; worklist mode reads a row list
+// Tail-tile range: dense mode splits [0, nT) evenly over gridDim.y; worklist mode reads a row list
 // (row_ptr / col lists keyed by (relation, head tile)).
 struct JoinStreamArgs {
   const uint16_t* A;
@@ -387,7 +393,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int LA = (BM * 4) / NT, LB = (BN * 4) / NT;
-  constexpr int ASZ = BM * kLdsRow, BSZ = BN * kLdsRow;      // elements per LDS buffer
+  constexpr int ASZ = BM * kSliceK, BSZ = BN * kSliceK;      // elements per LDS buffer (64-byte rows, swizzled)
   static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
 
   __shared__ __attribute__((aligned(16))) uint16_t As[2 * ASZ];
@@ -404,9 +410,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
     t_begin = (int)a.row_ptr[blockIdx.x]; t_end = (int)a.row_ptr[blockIdx.x + 1];
     cols = a.cols;
   } else {
-    tH = (int)blockIdx.y; rl = (int)blockIdx.z;
-    t_begin = (int)(((int64_t)a.nT * blockIdx.x) / gridDim.x);
-    t_end = (int)(((int64_t)a.nT * (blockIdx.x + 1)) / gridDim.x);
+    // grid = (head tiles, tail-tile ranges, relations): blocks that run together share a tail-tile range
+    tH = (int)blockIdx.x; rl = (int)blockIdx.z;
+    t_begin = (int)(((int64_t)a.nT * blockIdx.y) / gridDim.y);
+    t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
   }
   const int ntiles = t_end - t_begin;
   if (ntiles <= 0) return;
@@ -423,31 +430,48 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 
   // LDS addresses (elements): where this thread stores its chunks (chunk i sits NT / 4 rows below chunk 0),
   // and where it reads its fragments
-  const int st0 = (tid >> 2) * kLdsRow + (tid & 3) * 8;
-  constexpr int st_step = (NT / 4) * kLdsRow;
-  const int rd_a = (wm * WTM + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
-  const int rd_b = (wn * WTN + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+  const int st0 = (tid >> 2) * kSliceK + (((tid & 3) ^ lds_swizzle(tid >> 2)) * 8);
+  constexpr int st_step = (NT / 4) * kSliceK;      // NT / 4 is a multiple of 16 rows, so the swizzle repeats
+  // fragment of MFMA step s: logical 16-byte chunk 2 s + lane / 32 of row lane % 32; rows 32 apart share the swizzle
+  const int rsw = lds_swizzle(lane & 31);
+  const int rd_a = (wm * WTM + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
+  const int rd_b = (wn * WTN + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
+  const int rd_step = (((lane >> 5) ^ rsw) & 2) ? -16 : 16;   // chunk ^ 2: the second step's fragment
 
   // staging registers as vectors (not arrays), so they are plain SSA values for the compiler
   typedef uint32_t rega_t __attribute__((ext_vector_type(4 * LA)));
   typedef uint32_t regb_t __attribute__((ext_vector_type(4 * LB)));
   rega_t ra;
   regb_t rb;
+
+#define KGC_GLOAD()                                                                               \
+  do {                                                                                            \
+    _Pragma("unroll") for (int i = 0; i < LA; ++i) {                                              \
+      const uint4 t = *(const uint4*)(pA + voff + (uint32_t)(i * NT * 16));                       \
+      ra[4 * i] = t.x; ra[4 * i + 1] = t.y; ra[4 * i + 2] = t.z; ra[4 * i + 3] = t.w;             \
+    }                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                              \
+      const uint4 t = *(const uint4*)(pB + voff + (uint32_t)(i * NT * 16));                       \
+      rb[4 * i] = t.x; rb[4 * i + 1] = t.y; rb[4 * i + 2] = t.z; rb[4 * i + 3] = t.w;             \
+    }                                                                                             \
+  } while (0)
+#define KGC_SSTORE(AW, BW)                                                                        \
+  do {                                                                                            \
+    _Pragma("unroll") for (int i = 0; i < LA; ++i)                                                \
+      *(uint4*)(&(AW)[st0 + i * st_step]) = make_uint4(ra[4 * i], ra[4 * i + 1], ra[4 * i + 2], ra[4 * i + 3]); \
+    _Pragma("unroll") for (int i = 0; i < LB; ++i)                                                \
+      *(uint4*)(&(BW)[st0 + i * st_step]) = make_uint4(rb[4 * i], rb[4 * i + 1], rb[4 * i + 2], rb[4 * i + 3]); \
+  } while (0)
+#define KGC_MFMA_STEP(FA, FB)                                                                     \
+  do {                                                                                            \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j)                                              \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[i], FB[j], acc[i][j], 0, 0, 0);    \
+  } while (0)
+
   // prologue: first slice -> registers -> LDS buffer 0
-#pragma unroll
-  for (int i = 0; i < LA; ++i) {
-    const uint4 t = *(const uint4*)(pA + voff + (uint32_t)(i * NT * 16));
-    ra[4 * i] = t.x; ra[4 * i + 1] = t.y; ra[4 * i + 2] = t.z; ra[4 * i + 3] = t.w;
-  }
-#pragma unroll
-  for (int i = 0; i < LB; ++i) {
-    const uint4 t = *(const uint4*)(pB + voff + (uint32_t)(i * NT * 16));
-    rb[4 * i] = t.x; rb[4 * i + 1] = t.y; rb[4 * i + 2] = t.z; rb[4 * i + 3] = t.w;
-  }
-#pragma unroll
-  for (int i = 0; i < LA; ++i) *(uint4*)(&As[st0 + i * st_step]) = make_uint4(ra[4 * i], ra[4 * i + 1], ra[4 * i + 2], ra[4 * i + 3]);
-#pragma unroll
-  for (int i = 0; i < LB; ++i) *(uint4*)(&Bs[st0 + i * st_step]) = make_uint4(rb[4 * i], rb[4 * i + 1], rb[4 * i + 2], rb[4 * i + 3]);
+  KGC_GLOAD();
+  KGC_SSTORE(As, Bs);
   __syncthreads();
 
   const float thr = a.prm->thr;
@@ -455,13 +479,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
   int buf = 0;
 
   for (int ti = 0; ti < ntiles; ++ti) {
-    f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    f32x16_t acc[TM][TN];          // first written by the ks == 0 step, whose MFMAs take a zero C operand
     const int tcol_cur = tcol;
 
     for (int ks = 0; ks < KS; ++ks) {
@@ -477,53 +495,40 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
           pA += slice_bytes;
           pB += slice_bytes;
         }
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-          const uint4 t = *(const uint4*)(pA + voff + (uint32_t)(i * NT * 16));
-          ra[4 * i] = t.x; ra[4 * i + 1] = t.y; ra[4 * i + 2] = t.z; ra[4 * i + 3] = t.w;
-        }
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-          const uint4 t = *(const uint4*)(pB + voff + (uint32_t)(i * NT * 16));
-          rb[4 * i] = t.x; rb[4 * i + 1] = t.y; rb[4 * i + 2] = t.z; rb[4 * i + 3] = t.w;
-        }
+        KGC_GLOAD();
       }
       // ---- MFMA on the current slice ----
       const uint16_t* Ac = As + buf * ASZ + rd_a;
       const uint16_t* Bc = Bs + buf * BSZ + rd_b;
       {
-        bf16x8_t fa[TM], fb[TN];
+        // all fragments of both MFMA steps are requested first, so the second step's LDS latency hides
+        // behind the first step's MFMAs (the last slice of a tile may hold one step only)
+        const bool two = !last_slice || last_two;
+        bf16x8_t fa[TM], fb[TN], ga[TM], gb[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kLdsRow);
+        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kLdsRow);
+        for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kSliceK);
+        if (two) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+          for (int i = 0; i < TM; ++i) ga[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK + rd_step);
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-      }
-      if (!last_slice || last_two) {
-        bf16x8_t fa[TM], fb[TN];
+          for (int j = 0; j < TN; ++j) gb[j] = *(const bf16x8_t*)(Bc + j * 32 * kSliceK + rd_step);
+        }
+        if (ks == 0) {
+          const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kLdsRow + 16);
+          for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kLdsRow + 16);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], zero16, 0, 0, 0);
+        } else {
+          KGC_MFMA_STEP(fa, fb);
+        }
+        if (two) KGC_MFMA_STEP(ga, gb);
       }
       // ---- stage the prefetched slice into the other buffer ----
-      if (has_next) {
-        uint16_t* Aw = As + (buf ^ 1) * ASZ;
-        uint16_t* Bw = Bs + (buf ^ 1) * BSZ;
-#pragma unroll
-        for (int i = 0; i < LA; ++i) *(uint4*)(&Aw[st0 + i * st_step]) = make_uint4(ra[4 * i], ra[4 * i + 1], ra[4 * i + 2], ra[4 * i + 3]);
-#pragma unroll
-        for (int i = 0; i < LB; ++i) *(uint4*)(&Bw[st0 + i * st_step]) = make_uint4(rb[4 * i], rb[4 * i + 1], rb[4 * i + 2], rb[4 * i + 3]);
-      }
+      if (has_next) KGC_SSTORE(As + (buf ^ 1) * ASZ, Bs + (buf ^ 1) * BSZ);
       __syncthreads();
       buf ^= 1;
     }
@@ -564,6 +569,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
       }
     }
   }
+#undef KGC_GLOAD
+#undef KGC_SSTORE
+#undef KGC_MFMA_STEP
 }
 
 // ---------------------------------------------------------------------------------------------
