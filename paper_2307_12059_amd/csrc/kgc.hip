@@ -19,6 +19,7 @@ constexpr int kMaxD = 960;                      // keeps kernel 1's LDS tile und
 constexpr int64_t kSlotAlign = 256;            // rows are padded to a multiple of the largest tile
 constexpr int64_t kDefaultWorkspace = 16ll << 30;
 constexpr int64_t kL2RangeBytes = 1ll << 20;
+constexpr size_t kMaxLds = 160 * 1024;         // LDS per workgroup on gfx950
 
 struct DevBuf {
   void* p = nullptr;
@@ -82,22 +83,26 @@ struct TileCfg {
   int bm, bn, threads;
   void (*tile_kernel)(const JoinArgs);            // one block per tile pair
   void (*stream_kernel)(const JoinStreamArgs);    // one block per (relation, head tile), streaming over tail tiles
+  bool head_resident;                             // stream_kernel keeps the head tile's K slices in LDS (dynamic LDS)
 };
 
 // Tile variants of kernel 2 (tile_cfg = index + 1).
 const TileCfg kL2Tiles[] = {
-    {128, 128, 256, k_join_l2<128, 128, 2, 2>, nullptr},
-    {256, 128, 256, k_join_l2<256, 128, 2, 2>, nullptr},
-    {256, 256, 256, k_join_l2<256, 256, 2, 2>, nullptr},
-    {128, 128, 512, k_join_l2<128, 128, 4, 2>, nullptr},
-    {256, 256, 512, k_join_l2<256, 256, 4, 2>, nullptr},
-    {256, 256, 256, nullptr, k_join_l2_stream<256, 256, 2, 2, 1>},
-    {256, 128, 256, nullptr, k_join_l2_stream<256, 128, 2, 2, 2>},
-    {128, 128, 256, nullptr, k_join_l2_stream<128, 128, 2, 2, 2>},
-    {256, 256, 512, nullptr, k_join_l2_stream<256, 256, 4, 2, 1>},
-    {128, 256, 256, nullptr, k_join_l2_stream<128, 256, 2, 2, 2>},
+    {128, 128, 256, k_join_l2<128, 128, 2, 2>, nullptr, false},
+    {256, 128, 256, k_join_l2<256, 128, 2, 2>, nullptr, false},
+    {256, 256, 256, k_join_l2<256, 256, 2, 2>, nullptr, false},
+    {128, 128, 512, k_join_l2<128, 128, 4, 2>, nullptr, false},
+    {256, 256, 512, k_join_l2<256, 256, 4, 2>, nullptr, false},
+    {256, 256, 256, nullptr, k_join_l2_stream<256, 256, 2, 2, 1>, false},
+    {256, 128, 256, nullptr, k_join_l2_stream<256, 128, 2, 2, 2>, false},
+    {128, 128, 256, nullptr, k_join_l2_stream<128, 128, 2, 2, 2>, false},
+    {256, 256, 512, nullptr, k_join_l2_stream<256, 256, 4, 2, 1>, false},
+    {128, 256, 256, nullptr, k_join_l2_stream<128, 256, 2, 2, 2>, false},
+    {256, 256, 512, nullptr, k_join_l2_ares<256, 4, 2>, true},
+    {256, 256, 512, nullptr, k_join_l2_ares<256, 2, 4>, true},
+    {256, 128, 512, nullptr, k_join_l2_ares<128, 4, 2>, true},
 };
-constexpr int kDefaultL2Tile = 9;                 // index into kL2Tiles
+constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles
 constexpr int kNumL2Tiles = (int)(sizeof(kL2Tiles) / sizeof(kL2Tiles[0]));
 
 int check_common(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R) {
@@ -310,8 +315,15 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         int64_t nsplit = (nT * tile_bytes + kL2RangeBytes - 1) / kL2RangeBytes;
         nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
         nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
-        hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB), dim3(tc.threads), 0, st,
-                           sa);
+        size_t dyn_lds = 0;
+        if (tc.head_resident) {
+          dyn_lds = ((size_t)KS * 256 + 2 * (size_t)BN) * kSliceK * 2;
+          if (dyn_lds > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
+          KGC_HIP(hd, hipFuncSetAttribute((const void*)tc.stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)dyn_lds));
+        }
+        hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB), dim3(tc.threads), dyn_lds,
+                           st, sa);
       } else {
         hipLaunchKernelGGL(tc.tile_kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);
       }

@@ -575,6 +575,201 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 }
 
 // ---------------------------------------------------------------------------------------------
+// Kernel 2, head-resident form.  As the streaming form, but the block first copies ALL K slices of its
+// head tile (the staged a = h + r rows, 256 x KS x 64 bytes) into LDS and keeps them there, so only the
+// tail rows are streamed: half the global -> LDS traffic per tile, and the L2 only has to hold the tail
+// range.  Tail slices are prefetched two slices ahead through two register sets.  Needs
+// (KS * 256 + 2 * BN) * 64 bytes of LDS, i.e. KS <= 7 (d <= 218) with BN = 256.
+template <int BN, int WGM, int WGN>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStreamArgs a) {
+  constexpr int BM = 256;
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int LA = (BM * 4) / NT, LB = (BN * 4) / NT;
+  constexpr int ASZ = BM * kSliceK, BSZ = BN * kSliceK;
+  static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
+
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [KS][BM][32] head slices, then [2][BN][32] tail slices
+  const int KS = a.KS;
+  uint16_t* Ares = lds;
+  uint16_t* Bs = lds + KS * ASZ;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  int tH, rl, t_begin, t_end;
+  const uint32_t* cols = nullptr;
+  if (a.row_ptr) {
+    const uint32_t key = a.row_key[blockIdx.x];
+    rl = (int)(key >> 16); tH = (int)(key & 0xffffu);
+    t_begin = (int)a.row_ptr[blockIdx.x]; t_end = (int)a.row_ptr[blockIdx.x + 1];
+    cols = a.cols;
+  } else {
+    tH = (int)blockIdx.x; rl = (int)blockIdx.z;
+    t_begin = (int)(((int64_t)a.nT * blockIdx.y) / gridDim.y);
+    t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
+  }
+  const int ntiles = t_end - t_begin;
+  if (ntiles <= 0) return;
+  const int64_t slice_bytes = a.Nslots * kSliceK * 2;
+  const uint32_t voff = (uint32_t)tid * 16u;
+  const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * (kSliceK * 2);
+  const char* Bbase = (const char*)a.B;
+  int tcol = cols ? (int)cols[t_begin] : t_begin;
+  const char* pB = Bbase + (int64_t)tcol * BN * (kSliceK * 2);
+
+  const int st0 = (tid >> 2) * kSliceK + (((tid & 3) ^ lds_swizzle(tid >> 2)) * 8);
+  constexpr int st_step = (NT / 4) * kSliceK;
+  const int rsw = lds_swizzle(lane & 31);
+  const int rd_a = (wm * WTM + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
+  const int rd_b = (wn * WTN + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
+  const int rd_step = (((lane >> 5) ^ rsw) & 2) ? -16 : 16;
+
+  // ---- head tile: all K slices into LDS, once ----
+  for (int ks = 0; ks < KS; ++ks) {
+    uint4 t[LA];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) t[i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+#pragma unroll
+    for (int i = 0; i < LA; ++i) *(uint4*)(&Ares[ks * ASZ + st0 + i * st_step]) = t[i];
+  }
+
+  typedef uint32_t regb_t __attribute__((ext_vector_type(4 * LB)));
+  regb_t rb0, rb1;
+  int pf_k = 0, pf_t = 0, pf_i = 0;
+#define KGC_GLOAD(RB)                                                                             \
+  do {                                                                                            \
+    _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                              \
+      const uint4 t = *(const uint4*)(pB + voff + (uint32_t)(i * NT * 16));                       \
+      RB[4 * i] = t.x; RB[4 * i + 1] = t.y; RB[4 * i + 2] = t.z; RB[4 * i + 3] = t.w;             \
+    }                                                                                             \
+    /* advance the cursor; past the end of the stream it stays on the last slice, so that the loads can be   */ \
+    /* issued unconditionally (straight-line code lets the compiler count outstanding loads exactly)        */ \
+    if (++pf_i < total) {                                                                         \
+      if (++pf_k == KS) {                                                                         \
+        pf_k = 0;                                                                                 \
+        ++pf_t;                                                                                   \
+        tcol = cols ? (int)cols[t_begin + pf_t] : t_begin + pf_t;                                 \
+        pB = Bbase + (int64_t)tcol * BN * (kSliceK * 2);                                          \
+      } else {                                                                                    \
+        pB += slice_bytes;                                                                        \
+      }                                                                                           \
+    }                                                                                             \
+  } while (0)
+#define KGC_SSTORE(BUF, RB)                                                                       \
+  do {                                                                                            \
+    _Pragma("unroll") for (int i = 0; i < LB; ++i)                                                \
+      *(uint4*)(&Bs[(BUF) * BSZ + st0 + i * st_step]) =                                           \
+          make_uint4(RB[4 * i], RB[4 * i + 1], RB[4 * i + 2], RB[4 * i + 3]);                     \
+  } while (0)
+#define KGC_MFMA_STEP(FA, FB)                                                                     \
+  do {                                                                                            \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j)                                              \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[i], FB[j], acc[i][j], 0, 0, 0);    \
+  } while (0)
+
+  const float thr = a.prm->thr;
+  const int last_two = (a.k16 - (KS - 1) * 2) >= 2;
+  const int total = ntiles * KS;
+  int ck = 0, ct = 0;
+  int tcol_cur = tcol;
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // MFMA on tail slice in buffer BUF against head slice ck; at the end of a tile the filter on the squared
+  // distance, the rare exact path, and the move to the next tile.  MFMA 32x32 accumulator layout: register v
+  // of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
+#define KGC_COMPUTE(BUF)                                                                          \
+  do {                                                                                            \
+    const uint16_t* Ac = Ares + ck * ASZ + rd_a;                                                  \
+    const uint16_t* Bc = Bs + (BUF) * BSZ + rd_b;                                                 \
+    const bool last_slice = (ck == KS - 1);                                                       \
+    const bool two = !last_slice || last_two;                                                     \
+    bf16x8_t fa[TM], fb[TN], ga[TM], gb[TN];                                                      \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK); \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kSliceK); \
+    if (two) {                                                                                    \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i) ga[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK + rd_step); \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j) gb[j] = *(const bf16x8_t*)(Bc + j * 32 * kSliceK + rd_step); \
+    }                                                                                             \
+    if (ck == 0) {                                                                                \
+      const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], zero16, 0, 0, 0);     \
+    } else {                                                                                      \
+      KGC_MFMA_STEP(fa, fb);                                                                      \
+    }                                                                                             \
+    if (two) KGC_MFMA_STEP(ga, gb);                                                               \
+    if (last_slice) {                                                                             \
+      float mn = acc[0][0][0];                                                                    \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+          _Pragma("unroll") for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);            \
+      if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {                                       \
+        const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
+        const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;                                  \
+        constexpr int NW = (TM * TN + 3) / 4;                                                     \
+        _Pragma("unroll") for (int w = 0; w < NW; ++w) {                                          \
+          unsigned long long cm = 0ull;                                                           \
+          _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                         \
+            const int tile = w * 4 + q;                                                           \
+            if (tile < TM * TN) {                                                                 \
+              const int i = tile / TN, j = tile % TN;                                             \
+              _Pragma("unroll") for (int v = 0; v < 16; ++v)                                      \
+                if (acc[i][j][v] <= thr) cm |= 1ull << (q * 16 + v);                              \
+            }                                                                                     \
+          }                                                                                       \
+          if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;                          \
+          recheck_and_emit(cm, a.r0 + rl, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) { \
+            const int tile = w * 4 + (e >> 4), v = e & 15;                                        \
+            const int i = tile / TN, j = tile % TN;                                               \
+            hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);                     \
+            tslot = tbase + j * 32 + (src & 31);                                                  \
+          });                                                                                     \
+        }                                                                                         \
+      }                                                                                           \
+      ck = 0;                                                                                     \
+      if (++ct < ntiles) tcol_cur = cols ? (int)cols[t_begin + ct] : t_begin + ct;                \
+    } else {                                                                                      \
+      ++ck;                                                                                       \
+    }                                                                                             \
+  } while (0)
+
+  // prologue: tail slices 0 and 1 in flight, slice 0 staged (the barrier also publishes the head tile)
+  KGC_GLOAD(rb0);
+  KGC_GLOAD(rb1);
+  KGC_SSTORE(0, rb0);
+  __syncthreads();
+
+  for (int i = 0; i < total; i += 2) {
+    // even step: slice i is in buffer 0; set 0 is free for slice i + 2; set 1 holds slice i + 1
+    KGC_GLOAD(rb0);
+    KGC_COMPUTE(0);
+    KGC_SSTORE(1, rb1);
+    __syncthreads();
+    if (i + 1 >= total) break;
+    // odd step: slice i + 1 is in buffer 1; set 1 is free for slice i + 3; set 0 holds slice i + 2
+    KGC_GLOAD(rb1);
+    KGC_COMPUTE(1);
+    KGC_SSTORE(0, rb0);
+    __syncthreads();
+  }
+#undef KGC_GLOAD
+#undef KGC_SSTORE
+#undef KGC_MFMA_STEP
+#undef KGC_COMPUTE
+}
+
+// ---------------------------------------------------------------------------------------------
 struct JoinL1Args {
   const JoinParams* prm;
   int64_t Nslots;

@@ -52,7 +52,7 @@ def test_hand_case(p, delta, count):
     assert got["count"] == count == ref["count"]
 
 
-@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13])
 def test_c1_l2_full_parity(tile_cfg):
     wl = workloads.generate("c1_tiny_l2")
     got, ref, rep = _check(wl.E, wl.Rv, 2, wl.delta, tile_cfg=tile_cfg)
@@ -141,7 +141,7 @@ def test_zero_relation_symmetry():
 def test_repeatable_and_tile_independent():
     wl = workloads.generate("c1_tiny_l2", N=1500, R=4)
     ref = None
-    for tile_cfg in (1, 1, 2, 6, 8, 10):
+    for tile_cfg in (1, 1, 2, 6, 8, 10, 11, 13):
         got = _run(wl.E, wl.Rv, 2, 0.7, tile_cfg=tile_cfg)
         key = np.sort((got["r"].astype(np.int64) * 1500 + got["h"]) * 1500 + got["t"])
         assert ref is None or np.array_equal(ref, key)
