@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "kgc_kernels.h"
+#include "kgc_prune.h"
 
 using namespace kgc;
 
@@ -20,6 +21,7 @@ constexpr int64_t kSlotAlign = 256;            // rows are padded to a multiple 
 constexpr int64_t kDefaultWorkspace = 16ll << 30;
 constexpr int64_t kL2RangeBytes = 1ll << 20;
 constexpr size_t kMaxLds = 160 * 1024;         // LDS per workgroup on gfx950
+constexpr int64_t kMaxTileList = 128ll << 20;  // entries of the surviving-tile list per relation batch (4 bytes each)
 
 struct DevBuf {
   void* p = nullptr;
@@ -35,6 +37,9 @@ struct kgc_handle {
   std::string err;
   kgc_stats stats{};
   DevBuf slot_ent, opB, opA, normsB, normsA, counters, params;
+  // pruning scratch
+  DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
+  GroupState* host_gstate = nullptr;           // pinned
   DevCounters* host_counters = nullptr;        // pinned
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   std::vector<hipEvent_t> join_ev;             // pairs around each join launch
@@ -149,6 +154,10 @@ int kgc_create(const kgc_config* cfg, kgc_handle** out) {
     delete h;
     return KGC_E_NOMEM;
   }
+  if (hipHostMalloc((void**)&h->host_gstate, sizeof(GroupState), hipHostMallocDefault) != hipSuccess) {
+    kgc_destroy(h);
+    return KGC_E_NOMEM;
+  }
   for (auto& e : h->ev)
     if (hipEventCreate(&e) != hipSuccess) { kgc_destroy(h); return KGC_E_HIP; }
   *out = h;
@@ -159,6 +168,10 @@ void kgc_destroy(kgc_handle* h) {
   if (!h) return;
   release(h->slot_ent); release(h->opB); release(h->opA); release(h->normsB); release(h->normsA);
   release(h->counters); release(h->params);
+  for (DevBuf* b : {&h->gstate, &h->unc_a, &h->unc_b, &h->group_of, &h->piv_ent, &h->best, &h->gsize, &h->goff, &h->gfill,
+                    &h->cent, &h->rad, &h->bitmap, &h->row_start, &h->row_count, &h->cols})
+    release(*b);
+  if (h->host_gstate) (void)hipHostFree(h->host_gstate);
   if (h->host_counters) (void)hipHostFree(h->host_counters);
   for (auto& e : h->ev)
     if (e) (void)hipEventDestroy(e);
@@ -194,14 +207,14 @@ int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* R
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
   if (nB) {
     k_stage_operands<false><<<g, 256, stage_lds, st>>>(E, Rvecs, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Nslots, KS,
-                                               (uint16_t*)hd->opB.p, (float*)hd->normsB.p, nullptr);
+                                               (uint16_t*)hd->opB.p, (float*)hd->normsB.p, nullptr, nullptr, 0, 1);
     k_scatter_norms<<<grid_for(Nslots, 256), 256, 0, st>>>((const float*)hd->normsB.p, (const int32_t*)hd->slot_ent.p,
                                                            Nslots, N, 1, nB);
   }
   if (nA) {
     for (int r = 0; r < R; ++r) {
       k_stage_operands<true><<<g, 256, stage_lds, st>>>(E, Rvecs, dtype, d, r, 1, (const int32_t*)hd->slot_ent.p, Nslots, KS,
-                                                (uint16_t*)hd->opA.p, (float*)hd->normsB.p, nullptr);
+                                                (uint16_t*)hd->opA.p, (float*)hd->normsB.p, nullptr, nullptr, 0, 1);
       k_scatter_norms<<<grid_for(Nslots, 256), 256, 0, st>>>((const float*)hd->normsB.p,
                                                              (const int32_t*)hd->slot_ent.p, Nslots, N, 1,
                                                              nA + (int64_t)r * N);
@@ -230,33 +243,110 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
 
   hipStream_t st = hd->stream;
   const int dtype = hd->cfg.dtype;
+  const bool prune = hd->cfg.prune != KGC_PRUNE_OFF;
 
   // tile shape
   int tile_id = hd->cfg.tile_cfg > 0 ? hd->cfg.tile_cfg - 1 : kDefaultL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
+  if (p == 2 && prune && !tc.stream_kernel)
+    return fail(hd, KGC_E_INVALID, "this tile variant has no pruned mode; choose a streaming variant");
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
-  const int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
-  const int nH = (int)(Nslots / BM), nT = (int)(Nslots / BN);
   const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
   const int k16 = (d + kNormCols + 15) / 16;
 
-  // relation batches: staged A operands of a batch must fit the workspace, and the grid 2^31 blocks
+  if ((rc = ensure(hd, hd->counters, sizeof(DevCounters))) || (rc = ensure(hd, hd->params, sizeof(JoinParams))))
+    return rc;
+  DevCounters* cnt = (DevCounters*)hd->counters.p;
+  JoinParams* prm = (JoinParams*)hd->params.p;
+
+  KGC_HIP(hd, hipEventRecord(hd->ev[0], st));
+  k_fill_u32<<<grid_for(sizeof(DevCounters) / 4, 256), 256, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
+
+  // ---- row order: identity, or entities grouped around local pivots (pruning) ----
+  int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
+  uint64_t n_groups = 0;
+  if (prune) {
+    // worst case: every group of kSmallGroup rows is padded to a micro-tile
+    const int64_t max_padded_groups = std::min<int64_t>(kMaxGroups, N / kSmallGroup + 1);
+    const int64_t slots_cap = ((N + (kMicro - 1) * max_padded_groups) + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
+    if ((rc = ensure(hd, hd->slot_ent, slots_cap * 4)) || (rc = ensure(hd, hd->gstate, sizeof(GroupState))) ||
+        (rc = ensure(hd, hd->unc_a, N * 4)) || (rc = ensure(hd, hd->unc_b, N * 4)) ||
+        (rc = ensure(hd, hd->group_of, N * 4)) || (rc = ensure(hd, hd->piv_ent, kPivotsPerRound * 4)) ||
+        (rc = ensure(hd, hd->best, N * 8)) || (rc = ensure(hd, hd->gsize, kMaxGroups * 4)) ||
+        (rc = ensure(hd, hd->goff, kMaxGroups * 4)) || (rc = ensure(hd, hd->gfill, kMaxGroups * 4)))
+      return rc;
+    GroupState* gs = (GroupState*)hd->gstate.p;
+    int32_t* unc = (int32_t*)hd->unc_a.p;
+    int32_t* unc_next = (int32_t*)hd->unc_b.p;
+    const float radius_mult = hd->cfg.group_radius > 0.f ? hd->cfg.group_radius : 2.0f;
+    const float tau = delta > 0.f ? radius_mult * delta : 0.f;
+    const int gN = grid_for(N, 256);
+    k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
+    for (int round = 0; round < kGroupRounds; ++round) {
+      // sampling density of the pivots among the still uncovered entities: 1/16, 1/16, 1/8, 1/8, 1/4, 1/2
+      static const int kShift[kGroupRounds] = {4, 4, 3, 3, 2, 1};
+      k_round_begin<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->piv_ent.p, (unsigned long long*)hd->best.p,
+                                       kShift[round]);
+      TileDistArgs ta{};
+      ta.X = E; ta.dtypeX = dtype; ta.row_ids = unc; ta.n_rows_dev = &gs->n_unc; ta.n_rows = N;
+      ta.Y = E; ta.dtypeY = dtype; ta.col_ids = (const int32_t*)hd->piv_ent.p; ta.n_cols_dev = &gs->n_piv;
+      ta.n_cols = kPivotsPerRound;
+      ta.shift = nullptr; ta.dtype_shift = dtype; ta.r0 = 0; ta.d = d; ta.best = (unsigned long long*)hd->best.p;
+      ta.delta = tau;
+      const dim3 g((unsigned)((std::min<int64_t>(kPivotsPerRound, N) + 127) / 128), (unsigned)((N + 127) / 128), 1);
+      if (p == 2) k_tile_dist<2, kEpiAssign><<<g, 256, 0, st>>>(ta);
+      else k_tile_dist<1, kEpiAssign><<<g, 256, 0, st>>>(ta);
+      k_round_commit<<<gN, 256, 0, st>>>(gs, unc, (const unsigned long long*)hd->best.p, (int32_t*)hd->group_of.p,
+                                        unc_next);
+      k_round_end<<<1, 64, 0, st>>>(gs);
+      std::swap(unc, unc_next);
+    }
+    k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gsize.p, kMaxGroups, 0u);
+    k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gfill.p, kMaxGroups, 0u);
+    k_fill_u32<<<grid_for(slots_cap, 256), 256, 0, st>>>((uint32_t*)hd->slot_ent.p, slots_cap, 0xffffffffu);
+    k_group_hist<<<gN, 256, 0, st>>>((const int32_t*)hd->group_of.p, N, (int32_t*)hd->gsize.p);
+    k_group_layout<<<1, 64, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign);
+    k_scatter_slots<<<gN, 256, 0, st>>>(gs, (const int32_t*)hd->group_of.p, (const int32_t*)hd->goff.p,
+                                       (int32_t*)hd->gfill.p, N, (int32_t*)hd->slot_ent.p);
+    KGC_HIP(hd, hipGetLastError());
+    // the layout decides the number of rows, which sizes every later launch: one small read-back
+    KGC_HIP(hd, hipMemcpyAsync(hd->host_gstate, gs, sizeof(GroupState), hipMemcpyDeviceToHost, st));
+    KGC_HIP(hd, hipStreamSynchronize(st));
+    Nslots = hd->host_gstate->n_slots;
+    n_groups = (uint64_t)hd->host_gstate->n_groups;
+    if (Nslots < N || Nslots > slots_cap || Nslots % kSlotAlign) return fail(hd, KGC_E_HIP, "group layout out of range");
+  } else {
+    if ((rc = ensure(hd, hd->slot_ent, Nslots * 4))) return rc;
+    k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
+  }
+  const int32_t* slot_ent = (const int32_t*)hd->slot_ent.p;
+  const int nH = (int)(Nslots / BM), nT = (int)(Nslots / BN);
+  const int64_t n_micro = Nslots / kMicro;
+  const int words_per_row = (nT + 31) / 32;
+  const int64_t tiles_per_rel = (int64_t)nH * nT;
+  if (nH > 65535) return fail(hd, KGC_E_INVALID, "N too large for one launch grid");
+
+  // ---- relation batches: staged A operands (L2) and the tile lists (pruning) must fit the workspace ----
   const int64_t ws = hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
   const size_t opA_per_rel = (p == 2) ? (size_t)KS * Nslots * kSliceK * 2 : 0;
   int64_t RBmax = R;
   if (p == 2) RBmax = std::max<int64_t>(1, std::min<int64_t>(R, ws / (int64_t)(opA_per_rel + Nslots * 4)));
-  // dense launches use a (tail tile, head tile, relation) grid; y and z are limited to 65535 blocks
-  const int64_t tiles_per_rel = (int64_t)nH * nT;
+  if (prune) RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, kMaxTileList / tiles_per_rel));
   RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, 65535));
-  if (nH > 65535) return fail(hd, KGC_E_INVALID, "N too large for one launch grid");
+  if (prune && tiles_per_rel > kMaxTileList) return fail(hd, KGC_E_INVALID, "N too large for the pruned tile list");
 
-  if ((rc = ensure(hd, hd->slot_ent, Nslots * 4)) || (rc = ensure(hd, hd->counters, sizeof(DevCounters))) ||
-      (rc = ensure(hd, hd->params, sizeof(JoinParams))))
-    return rc;
   if (p == 2) {
     if ((rc = ensure(hd, hd->opB, (size_t)KS * Nslots * kSliceK * 2)) ||
         (rc = ensure(hd, hd->opA, opA_per_rel * (size_t)RBmax)) || (rc = ensure(hd, hd->normsB, Nslots * 4)) ||
         (rc = ensure(hd, hd->normsA, (size_t)RBmax * Nslots * 4)))
+      return rc;
+  }
+  if (prune) {
+    if ((rc = ensure(hd, hd->cent, (size_t)n_micro * d * 4)) || (rc = ensure(hd, hd->rad, n_micro * 4)) ||
+        (rc = ensure(hd, hd->bitmap, (size_t)RBmax * nH * words_per_row * 4)) ||
+        (rc = ensure(hd, hd->row_start, (size_t)RBmax * nH * 4)) ||
+        (rc = ensure(hd, hd->row_count, (size_t)RBmax * nH * 4)) ||
+        (rc = ensure(hd, hd->cols, (size_t)RBmax * tiles_per_rel * 4)))
       return rc;
   }
   const int nbatch = (int)((R + RBmax - 1) / RBmax);
@@ -266,24 +356,20 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
     hd->join_ev.push_back(e);
   }
 
-  DevCounters* cnt = (DevCounters*)hd->counters.p;
-  JoinParams* prm = (JoinParams*)hd->params.p;
-  const int32_t* slot_ent = (const int32_t*)hd->slot_ent.p;
-
-  KGC_HIP(hd, hipEventRecord(hd->ev[0], st));
-  k_fill_u32<<<grid_for(sizeof(DevCounters) / 4, 256), 256, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
-  k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
-
   RecheckCtx cx;
   cx.E = E; cx.Rv = Rvecs; cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
   cx.delta = (double)delta; cx.out = out_triples; cx.cap = cap;
   cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates;
 
-  float ms_pre_extra = 0.f;
+  KGC_HIP(hd, hipEventRecord(hd->ev[3], st));     // end of grouping
+  if (prune) {
+    if (p == 2) k_micro_summary<2><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p, (float*)hd->rad.p);
+    else k_micro_summary<1><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p, (float*)hd->rad.p);
+  }
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
   if (p == 2) {
     k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
-        E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b);
+        E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b, nullptr, 0, 1);
   } else {
     k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(E, N, d, dtype, cnt->max_a);
     k_row_l1_max<<<grid_for((int64_t)R * 32, 256), 256, 0, st>>>(Rvecs, R, d, dtype, cnt->max_b);
@@ -294,27 +380,54 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   int b = 0;
   for (int64_t r0 = 0; r0 < R; r0 += RBmax, ++b) {
     const int RB = (int)std::min<int64_t>(RBmax, R - r0);
+    const uint32_t* row_start = nullptr;
+    const uint32_t* row_count = nullptr;
+    const uint32_t* cols = nullptr;
+    if (prune) {
+      // a2: bound test on micro-tile pairs -> bitmap of join tiles -> per-row lists of surviving tail tiles
+      const int64_t bm_words = (int64_t)RB * nH * words_per_row;
+      k_fill_u32<<<grid_for(bm_words, 256), 256, 0, st>>>((uint32_t*)hd->bitmap.p, bm_words, 0u);
+      TileDistArgs ta{};
+      ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.row_ids = nullptr; ta.n_rows_dev = nullptr; ta.n_rows = n_micro;
+      ta.Y = hd->cent.p; ta.dtypeY = KGC_F32; ta.col_ids = nullptr; ta.n_cols_dev = nullptr; ta.n_cols = n_micro;
+      ta.shift = Rvecs; ta.dtype_shift = dtype; ta.r0 = (int)r0; ta.d = d;
+      ta.rad = (const float*)hd->rad.p; ta.delta = delta; ta.bitmap = (uint32_t*)hd->bitmap.p;
+      ta.nH = nH; ta.words_per_row = words_per_row; ta.micro_per_bm = BM / kMicro; ta.micro_per_bn = BN / kMicro;
+      const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), (unsigned)RB);
+      if (delta >= 0.f) {
+        if (p == 2) k_tile_dist<2, kEpiBound><<<g, 256, 0, st>>>(ta);
+        else k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
+      }
+      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 2, 0u);
+      k_rows_from_bitmap<<<(unsigned)((int64_t)RB * nH), 64, 0, st>>>(
+          (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
+          (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor);
+      k_add_u64<<<1, 64, 0, st>>>(&cnt->tiles, &cnt->tile_cursor);
+      row_start = (const uint32_t*)hd->row_start.p;
+      row_count = (const uint32_t*)hd->row_count.p;
+      cols = (const uint32_t*)hd->cols.p;
+    }
     if (p == 2) {
       k_stage_operands<true><<<grid_for((int64_t)RB * (Nslots / kStageRows), 1), 256, stage_lds, st>>>(
           E, Rvecs, dtype, d, (int)r0, RB, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p,
-          cnt->max_a);
+          cnt->max_a, row_count, nH, BM);
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
-      JoinArgs ja;
-      ja.A = (const uint16_t*)hd->opA.p; ja.B = (const uint16_t*)hd->opB.p; ja.prm = prm;
-      ja.Nslots = Nslots; ja.KS = KS; ja.k16 = k16; ja.nH = nH; ja.nT = nT; ja.r0 = (int)r0; ja.RB = RB;
-      ja.worklist = nullptr; ja.cx = cx;
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
       if (tc.stream_kernel) {
         JoinStreamArgs sa;
-        sa.A = ja.A; sa.B = ja.B; sa.prm = prm; sa.Nslots = Nslots; sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT;
-        sa.r0 = (int)r0; sa.RB = RB; sa.row_ptr = nullptr; sa.row_key = nullptr; sa.cols = nullptr; sa.cx = cx;
-        // Tail tiles are cut into ranges of about kL2RangeBytes of staged B rows, so that the blocks running at
-        // the same time (consecutive head tiles of one range) keep their B rows in the 4 MiB L2 of their XCD;
-        // small problems are cut further to fill the chip.
-        const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
-        int64_t nsplit = (nT * tile_bytes + kL2RangeBytes - 1) / kL2RangeBytes;
-        nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
-        nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
+        sa.A = (const uint16_t*)hd->opA.p; sa.B = (const uint16_t*)hd->opB.p; sa.prm = prm; sa.Nslots = Nslots;
+        sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = (int)r0; sa.RB = RB;
+        sa.row_start = row_start; sa.row_count = row_count; sa.cols = cols; sa.cx = cx;
+        // Dense: tail tiles are cut into ranges of about kL2RangeBytes of staged B rows, so that the blocks
+        // running at the same time (consecutive head tiles of one range) keep their B rows in the 4 MiB L2 of
+        // their XCD; small problems are cut further to fill the chip.  Pruned: one block per row.
+        int64_t nsplit = 1;
+        if (!prune) {
+          const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
+          nsplit = (nT * tile_bytes + kL2RangeBytes - 1) / kL2RangeBytes;
+          nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
+          nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
+        }
         size_t dyn_lds = 0;
         if (tc.head_resident) {
           dyn_lds = ((size_t)KS * 256 + 2 * (size_t)BN) * kSliceK * 2;
@@ -325,21 +438,24 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB), dim3(tc.threads), dyn_lds,
                            st, sa);
       } else {
+        JoinArgs ja;
+        ja.A = (const uint16_t*)hd->opA.p; ja.B = (const uint16_t*)hd->opB.p; ja.prm = prm;
+        ja.Nslots = Nslots; ja.KS = KS; ja.k16 = k16; ja.nH = nH; ja.nT = nT; ja.r0 = (int)r0; ja.RB = RB; ja.cx = cx;
         hipLaunchKernelGGL(tc.tile_kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);
       }
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else {
       JoinL1Args la;
       la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = (int)r0; la.RB = RB;
-      la.worklist = nullptr; la.cx = cx;
+      la.row_start = row_start; la.row_count = row_count; la.cols = cols; la.cx = cx;
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
-      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(256), 0, st, la);
+      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)(prune ? 1 : nT), (unsigned)nH, (unsigned)RB), dim3(256), 0, st, la);
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     }
     hd->stats.join_launches++;
   }
   KGC_HIP(hd, hipGetLastError());
-  KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 16, hipMemcpyDeviceToHost, st));
+  KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 40, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
   KGC_HIP(hd, hipStreamSynchronize(st));
 
@@ -347,22 +463,27 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   s.emitted = hd->host_counters->hits;
   s.candidates = hd->host_counters->candidates;
   s.tiles_total = (uint64_t)tiles_per_rel * (uint64_t)R;
-  s.tiles_evaluated = s.tiles_total;
-  s.tiles_pruned = 0;
-  s.pairs_evaluated = s.triples_total;
+  s.tiles_evaluated = prune ? hd->host_counters->tiles : s.tiles_total;
+  s.tiles_pruned = s.tiles_total - s.tiles_evaluated;
+  s.pairs_evaluated = prune ? s.tiles_evaluated * (uint64_t)BM * (uint64_t)BN : s.triples_total;
+  s.groups = n_groups;
   s.tile_m = BM; s.tile_n = BN;
   s.k_padded = (p == 2) ? k16 * 16 : d;
   s.relation_batches = nbatch;
-  float ms = 0.f;
+  // phase times from the events: [ev0 grouping ev3 | summaries + B staging ev1 | per batch: bound test + A staging | join]
+  float ms = 0.f, ms_group = 0.f, ms_between = 0.f;
   (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);
-  (void)hipEventElapsedTime(&s.ms_precompute, hd->ev[0], hd->ev[1]);
+  (void)hipEventElapsedTime(&ms_group, hd->ev[0], hd->ev[3]);
+  (void)hipEventElapsedTime(&s.ms_precompute, hd->ev[3], hd->ev[1]);
   for (int i = 0; i < nbatch; ++i) {
     if (hipEventElapsedTime(&ms, hd->join_ev[2 * i], hd->join_ev[2 * i + 1]) == hipSuccess) s.ms_join += ms;
-    if (i > 0 && hipEventElapsedTime(&ms, hd->join_ev[2 * i - 1], hd->join_ev[2 * i]) == hipSuccess) ms_pre_extra += ms;
+    hipEvent_t prev = i == 0 ? hd->ev[1] : hd->join_ev[2 * i - 1];
+    if (hipEventElapsedTime(&ms, prev, hd->join_ev[2 * i]) == hipSuccess) ms_between += ms;
   }
-  if (nbatch > 0 && hipEventElapsedTime(&ms, hd->ev[1], hd->join_ev[0]) == hipSuccess) ms_pre_extra += ms;
-  s.ms_precompute += ms_pre_extra;
-  s.ms_prune = 0.f;
+  // the per-batch gap holds the bound test (pruning) and the A staging (precompute); it is booked under pruning
+  // when pruning is on, since A staging then only touches surviving head tiles
+  s.ms_prune = prune ? ms_group + ms_between : 0.f;
+  if (!prune) s.ms_precompute += ms_group + ms_between;
 
   *count = s.emitted;
   return s.emitted > cap ? KGC_OVERFLOW : KGC_OK;

@@ -35,6 +35,9 @@ struct JoinParams {
 struct DevCounters {
   unsigned long long hits;        // true number of qualifying triples
   unsigned long long candidates;  // triples re-scored in double
+  unsigned long long tile_cursor; // next free entry of the surviving-tile list (per relation batch)
+  unsigned long long tile_pad;    // (kept zero; cleared together with the cursor)
+  unsigned long long tiles;       // surviving tiles over all batches
   unsigned int max_a[1024];       // running maxima of ||bf16(h + r)||^2 (L2) or ||e||_1 (L1), float bits, spread over slots
   unsigned int max_b[1024];       // running maxima of ||bf16(t)||^2 (L2) or ||r||_1 (L1)
 };
@@ -42,6 +45,10 @@ struct DevCounters {
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
+}
+
+__global__ void k_add_u64(unsigned long long* dst, const unsigned long long* src) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *dst += *src;
 }
 
 // slot -> entity for the dense order: identity, -1 on the padding rows
@@ -67,7 +74,8 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
                                                         int dtype, int d, int r0, int RB,
                                                         const int32_t* __restrict__ slot_ent, int64_t Nslots, int KS,
                                                         uint16_t* __restrict__ out, float* __restrict__ norms,
-                                                        unsigned int* __restrict__ max_slots) {
+                                                        unsigned int* __restrict__ max_slots,
+                                                        const uint32_t* __restrict__ row_count, int nH, int bm) {
   extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [kStageRows][KS * 32 + 8]
   __shared__ int32_t ents[kStageRows];
   __shared__ float wmax[4];
@@ -79,6 +87,8 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
   for (int64_t g = blockIdx.x; g < ngroups; g += gridDim.x) {
     const int rl = (int)(g / groups_per_rel);
     const int64_t slot0 = (g - (int64_t)rl * groups_per_rel) * kStageRows;
+    // pruned joins stage only the head tiles that still have tail tiles to meet
+    if (row_count && row_count[(int64_t)rl * nH + slot0 / bm] == 0) continue;
     __syncthreads();                                   // previous group fully written out
     if (tid < kStageRows) ents[tid] = slot_ent[slot0 + tid];
     __syncthreads();
@@ -233,7 +243,6 @@ struct JoinArgs {
   int k16;                  // 16-wide MFMA steps that hold data (the last slice may be half empty)
   int nH, nT;               // tiles along heads / tails
   int r0, RB;               // first relation and number of relations of this batch
-  const uint32_t* worklist; // NULL: dense grid; else packed (r_local, tile_h, tile_t) triples, 3 words each
   RecheckCtx cx;
 };
 
@@ -256,13 +265,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_join_l2(const JoinArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  int tH, tT, rl;
-  if (a.worklist) {
-    const uint32_t* w = a.worklist + (int64_t)blockIdx.x * 3;
-    rl = (int)w[0]; tH = (int)w[1]; tT = (int)w[2];
-  } else {
-    tT = (int)blockIdx.x; tH = (int)blockIdx.y; rl = (int)blockIdx.z;
-  }
+  const int tT = (int)blockIdx.x, tH = (int)blockIdx.y, rl = (int)blockIdx.z;
 
   const int64_t slice_elems = a.Nslots * kSliceK;
   const uint16_t* Ab = a.A + (int64_t)rl * a.KS * slice_elems + (int64_t)tH * BM * kSliceK;
@@ -371,8 +374,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_join_l2(const JoinArgs a) {
 // tiles; the K slices of all those tiles form one continuous stream that is prefetched two slices
 // ahead through registers into a double-buffered LDS stage, so the global-memory latency of a slice
 // is covered by the MFMA work of the two slices before it, also across tile boundaries.
-// Tail-tile range: dense mode splits [0, nT) evenly over gridDim.y; worklist mode reads a row list
-// (row_ptr / col lists keyed by (relation, head tile)).
+// Tail-tile range: dense mode splits [0, nT) evenly over gridDim.y; pruned mode reads the row's list of
+// surviving tail tiles.
 struct JoinStreamArgs {
   const uint16_t* A;
   const uint16_t* B;
@@ -381,9 +384,9 @@ struct JoinStreamArgs {
   int KS, k16;
   int nH, nT;
   int r0, RB;
-  const uint32_t* row_ptr;   // NULL: dense.  Else row_ptr[row], row_ptr[row + 1] delimit this block's tail tiles
-  const uint32_t* row_key;   // row -> (r_local << 16 | head tile) when row_ptr is given
-  const uint32_t* cols;      // tail tile numbers
+  const uint32_t* row_start; // NULL: dense.  Else row = r_local * nH + head tile owns cols[row_start[row] .. + row_count[row])
+  const uint32_t* row_count;
+  const uint32_t* cols;      // surviving tail tile numbers, ascending within a row
   RecheckCtx cx;
 };
 
@@ -404,10 +407,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
-  if (a.row_ptr) {
-    const uint32_t key = a.row_key[blockIdx.x];
-    rl = (int)(key >> 16); tH = (int)(key & 0xffffu);
-    t_begin = (int)a.row_ptr[blockIdx.x]; t_end = (int)a.row_ptr[blockIdx.x + 1];
+  if (a.row_start) {
+    tH = (int)blockIdx.x; rl = (int)blockIdx.z;
+    const int64_t row = (int64_t)rl * a.nH + tH;
+    t_begin = (int)a.row_start[row]; t_end = t_begin + (int)a.row_count[row];
     cols = a.cols;
   } else {
     // grid = (head tiles, tail-tile ranges, relations): blocks that run together share a tail-tile range
@@ -600,10 +603,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
 
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
-  if (a.row_ptr) {
-    const uint32_t key = a.row_key[blockIdx.x];
-    rl = (int)(key >> 16); tH = (int)(key & 0xffffu);
-    t_begin = (int)a.row_ptr[blockIdx.x]; t_end = (int)a.row_ptr[blockIdx.x + 1];
+  if (a.row_start) {
+    tH = (int)blockIdx.x; rl = (int)blockIdx.z;
+    const int64_t row = (int64_t)rl * a.nH + tH;
+    t_begin = (int)a.row_start[row]; t_end = t_begin + (int)a.row_count[row];
     cols = a.cols;
   } else {
     tH = (int)blockIdx.x; rl = (int)blockIdx.z;
@@ -775,14 +778,17 @@ struct JoinL1Args {
   int64_t Nslots;
   int nH, nT;
   int r0, RB;
-  const uint32_t* worklist;
+  const uint32_t* row_start;   // NULL: dense (one block per tile, grid = (nT, nH, RB)); else see JoinStreamArgs
+  const uint32_t* row_count;
+  const uint32_t* cols;
   RecheckCtx cx;
 };
 
-// Kernel 3.  One block of 256 threads scores a 128 x 128 tile of (heads, tails) for one relation in
-// float32 vector arithmetic only: acc += |(h_k + r_k) - t_k| (Section 4.3's dist for p = 1).  The
-// tile is staged through LDS in 16-dimension slices, dimension-major, a = h + r formed while staging;
-// each thread keeps an 8 x 8 block of sums in registers (two 4-row groups x two 4-column groups).
+// Kernel 3.  One block of 256 threads scores 128 x 128 tiles of (heads, tails) for one relation in
+// float32 vector arithmetic only: acc += |(h_k + r_k) - t_k| (Section 4.3's dist for p = 1).  A tile is
+// staged through LDS in 16-dimension slices, dimension-major, a = h + r formed while staging; each
+// thread keeps an 8 x 8 block of sums in registers (two 4-row groups x two 4-column groups).  In pruned
+// mode the block walks the surviving tail tiles of its (relation, head tile) row.
 constexpr int kL1Tile = 128;
 constexpr int kL1K = 16;
 __global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
@@ -792,78 +798,86 @@ __global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
   __shared__ int32_t hent[BM], tent[BN];
 
   const int tid = threadIdx.x, wave = tid >> 6;
-  int tH, tT, rl;
-  if (a.worklist) {
-    const uint32_t* w = a.worklist + (int64_t)blockIdx.x * 3;
-    rl = (int)w[0]; tH = (int)w[1]; tT = (int)w[2];
+  int tH, rl, t_begin, t_end;
+  const uint32_t* cols = nullptr;
+  if (a.row_start) {
+    tH = (int)blockIdx.y; rl = (int)blockIdx.z;
+    const int64_t row = (int64_t)rl * a.nH + tH;
+    t_begin = (int)a.row_start[row]; t_end = t_begin + (int)a.row_count[row];
+    cols = a.cols;
   } else {
-    tT = (int)blockIdx.x; tH = (int)blockIdx.y; rl = (int)blockIdx.z;
+    t_begin = (int)blockIdx.x; t_end = t_begin + 1; tH = (int)blockIdx.y; rl = (int)blockIdx.z;
   }
+  if (t_end <= t_begin) return;
   const int r = a.r0 + rl;
   const int d = a.cx.d, dtype = a.cx.dtype;
-  if (tid < BM) hent[tid] = a.cx.slot_ent[(int64_t)tH * BM + tid];
-  else tent[tid - BM] = a.cx.slot_ent[(int64_t)tT * BN + (tid - BM)];
-  __syncthreads();
-
+  const float thr = a.prm->thr;
   const int tx = tid & 15, ty = tid >> 4;
-  float acc[8][8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
-
   // staging assignment: thread -> (row = tid / 2, eight dimensions starting at (tid % 2) * 8)
   const int srow = tid >> 1, sk0 = (tid & 1) * 8;
-  const int he = hent[srow], te = tent[srow];
-  const int64_t ho = (int64_t)(he < 0 ? 0 : he) * d, to = (int64_t)(te < 0 ? 0 : te) * d, ro = (int64_t)r * d;
+  const int64_t ro = (int64_t)r * d;
+  if (tid < BM) hent[tid] = a.cx.slot_ent[(int64_t)tH * BM + tid];
 
-  for (int k0 = 0; k0 < d; k0 += BK) {
-    float va[8], vb[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int k = k0 + sk0 + q;
-      const bool in = k < d;
-      va[q] = in ? ld_elem(a.cx.E, ho + k, dtype) + ld_elem(a.cx.Rv, ro + k, dtype) : 0.f;
-      vb[q] = in ? ld_elem(a.cx.E, to + k, dtype) : 0.f;
-    }
-    __syncthreads();                        // previous slice fully consumed
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      As[sk0 + q][srow] = va[q];
-      Bs[sk0 + q][srow] = vb[q];
-    }
+  for (int ti = t_begin; ti < t_end; ++ti) {
+    const int tT = cols ? (int)cols[ti] : ti;
+    __syncthreads();                        // previous tile done with tent / As / Bs
+    if (tid >= BM) tent[tid - BM] = a.cx.slot_ent[(int64_t)tT * BN + (tid - BM)];
     __syncthreads();
+    float acc[8][8];
 #pragma unroll
-    for (int k = 0; k < BK; ++k) {
-      const float4 a0 = *(const float4*)(&As[k][ty * 4]);
-      const float4 a1 = *(const float4*)(&As[k][64 + ty * 4]);
-      const float4 b0 = *(const float4*)(&Bs[k][tx * 4]);
-      const float4 b1 = *(const float4*)(&Bs[k][64 + tx * 4]);
-      const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-      const float bv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] += fabsf(av[i] - bv[j]);
-    }
-  }
+      for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+    const int he = hent[srow], te = tent[srow];
+    const int64_t ho = (int64_t)(he < 0 ? 0 : he) * d, to = (int64_t)(te < 0 ? 0 : te) * d;
 
-  const float thr = a.prm->thr;
-  unsigned long long cm = 0ull;
+    for (int k0 = 0; k0 < d; k0 += BK) {
+      float va[8], vb[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+      for (int q = 0; q < 8; ++q) {
+        const int k = k0 + sk0 + q;
+        const bool in = k < d;
+        va[q] = in ? ld_elem(a.cx.E, ho + k, dtype) + ld_elem(a.cx.Rv, ro + k, dtype) : 0.f;
+        vb[q] = in ? ld_elem(a.cx.E, to + k, dtype) : 0.f;
+      }
+      __syncthreads();                      // previous slice fully consumed
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (acc[i][j] <= thr) cm |= 1ull << (i * 8 + j);
-  if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) return;
-  const int64_t hbase = (int64_t)tH * BM, tbase = (int64_t)tT * BN;
-  recheck_and_emit(cm, r, a.cx, [&](int e, int src, int64_t& hslot, int64_t& tslot) {
-    const int stid = wave * 64 + src;
-    const int sx = stid & 15, sy = stid >> 4;
-    const int i = e >> 3, j = e & 7;
-    hslot = hbase + (i >> 2) * 64 + sy * 4 + (i & 3);
-    tslot = tbase + (j >> 2) * 64 + sx * 4 + (j & 3);
-  });
+      for (int q = 0; q < 8; ++q) {
+        As[sk0 + q][srow] = va[q];
+        Bs[sk0 + q][srow] = vb[q];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < BK; ++k) {
+        const float4 a0 = *(const float4*)(&As[k][ty * 4]);
+        const float4 a1 = *(const float4*)(&As[k][64 + ty * 4]);
+        const float4 b0 = *(const float4*)(&Bs[k][tx * 4]);
+        const float4 b1 = *(const float4*)(&Bs[k][64 + tx * 4]);
+        const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        const float bv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[i][j] += fabsf(av[i] - bv[j]);
+      }
+    }
+
+    unsigned long long cm = 0ull;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (acc[i][j] <= thr) cm |= 1ull << (i * 8 + j);
+    if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;
+    const int64_t hbase = (int64_t)tH * BM, tbase = (int64_t)tT * BN;
+    recheck_and_emit(cm, r, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
+      const int stid = wave * 64 + src;
+      const int sx = stid & 15, sy = stid >> 4;
+      const int i = e >> 3, j = e & 7;
+      hslot = hbase + (i >> 2) * 64 + sy * 4 + (i & 3);
+      tslot = tbase + (j >> 2) * 64 + sx * 4 + (j & 3);
+    });
+  }
 }
 
 }  // namespace kgc

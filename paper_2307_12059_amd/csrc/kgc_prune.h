@@ -1,0 +1,337 @@
+// Block-level pruning for the TransE completion join (gfx950).
+//
+// The paper filters pairs with one pivot p: dist(a, b) >= |dist(p, a) - dist(p, b)| (Lemma 1, Section 4.4)
+// and turns that into index ranges over pivot-sorted lists (Lemma 2).  On embeddings whose norms
+// concentrate, the single zero pivot of Section 4.5 separates little, so this build applies the same
+// triangle-inequality argument with LOCAL pivots: entities are grouped around pivot entities, stored
+// group by group, and every 32-row micro-tile m gets a centre c_m and a radius rho_m >= dist(e, c_m)
+// for its rows.  For a = h + r with h in micro-tile H and b = t in micro-tile T,
+//     dist(a, b) >= dist(c_H + r, c_T) - rho_H - rho_T          (triangle inequality, twice)
+// so the pair of micro-tiles is skipped when that bound exceeds delta.  A join tile is evaluated iff one
+// of its micro-tile pairs survives.  All of it is done in the metric of the join (L1 or L2); bounds are
+// computed in float32 and widened by a relative slack so that rounding can only keep more, never drop.
+#pragma once
+#include "kgc_device.h"
+
+namespace kgc {
+
+constexpr int kMicro = 32;                 // rows per micro-tile (the MFMA tile height)
+constexpr int kGroupRounds = 6;            // covering rounds
+constexpr int kPivotsPerRound = 4096;      // pivots drawn from the uncovered entities per round
+constexpr int kMaxGroups = kGroupRounds * kPivotsPerRound;
+constexpr int kSmallGroup = 16;            // smaller groups are packed, unpadded, into the tail region
+constexpr float kBoundSlack = 2e-4f;       // relative widening of float32 distance sums (d <= 960 terms)
+
+struct GroupState {
+  int32_t n_unc;        // uncovered entities in the current list
+  int32_t n_unc_next;   // ... appended to the next list
+  int32_t n_piv;        // pivots of the current round
+  int32_t n_groups;     // groups formed so far
+  int32_t n_slots;      // rows after layout, multiple of the slot alignment
+  int32_t tail_base;    // first slot of the unpadded tail region
+  int32_t tail_fill;    // running count of rows placed in the tail region
+  int32_t n_micro_used; // micro-tiles that hold at least one entity
+};
+
+__global__ void k_group_init(GroupState* gs, int32_t* unc, int32_t* group_of, int64_t N) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) {
+    gs->n_unc = (int32_t)N; gs->n_unc_next = 0; gs->n_piv = 0; gs->n_groups = 0;
+    gs->n_slots = 0; gs->tail_base = 0; gs->tail_fill = 0; gs->n_micro_used = 0;
+  }
+  if (i < N) { unc[i] = (int32_t)i; group_of[i] = -1; }
+}
+
+// Start of a round: pivots are an even-stride sample (one in 2^shift, at most kPivotsPerRound) of the
+// uncovered list; nearest-pivot records are reset.
+__global__ void k_round_begin(GroupState* gs, const int32_t* unc, int32_t* piv_ent, unsigned long long* best,
+                              int shift) {
+  const int n_unc = gs->n_unc;
+  int n_piv = n_unc >> shift;
+  n_piv = n_piv < 1 ? (n_unc > 0 ? 1 : 0) : n_piv;
+  n_piv = n_piv < kPivotsPerRound ? n_piv : kPivotsPerRound;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_piv) piv_ent[i] = unc[(int64_t)i * n_unc / n_piv];   // n_piv > 0 here
+  if (i < n_unc) best[i] = ~0ull;
+  if (i == 0) { gs->n_piv = n_piv; gs->n_unc_next = 0; }
+}
+
+// End of a round: an uncovered entity joins the group of the pivot the assignment found within tau, if any.
+__global__ void k_round_commit(GroupState* gs, const int32_t* unc, const unsigned long long* best,
+                               int32_t* group_of, int32_t* unc_next) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= gs->n_unc) return;
+  const unsigned long long b = best[i];
+  const int ent = unc[i];
+  if (b != ~0ull) group_of[ent] = gs->n_groups + (int)(uint32_t)(b >> 32);
+  else unc_next[atomicAdd(&gs->n_unc_next, 1)] = ent;
+}
+
+__global__ void k_round_end(GroupState* gs) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    gs->n_groups += gs->n_piv;
+    gs->n_unc = gs->n_unc_next;
+    gs->n_piv = 0;
+  }
+}
+
+__global__ void k_group_hist(const int32_t* group_of, int64_t N, int32_t* gsize) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < N && group_of[i] >= 0) atomicAdd(&gsize[group_of[i]], 1);
+}
+
+// Slot layout: groups of at least kSmallGroup rows start on a micro-tile boundary and are padded to one;
+// all other rows follow, packed.  One thread: at most kMaxGroups iterations.
+__global__ void k_group_layout(GroupState* gs, const int32_t* gsize, int32_t* goff, int64_t N, int slot_align) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int cur = 0, placed = 0;
+  const int G = gs->n_groups;
+  for (int g = 0; g < G; ++g) {
+    const int sz = gsize[g];
+    if (sz >= kSmallGroup) {
+      goff[g] = cur;
+      cur += (sz + kMicro - 1) / kMicro * kMicro;
+      placed += sz;
+    } else {
+      goff[g] = -1;
+    }
+  }
+  gs->tail_base = cur;
+  gs->tail_fill = 0;
+  const int64_t total = (int64_t)cur + (N - placed);
+  gs->n_slots = (int32_t)((total + slot_align - 1) / slot_align * slot_align);
+}
+
+__global__ void k_scatter_slots(GroupState* gs, const int32_t* group_of, const int32_t* goff, int32_t* gfill,
+                                int64_t N, int32_t* slot_ent) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  const int g = group_of[i];
+  int slot;
+  if (g >= 0 && goff[g] >= 0) slot = goff[g] + atomicAdd(&gfill[g], 1);
+  else slot = gs->tail_base + atomicAdd(&gs->tail_fill, 1);
+  slot_ent[slot] = (int32_t)i;
+}
+
+// One wave per micro-tile: centre = mean of its rows, radius = max distance of a row to the centre (in
+// the join's metric), widened for float32 rounding.  An empty micro-tile gets radius -1.
+template <int P>
+__global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E, int dtype, int d,
+                                                      const int32_t* __restrict__ slot_ent, int64_t n_micro,
+                                                      float* __restrict__ cent, float* __restrict__ rad) {
+  const int64_t m = blockIdx.x;
+  if (m >= n_micro) return;
+  const int lane = threadIdx.x;
+  __shared__ int32_t ents[kMicro];
+  if (lane < kMicro) ents[lane] = slot_ent[m * kMicro + lane];
+  __syncthreads();
+  int cnt = 0;
+  for (int q = 0; q < kMicro; ++q) cnt += ents[q] >= 0;
+  float* c = cent + m * d;
+  if (cnt == 0) {
+    for (int k = lane; k < d; k += 64) c[k] = 0.f;
+    if (lane == 0) rad[m] = -1.f;
+    return;
+  }
+  const float inv = 1.f / (float)cnt;
+  for (int k = lane; k < d; k += 64) {
+    float s = 0.f;
+    for (int q = 0; q < kMicro; ++q)
+      if (ents[q] >= 0) s += ld_elem(E, (int64_t)ents[q] * d + k, dtype);
+    c[k] = s * inv;
+  }
+  __syncthreads();   // centre visible to the whole wave (same block)
+  float rmax = 0.f;
+  for (int q = 0; q < kMicro; ++q) {
+    if (ents[q] < 0) continue;
+    float s = 0.f;
+    for (int k = lane; k < d; k += 64) {
+      const float x = ld_elem(E, (int64_t)ents[q] * d + k, dtype) - c[k];
+      s += (P == 2) ? x * x : fabsf(x);
+    }
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    rmax = fmaxf(rmax, (P == 2) ? sqrtf(s) : s);
+  }
+  if (lane == 0) rad[m] = rmax * (1.f + kBoundSlack) + 1e-30f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic 128 x 128 distance tile in float32 vector arithmetic (no MFMA): rows x_i (+ shift), columns y_j,
+// dist_p(x_i + shift, y_j) for p = 1 or 2, K staged through LDS in 16-dimension slices, 8 x 8 results
+// per thread.  Two epilogues:
+//   ASSIGN  first column within delta (= the group radius tau) of every row -> atomicMin on a packed
+//           (column position, distance bits) word
+//   BOUND   rows and columns are micro-tile centres; a micro-tile pair survives when
+//           dist - rho_row - rho_col <= delta (with slack), and then sets the bit of its join tile
+enum { kEpiAssign = 0, kEpiBound = 1 };
+
+struct TileDistArgs {
+  const void* X; int dtypeX; const int32_t* row_ids; const int32_t* n_rows_dev; int64_t n_rows;
+  const void* Y; int dtypeY; const int32_t* col_ids; const int32_t* n_cols_dev; int64_t n_cols;
+  const void* shift; int dtype_shift; int r0;     // optional vector added to every row: shift[(r0 + blockIdx.z) * d ...]
+  int d;
+  unsigned long long* best;                        // ASSIGN
+  const float* rad; float delta; uint32_t* bitmap; // BOUND
+  int nH, words_per_row, micro_per_bm, micro_per_bn;
+};
+
+template <int P, int EPI>
+__global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
+  constexpr int BM = 128, BN = 128, BK = 16;
+  __shared__ __attribute__((aligned(16))) float As[BK][BM];
+  __shared__ __attribute__((aligned(16))) float Bs[BK][BN];
+  __shared__ int32_t rid[BM], cid[BN];
+  const int tid = threadIdx.x;
+  const int64_t n_rows = a.n_rows_dev ? (int64_t)*a.n_rows_dev : a.n_rows;
+  const int64_t n_cols = a.n_cols_dev ? (int64_t)*a.n_cols_dev : a.n_cols;
+  const int64_t row0 = (int64_t)blockIdx.y * BM, col0 = (int64_t)blockIdx.x * BN;
+  if (row0 >= n_rows || col0 >= n_cols) return;
+  if (tid < BM) {
+    const int64_t r = row0 + tid;
+    rid[tid] = r < n_rows ? (a.row_ids ? a.row_ids[r] : (int32_t)r) : -1;
+  } else {
+    const int64_t c = col0 + (tid - BM);
+    cid[tid - BM] = c < n_cols ? (a.col_ids ? a.col_ids[c] : (int32_t)c) : -1;
+  }
+  __syncthreads();
+  const int d = a.d;
+  const int tx = tid & 15, ty = tid >> 4;
+  float acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+  const int srow = tid >> 1, sk0 = (tid & 1) * 8;
+  const int re = rid[srow], ce = cid[srow];
+  const int64_t xo = (int64_t)(re < 0 ? 0 : re) * d, yo = (int64_t)(ce < 0 ? 0 : ce) * d;
+  const int64_t so = (int64_t)(a.r0 + (int)blockIdx.z) * d;
+  for (int k0 = 0; k0 < d; k0 += BK) {
+    float va[8], vb[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int k = k0 + sk0 + q;
+      const bool in = k < d;
+      float x = in ? ld_elem(a.X, xo + k, a.dtypeX) : 0.f;
+      if (in && a.shift) x += ld_elem(a.shift, so + k, a.dtype_shift);
+      va[q] = x;
+      vb[q] = in ? ld_elem(a.Y, yo + k, a.dtypeY) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      As[sk0 + q][srow] = va[q];
+      Bs[sk0 + q][srow] = vb[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < BK; ++k) {
+      const float4 a0 = *(const float4*)(&As[k][ty * 4]);
+      const float4 a1 = *(const float4*)(&As[k][64 + ty * 4]);
+      const float4 b0 = *(const float4*)(&Bs[k][tx * 4]);
+      const float4 b1 = *(const float4*)(&Bs[k][64 + tx * 4]);
+      const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+      const float bv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float x = av[i] - bv[j];
+          acc[i][j] += (P == 2) ? x * x : fabsf(x);
+        }
+    }
+  }
+  // rows of this thread: (i >> 2) * 64 + ty * 4 + (i & 3); columns: (j >> 2) * 64 + tx * 4 + (j & 3)
+  if (EPI == kEpiAssign) {
+    // Among the columns (pivots) within tau of the row, the one with the LOWEST position wins, not the
+    // nearest: when a natural cluster received several pivots, all its rows then agree on one of them
+    // instead of splitting the cluster between them.
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int lr = (i >> 2) * 64 + ty * 4 + (i & 3);
+      unsigned long long bestv = ~0ull;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int lc = (j >> 2) * 64 + tx * 4 + (j & 3);
+        const float dist = (P == 2) ? sqrtf(acc[i][j]) : acc[i][j];
+        if (cid[lc] >= 0 && dist <= a.delta) {
+          const unsigned long long v =
+              ((unsigned long long)(uint32_t)(col0 + lc) << 32) | (unsigned long long)__float_as_uint(dist);
+          bestv = v < bestv ? v : bestv;
+        }
+      }
+      // the 16 threads that share a row are 16 consecutive lanes
+#pragma unroll
+      for (int off = 8; off > 0; off >>= 1) {
+        const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)(bestv & 0xffffffffull), off, 16);
+        const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(bestv >> 32), off, 16);
+        const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+        bestv = o < bestv ? o : bestv;
+      }
+      if (tx == 0 && rid[lr] >= 0 && bestv != ~0ull) atomicMin(&a.best[row0 + lr], bestv);
+    }
+  } else {
+    const int rl = (int)blockIdx.z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int lr = (i >> 2) * 64 + ty * 4 + (i & 3);
+      if (rid[lr] < 0) continue;
+      const float rr = a.rad[row0 + lr];
+      if (rr < 0.f) continue;                                  // empty micro-tile
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int lc = (j >> 2) * 64 + tx * 4 + (j & 3);
+        if (cid[lc] < 0) continue;
+        const float rc = a.rad[col0 + lc];
+        if (rc < 0.f) continue;
+        const float dist = (P == 2) ? sqrtf(acc[i][j]) : acc[i][j];
+        const float lb = dist * (1.f - kBoundSlack) - rr - rc;  // radii already carry their slack
+        if (lb <= a.delta * (1.f + kBoundSlack)) {
+          const int tH = (int)((row0 + lr) / a.micro_per_bm), tT = (int)((col0 + lc) / a.micro_per_bn);
+          atomicOr(&a.bitmap[((int64_t)rl * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
+        }
+      }
+    }
+  }
+}
+
+// One wave per (relation, head tile) row of the bitmap: count the surviving tail tiles, reserve a range
+// of the column list with one atomic, write the tile numbers in ascending order.
+__global__ __launch_bounds__(64) void k_rows_from_bitmap(const uint32_t* __restrict__ bitmap, int words_per_row,
+                                                         int64_t n_rows, uint32_t* __restrict__ row_start,
+                                                         uint32_t* __restrict__ row_count, uint32_t* __restrict__ cols,
+                                                         unsigned long long* __restrict__ total) {
+  const int64_t row = blockIdx.x;
+  if (row >= n_rows) return;
+  const int lane = threadIdx.x;
+  const uint32_t* w = bitmap + row * words_per_row;
+  uint32_t cnt = 0;
+  for (int i = lane; i < words_per_row; i += 64) cnt += __builtin_popcount(w[i]);
+  for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
+  unsigned long long base = 0;
+  if (lane == 0 && cnt) base = atomicAdd(total, (unsigned long long)cnt);
+  base = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(base >> 32), 0) << 32) |
+         (uint32_t)__shfl((int)(uint32_t)(base & 0xffffffffull), 0);
+  if (lane == 0) { row_start[row] = (uint32_t)base; row_count[row] = cnt; }
+  if (cnt == 0) return;
+  // ascending order: words in chunks of 64, prefix of popcounts across lanes
+  uint32_t run = 0;
+  for (int i0 = 0; i0 < words_per_row; i0 += 64) {
+    const int i = i0 + lane;
+    uint32_t word = i < words_per_row ? w[i] : 0u;
+    const uint32_t pc = __builtin_popcount(word);
+    uint32_t pre = pc;
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t o = __shfl_up(pre, off, 64);
+      if (lane >= off) pre += o;
+    }
+    uint32_t pos = run + pre - pc;
+    while (word) {
+      const int b = __builtin_ctz(word);
+      word &= word - 1;
+      cols[base + pos++] = (uint32_t)(i * 32 + b);
+    }
+    run += __shfl(pre, 63, 64);
+  }
+}
+
+}  // namespace kgc

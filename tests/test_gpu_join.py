@@ -52,10 +52,18 @@ def test_hand_case(p, delta, count):
     assert got["count"] == count == ref["count"]
 
 
+PRUNE_OFF, PRUNE_ON = 1, 2
+
+
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
 @pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13])
-def test_c1_l2_full_parity(tile_cfg):
+def test_c1_l2_full_parity(tile_cfg, prune):
+    if prune == PRUNE_ON and 1 <= tile_cfg <= 5:
+        pytest.skip("one-block-per-tile variants have no pruned mode")
     wl = workloads.generate("c1_tiny_l2")
-    got, ref, rep = _check(wl.E, wl.Rv, 2, wl.delta, tile_cfg=tile_cfg)
+    got, ref, rep = _check(wl.E, wl.Rv, 2, wl.delta, tile_cfg=tile_cfg, prune=prune)
+    if prune == PRUNE_ON:
+        assert got["stats"]["tiles_pruned"] > 0 and got["stats"]["groups"] > 0
     assert ref["count"] == 3640 and rep["boundary_band"] <= 40
     # the hit decision is taken in double on both sides, so even the boundary band agrees here
     assert rep["only_gpu_in_band"] == 0 and rep["only_oracle_in_band"] == 0
@@ -63,18 +71,20 @@ def test_c1_l2_full_parity(tile_cfg):
     assert st["triples_total"] == 2000 * 2000 * 8 and st["emitted"] == got["count"] and st["candidates"] >= got["count"]
 
 
-def test_c1_l1_full_parity():
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
+def test_c1_l1_full_parity(prune):
     wl = workloads.generate("c1_tiny_l2")
     h, r, t = workloads.sample_uniform_triples(wl, 200_000, 77)
     delta = float(np.float32(np.sort(oracle.dist_triples(wl.E, wl.Rv, 1, h, r, t))[40]))
-    got, ref, rep = _check(wl.E, wl.Rv, 1, delta)
+    got, ref, rep = _check(wl.E, wl.Rv, 1, delta, prune=prune)
     assert ref["count"] > 1000
 
 
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
 @pytest.mark.parametrize("p", [1, 2])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("N,R,d", [(300, 3, 37), (257, 2, 200), (129, 1, 7), (1, 1, 1), (700, 5, 122)])
-def test_ragged_shapes(p, dtype, N, R, d):
+def test_ragged_shapes(p, dtype, N, R, d, prune):
     g = np.random.default_rng(N * 1000 + d)
     cent = g.standard_normal((4, d))
     E = (cent[g.integers(0, 4, N)] + 0.1 * g.standard_normal((N, d))).astype(np.float32)
@@ -85,22 +95,25 @@ def test_ragged_shapes(p, dtype, N, R, d):
     n = min(20000, N * N * R)
     hh, rr, tt = g.integers(0, N, n), g.integers(0, R, n), g.integers(0, N, n)
     delta = float(np.float32(np.quantile(oracle.dist_triples(E, Rv, p, hh, rr, tt), 0.02)))
-    got, ref, rep = _check(E, Rv, p, delta, dtype=dtype)
+    got, ref, rep = _check(E, Rv, p, delta, dtype=dtype, prune=prune)
     assert ref["count"] > 0
 
 
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
 @pytest.mark.parametrize("p", [1, 2])
-def test_edge_cases(p):
+def test_edge_cases(p, prune):
     import paper_2307_12059_amd as kgc
     torch = _torch()
     wl = workloads.generate("c1_tiny_l2", N=400, R=3)
     E, Rv = wl.E, wl.Rv
     # negative threshold and empty inputs: valid, empty
-    assert _run(E, Rv, p, -1.0)["count"] == 0
-    assert _run(E[:0], Rv, p, 1.0)["count"] == 0
-    assert _run(E, Rv[:0], p, 1.0)["count"] == 0
+    assert _run(E, Rv, p, -1.0, prune=prune)["count"] == 0
+    assert _run(E[:0], Rv, p, 1.0, prune=prune)["count"] == 0
+    assert _run(E, Rv[:0], p, 1.0, prune=prune)["count"] == 0
+    # zero threshold: only exact coincidences (r = 0 gives the N self pairs)
+    assert _run(E, np.zeros_like(Rv[:1]), p, 0.0, prune=prune)["count"] == 400
     # infinite threshold: every triple, each once
-    got = _run(E[:70], Rv[:2], p, float("inf"), cap=70 * 70 * 2)
+    got = _run(E[:70], Rv[:2], p, float("inf"), cap=70 * 70 * 2, prune=prune)
     assert got["count"] == 70 * 70 * 2
     assert np.unique((got["r"].astype(np.int64) * 70 + got["h"]) * 70 + got["t"]).size == 70 * 70 * 2
     np.testing.assert_allclose(got["dist"], oracle.dist_triples(E[:70], Rv[:2], p, got["h"], got["r"], got["t"]),
@@ -108,12 +121,12 @@ def test_edge_cases(p):
     # overflow: true count reported, cap valid records, all of them real hits
     ref = oracle.join(E, Rv, p, 3.0 if p == 2 else 14.0)
     assert ref["count"] > 50
-    got = _run(E, Rv, p, 3.0 if p == 2 else 14.0, cap=17)
+    got = _run(E, Rv, p, 3.0 if p == 2 else 14.0, cap=17, prune=prune)
     assert got["code"] == kgc.KGC_OVERFLOW and got["count"] == ref["count"] and got["h"].size == 17
     refset = set(zip(ref["r"].tolist(), ref["h"].tolist(), ref["t"].tolist()))
     assert all(k in refset for k in zip(got["r"].tolist(), got["h"].tolist(), got["t"].tolist()))
     # cap == 0 with a NULL buffer only counts
-    j = kgc.Join()
+    j = kgc.Join(prune=prune)
     rc, cnt = kgc.kgc_join(j.handle, _dev(E).data_ptr(), 400, 32, _dev(Rv).data_ptr(), 3, p,
                            3.0 if p == 2 else 14.0, 0, 0)
     assert rc == kgc.KGC_OVERFLOW and cnt == ref["count"]
@@ -131,9 +144,10 @@ def test_edge_cases(p):
     j.close()
 
 
-def test_zero_relation_symmetry():
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
+def test_zero_relation_symmetry(prune):
     wl = workloads.generate("c1_tiny_l2", N=500, R=1)
-    got = _run(wl.E, np.zeros_like(wl.Rv), 2, 0.8)
+    got = _run(wl.E, np.zeros_like(wl.Rv), 2, 0.8, prune=prune)
     S = set(zip(got["h"].tolist(), got["t"].tolist()))
     assert all((t, h) in S for (h, t) in S) and all((i, i) in S for i in range(500))
 
@@ -141,8 +155,8 @@ def test_zero_relation_symmetry():
 def test_repeatable_and_tile_independent():
     wl = workloads.generate("c1_tiny_l2", N=1500, R=4)
     ref = None
-    for tile_cfg in (1, 1, 2, 6, 8, 10, 11, 13):
-        got = _run(wl.E, wl.Rv, 2, 0.7, tile_cfg=tile_cfg)
+    for tile_cfg, prune in ((1, 1), (1, 1), (2, 1), (6, 1), (8, 1), (10, 1), (11, 1), (13, 1), (9, 2), (9, 2), (10, 2), (0, 2)):
+        got = _run(wl.E, wl.Rv, 2, 0.7, tile_cfg=tile_cfg, prune=prune)
         key = np.sort((got["r"].astype(np.int64) * 1500 + got["h"]) * 1500 + got["t"])
         assert ref is None or np.array_equal(ref, key)
         ref = key
