@@ -39,6 +39,7 @@ struct kgc_handle {
   DevBuf slot_ent, opB, opA, normsB, normsA, counters, params;
   // pruning scratch
   DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
+  DevBuf active_rows, cnorm, gram, relu, reln;
   GroupState* host_gstate = nullptr;           // pinned
   DevCounters* host_counters = nullptr;        // pinned
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -169,7 +170,8 @@ void kgc_destroy(kgc_handle* h) {
   release(h->slot_ent); release(h->opB); release(h->opA); release(h->normsB); release(h->normsA);
   release(h->counters); release(h->params);
   for (DevBuf* b : {&h->gstate, &h->unc_a, &h->unc_b, &h->group_of, &h->piv_ent, &h->best, &h->gsize, &h->goff, &h->gfill,
-                    &h->cent, &h->rad, &h->bitmap, &h->row_start, &h->row_count, &h->cols})
+                    &h->cent, &h->rad, &h->bitmap, &h->row_start, &h->row_count, &h->cols, &h->active_rows, &h->cnorm,
+                    &h->gram, &h->relu, &h->reln})
     release(*b);
   if (h->host_gstate) (void)hipHostFree(h->host_gstate);
   if (h->host_counters) (void)hipHostFree(h->host_counters);
@@ -207,14 +209,14 @@ int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* R
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
   if (nB) {
     k_stage_operands<false><<<g, 256, stage_lds, st>>>(E, Rvecs, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Nslots, KS,
-                                               (uint16_t*)hd->opB.p, (float*)hd->normsB.p, nullptr, nullptr, 0, 1);
+                                               (uint16_t*)hd->opB.p, (float*)hd->normsB.p, nullptr, nullptr, nullptr, 0, kStageRows);
     k_scatter_norms<<<grid_for(Nslots, 256), 256, 0, st>>>((const float*)hd->normsB.p, (const int32_t*)hd->slot_ent.p,
                                                            Nslots, N, 1, nB);
   }
   if (nA) {
     for (int r = 0; r < R; ++r) {
       k_stage_operands<true><<<g, 256, stage_lds, st>>>(E, Rvecs, dtype, d, r, 1, (const int32_t*)hd->slot_ent.p, Nslots, KS,
-                                                (uint16_t*)hd->opA.p, (float*)hd->normsB.p, nullptr, nullptr, 0, 1);
+                                                (uint16_t*)hd->opA.p, (float*)hd->normsB.p, nullptr, nullptr, nullptr, 0, kStageRows);
       k_scatter_norms<<<grid_for(Nslots, 256), 256, 0, st>>>((const float*)hd->normsB.p,
                                                              (const int32_t*)hd->slot_ent.p, Nslots, N, 1,
                                                              nA + (int64_t)r * N);
@@ -346,7 +348,11 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         (rc = ensure(hd, hd->bitmap, (size_t)RBmax * nH * words_per_row * 4)) ||
         (rc = ensure(hd, hd->row_start, (size_t)RBmax * nH * 4)) ||
         (rc = ensure(hd, hd->row_count, (size_t)RBmax * nH * 4)) ||
-        (rc = ensure(hd, hd->cols, (size_t)RBmax * tiles_per_rel * 4)))
+        (rc = ensure(hd, hd->cols, (size_t)RBmax * tiles_per_rel * 4)) ||
+        (rc = ensure(hd, hd->active_rows, (size_t)RBmax * nH * 4)) || (rc = ensure(hd, hd->cnorm, n_micro * 4)))
+      return rc;
+    if (p == 2 && ((rc = ensure(hd, hd->gram, (size_t)n_micro * n_micro * 4)) ||
+                   (rc = ensure(hd, hd->relu, (size_t)RBmax * n_micro * 4)) || (rc = ensure(hd, hd->reln, RBmax * 4))))
       return rc;
   }
   const int nbatch = (int)((R + RBmax - 1) / RBmax);
@@ -363,13 +369,24 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
 
   KGC_HIP(hd, hipEventRecord(hd->ev[3], st));     // end of grouping
   if (prune) {
-    if (p == 2) k_micro_summary<2><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p, (float*)hd->rad.p);
-    else k_micro_summary<1><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p, (float*)hd->rad.p);
+    if (p == 2) {
+      k_micro_summary<2><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p,
+                                                            (float*)hd->rad.p, (float*)hd->cnorm.p);
+      // squared distances between all micro-tile centres, once: the part of the bound that no relation changes
+      TileDistArgs ta{};
+      ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.n_rows = n_micro; ta.Y = hd->cent.p; ta.dtypeY = KGC_F32;
+      ta.n_cols = n_micro; ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.d = d; ta.matrix = (float*)hd->gram.p;
+      const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), 1);
+      k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
+    } else {
+      k_micro_summary<1><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p,
+                                                            (float*)hd->rad.p, (float*)hd->cnorm.p);
+    }
   }
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
   if (p == 2) {
     k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
-        E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b, nullptr, 0, 1);
+        E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b, nullptr, nullptr, 0, kStageRows);
   } else {
     k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(E, N, d, dtype, cnt->max_a);
     k_row_l1_max<<<grid_for((int64_t)R * 32, 256), 256, 0, st>>>(Rvecs, R, d, dtype, cnt->max_b);
@@ -383,41 +400,60 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
     const uint32_t* row_start = nullptr;
     const uint32_t* row_count = nullptr;
     const uint32_t* cols = nullptr;
+    const uint32_t* active_rows = nullptr;
+    const unsigned int* n_active = nullptr;
     if (prune) {
       // a2: bound test on micro-tile pairs -> bitmap of join tiles -> per-row lists of surviving tail tiles
       const int64_t bm_words = (int64_t)RB * nH * words_per_row;
       k_fill_u32<<<grid_for(bm_words, 256), 256, 0, st>>>((uint32_t*)hd->bitmap.p, bm_words, 0u);
-      TileDistArgs ta{};
-      ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.row_ids = nullptr; ta.n_rows_dev = nullptr; ta.n_rows = n_micro;
-      ta.Y = hd->cent.p; ta.dtypeY = KGC_F32; ta.col_ids = nullptr; ta.n_cols_dev = nullptr; ta.n_cols = n_micro;
-      ta.shift = Rvecs; ta.dtype_shift = dtype; ta.r0 = (int)r0; ta.d = d;
-      ta.rad = (const float*)hd->rad.p; ta.delta = delta; ta.bitmap = (uint32_t*)hd->bitmap.p;
-      ta.nH = nH; ta.words_per_row = words_per_row; ta.micro_per_bm = BM / kMicro; ta.micro_per_bn = BN / kMicro;
-      const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), (unsigned)RB);
-      if (delta >= 0.f) {
-        if (p == 2) k_tile_dist<2, kEpiBound><<<g, 256, 0, st>>>(ta);
-        else k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
+      if (delta >= 0.f && p == 2) {
+        k_rel_centre_dot<<<grid_for((n_micro + 1) * RB * 64, 256), 256, 0, st>>>(
+            Rvecs, dtype, d, (int)r0, RB, (const float*)hd->cent.p, n_micro, (float*)hd->relu.p, (float*)hd->reln.p);
+        BoundL2Args ba;
+        ba.D = (const float*)hd->gram.p; ba.u = (const float*)hd->relu.p; ba.rn = (const float*)hd->reln.p;
+        ba.rad = (const float*)hd->rad.p; ba.cnorm = (const float*)hd->cnorm.p; ba.n_micro = n_micro; ba.RB = RB;
+        ba.d = d; ba.delta = delta; ba.bitmap = (uint32_t*)hd->bitmap.p; ba.nH = nH; ba.words_per_row = words_per_row;
+        ba.micro_per_bm = BM / kMicro; ba.micro_per_bn = BN / kMicro;
+        const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)n_micro, (unsigned)((RB + kRelChunk - 1) / kRelChunk));
+        k_bound_l2<<<g, 256, 0, st>>>(ba);
+      } else if (delta >= 0.f) {
+        TileDistArgs ta{};
+        ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.row_ids = nullptr; ta.n_rows_dev = nullptr; ta.n_rows = n_micro;
+        ta.Y = hd->cent.p; ta.dtypeY = KGC_F32; ta.col_ids = nullptr; ta.n_cols_dev = nullptr; ta.n_cols = n_micro;
+        ta.shift = Rvecs; ta.dtype_shift = dtype; ta.r0 = (int)r0; ta.d = d;
+        ta.rad = (const float*)hd->rad.p; ta.delta = delta; ta.bitmap = (uint32_t*)hd->bitmap.p;
+        ta.nH = nH; ta.words_per_row = words_per_row; ta.micro_per_bm = BM / kMicro; ta.micro_per_bn = BN / kMicro;
+        const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), (unsigned)RB);
+        k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
       }
-      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 2, 0u);
+      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 4, 0u);      // cursor and n_active
       k_rows_from_bitmap<<<(unsigned)((int64_t)RB * nH), 64, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
-          (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor);
+          (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p,
+          &cnt->n_active);
       k_add_u64<<<1, 64, 0, st>>>(&cnt->tiles, &cnt->tile_cursor);
       row_start = (const uint32_t*)hd->row_start.p;
       row_count = (const uint32_t*)hd->row_count.p;
       cols = (const uint32_t*)hd->cols.p;
+      active_rows = (const uint32_t*)hd->active_rows.p;
+      n_active = &cnt->n_active;
     }
+    // pruned launches stride a fixed grid over the active rows (their number is only known on the device)
+    const unsigned row_grid = (unsigned)std::min<int64_t>((int64_t)RB * nH, 4096);
     if (p == 2) {
-      k_stage_operands<true><<<grid_for((int64_t)RB * (Nslots / kStageRows), 1), 256, stage_lds, st>>>(
+      const int stage_grid = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 16384)
+                                   : grid_for((int64_t)RB * (Nslots / kStageRows), 1);
+      k_stage_operands<true><<<stage_grid, 256, stage_lds, st>>>(
           E, Rvecs, dtype, d, (int)r0, RB, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p,
-          cnt->max_a, row_count, nH, BM);
+          cnt->max_a, active_rows, n_active, nH, BM);
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
       if (tc.stream_kernel) {
         JoinStreamArgs sa;
         sa.A = (const uint16_t*)hd->opA.p; sa.B = (const uint16_t*)hd->opB.p; sa.prm = prm; sa.Nslots = Nslots;
         sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = (int)r0; sa.RB = RB;
-        sa.row_start = row_start; sa.row_count = row_count; sa.cols = cols; sa.cx = cx;
+        sa.row_start = row_start; sa.row_count = row_count; sa.cols = cols; sa.active_rows = active_rows;
+        sa.n_active = n_active; sa.cx = cx;
         // Dense: tail tiles are cut into ranges of about kL2RangeBytes of staged B rows, so that the blocks
         // running at the same time (consecutive head tiles of one range) keep their B rows in the 4 MiB L2 of
         // their XCD; small problems are cut further to fill the chip.  Pruned: one block per row.
@@ -435,8 +471,8 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
           KGC_HIP(hd, hipFuncSetAttribute((const void*)tc.stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                           (int)dyn_lds));
         }
-        hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB), dim3(tc.threads), dyn_lds,
-                           st, sa);
+        const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB);
+        hipLaunchKernelGGL(tc.stream_kernel, grid, dim3(tc.threads), dyn_lds, st, sa);
       } else {
         JoinArgs ja;
         ja.A = (const uint16_t*)hd->opA.p; ja.B = (const uint16_t*)hd->opB.p; ja.prm = prm;
@@ -447,15 +483,17 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
     } else {
       JoinL1Args la;
       la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = (int)r0; la.RB = RB;
-      la.row_start = row_start; la.row_count = row_count; la.cols = cols; la.cx = cx;
+      la.row_start = row_start; la.row_count = row_count; la.cols = cols; la.active_rows = active_rows;
+      la.n_active = n_active; la.cx = cx;
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
-      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)(prune ? 1 : nT), (unsigned)nH, (unsigned)RB), dim3(256), 0, st, la);
+      hipLaunchKernelGGL(k_join_l1, prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(256), 0,
+                         st, la);
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     }
     hd->stats.join_launches++;
   }
   KGC_HIP(hd, hipGetLastError());
-  KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 40, hipMemcpyDeviceToHost, st));
+  KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 48, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
   KGC_HIP(hd, hipStreamSynchronize(st));
 

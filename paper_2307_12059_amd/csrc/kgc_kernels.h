@@ -36,7 +36,8 @@ struct DevCounters {
   unsigned long long hits;        // true number of qualifying triples
   unsigned long long candidates;  // triples re-scored in double
   unsigned long long tile_cursor; // next free entry of the surviving-tile list (per relation batch)
-  unsigned long long tile_pad;    // (kept zero; cleared together with the cursor)
+  unsigned int n_active;          // rows (relation, head tile) of the batch that still have tail tiles
+  unsigned int pad0;
   unsigned long long tiles;       // surviving tiles over all batches
   unsigned int max_a[1024];       // running maxima of ||bf16(h + r)||^2 (L2) or ||e||_1 (L1), float bits, spread over slots
   unsigned int max_b[1024];       // running maxima of ||bf16(t)||^2 (L2) or ||r||_1 (L1)
@@ -75,20 +76,30 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
                                                         const int32_t* __restrict__ slot_ent, int64_t Nslots, int KS,
                                                         uint16_t* __restrict__ out, float* __restrict__ norms,
                                                         unsigned int* __restrict__ max_slots,
-                                                        const uint32_t* __restrict__ row_count, int nH, int bm) {
+                                                        const uint32_t* __restrict__ active_rows,
+                                                        const unsigned int* __restrict__ n_active, int nH, int bm) {
   extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [kStageRows][KS * 32 + 8]
   __shared__ int32_t ents[kStageRows];
   __shared__ float wmax[4];
   const int tid = threadIdx.x;
   const int W = KS * kSliceK + 8;
+  // dense joins stage every row group of every relation of the batch; pruned joins only the head tiles
+  // (rows of the active list) that still have tail tiles to meet
   const int64_t groups_per_rel = Nslots / kStageRows;
-  const int64_t ngroups = groups_per_rel * RB;
+  const int groups_per_tile = bm / kStageRows;
+  const int64_t ngroups = active_rows ? (int64_t)*n_active * groups_per_tile : groups_per_rel * RB;
   float vmax = 0.f;
   for (int64_t g = blockIdx.x; g < ngroups; g += gridDim.x) {
-    const int rl = (int)(g / groups_per_rel);
-    const int64_t slot0 = (g - (int64_t)rl * groups_per_rel) * kStageRows;
-    // pruned joins stage only the head tiles that still have tail tiles to meet
-    if (row_count && row_count[(int64_t)rl * nH + slot0 / bm] == 0) continue;
+    int rl;
+    int64_t slot0;
+    if (active_rows) {
+      const int64_t row = (int64_t)active_rows[g / groups_per_tile];
+      rl = (int)(row / nH);
+      slot0 = (row - (int64_t)rl * nH) * bm + (g % groups_per_tile) * kStageRows;
+    } else {
+      rl = (int)(g / groups_per_rel);
+      slot0 = (g - (int64_t)rl * groups_per_rel) * kStageRows;
+    }
     __syncthreads();                                   // previous group fully written out
     if (tid < kStageRows) ents[tid] = slot_ent[slot0 + tid];
     __syncthreads();
@@ -387,6 +398,8 @@ struct JoinStreamArgs {
   const uint32_t* row_start; // NULL: dense.  Else row = r_local * nH + head tile owns cols[row_start[row] .. + row_count[row])
   const uint32_t* row_count;
   const uint32_t* cols;      // surviving tail tile numbers, ascending within a row
+  const uint32_t* active_rows;   // pruned mode: the rows with row_count > 0 ...
+  const unsigned int* n_active;  // ... and how many there are; the grid strides over them
   RecheckCtx cx;
 };
 
@@ -405,13 +418,17 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
+  // pruned mode: the grid strides over the rows (relation, head tile) that still have tail tiles
+  for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
   if (a.row_start) {
-    tH = (int)blockIdx.x; rl = (int)blockIdx.z;
-    const int64_t row = (int64_t)rl * a.nH + tH;
+    if (row_i >= *a.n_active) break;
+    const int64_t row = (int64_t)a.active_rows[row_i];
+    rl = (int)(row / a.nH); tH = (int)(row - (int64_t)rl * a.nH);
     t_begin = (int)a.row_start[row]; t_end = t_begin + (int)a.row_count[row];
     cols = a.cols;
+    __syncthreads();                    // the previous row is done with the LDS buffers
   } else {
     // grid = (head tiles, tail-tile ranges, relations): blocks that run together share a tail-tile range
     tH = (int)blockIdx.x; rl = (int)blockIdx.z;
@@ -419,7 +436,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
     t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
   }
   const int ntiles = t_end - t_begin;
-  if (ntiles <= 0) return;
+  if (ntiles <= 0) break;
   const int KS = a.KS;
   const int64_t slice_bytes = a.Nslots * kSliceK * 2;
 
@@ -575,6 +592,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 #undef KGC_GLOAD
 #undef KGC_SSTORE
 #undef KGC_MFMA_STEP
+  if (!a.row_start) break;
+  }   // rows
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -601,20 +620,23 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
+  for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
   if (a.row_start) {
-    tH = (int)blockIdx.x; rl = (int)blockIdx.z;
-    const int64_t row = (int64_t)rl * a.nH + tH;
+    if (row_i >= *a.n_active) break;
+    const int64_t row = (int64_t)a.active_rows[row_i];
+    rl = (int)(row / a.nH); tH = (int)(row - (int64_t)rl * a.nH);
     t_begin = (int)a.row_start[row]; t_end = t_begin + (int)a.row_count[row];
     cols = a.cols;
+    __syncthreads();                    // the previous row is done with the LDS buffers
   } else {
     tH = (int)blockIdx.x; rl = (int)blockIdx.z;
     t_begin = (int)(((int64_t)a.nT * blockIdx.y) / gridDim.y);
     t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
   }
   const int ntiles = t_end - t_begin;
-  if (ntiles <= 0) return;
+  if (ntiles <= 0) break;
   const int64_t slice_bytes = a.Nslots * kSliceK * 2;
   const uint32_t voff = (uint32_t)tid * 16u;
   const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * (kSliceK * 2);
@@ -770,6 +792,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
 #undef KGC_SSTORE
 #undef KGC_MFMA_STEP
 #undef KGC_COMPUTE
+  if (!a.row_start) break;
+  }   // rows
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -781,6 +805,8 @@ struct JoinL1Args {
   const uint32_t* row_start;   // NULL: dense (one block per tile, grid = (nT, nH, RB)); else see JoinStreamArgs
   const uint32_t* row_count;
   const uint32_t* cols;
+  const uint32_t* active_rows;
+  const unsigned int* n_active;
   RecheckCtx cx;
 };
 
@@ -798,17 +824,20 @@ __global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
   __shared__ int32_t hent[BM], tent[BN];
 
   const int tid = threadIdx.x, wave = tid >> 6;
+  for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
   if (a.row_start) {
-    tH = (int)blockIdx.y; rl = (int)blockIdx.z;
-    const int64_t row = (int64_t)rl * a.nH + tH;
+    if (row_i >= *a.n_active) break;
+    const int64_t row = (int64_t)a.active_rows[row_i];
+    rl = (int)(row / a.nH); tH = (int)(row - (int64_t)rl * a.nH);
     t_begin = (int)a.row_start[row]; t_end = t_begin + (int)a.row_count[row];
     cols = a.cols;
+    __syncthreads();                      // the previous row is done with hent
   } else {
     t_begin = (int)blockIdx.x; t_end = t_begin + 1; tH = (int)blockIdx.y; rl = (int)blockIdx.z;
   }
-  if (t_end <= t_begin) return;
+  if (t_end <= t_begin) break;
   const int r = a.r0 + rl;
   const int d = a.cx.d, dtype = a.cx.dtype;
   const float thr = a.prm->thr;
@@ -878,6 +907,8 @@ __global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
       tslot = tbase + (j >> 2) * 64 + sx * 4 + (j & 3);
     });
   }
+  if (!a.row_start) break;
+  }   // rows
 }
 
 }  // namespace kgc

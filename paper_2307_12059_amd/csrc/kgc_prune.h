@@ -118,7 +118,8 @@ __global__ void k_scatter_slots(GroupState* gs, const int32_t* group_of, const i
 template <int P>
 __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E, int dtype, int d,
                                                       const int32_t* __restrict__ slot_ent, int64_t n_micro,
-                                                      float* __restrict__ cent, float* __restrict__ rad) {
+                                                      float* __restrict__ cent, float* __restrict__ rad,
+                                                      float* __restrict__ cnorm) {
   const int64_t m = blockIdx.x;
   if (m >= n_micro) return;
   const int lane = threadIdx.x;
@@ -130,16 +131,20 @@ __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E
   float* c = cent + m * d;
   if (cnt == 0) {
     for (int k = lane; k < d; k += 64) c[k] = 0.f;
-    if (lane == 0) rad[m] = -1.f;
+    if (lane == 0) { rad[m] = -1.f; cnorm[m] = 0.f; }
     return;
   }
   const float inv = 1.f / (float)cnt;
+  float c2 = 0.f;
   for (int k = lane; k < d; k += 64) {
     float s = 0.f;
     for (int q = 0; q < kMicro; ++q)
       if (ents[q] >= 0) s += ld_elem(E, (int64_t)ents[q] * d + k, dtype);
     c[k] = s * inv;
+    c2 += (s * inv) * (s * inv);
   }
+  for (int off = 32; off > 0; off >>= 1) c2 += __shfl_xor(c2, off, 64);
+  if (lane == 0) cnorm[m] = sqrtf(c2) * (1.f + kBoundSlack);
   __syncthreads();   // centre visible to the whole wave (same block)
   float rmax = 0.f;
   for (int q = 0; q < kMicro; ++q) {
@@ -161,9 +166,10 @@ __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E
 // per thread.  Two epilogues:
 //   ASSIGN  first column within delta (= the group radius tau) of every row -> atomicMin on a packed
 //           (column position, distance bits) word
+//   MATRIX  the p-th power of every distance is written to a row-major n_rows x n_cols matrix
 //   BOUND   rows and columns are micro-tile centres; a micro-tile pair survives when
 //           dist - rho_row - rho_col <= delta (with slack), and then sets the bit of its join tile
-enum { kEpiAssign = 0, kEpiBound = 1 };
+enum { kEpiAssign = 0, kEpiBound = 1, kEpiMatrix = 2 };
 
 struct TileDistArgs {
   const void* X; int dtypeX; const int32_t* row_ids; const int32_t* n_rows_dev; int64_t n_rows;
@@ -171,6 +177,7 @@ struct TileDistArgs {
   const void* shift; int dtype_shift; int r0;     // optional vector added to every row: shift[(r0 + blockIdx.z) * d ...]
   int d;
   unsigned long long* best;                        // ASSIGN
+  float* matrix;                                   // MATRIX
   const float* rad; float delta; uint32_t* bitmap; // BOUND
   int nH, words_per_row, micro_per_bm, micro_per_bn;
 };
@@ -269,6 +276,20 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
       }
       if (tx == 0 && rid[lr] >= 0 && bestv != ~0ull) atomicMin(&a.best[row0 + lr], bestv);
     }
+  } else if (EPI == kEpiMatrix) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int lr = (i >> 2) * 64 + ty * 4 + (i & 3);
+      if (rid[lr] < 0) continue;
+#pragma unroll
+      for (int jg = 0; jg < 2; ++jg) {
+        const int lc = jg * 64 + tx * 4;
+        float* o = a.matrix + (row0 + lr) * n_cols + col0 + lc;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (cid[lc + j] >= 0) o[j] = acc[i][jg * 4 + j];
+      }
+    }
   } else {
     const int rl = (int)blockIdx.z;
 #pragma unroll
@@ -294,12 +315,73 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
   }
 }
 
+// L2 only.  u[rl][m] = r . c_m and rn[rl] = ||r||^2 for the relations of a batch: one wave per (rl, m).
+__global__ __launch_bounds__(256) void k_rel_centre_dot(const void* __restrict__ Rv, int dtype, int d, int r0, int RB,
+                                                        const float* __restrict__ cent, int64_t n_micro,
+                                                        float* __restrict__ u, float* __restrict__ rn) {
+  const int lane = threadIdx.x & 63;
+  const int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int64_t per_rel = n_micro + 1;                       // the extra item computes ||r||^2
+  if (w >= per_rel * RB) return;
+  const int rl = (int)(w / per_rel);
+  const int64_t m = w - (int64_t)rl * per_rel;
+  const int64_t ro = (int64_t)(r0 + rl) * d;
+  float s = 0.f;
+  if (m == n_micro) {
+    for (int k = lane; k < d; k += 64) { const float x = ld_elem(Rv, ro + k, dtype); s += x * x; }
+  } else {
+    const float* c = cent + m * d;
+    for (int k = lane; k < d; k += 64) s += ld_elem(Rv, ro + k, dtype) * c[k];
+  }
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (lane == 0) {
+    if (m == n_micro) rn[rl] = s; else u[(int64_t)rl * n_micro + m] = s;
+  }
+}
+
+// L2 only.  The squared centre distance of a micro-tile pair under relation r expands into parts that do
+// not need a d-dimensional loop per (r, H, T):
+//     ||c_H + r - c_T||^2 = ||c_H - c_T||^2 + 2 (r.c_H - r.c_T) + ||r||^2 = D[H][T] + 2 (u[r][H] - u[r][T]) + rn[r]
+// (the same observation that makes distB independent of r in Section 5.2, applied to the bound).  One thread
+// tests one (H, T) pair against kRelChunk relations.  The float32 cancellation error of the sum is bounded by
+// err = 2 (d + 8) 2^-24 ||r|| (||c_H|| + ||c_T||) + 2^-20 D and added on the keeping side.
+constexpr int kRelChunk = 16;
+struct BoundL2Args {
+  const float* D; const float* u; const float* rn; const float* rad; const float* cnorm;
+  int64_t n_micro; int RB; int d; float delta;
+  uint32_t* bitmap; int nH, words_per_row, micro_per_bm, micro_per_bn;
+};
+__global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
+  const int64_t mT = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t mH = blockIdx.y;
+  if (mT >= a.n_micro) return;
+  const float rH = a.rad[mH], rT = a.rad[mT];
+  if (rH < 0.f || rT < 0.f) return;                          // empty micro-tile
+  const float D = a.D[mH * a.n_micro + mT];
+  const float reach = a.delta * (1.f + kBoundSlack) + rH + rT;
+  const float reach2 = reach * reach * (1.f + kBoundSlack);
+  const float cs = a.cnorm[mH] + a.cnorm[mT];
+  const float eD = D * 9.6e-7f;
+  const float ek = 2.f * (float)(a.d + 8) * 6e-8f * cs;
+  const int tH = (int)(mH / a.micro_per_bm), tT = (int)(mT / a.micro_per_bn);
+  const int rl0 = (int)blockIdx.z * kRelChunk;
+  const int rl1 = rl0 + kRelChunk < a.RB ? rl0 + kRelChunk : a.RB;
+  for (int rl = rl0; rl < rl1; ++rl) {
+    const float rn = a.rn[rl];
+    const float dist2 = D + 2.f * (a.u[(int64_t)rl * a.n_micro + mH] - a.u[(int64_t)rl * a.n_micro + mT]) + rn;
+    if (dist2 <= reach2 + eD + ek * sqrtf(rn))
+      atomicOr(&a.bitmap[((int64_t)rl * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
+  }
+}
+
 // One wave per (relation, head tile) row of the bitmap: count the surviving tail tiles, reserve a range
 // of the column list with one atomic, write the tile numbers in ascending order.
 __global__ __launch_bounds__(64) void k_rows_from_bitmap(const uint32_t* __restrict__ bitmap, int words_per_row,
                                                          int64_t n_rows, uint32_t* __restrict__ row_start,
                                                          uint32_t* __restrict__ row_count, uint32_t* __restrict__ cols,
-                                                         unsigned long long* __restrict__ total) {
+                                                         unsigned long long* __restrict__ total,
+                                                         uint32_t* __restrict__ active_rows,
+                                                         unsigned int* __restrict__ n_active) {
   const int64_t row = blockIdx.x;
   if (row >= n_rows) return;
   const int lane = threadIdx.x;
@@ -311,7 +393,11 @@ __global__ __launch_bounds__(64) void k_rows_from_bitmap(const uint32_t* __restr
   if (lane == 0 && cnt) base = atomicAdd(total, (unsigned long long)cnt);
   base = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(base >> 32), 0) << 32) |
          (uint32_t)__shfl((int)(uint32_t)(base & 0xffffffffull), 0);
-  if (lane == 0) { row_start[row] = (uint32_t)base; row_count[row] = cnt; }
+  if (lane == 0) {
+    row_start[row] = (uint32_t)base;
+    row_count[row] = cnt;
+    if (cnt) active_rows[atomicAdd(n_active, 1u)] = (uint32_t)row;    // rows that still have work, in any order
+  }
   if (cnt == 0) return;
   // ascending order: words in chunks of 64, prefix of popcounts across lanes
   uint32_t run = 0;
