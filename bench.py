@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--also-dense", type=int, default=3, help="extra dense (prune off) steps reported beside a pruned run")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="only run a plain device copy of this many MiB (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -70,6 +72,15 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.calibrate_copy > 0:
+        n = args.calibrate_copy * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_MiB": args.calibrate_copy, "bytes_read": n * 4, "bytes_written": n * 4, "copies": 3}))
+        return
     wl = workloads.generate(args.workload)
     spec = wl.spec
     N, R, d, p = spec.N, spec.R, spec.d, spec.p
@@ -109,7 +120,9 @@ def main():
                     "peak": PEAK_VALU_TLANEOPS, "unit": "Tlane-op/s"}
         roof["frac"] = roof["achieved"] / roof["peak"]
         roof["traffic"] = None
-        roof["kernel"] = "k_join_l2_stream" if p == 2 else "k_join_l1"
+        v = st["join_variant"]
+        roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_ares" if v >= 11 else "k_join_l2_stream" if v >= 6 else "k_join_l2")
+        roof["tile_cfg"] = v
         roof["launches_per_step"] = launches
         roof["avg_launch_ms"] = ms_join / launches
         return {"ms_per_step": dt * 1e3 / steps, "count": res["count"], "code": res["code"], "stats": st,

@@ -58,7 +58,8 @@ typedef struct {
     int64_t workspace_bytes;  /* cap on scratch held for staged operands; 0 = 16 GiB.  Larger joins run in relation batches */
     void*   stream;           /* hipStream_t to enqueue on; NULL = the default stream */
     float   group_radius;     /* pruning only: radius of entity groups as a multiple of delta; 0 = 2.0 */
-    int32_t reserved[5];      /* must be zero */
+    int32_t range_kib;        /* dense L2 join: KiB of staged tail rows one block walks (L2 blocking); 0 = automatic */
+    int32_t reserved[4];      /* must be zero */
 } kgc_config;
 
 /* Counters and timings of the last kgc_join on a handle. */
@@ -79,6 +80,8 @@ typedef struct {
     int32_t  tile_m, tile_n;    /* tile shape used (heads x tails) */
     int32_t  k_padded;          /* contraction length after appending the norm columns and padding (L2) */
     int32_t  relation_batches;
+    int32_t  join_variant;      /* which join kernel ran: 0 = L1 (VALU); for L2 the tile_cfg number that was used */
+    int32_t  reserved;
 } kgc_stats;
 
 /* Create a handle.  cfg may be NULL (defaults).  Returns KGC_OK and stores the handle in *out (host),

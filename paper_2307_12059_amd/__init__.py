@@ -33,7 +33,7 @@ class kgc_triple(ctypes.Structure):
 class kgc_config(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("max_d", ctypes.c_int32), ("prune", ctypes.c_int32),
                 ("tile_cfg", ctypes.c_int32), ("workspace_bytes", ctypes.c_int64), ("stream", ctypes.c_void_p),
-                ("group_radius", ctypes.c_float), ("reserved", ctypes.c_int32 * 5)]
+                ("group_radius", ctypes.c_float), ("range_kib", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
 
 
 class kgc_stats(ctypes.Structure):
@@ -43,7 +43,8 @@ class kgc_stats(ctypes.Structure):
                 ("emitted", ctypes.c_uint64), ("join_launches", ctypes.c_uint64), ("groups", ctypes.c_uint64),
                 ("ms_total", ctypes.c_float), ("ms_precompute", ctypes.c_float), ("ms_prune", ctypes.c_float),
                 ("ms_join", ctypes.c_float), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
-                ("k_padded", ctypes.c_int32), ("relation_batches", ctypes.c_int32)]
+                ("k_padded", ctypes.c_int32), ("relation_batches", ctypes.c_int32), ("join_variant", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
     def as_dict(self) -> dict:
         return {name: getattr(self, name) for name, _ in self._fields_}
@@ -136,7 +137,7 @@ class Join:
     """
 
     def __init__(self, dtype: str = "f32", prune: int = KGC_PRUNE_AUTO, tile_cfg: int = 0, max_d: int = 0,
-                 workspace_bytes: int = 0, group_radius: float = 0.0):
+                 workspace_bytes: int = 0, group_radius: float = 0.0, range_kib: int = 0):
         import torch
 
         if not torch.cuda.is_available():
@@ -148,6 +149,7 @@ class Join:
         cfg.max_d = max_d
         cfg.workspace_bytes = workspace_bytes
         cfg.group_radius = group_radius
+        cfg.range_kib = range_kib
         cfg.stream = torch.cuda.current_stream().cuda_stream
         rc, h = kgc_create(cfg)
         if rc != KGC_OK:

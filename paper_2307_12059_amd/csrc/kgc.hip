@@ -20,6 +20,7 @@ constexpr int kMaxD = 960;                      // keeps kernel 1's LDS tile und
 constexpr int64_t kSlotAlign = 256;            // rows are padded to a multiple of the largest tile
 constexpr int64_t kDefaultWorkspace = 16ll << 30;
 constexpr int64_t kL2RangeBytes = 1ll << 20;
+constexpr int64_t kL2RangeBytesResident = 3ll << 20;   // head-resident blocks leave the whole L2 to the tail rows
 constexpr size_t kMaxLds = 160 * 1024;         // LDS per workgroup on gfx950
 constexpr int64_t kMaxTileList = 128ll << 20;  // entries of the surviving-tile list per relation batch (4 bytes each)
 
@@ -108,7 +109,8 @@ const TileCfg kL2Tiles[] = {
     {256, 256, 512, nullptr, k_join_l2_ares<256, 2, 4>, true},
     {256, 128, 512, nullptr, k_join_l2_ares<128, 4, 2>, true},
 };
-constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles
+constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles: streaming, 256 x 256, 8 waves
+constexpr int kResidentL2Tile = 11;               // head-resident, 256 x 256, 8 waves (2 x 4)
 constexpr int kNumL2Tiles = (int)(sizeof(kL2Tiles) / sizeof(kL2Tiles[0]));
 
 int check_common(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R) {
@@ -141,7 +143,7 @@ int kgc_create(const kgc_config* cfg, kgc_handle** out) {
   if (c.prune < KGC_PRUNE_AUTO || c.prune > KGC_PRUNE_ON) return KGC_E_INVALID;
   if (c.max_d < 0 || c.max_d > kMaxD || c.workspace_bytes < 0 || c.tile_cfg < 0 || c.tile_cfg > kNumL2Tiles)
     return KGC_E_INVALID;
-  if (!(c.group_radius >= 0.f)) return KGC_E_INVALID;
+  if (!(c.group_radius >= 0.f) || c.range_kib < 0) return KGC_E_INVALID;
   for (int v : c.reserved)
     if (v != 0) return KGC_E_INVALID;
   int ndev = 0;
@@ -248,13 +250,15 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   const bool prune = hd->cfg.prune != KGC_PRUNE_OFF;
 
   // tile shape
-  int tile_id = hd->cfg.tile_cfg > 0 ? hd->cfg.tile_cfg - 1 : kDefaultL2Tile;
+  const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
+  const int k16 = (d + kNormCols + 15) / 16;
+  // automatic choice: the head-resident kernel while its LDS tile fits (d <= 218), else the streaming one
+  int tile_id = hd->cfg.tile_cfg > 0 ? hd->cfg.tile_cfg - 1
+                : (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile);
   const TileCfg tc = kL2Tiles[tile_id];
   if (p == 2 && prune && !tc.stream_kernel)
     return fail(hd, KGC_E_INVALID, "this tile variant has no pruned mode; choose a streaming variant");
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
-  const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
-  const int k16 = (d + kNormCols + 15) / 16;
 
   if ((rc = ensure(hd, hd->counters, sizeof(DevCounters))) || (rc = ensure(hd, hd->params, sizeof(JoinParams))))
     return rc;
@@ -460,7 +464,9 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         int64_t nsplit = 1;
         if (!prune) {
           const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
-          nsplit = (nT * tile_bytes + kL2RangeBytes - 1) / kL2RangeBytes;
+          const int64_t range_bytes = hd->cfg.range_kib > 0 ? (int64_t)hd->cfg.range_kib * 1024
+                                      : (tc.head_resident ? kL2RangeBytesResident : kL2RangeBytes);
+          nsplit = (nT * tile_bytes + range_bytes - 1) / range_bytes;
           nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
           nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
         }
@@ -508,6 +514,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   s.tile_m = BM; s.tile_n = BN;
   s.k_padded = (p == 2) ? k16 * 16 : d;
   s.relation_batches = nbatch;
+  s.join_variant = (p == 2) ? tile_id + 1 : 0;
   // phase times from the events: [ev0 grouping ev3 | summaries + B staging ev1 | per batch: bound test + A staging | join]
   float ms = 0.f, ms_group = 0.f, ms_between = 0.f;
   (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);

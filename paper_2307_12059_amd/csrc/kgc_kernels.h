@@ -718,13 +718,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
     const uint16_t* Bc = Bs + (BUF) * BSZ + rd_b;                                                 \
     const bool last_slice = (ck == KS - 1);                                                       \
     const bool two = !last_slice || last_two;                                                     \
-    bf16x8_t fa[TM], fb[TN], ga[TM], gb[TN];                                                      \
+    bf16x8_t fa[TM], fb[TN];                                                                      \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK); \
     _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kSliceK); \
-    if (two) {                                                                                    \
-      _Pragma("unroll") for (int i = 0; i < TM; ++i) ga[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK + rd_step); \
-      _Pragma("unroll") for (int j = 0; j < TN; ++j) gb[j] = *(const bf16x8_t*)(Bc + j * 32 * kSliceK + rd_step); \
-    }                                                                                             \
     if (ck == 0) {                                                                                \
       const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
       _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
@@ -733,7 +729,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
     } else {                                                                                      \
       KGC_MFMA_STEP(fa, fb);                                                                      \
     }                                                                                             \
-    if (two) KGC_MFMA_STEP(ga, gb);                                                               \
+    if (two) {                                                                                    \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK + rd_step); \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kSliceK + rd_step); \
+      KGC_MFMA_STEP(fa, fb);                                                                      \
+    }                                                                                             \
     if (last_slice) {                                                                             \
       float mn = acc[0][0][0];                                                                    \
       _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \

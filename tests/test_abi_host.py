@@ -26,7 +26,7 @@ def test_version_and_struct_sizes():
     assert re.fullmatch(r"\d+\.\d+\.\d+", kgc.kgc_version())
     assert ctypes.sizeof(kgc.kgc_triple) == 16
     assert ctypes.sizeof(kgc.kgc_config) == 56
-    assert ctypes.sizeof(kgc.kgc_stats) == 104
+    assert ctypes.sizeof(kgc.kgc_stats) == 112
 
 
 def test_null_arguments_are_rejected_without_a_device():
