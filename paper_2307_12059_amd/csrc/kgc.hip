@@ -254,7 +254,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   const int k16 = (d + kNormCols + 15) / 16;
   // automatic choice: the head-resident kernel while its LDS tile fits (d <= 218), else the streaming one
   int tile_id = hd->cfg.tile_cfg > 0 ? hd->cfg.tile_cfg - 1
-                : (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile);
+                : (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile);
   const TileCfg tc = kL2Tiles[tile_id];
   if (p == 2 && prune && !tc.stream_kernel)
     return fail(hd, KGC_E_INVALID, "this tile variant has no pruned mode; choose a streaming variant");
@@ -473,7 +473,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         size_t dyn_lds = 0;
         if (tc.head_resident) {
           dyn_lds = ((size_t)KS * 256 + 2 * (size_t)BN) * kSliceK * 2;
-          if (dyn_lds > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
+          if (dyn_lds + sizeof(BlockQueue) > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
           KGC_HIP(hd, hipFuncSetAttribute((const void*)tc.stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                           (int)dyn_lds));
         }

@@ -73,6 +73,64 @@ struct RecheckCtx {
   unsigned long long* cand_counter;
 };
 
+// Exact score of one triple by a 16-lane group (the TransE distance of Section 4.3 in double):
+// x_k = (E[h][k] + Rv[r][k]) - E[t][k], s = sum x_k^2 or |x_k|, tree-reduced over the group; every lane of
+// the group returns the norm.  When the rows are 16-byte aligned (d % 4 == 0 for float32, d % 8 == 0 for
+// bfloat16) each lane reads 16-byte chunks, so that a candidate costs a couple of memory round trips
+// rather than one per dimension.
+__device__ __forceinline__ double group16_exact_dist(const RecheckCtx& cx, int32_t h, int32_t r, int32_t t, int sub) {
+  const int d = cx.d;
+  const int64_t ho = (int64_t)h * d, to = (int64_t)t * d, ro = (int64_t)r * d;
+  double s0 = 0.0, s1 = 0.0;
+  const bool p2 = cx.p == 2;
+  if (cx.dtype == KGC_F32 && (d & 3) == 0) {
+    const float4* eh = (const float4*)((const float*)cx.E + ho);
+    const float4* et = (const float4*)((const float*)cx.E + to);
+    const float4* rv = (const float4*)((const float*)cx.Rv + ro);
+    const int nch = d >> 2;
+#pragma unroll 1
+    for (int c = sub; c < nch; c += 16) {
+      const float4 a0 = eh[c], b0 = rv[c], t0 = et[c];
+      const double x0 = ((double)a0.x + (double)b0.x) - (double)t0.x, x1 = ((double)a0.y + (double)b0.y) - (double)t0.y;
+      const double x2 = ((double)a0.z + (double)b0.z) - (double)t0.z, x3 = ((double)a0.w + (double)b0.w) - (double)t0.w;
+      s0 += p2 ? (x0 * x0 + x1 * x1) : (fabs(x0) + fabs(x1));
+      s1 += p2 ? (x2 * x2 + x3 * x3) : (fabs(x2) + fabs(x3));
+    }
+  } else if (cx.dtype == KGC_BF16 && (d & 7) == 0) {
+    const uint4* eh = (const uint4*)((const uint16_t*)cx.E + ho);
+    const uint4* et = (const uint4*)((const uint16_t*)cx.E + to);
+    const uint4* rv = (const uint4*)((const uint16_t*)cx.Rv + ro);
+    const int nch = d >> 3;
+#pragma unroll 1
+    for (int c = sub; c < nch; c += 16) {
+      const uint4 a = eh[c], b = rv[c], tt = et[c];
+      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w}, tw[4] = {tt.x, tt.y, tt.z, tt.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const double xl = ((double)__uint_as_float(aw[q] << 16) + (double)__uint_as_float(bw[q] << 16)) -
+                          (double)__uint_as_float(tw[q] << 16);
+        const double xh = ((double)__uint_as_float(aw[q] & 0xffff0000u) + (double)__uint_as_float(bw[q] & 0xffff0000u)) -
+                          (double)__uint_as_float(tw[q] & 0xffff0000u);
+        s0 += p2 ? xl * xl : fabs(xl);
+        s1 += p2 ? xh * xh : fabs(xh);
+      }
+    }
+  } else {
+#pragma unroll 1
+    for (int k = sub; k < d; k += 16) {
+      const double x = ((double)ld_elem(cx.E, ho + k, cx.dtype) + (double)ld_elem(cx.Rv, ro + k, cx.dtype)) -
+                       (double)ld_elem(cx.E, to + k, cx.dtype);
+      s0 += p2 ? x * x : fabs(x);
+    }
+  }
+  double s = s0 + s1;
+  s += __shfl_xor(s, 8, 16);
+  s += __shfl_xor(s, 4, 16);
+  s += __shfl_xor(s, 2, 16);
+  s += __shfl_xor(s, 1, 16);
+  return p2 ? sqrt(s) : s;
+}
+
 // ---- second stage: exact re-scoring of filter candidates + compaction ----
 // `cm` holds, per lane, one bit for each of up to 64 accumulator elements of this lane that passed
 // the low-precision filter.  `map(e, lane, hslot, tslot)` turns (element, owning lane) into the two
@@ -106,26 +164,7 @@ __device__ __forceinline__ void recheck_and_emit(unsigned long long cm, int32_t 
       h = cx.slot_ent[hslot];
       t = cx.slot_ent[tslot];
       if (h >= 0 && t >= 0) {
-        const int64_t ho = (int64_t)h * cx.d, to = (int64_t)t * cx.d, ro = (int64_t)r * cx.d;
-        double s = 0.0;
-        if (cx.p == 2) {
-          for (int k = sub; k < cx.d; k += 16) {
-            const double x = ((double)ld_elem(cx.E, ho + k, cx.dtype) + (double)ld_elem(cx.Rv, ro + k, cx.dtype)) -
-                             (double)ld_elem(cx.E, to + k, cx.dtype);
-            s += x * x;
-          }
-        } else {
-          for (int k = sub; k < cx.d; k += 16) {
-            const double x = ((double)ld_elem(cx.E, ho + k, cx.dtype) + (double)ld_elem(cx.Rv, ro + k, cx.dtype)) -
-                             (double)ld_elem(cx.E, to + k, cx.dtype);
-            s += fabs(x);
-          }
-        }
-        s += __shfl_xor(s, 8, 16);
-        s += __shfl_xor(s, 4, 16);
-        s += __shfl_xor(s, 2, 16);
-        s += __shfl_xor(s, 1, 16);
-        const double dist = (cx.p == 2) ? sqrt(s) : s;
+        const double dist = group16_exact_dist(cx, h, r, t, sub);
         hit = dist <= cx.delta;
         distf = (float)dist;
       }
@@ -136,6 +175,107 @@ __device__ __forceinline__ void recheck_and_emit(unsigned long long cm, int32_t 
     if (cm != 0ull && rank < 4) cm &= cm - 1ull;           // the four served owners retire one element
     wave_append(hit && sub == 0, h, r, t, distf, cx.out, cx.cap, cx.hit_counter);
   }
+  if (lane == 0 && ncand) atomicAdd(cx.cand_counter, ncand);
+}
+
+// ---- block-cooperative form of the second stage ----
+// Candidates of a tile cluster in one or two waves (an aligned pair of entity groups is a 32 x 32 patch),
+// so re-scoring them inside the owning wave leaves the other waves idle.  Here every wave pushes its
+// candidates into a small LDS queue and ALL 16-lane groups of the block drain it, four per wave at a time.
+// The hits of a round are staged in LDS and leave with ONE global atomic per round: with a few hundred hits
+// per tile, one atomic per wave step on the single output counter was what bounded the pruned join.
+// Entered by the whole block together (the caller makes that decision block-uniform through q->flag).
+constexpr int kQueueCap = 512;
+struct BlockQueue {
+  unsigned int count;      // entries pushed in this round (may run past kQueueCap: those pushes are retried)
+  unsigned int pending;    // some wave still holds candidates after this round
+  unsigned int flag;       // set by any wave whose tile has candidates; read after the block barrier
+  unsigned int nhits;      // hits staged in this round
+  unsigned long long base; // where this round's hits go in the output (one global atomic per round)
+  unsigned long long ent[kQueueCap];   // (hslot << 32) | tslot
+  kgc_triple hits[kQueueCap];          // hits of this round, copied out together
+};
+
+template <int NWAVES, int NW, typename MapFn>
+__device__ __forceinline__ void block_recheck(unsigned long long (&cm)[NW], int32_t r, const RecheckCtx& cx,
+                                              BlockQueue* q, MapFn map) {
+  const int lane = lane_id();
+  const int wave = (int)(threadIdx.x >> 6);
+  const int grp = lane >> 4, sub = lane & 15;
+  unsigned long long ncand = 0ull;
+  for (;;) {
+    // 1. every wave appends candidates (one per lane and pass) until its masks are empty or the queue is full
+    for (int w = 0; w < NW; ++w) {
+      for (;;) {
+        const bool want = cm[w] != 0ull;
+        const unsigned long long b = __builtin_amdgcn_ballot_w64(want);
+        if (b == 0ull) break;
+        const int n = __builtin_popcountll(b);
+        const int first = __builtin_ctzll(b);
+        unsigned int base = 0u;
+        if (lane == first) base = atomicAdd(&q->count, (unsigned int)n);
+        base = (unsigned int)__shfl((int)base, first);
+        const unsigned rank =
+            __builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
+        if (want && base + rank < (unsigned)kQueueCap) {
+          const int e = (int)__builtin_ctzll(cm[w]);
+          int64_t hslot, tslot;
+          map(w * 64 + e, lane, hslot, tslot);
+          q->ent[base + rank] = ((unsigned long long)(uint32_t)hslot << 32) | (unsigned long long)(uint32_t)tslot;
+          cm[w] &= cm[w] - 1ull;
+        }
+        if (base + (unsigned)n >= (unsigned)kQueueCap) break;     // full: the rest waits for the next round
+      }
+    }
+    bool more = false;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) more |= cm[w] != 0ull;
+    if (__builtin_amdgcn_ballot_w64(more) != 0ull && lane == 0) q->pending = 1u;
+    __syncthreads();
+    const unsigned int qn = q->count < (unsigned)kQueueCap ? q->count : (unsigned)kQueueCap;
+    const unsigned int pend = q->pending;
+    // 2. all groups drain the queue: entry e0 + 4 * wave + group, exact distance in double, compaction
+    for (unsigned int e0 = 0; e0 < qn; e0 += NWAVES * 4) {
+      const unsigned int e = e0 + (unsigned)(wave * 4 + grp);
+      bool hit = false;
+      float distf = 0.f;
+      int32_t h = -1, t = -1;
+      if (e < qn) {
+        const unsigned long long ent = q->ent[e];
+        h = cx.slot_ent[(int64_t)(uint32_t)(ent >> 32)];
+        t = cx.slot_ent[(int64_t)(uint32_t)(ent & 0xffffffffull)];
+        if (h >= 0 && t >= 0) {
+          const double dist = group16_exact_dist(cx, h, r, t, sub);
+          hit = dist <= cx.delta;
+          distf = (float)dist;
+        }
+        if (sub == 0) ++ncand;
+      }
+      if (hit && sub == 0) {
+        kgc_triple rec;
+        rec.h = h; rec.r = r; rec.t = t; rec.dist = distf;
+        q->hits[atomicAdd(&q->nhits, 1u)] = rec;             // LDS atomic; at most one hit per entry
+      }
+    }
+    __syncthreads();
+    // 3. one global atomic reserves the output range of the whole round; all threads copy the hits out
+    const unsigned int nh = q->nhits;
+    if (threadIdx.x == 0 && nh) q->base = atomicAdd(cx.hit_counter, (unsigned long long)nh);
+    __syncthreads();
+    if (nh) {
+      const unsigned long long base = q->base;
+      for (unsigned int i = threadIdx.x; i < nh; i += NWAVES * 64) {
+        const unsigned long long pos = base + i;
+        if (pos < cx.cap) cx.out[pos] = q->hits[i];
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { q->count = 0u; q->pending = 0u; q->flag = 0u; q->nhits = 0u; }
+    __syncthreads();
+    if (!pend) break;
+  }
+  // per-wave candidate count (one lane per group counted its entries)
+  for (int off = 32; off > 0; off >>= 1) ncand += __shfl_xor((unsigned long long)ncand, off, 64);
   if (lane == 0 && ncand) atomicAdd(cx.cand_counter, ncand);
 }
 

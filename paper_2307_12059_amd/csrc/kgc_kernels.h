@@ -613,12 +613,14 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
   static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
 
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [KS][BM][32] head slices, then [2][BN][32] tail slices
+  __shared__ BlockQueue queue;
   const int KS = a.KS;
   uint16_t* Ares = lds;
   uint16_t* Bs = lds + KS * ASZ;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
+  if (tid == 0) { queue.count = 0u; queue.pending = 0u; queue.flag = 0u; queue.nhits = 0u; }   // published by the prologue barrier
 
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
@@ -699,7 +701,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
   const int last_two = (a.k16 - (KS - 1) * 2) >= 2;
   const int total = ntiles * KS;
   int ck = 0, ct = 0;
-  int tcol_cur = tcol;
+  int tcol_cur = tcol, done_tcol = tcol;
+  bool tile_done = false, done_has = false;
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -735,37 +738,55 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
       KGC_MFMA_STEP(fa, fb);                                                                      \
     }                                                                                             \
     if (last_slice) {                                                                             \
+      /* end of a tile: does any element pass the filter?  The exact path runs after the block barrier. */ \
       float mn = acc[0][0][0];                                                                    \
       _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
         _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
           _Pragma("unroll") for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);            \
-      if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {                                       \
-        const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
-        const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;                                  \
-        constexpr int NW = (TM * TN + 3) / 4;                                                     \
-        _Pragma("unroll") for (int w = 0; w < NW; ++w) {                                          \
-          unsigned long long cm = 0ull;                                                           \
-          _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                         \
-            const int tile = w * 4 + q;                                                           \
-            if (tile < TM * TN) {                                                                 \
-              const int i = tile / TN, j = tile % TN;                                             \
-              _Pragma("unroll") for (int v = 0; v < 16; ++v)                                      \
-                if (acc[i][j][v] <= thr) cm |= 1ull << (q * 16 + v);                              \
-            }                                                                                     \
-          }                                                                                       \
-          if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;                          \
-          recheck_and_emit(cm, a.r0 + rl, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) { \
-            const int tile = w * 4 + (e >> 4), v = e & 15;                                        \
-            const int i = tile / TN, j = tile % TN;                                               \
-            hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);                     \
-            tslot = tbase + j * 32 + (src & 31);                                                  \
-          });                                                                                     \
-        }                                                                                         \
-      }                                                                                           \
+      done_has = __builtin_amdgcn_ballot_w64(mn <= thr) != 0ull;                                  \
+      if (done_has && lane == 0) queue.flag = 1u;                                                 \
+      tile_done = true;                                                                           \
+      done_tcol = tcol_cur;                                                                       \
       ck = 0;                                                                                     \
       if (++ct < ntiles) tcol_cur = cols ? (int)cols[t_begin + ct] : t_begin + ct;                \
     } else {                                                                                      \
       ++ck;                                                                                       \
+    }                                                                                             \
+  } while (0)
+
+  // After the barrier that ends a tile's last slice: if any wave flagged candidates, the whole block
+  // re-scores them together.  MFMA 32x32 accumulator layout: register v of lane l holds row
+  // 8*(v/4) + 4*(l/32) + (v%4), column l%32; element index = (mfma tile * 16 + v).
+#define KGC_TILE_END()                                                                            \
+  do {                                                                                            \
+    if (tile_done) {                                                                              \
+      tile_done = false;                                                                          \
+      if (queue.flag) {                                                                           \
+        constexpr int NW = (TM * TN + 3) / 4;                                                     \
+        unsigned long long cm[NW];                                                                \
+        _Pragma("unroll") for (int w = 0; w < NW; ++w) {                                          \
+          cm[w] = 0ull;                                                                           \
+          if (done_has) {                                                                         \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
+              const int tile = w * 4 + q;                                                         \
+              if (tile < TM * TN) {                                                               \
+                const int i = tile / TN, j = tile % TN;                                           \
+                _Pragma("unroll") for (int v = 0; v < 16; ++v)                                    \
+                  if (acc[i][j][v] <= thr) cm[w] |= 1ull << (q * 16 + v);                         \
+              }                                                                                   \
+            }                                                                                     \
+          }                                                                                       \
+        }                                                                                         \
+        const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
+        const int64_t tbase = (int64_t)done_tcol * BN + wn * WTN;                                 \
+        block_recheck<WGM * WGN, NW>(cm, a.r0 + rl, a.cx, &queue,                                 \
+                                     [=](int e, int src, int64_t& hslot, int64_t& tslot) {        \
+          const int tile = e >> 4, v = e & 15;                                                    \
+          const int i = tile / TN, j = tile % TN;                                                 \
+          hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);                       \
+          tslot = tbase + j * 32 + (src & 31);                                                    \
+        });                                                                                       \
+      }                                                                                           \
     }                                                                                             \
   } while (0)
 
@@ -781,13 +802,16 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
     KGC_COMPUTE(0);
     KGC_SSTORE(1, rb1);
     __syncthreads();
+    KGC_TILE_END();
     if (i + 1 >= total) break;
     // odd step: slice i + 1 is in buffer 1; set 1 is free for slice i + 3; set 0 holds slice i + 2
     KGC_GLOAD(rb1);
     KGC_COMPUTE(1);
     KGC_SSTORE(0, rb0);
     __syncthreads();
+    KGC_TILE_END();
   }
+#undef KGC_TILE_END
 #undef KGC_GLOAD
 #undef KGC_SSTORE
 #undef KGC_MFMA_STEP
