@@ -311,7 +311,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
     k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gfill.p, kMaxGroups, 0u);
     k_fill_u32<<<grid_for(slots_cap, 256), 256, 0, st>>>((uint32_t*)hd->slot_ent.p, slots_cap, 0xffffffffu);
     k_group_hist<<<gN, 256, 0, st>>>((const int32_t*)hd->group_of.p, N, (int32_t*)hd->gsize.p);
-    k_group_layout<<<1, 64, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign);
+    k_group_layout<<<1, 1024, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign);
     k_scatter_slots<<<gN, 256, 0, st>>>(gs, (const int32_t*)hd->group_of.p, (const int32_t*)hd->goff.p,
                                        (int32_t*)hd->gfill.p, N, (int32_t*)hd->slot_ent.p);
     KGC_HIP(hd, hipGetLastError());

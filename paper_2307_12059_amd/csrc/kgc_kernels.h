@@ -841,13 +841,15 @@ struct JoinL1Args {
 // mode the block walks the surviving tail tiles of its (relation, head tile) row.
 constexpr int kL1Tile = 128;
 constexpr int kL1K = 16;
-__global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
+__global__ __launch_bounds__(256, 3) void k_join_l1(const JoinL1Args a) {
   constexpr int BM = kL1Tile, BN = kL1Tile, BK = kL1K;
   __shared__ __attribute__((aligned(16))) float As[BK][BM];
   __shared__ __attribute__((aligned(16))) float Bs[BK][BN];
   __shared__ int32_t hent[BM], tent[BN];
+  __shared__ BlockQueue queue;
 
   const int tid = threadIdx.x, wave = tid >> 6;
+  if (tid == 0) { queue.count = 0u; queue.pending = 0u; queue.flag = 0u; queue.nhits = 0u; }   // published by the first barrier
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
@@ -871,6 +873,7 @@ __global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
   const int64_t ro = (int64_t)r * d;
   if (tid < BM) hent[tid] = a.cx.slot_ent[(int64_t)tH * BM + tid];
 
+#pragma unroll 1
   for (int ti = t_begin; ti < t_end; ++ti) {
     const int tT = cols ? (int)cols[ti] : ti;
     __syncthreads();                        // previous tile done with tent / As / Bs
@@ -884,6 +887,7 @@ __global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
     const int he = hent[srow], te = tent[srow];
     const int64_t ho = (int64_t)(he < 0 ? 0 : he) * d, to = (int64_t)(te < 0 ? 0 : te) * d;
 
+#pragma unroll 1
     for (int k0 = 0; k0 < d; k0 += BK) {
       float va[8], vb[8];
 #pragma unroll
@@ -915,21 +919,25 @@ __global__ __launch_bounds__(256) void k_join_l1(const JoinL1Args a) {
       }
     }
 
-    unsigned long long cm = 0ull;
+    unsigned long long cm[1] = {0ull};
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        if (acc[i][j] <= thr) cm |= 1ull << (i * 8 + j);
-    if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;
-    const int64_t hbase = (int64_t)tH * BM, tbase = (int64_t)tT * BN;
-    recheck_and_emit(cm, r, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
-      const int stid = wave * 64 + src;
-      const int sx = stid & 15, sy = stid >> 4;
-      const int i = e >> 3, j = e & 7;
-      hslot = hbase + (i >> 2) * 64 + sy * 4 + (i & 3);
-      tslot = tbase + (j >> 2) * 64 + sx * 4 + (j & 3);
-    });
+        if (acc[i][j] <= thr) cm[0] |= 1ull << (i * 8 + j);
+    // the exact path is entered by the whole block or not at all
+    if (__builtin_amdgcn_ballot_w64(cm[0] != 0ull) != 0ull && (tid & 63) == 0) queue.flag = 1u;
+    __syncthreads();
+    if (queue.flag) {
+      const int64_t hbase = (int64_t)tH * BM, tbase = (int64_t)tT * BN;
+      block_recheck<4, 1>(cm, r, a.cx, &queue, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
+        const int stid = wave * 64 + src;
+        const int sx = stid & 15, sy = stid >> 4;
+        const int i = e >> 3, j = e & 7;
+        hslot = hbase + (i >> 2) * 64 + sy * 4 + (i & 3);
+        tslot = tbase + (j >> 2) * 64 + sx * 4 + (j & 3);
+      });
+    }
   }
   if (!a.row_start) break;
   }   // rows

@@ -81,25 +81,45 @@ __global__ void k_group_hist(const int32_t* group_of, int64_t N, int32_t* gsize)
 }
 
 // Slot layout: groups of at least kSmallGroup rows start on a micro-tile boundary and are padded to one;
-// all other rows follow, packed.  One thread: at most kMaxGroups iterations.
-__global__ void k_group_layout(GroupState* gs, const int32_t* gsize, int32_t* goff, int64_t N, int slot_align) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  int cur = 0, placed = 0;
+// all other rows follow, packed.  One block of 1024 threads: each thread owns a contiguous run of groups,
+// an exclusive scan over the threads' padded sizes gives the run offsets.
+__global__ __launch_bounds__(1024) void k_group_layout(GroupState* gs, const int32_t* gsize, int32_t* goff, int64_t N,
+                                                       int slot_align) {
+  __shared__ int part[1024];
+  __shared__ int placed_part[1024];
+  const int tid = threadIdx.x;
   const int G = gs->n_groups;
-  for (int g = 0; g < G; ++g) {
+  const int per = (G + 1023) / 1024;
+  const int g0 = tid * per, g1 = (g0 + per < G) ? g0 + per : G;
+  int sum = 0, placed = 0;
+  for (int g = g0; g < g1; ++g) {
     const int sz = gsize[g];
-    if (sz >= kSmallGroup) {
-      goff[g] = cur;
-      cur += (sz + kMicro - 1) / kMicro * kMicro;
-      placed += sz;
-    } else {
-      goff[g] = -1;
-    }
+    if (sz >= kSmallGroup) { sum += (sz + kMicro - 1) / kMicro * kMicro; placed += sz; }
   }
-  gs->tail_base = cur;
-  gs->tail_fill = 0;
-  const int64_t total = (int64_t)cur + (N - placed);
-  gs->n_slots = (int32_t)((total + slot_align - 1) / slot_align * slot_align);
+  part[tid] = sum;
+  placed_part[tid] = placed;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {          // inclusive scan, Hillis-Steele
+    const int v = tid >= off ? part[tid - off] : 0;
+    const int w = tid >= off ? placed_part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    placed_part[tid] += w;
+    __syncthreads();
+  }
+  int cur = part[tid] - sum;                           // exclusive prefix of this thread's run
+  for (int g = g0; g < g1; ++g) {
+    const int sz = gsize[g];
+    if (sz >= kSmallGroup) { goff[g] = cur; cur += (sz + kMicro - 1) / kMicro * kMicro; }
+    else goff[g] = -1;
+  }
+  if (tid == 1023) {
+    const int total_padded = part[1023];
+    gs->tail_base = total_padded;
+    gs->tail_fill = 0;
+    const int64_t total = (int64_t)total_padded + (N - placed_part[1023]);
+    gs->n_slots = (int32_t)((total + slot_align - 1) / slot_align * slot_align);
+  }
 }
 
 __global__ void k_scatter_slots(GroupState* gs, const int32_t* group_of, const int32_t* goff, int32_t* gfill,
