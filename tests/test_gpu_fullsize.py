@@ -112,3 +112,8 @@ def test_c3_l1_fullsize():
 
 def test_c4_large_l2_fullsize():
     _fullsize_checks("c4_large_l2", n_rel=12, max_entities=3000, modes=["prune"])
+
+
+def test_c5_scale_l2_fullsize():
+    # 10^15 triples: pruned mode only; recall is verified on the subsample only, precision on every emitted triple
+    _fullsize_checks("c5_scale_l2", n_rel=10, max_entities=5000, modes=["prune"])

@@ -214,7 +214,7 @@ def sample_aligned_triples(wl: Workload, n: int, seed: int):
 
 
 def cluster_aligned_subsample(wl: Workload, n_rel: int, max_entities: int, seed: int):
-    """Pick ``n_rel`` relations and all entities of the clusters they link (capped at ``max_entities``).
+    """Pick ``n_rel`` relations and the entities of the clusters they link (at most ``max_entities`` in total).
 
     Returns (entity_ids, relation_ids), both sorted.  A join restricted to these
     ids contains aligned triples, so a brute-force check on it is not vacuous.
@@ -223,7 +223,14 @@ def cluster_aligned_subsample(wl: Workload, n_rel: int, max_entities: int, seed:
     R = wl.Rv.shape[0]
     rel = np.sort(g.choice(R, size=min(n_rel, R), replace=False)).astype(np.int32)
     clusters = np.unique(np.concatenate([wl.rel_src[rel], wl.rel_dst[rel]]))
-    ent = np.nonzero(np.isin(wl.labels, clusters))[0]
-    if ent.size > max_entities:
-        ent = np.sort(g.choice(ent, size=max_entities, replace=False))
+    # every linked cluster keeps an equal share of the budget, so that skewed cluster sizes cannot crowd
+    # the small clusters (and with them the aligned triples) out of the sample
+    per_cluster = max(1, max_entities // max(1, clusters.size))
+    parts = []
+    for c in clusters:
+        members = np.nonzero(wl.labels == c)[0]
+        if members.size > per_cluster:
+            members = g.choice(members, size=per_cluster, replace=False)
+        parts.append(members)
+    ent = np.sort(np.concatenate(parts)) if parts else np.empty(0, np.int64)
     return ent.astype(np.int32), rel
