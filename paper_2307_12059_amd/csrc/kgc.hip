@@ -22,7 +22,7 @@ constexpr int64_t kDefaultWorkspace = 16ll << 30;
 constexpr int64_t kL2RangeBytes = 1ll << 20;
 constexpr int64_t kL2RangeBytesResident = 3ll << 20;   // head-resident blocks leave the whole L2 to the tail rows
 constexpr size_t kMaxLds = 160 * 1024;         // LDS per workgroup on gfx950
-constexpr int64_t kMaxTileList = 128ll << 20;  // entries of the surviving-tile list per relation batch (4 bytes each)
+constexpr int64_t kMaxTileList = 1ll << 30;    // entries of the surviving-tile list per relation batch (4 bytes each)
 
 struct DevBuf {
   void* p = nullptr;
@@ -418,7 +418,8 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         ba.rad = (const float*)hd->rad.p; ba.cnorm = (const float*)hd->cnorm.p; ba.n_micro = n_micro; ba.RB = RB;
         ba.d = d; ba.delta = delta; ba.bitmap = (uint32_t*)hd->bitmap.p; ba.nH = nH; ba.words_per_row = words_per_row;
         ba.micro_per_bm = BM / kMicro; ba.micro_per_bn = BN / kMicro;
-        const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)n_micro, (unsigned)((RB + kRelChunk - 1) / kRelChunk));
+        const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)((n_micro + kHeadChunk - 1) / kHeadChunk),
+                     (unsigned)((RB + kRelChunk - 1) / kRelChunk));
         k_bound_l2<<<g, 256, 0, st>>>(ba);
       } else if (delta >= 0.f) {
         TileDistArgs ta{};

@@ -362,8 +362,7 @@ __global__ __launch_bounds__(256) void k_rel_centre_dot(const void* __restrict__
 // L2 only.  The squared centre distance of a micro-tile pair under relation r expands into parts that do
 // not need a d-dimensional loop per (r, H, T):
 //     ||c_H + r - c_T||^2 = ||c_H - c_T||^2 + 2 (r.c_H - r.c_T) + ||r||^2 = D[H][T] + 2 (u[r][H] - u[r][T]) + rn[r]
-// (the same observation that makes distB independent of r in Section 5.2, applied to the bound).  One thread
-// tests one (H, T) pair against kRelChunk relations.  The float32 cancellation error of the sum is bounded by
+// (the same observation that makes distB independent of r in Section 5.2, applied to the bound).  The float32 cancellation error of the sum is bounded by
 // err = 2 (d + 8) 2^-24 ||r|| (||c_H|| + ||c_T||) + 2^-20 D and added on the keeping side.
 constexpr int kRelChunk = 16;
 struct BoundL2Args {
@@ -371,26 +370,61 @@ struct BoundL2Args {
   int64_t n_micro; int RB; int d; float delta;
   uint32_t* bitmap; int nH, words_per_row, micro_per_bm, micro_per_bn;
 };
+constexpr int kHeadChunk = 16;
 __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
-  const int64_t mT = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t mH = blockIdx.y;
-  if (mT >= a.n_micro) return;
-  const float rH = a.rad[mH], rT = a.rad[mT];
-  if (rH < 0.f || rT < 0.f) return;                          // empty micro-tile
-  const float D = a.D[mH * a.n_micro + mT];
-  const float reach = a.delta * (1.f + kBoundSlack) + rH + rT;
-  const float reach2 = reach * reach * (1.f + kBoundSlack);
-  const float cs = a.cnorm[mH] + a.cnorm[mT];
-  const float eD = D * 9.6e-7f;
-  const float ek = 2.f * (float)(a.d + 8) * 6e-8f * cs;
-  const int tH = (int)(mH / a.micro_per_bm), tT = (int)(mT / a.micro_per_bn);
+  // block = 256 tail micro-tiles x kHeadChunk head micro-tiles x kRelChunk relations; the per-head and
+  // per-relation scalars sit in LDS, the thread's own r.c_T values in registers, so one test costs one
+  // (shared) D load per kRelChunk relations and a handful of VALU operations
+  __shared__ float uH[kRelChunk][kHeadChunk];
+  __shared__ float rnS[kRelChunk], srnS[kRelChunk];
+  __shared__ float radH[kHeadChunk], cnH[kHeadChunk];
+  const int tid = threadIdx.x;
+  const int64_t mT = (int64_t)blockIdx.x * blockDim.x + tid;
+  const int64_t mH0 = (int64_t)blockIdx.y * kHeadChunk;
   const int rl0 = (int)blockIdx.z * kRelChunk;
-  const int rl1 = rl0 + kRelChunk < a.RB ? rl0 + kRelChunk : a.RB;
-  for (int rl = rl0; rl < rl1; ++rl) {
-    const float rn = a.rn[rl];
-    const float dist2 = D + 2.f * (a.u[(int64_t)rl * a.n_micro + mH] - a.u[(int64_t)rl * a.n_micro + mT]) + rn;
-    if (dist2 <= reach2 + eD + ek * sqrtf(rn))
-      atomicOr(&a.bitmap[((int64_t)rl * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
+  {
+    const int q = tid / kHeadChunk, hq = tid % kHeadChunk;      // 256 threads = kRelChunk x kHeadChunk
+    const int rl = rl0 + q;
+    const int64_t mH = mH0 + hq;
+    uH[q][hq] = (rl < a.RB && mH < a.n_micro) ? a.u[(int64_t)rl * a.n_micro + mH] : 0.f;
+    if (tid < kRelChunk) {
+      const float v = (rl0 + tid < a.RB) ? a.rn[rl0 + tid] : 0.f;
+      rnS[tid] = v;
+      srnS[tid] = sqrtf(v);
+    }
+    if (tid < kHeadChunk) {
+      const int64_t m = mH0 + tid;
+      radH[tid] = m < a.n_micro ? a.rad[m] : -1.f;
+      cnH[tid] = m < a.n_micro ? a.cnorm[m] : 0.f;
+    }
+  }
+  __syncthreads();
+  if (mT >= a.n_micro) return;
+  const float rT = a.rad[mT];
+  if (rT < 0.f) return;                                          // empty micro-tile
+  const float cT = a.cnorm[mT];
+  float uT[kRelChunk];
+  const int nrel = a.RB - rl0 < kRelChunk ? a.RB - rl0 : kRelChunk;
+#pragma unroll
+  for (int q = 0; q < kRelChunk; ++q) uT[q] = q < nrel ? a.u[(int64_t)(rl0 + q) * a.n_micro + mT] : 0.f;
+  const int tT = (int)(mT / a.micro_per_bn);
+  const float dsl = a.delta * (1.f + kBoundSlack);
+  const float kk = 2.f * (float)(a.d + 8) * 6e-8f;
+  for (int hq = 0; hq < kHeadChunk; ++hq) {
+    const float rH = radH[hq];
+    if (rH < 0.f) continue;                                      // empty or past the end
+    const int64_t mH = mH0 + hq;
+    const float D = a.D[mH * a.n_micro + mT];
+    const float reach = dsl + rH + rT;
+    const float lim = reach * reach * (1.f + kBoundSlack) + D * 9.6e-7f;
+    const float ek = kk * (cnH[hq] + cT);
+    const int tH = (int)(mH / a.micro_per_bm);
+#pragma unroll
+    for (int q = 0; q < kRelChunk; ++q) {
+      const float dist2 = D + 2.f * (uH[q][hq] - uT[q]) + rnS[q];
+      if (q < nrel && dist2 <= lim + ek * srnS[q])
+        atomicOr(&a.bitmap[((int64_t)(rl0 + q) * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
+    }
   }
 }
 
