@@ -21,6 +21,14 @@ PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA
 PEAK_VALU_TLANEOPS = 39.3          # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz, plain (unpacked) float32 lane-ops
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch of the dense join kernel, from separate rocprofv3 --pmc runs of this script
+# (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 KiB, factors from a plain 1 GiB copy; see profiles/traffic_*.txt).
+# Counters cannot be read from inside the timed run, so the figure is attached to the matching configuration.
+MEASURED_TRAFFIC_BYTES = {
+    ("c2_mid_l2", "k_join_l2_ares", "dense"): 2.63e10,
+    ("c4_large_l2", "k_join_l2_ares", "dense"): 3.09e11,
+}
+
 
 def cpu_baseline(wl, target_seconds=12.0):
     """The oracle as it stands (brute-force mode, all host threads) on a bounded sample of the workload."""
@@ -119,7 +127,7 @@ def main():
             roof = {"bound": "alu", "achieved": work / (ms_join * 1e-3) / 1e12 if ms_join > 0 else 0.0,
                     "peak": PEAK_VALU_TLANEOPS, "unit": "Tlane-op/s"}
         roof["frac"] = roof["achieved"] / roof["peak"]
-        roof["traffic"] = None
+        roof["traffic"] = None      # filled below for configurations with a committed counter measurement
         v = st["join_variant"]
         roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_ares" if v >= 11 else "k_join_l2_stream" if v >= 6 else "k_join_l2")
         roof["tile_cfg"] = v
@@ -135,6 +143,10 @@ def main():
     dense = main_run if args.prune == "off" else (run(False, args.also_dense, 1) if args.also_dense > 0 else None)
     roof = dict((dense or main_run)["roofline"])
     roof["measured_in"] = "dense (prune off) steps of this invocation" if dense is not None else "the timed (pruned) steps"
+    if dense is not None:
+        roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((spec.name, roof["kernel"], "dense"))
+        roof["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, separate runs)"
+        roof["algorithmic_bytes"] = (2.0 * (main_run["stats"]["k_padded"] + 31) // 32 * 32 * N * R + 0) if p == 2 else None
     line = {
         "metric": "triple_scores_per_sec_effective",
         "value": N * N * R / (main_run["ms_per_step"] * 1e-3),
