@@ -83,7 +83,8 @@ def test_c1_l1_full_parity(prune):
 @pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
 @pytest.mark.parametrize("p", [1, 2])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("N,R,d", [(300, 3, 37), (257, 2, 200), (129, 1, 7), (1, 1, 1), (700, 5, 122)])
+@pytest.mark.parametrize("N,R,d", [(300, 3, 37), (257, 2, 200), (129, 1, 7), (1, 1, 1), (700, 5, 122),
+                                   (600, 3, 300), (300, 2, 960), (520, 2, 218), (520, 2, 219)])
 def test_ragged_shapes(p, dtype, N, R, d, prune):
     g = np.random.default_rng(N * 1000 + d)
     cent = g.standard_normal((4, d))
