@@ -90,24 +90,25 @@ struct TileCfg {
   int bm, bn, threads;
   void (*tile_kernel)(const JoinArgs);            // one block per tile pair
   void (*stream_kernel)(const JoinStreamArgs);    // one block per (relation, head tile), streaming over tail tiles
+  void (*listed_kernel)(const JoinStreamArgs);    // the same kernel walking the tile lists of pruned mode
   bool head_resident;                             // stream_kernel keeps the head tile's K slices in LDS (dynamic LDS)
 };
 
 // Tile variants of kernel 2 (tile_cfg = index + 1).
 const TileCfg kL2Tiles[] = {
-    {128, 128, 256, k_join_l2<128, 128, 2, 2>, nullptr, false},
-    {256, 128, 256, k_join_l2<256, 128, 2, 2>, nullptr, false},
-    {256, 256, 256, k_join_l2<256, 256, 2, 2>, nullptr, false},
-    {128, 128, 512, k_join_l2<128, 128, 4, 2>, nullptr, false},
-    {256, 256, 512, k_join_l2<256, 256, 4, 2>, nullptr, false},
-    {256, 256, 256, nullptr, k_join_l2_stream<256, 256, 2, 2, 1>, false},
-    {256, 128, 256, nullptr, k_join_l2_stream<256, 128, 2, 2, 2>, false},
-    {128, 128, 256, nullptr, k_join_l2_stream<128, 128, 2, 2, 2>, false},
-    {256, 256, 512, nullptr, k_join_l2_stream<256, 256, 4, 2, 1>, false},
-    {128, 256, 256, nullptr, k_join_l2_stream<128, 256, 2, 2, 2>, false},
-    {256, 256, 512, nullptr, k_join_l2_ares<256, 4, 2>, true},
-    {256, 256, 512, nullptr, k_join_l2_ares<256, 2, 4>, true},
-    {256, 128, 512, nullptr, k_join_l2_ares<128, 4, 2>, true},
+    {128, 128, 256, k_join_l2<128, 128, 2, 2>, nullptr, nullptr, false},
+    {256, 128, 256, k_join_l2<256, 128, 2, 2>, nullptr, nullptr, false},
+    {256, 256, 256, k_join_l2<256, 256, 2, 2>, nullptr, nullptr, false},
+    {128, 128, 512, k_join_l2<128, 128, 4, 2>, nullptr, nullptr, false},
+    {256, 256, 512, k_join_l2<256, 256, 4, 2>, nullptr, nullptr, false},
+    {256, 256, 256, nullptr, k_join_l2_stream<256, 256, 2, 2, 1, false>, k_join_l2_stream<256, 256, 2, 2, 1, true>, false},
+    {256, 128, 256, nullptr, k_join_l2_stream<256, 128, 2, 2, 2, false>, k_join_l2_stream<256, 128, 2, 2, 2, true>, false},
+    {128, 128, 256, nullptr, k_join_l2_stream<128, 128, 2, 2, 2, false>, k_join_l2_stream<128, 128, 2, 2, 2, true>, false},
+    {256, 256, 512, nullptr, k_join_l2_stream<256, 256, 4, 2, 1, false>, k_join_l2_stream<256, 256, 4, 2, 1, true>, false},
+    {128, 256, 256, nullptr, k_join_l2_stream<128, 256, 2, 2, 2, false>, k_join_l2_stream<128, 256, 2, 2, 2, true>, false},
+    {256, 256, 512, nullptr, k_join_l2_ares<256, 4, 2, false>, k_join_l2_ares<256, 4, 2, true>, true},
+    {256, 256, 512, nullptr, k_join_l2_ares<256, 2, 4, false>, k_join_l2_ares<256, 2, 4, true>, true},
+    {256, 128, 512, nullptr, k_join_l2_ares<128, 4, 2, false>, k_join_l2_ares<128, 4, 2, true>, true},
 };
 constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles: streaming, 256 x 256, 8 waves
 constexpr int kResidentL2Tile = 11;               // head-resident, 256 x 256, 8 waves (2 x 4)
@@ -471,15 +472,15 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
           nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
           nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
         }
+        void (*kern)(const JoinStreamArgs) = prune ? tc.listed_kernel : tc.stream_kernel;
         size_t dyn_lds = 0;
         if (tc.head_resident) {
           dyn_lds = ((size_t)KS * 256 + 2 * (size_t)BN) * kSliceK * 2;
           if (dyn_lds + sizeof(BlockQueue) > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
-          KGC_HIP(hd, hipFuncSetAttribute((const void*)tc.stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                          (int)dyn_lds));
+          KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
         }
         const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB);
-        hipLaunchKernelGGL(tc.stream_kernel, grid, dim3(tc.threads), dyn_lds, st, sa);
+        hipLaunchKernelGGL(kern, grid, dim3(tc.threads), dyn_lds, st, sa);
       } else {
         JoinArgs ja;
         ja.A = (const uint16_t*)hd->opA.p; ja.B = (const uint16_t*)hd->opB.p; ja.prm = prm;

@@ -403,7 +403,10 @@ struct JoinStreamArgs {
   RecheckCtx cx;
 };
 
-template <int BM, int BN, int WGM, int WGN, int MINB>
+// LISTED: the block walks tile lists (pruned mode); otherwise the grid enumerates the dense problem and the
+// kernel holds no load of the list in its inner loop (such a load would make every tile end wait for all
+// outstanding prefetches).
+template <int BM, int BN, int WGM, int WGN, int MINB, bool LISTED>
 __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const JoinStreamArgs a) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -422,7 +425,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
-  if (a.row_start) {
+  if constexpr (LISTED) {
     if (row_i >= *a.n_active) break;
     const int64_t row = (int64_t)a.active_rows[row_i];
     rl = (int)(row / a.nH); tH = (int)(row - (int64_t)rl * a.nH);
@@ -592,7 +595,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 #undef KGC_GLOAD
 #undef KGC_SSTORE
 #undef KGC_MFMA_STEP
-  if (!a.row_start) break;
+  if (!LISTED) break;
   }   // rows
 }
 
@@ -602,7 +605,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 // tail rows are streamed: half the global -> LDS traffic per tile, and the L2 only has to hold the tail
 // range.  Tail slices are prefetched two slices ahead through two register sets.  Needs
 // (KS * 256 + 2 * BN) * 64 bytes of LDS, i.e. KS <= 7 (d <= 218) with BN = 256.
-template <int BN, int WGM, int WGN>
+template <int BN, int WGM, int WGN, bool LISTED>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStreamArgs a) {
   constexpr int BM = 256;
   constexpr int NT = WGM * WGN * 64;
@@ -625,7 +628,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
-  if (a.row_start) {
+  if constexpr (LISTED) {
     if (row_i >= *a.n_active) break;
     const int64_t row = (int64_t)a.active_rows[row_i];
     rl = (int)(row / a.nH); tH = (int)(row - (int64_t)rl * a.nH);
@@ -796,6 +799,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
   KGC_SSTORE(0, rb0);
   __syncthreads();
 
+  // Both steps run to their end in every iteration (an odd number of slices only skips the second step's
+  // arithmetic): with no way out of the middle of the body, every path reaches the top of the loop with
+  // the same loads outstanding, so the compiler needs no wait there.
   for (int i = 0; i < total; i += 2) {
     // even step: slice i is in buffer 0; set 0 is free for slice i + 2; set 1 holds slice i + 1
     KGC_GLOAD(rb0);
@@ -803,10 +809,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
     KGC_SSTORE(1, rb1);
     __syncthreads();
     KGC_TILE_END();
-    if (i + 1 >= total) break;
     // odd step: slice i + 1 is in buffer 1; set 1 is free for slice i + 3; set 0 holds slice i + 2
     KGC_GLOAD(rb1);
-    KGC_COMPUTE(1);
+    if (i + 1 < total) KGC_COMPUTE(1);
     KGC_SSTORE(0, rb0);
     __syncthreads();
     KGC_TILE_END();
@@ -816,7 +821,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
 #undef KGC_SSTORE
 #undef KGC_MFMA_STEP
 #undef KGC_COMPUTE
-  if (!a.row_start) break;
+  if (!LISTED) break;
   }   // rows
 }
 
