@@ -92,23 +92,29 @@ struct TileCfg {
   void (*stream_kernel)(const JoinStreamArgs);    // one block per (relation, head tile), streaming over tail tiles
   void (*listed_kernel)(const JoinStreamArgs);    // the same kernel walking the tile lists of pruned mode
   bool head_resident;                             // stream_kernel keeps the head tile's K slices in LDS (dynamic LDS)
+  size_t static_lds;                              // head-resident kernels: bytes of their candidate queue
+  int blocks_per_cu;                              // head-resident kernels: workgroups meant to share one CU's LDS
+  int tail_buffers;                               // head-resident kernels: tail slices held in LDS (0: tail rows bypass LDS)
 };
 
 // Tile variants of kernel 2 (tile_cfg = index + 1).
 const TileCfg kL2Tiles[] = {
-    {128, 128, 256, k_join_l2<128, 128, 2, 2>, nullptr, nullptr, false},
-    {256, 128, 256, k_join_l2<256, 128, 2, 2>, nullptr, nullptr, false},
-    {256, 256, 256, k_join_l2<256, 256, 2, 2>, nullptr, nullptr, false},
-    {128, 128, 512, k_join_l2<128, 128, 4, 2>, nullptr, nullptr, false},
-    {256, 256, 512, k_join_l2<256, 256, 4, 2>, nullptr, nullptr, false},
-    {256, 256, 256, nullptr, k_join_l2_stream<256, 256, 2, 2, 1, false>, k_join_l2_stream<256, 256, 2, 2, 1, true>, false},
-    {256, 128, 256, nullptr, k_join_l2_stream<256, 128, 2, 2, 2, false>, k_join_l2_stream<256, 128, 2, 2, 2, true>, false},
-    {128, 128, 256, nullptr, k_join_l2_stream<128, 128, 2, 2, 2, false>, k_join_l2_stream<128, 128, 2, 2, 2, true>, false},
-    {256, 256, 512, nullptr, k_join_l2_stream<256, 256, 4, 2, 1, false>, k_join_l2_stream<256, 256, 4, 2, 1, true>, false},
-    {128, 256, 256, nullptr, k_join_l2_stream<128, 256, 2, 2, 2, false>, k_join_l2_stream<128, 256, 2, 2, 2, true>, false},
-    {256, 256, 512, nullptr, k_join_l2_ares<256, 4, 2, false>, k_join_l2_ares<256, 4, 2, true>, true},
-    {256, 256, 512, nullptr, k_join_l2_ares<256, 2, 4, false>, k_join_l2_ares<256, 2, 4, true>, true},
-    {256, 128, 512, nullptr, k_join_l2_ares<128, 4, 2, false>, k_join_l2_ares<128, 4, 2, true>, true},
+    {128, 128, 256, k_join_l2<128, 128, 2, 2>, nullptr, nullptr, false, 0, 1, 2},
+    {256, 128, 256, k_join_l2<256, 128, 2, 2>, nullptr, nullptr, false, 0, 1, 2},
+    {256, 256, 256, k_join_l2<256, 256, 2, 2>, nullptr, nullptr, false, 0, 1, 2},
+    {128, 128, 512, k_join_l2<128, 128, 4, 2>, nullptr, nullptr, false, 0, 1, 2},
+    {256, 256, 512, k_join_l2<256, 256, 4, 2>, nullptr, nullptr, false, 0, 1, 2},
+    {256, 256, 256, nullptr, k_join_l2_stream<256, 256, 2, 2, 1, false>, k_join_l2_stream<256, 256, 2, 2, 1, true>, false, 0, 1, 2},
+    {256, 128, 256, nullptr, k_join_l2_stream<256, 128, 2, 2, 2, false>, k_join_l2_stream<256, 128, 2, 2, 2, true>, false, 0, 1, 2},
+    {128, 128, 256, nullptr, k_join_l2_stream<128, 128, 2, 2, 2, false>, k_join_l2_stream<128, 128, 2, 2, 2, true>, false, 0, 1, 2},
+    {256, 256, 512, nullptr, k_join_l2_stream<256, 256, 4, 2, 1, false>, k_join_l2_stream<256, 256, 4, 2, 1, true>, false, 0, 1, 2},
+    {128, 256, 256, nullptr, k_join_l2_stream<128, 256, 2, 2, 2, false>, k_join_l2_stream<128, 256, 2, 2, 2, true>, false, 0, 1, 2},
+    {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 4, 2, 1, 512, false>, k_join_l2_ares<256, 256, 4, 2, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
+    {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 2, 4, 1, 512, false>, k_join_l2_ares<256, 256, 2, 4, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
+    {256, 128, 512, nullptr, k_join_l2_ares<256, 128, 4, 2, 1, 512, false>, k_join_l2_ares<256, 128, 4, 2, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
+    {128, 128, 256, nullptr, k_join_l2_ares<128, 128, 2, 2, 2, 256, false>, k_join_l2_ares<128, 128, 2, 2, 2, 256, true>, true, sizeof(BlockQueueT<256>), 2, 2},
+    {256, 256, 512, nullptr, k_join_l2_direct<2, 4>, nullptr, true, 0, 1, 0},
+    {256, 256, 512, nullptr, k_join_l2_direct<1, 8>, nullptr, true, 0, 1, 0},
 };
 constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles: streaming, 256 x 256, 8 waves
 constexpr int kResidentL2Tile = 11;               // head-resident, 256 x 256, 8 waves (2 x 4)
@@ -257,7 +263,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   int tile_id = hd->cfg.tile_cfg > 0 ? hd->cfg.tile_cfg - 1
                 : (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile);
   const TileCfg tc = kL2Tiles[tile_id];
-  if (p == 2 && prune && !tc.stream_kernel)
+  if (p == 2 && prune && !tc.listed_kernel)
     return fail(hd, KGC_E_INVALID, "this tile variant has no pruned mode; choose a streaming variant");
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
 
@@ -475,8 +481,8 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         void (*kern)(const JoinStreamArgs) = prune ? tc.listed_kernel : tc.stream_kernel;
         size_t dyn_lds = 0;
         if (tc.head_resident) {
-          dyn_lds = ((size_t)KS * 256 + 2 * (size_t)BN) * kSliceK * 2;
-          if (dyn_lds + sizeof(BlockQueue) > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
+          dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
+          if ((dyn_lds + tc.static_lds) * tc.blocks_per_cu > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
           KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
         }
         const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB);

@@ -9,6 +9,7 @@ namespace kgc {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 // ---- bfloat16 <-> float32 (bf16 = upper half of an IEEE float32; round to nearest, ties to even) ----
@@ -185,20 +186,23 @@ __device__ __forceinline__ void recheck_and_emit(unsigned long long cm, int32_t 
 // The hits of a round are staged in LDS and leave with ONE global atomic per round: with a few hundred hits
 // per tile, one atomic per wave step on the single output counter was what bounded the pruned join.
 // Entered by the whole block together (the caller makes that decision block-uniform through q->flag).
-constexpr int kQueueCap = 512;
-struct BlockQueue {
-  unsigned int count;      // entries pushed in this round (may run past kQueueCap: those pushes are retried)
+template <int CAP>
+struct BlockQueueT {
+  static constexpr int kCap = CAP;
+  unsigned int count;      // entries pushed in this round (may run past CAP: those pushes are retried)
   unsigned int pending;    // some wave still holds candidates after this round
   unsigned int flag;       // set by any wave whose tile has candidates; read after the block barrier
   unsigned int nhits;      // hits staged in this round
   unsigned long long base; // where this round's hits go in the output (one global atomic per round)
-  unsigned long long ent[kQueueCap];   // (hslot << 32) | tslot
-  kgc_triple hits[kQueueCap];          // hits of this round, copied out together
+  unsigned long long ent[CAP];   // (hslot << 32) | tslot
+  kgc_triple hits[CAP];          // hits of this round, copied out together
 };
+using BlockQueue = BlockQueueT<512>;
 
-template <int NWAVES, int NW, typename MapFn>
+template <int NWAVES, int NW, typename Queue, typename MapFn>
 __device__ __forceinline__ void block_recheck(unsigned long long (&cm)[NW], int32_t r, const RecheckCtx& cx,
-                                              BlockQueue* q, MapFn map) {
+                                              Queue* q, MapFn map) {
+  constexpr int kQueueCap = Queue::kCap;
   const int lane = lane_id();
   const int wave = (int)(threadIdx.x >> 6);
   const int grp = lane >> 4, sub = lane & 15;

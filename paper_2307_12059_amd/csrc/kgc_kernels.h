@@ -601,13 +601,14 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 
 // ---------------------------------------------------------------------------------------------
 // Kernel 2, head-resident form.  As the streaming form, but the block first copies ALL K slices of its
-// head tile (the staged a = h + r rows, 256 x KS x 64 bytes) into LDS and keeps them there, so only the
+// head tile (the staged a = h + r rows, BM x KS x 64 bytes) into LDS and keeps them there, so only the
 // tail rows are streamed: half the global -> LDS traffic per tile, and the L2 only has to hold the tail
 // range.  Tail slices are prefetched two slices ahead through two register sets.  Needs
-// (KS * 256 + 2 * BN) * 64 bytes of LDS, i.e. KS <= 7 (d <= 218) with BN = 256.
-template <int BN, int WGM, int WGN, bool LISTED>
-__global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStreamArgs a) {
-  constexpr int BM = 256;
+// (KS * BM + 2 * BN) * 64 bytes of LDS plus the candidate queue (QCAP entries of 24 bytes): KS <= 7
+// (d <= 218) with one 256 x 256 block per CU, or with two 128 x 128 blocks per CU whose barriers and
+// tile ends then fall at different times, so that one block's MFMAs fill the other's bubbles.
+template <int BM, int BN, int WGM, int WGN, int MINB, int QCAP, bool LISTED>
+__global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const JoinStreamArgs a) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -616,7 +617,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
   static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
 
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [KS][BM][32] head slices, then [2][BN][32] tail slices
-  __shared__ BlockQueue queue;
+  __shared__ BlockQueueT<QCAP> queue;
   const int KS = a.KS;
   uint16_t* Ares = lds;
   uint16_t* Bs = lds + KS * ASZ;
@@ -823,6 +824,178 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_ares(const JoinStr
 #undef KGC_COMPUTE
   if (!LISTED) break;
   }   // rows
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 2, barrier-free form (dense mode only).  The head tile is resident in LDS as above, but the tail
+// rows never pass through LDS: every wave reads the MFMA fragments of ITS OWN WTN tail columns straight from
+// the staged operand array into registers (lane l takes row l % 32 of a 32-row group, 16 bytes at offset
+// 16 * (l / 32) for the first K step of a slice and 32 bytes further for the second: the layout the MFMA
+// wants), two slices ahead of their use through three register sets.  Nothing in the loop is shared between
+// waves, so it holds no barrier and no LDS store: the LDS only serves the head fragments, and the waves of
+// a block drift apart, so that one wave's MFMAs cover the other's waits.  The waves that share tail columns
+// (same wn) read the same lines, mostly one after the other out of the CU's vector cache.
+// LDS: KS * 256 * 64 bytes (KS <= 9, d <= 282).  Candidates are re-scored by the owning wave.
+template <int WGM, int WGN>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinStreamArgs a) {
+  constexpr int BM = 256, BN = 256;
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int LA = (BM * 4) / NT;
+  constexpr int ASZ = BM * kSliceK;
+  constexpr int ROWB = kSliceK * 2;                       // bytes of one staged row slice
+  static_assert(LA * NT == BM * 4, "tile rows must divide over the threads");
+
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [KS][BM][32] head slices
+  const int KS = a.KS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  const int tH = (int)blockIdx.x, rl = (int)blockIdx.z;
+  const int t_begin = (int)(((int64_t)a.nT * blockIdx.y) / gridDim.y);
+  const int t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
+  const int ntiles = t_end - t_begin;
+  if (ntiles <= 0) return;
+  const int64_t slice_bytes = a.Nslots * ROWB;
+
+  // ---- head tile: all K slices into LDS, once (swizzled as in the other forms) ----
+  {
+    const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * ROWB;
+    const uint32_t voff = (uint32_t)tid * 16u;
+    const int st0 = (tid >> 2) * kSliceK + (((tid & 3) ^ lds_swizzle(tid >> 2)) * 8);
+    constexpr int st_step = (NT / 4) * kSliceK;
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 t[LA];
+#pragma unroll
+      for (int i = 0; i < LA; ++i) t[i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+#pragma unroll
+      for (int i = 0; i < LA; ++i) *(uint4*)(&lds[ks * ASZ + st0 + i * st_step]) = t[i];
+    }
+  }
+  __syncthreads();          // the only barrier: the head tile is complete
+
+  const int rsw = lds_swizzle(lane & 31);
+  const int rd_a = (wm * WTM + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
+  const int rd_step = (((lane >> 5) ^ rsw) & 2) ? -16 : 16;
+
+  // tail fragments of this lane: row (lane % 32) of each 32-row group of the wave's columns
+  const char* Bw = (const char*)a.B + ((int64_t)wn * WTN + (lane & 31)) * ROWB + (lane >> 5) * 16;
+  const char* pB = Bw + (int64_t)t_begin * BN * ROWB;
+  const int total = ntiles * KS;
+  int pf_k = 0, pf_t = 0, pf_i = 0;
+
+  typedef uint32_t regq_t __attribute__((ext_vector_type(8 * TN)));   // TN column groups x 2 K steps x 4 registers
+  regq_t q0, q1, q2;
+#define KGC_GLOAD(Q)                                                                              \
+  do {                                                                                            \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                              \
+      const uint4 t0 = *(const uint4*)(pB + j * 32 * ROWB);                                       \
+      const uint4 t1 = *(const uint4*)(pB + j * 32 * ROWB + 32);                                  \
+      Q[8 * j] = t0.x; Q[8 * j + 1] = t0.y; Q[8 * j + 2] = t0.z; Q[8 * j + 3] = t0.w;             \
+      Q[8 * j + 4] = t1.x; Q[8 * j + 5] = t1.y; Q[8 * j + 6] = t1.z; Q[8 * j + 7] = t1.w;         \
+    }                                                                                             \
+    /* the cursor stops on the last slice, so the loads are unconditional (and the compiler can count them) */ \
+    if (++pf_i < total) {                                                                         \
+      if (++pf_k == KS) {                                                                         \
+        pf_k = 0;                                                                                 \
+        ++pf_t;                                                                                   \
+        pB = Bw + (int64_t)(t_begin + pf_t) * BN * ROWB;                                          \
+      } else {                                                                                    \
+        pB += slice_bytes;                                                                        \
+      }                                                                                           \
+    }                                                                                             \
+  } while (0)
+#define KGC_FRAG(Q, J, STEP)                                                                      \
+  __builtin_bit_cast(bf16x8_t, u32x4_t{Q[8 * (J) + 4 * (STEP)], Q[8 * (J) + 4 * (STEP) + 1],      \
+                                       Q[8 * (J) + 4 * (STEP) + 2], Q[8 * (J) + 4 * (STEP) + 3]})
+
+  const float thr = a.prm->thr;
+  const int last_two = (a.k16 - (KS - 1) * 2) >= 2;
+  int ck = 0, ct = 0;
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // One slice: head fragments from LDS, tail fragments from register set Q; at the end of a tile the filter
+  // on the squared distance and the rare exact path.  MFMA 32x32 accumulator layout: register v of lane l
+  // holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
+#define KGC_COMPUTE(Q)                                                                            \
+  do {                                                                                            \
+    const uint16_t* Ac = lds + ck * ASZ + rd_a;                                                   \
+    const bool last_slice = (ck == KS - 1);                                                       \
+    const bool two = !last_slice || last_two;                                                     \
+    bf16x8_t fa[TM];                                                                              \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK); \
+    if (ck == 0) {                                                                                \
+      const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], KGC_FRAG(Q, j, 0), zero16, 0, 0, 0); \
+    } else {                                                                                      \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], KGC_FRAG(Q, j, 0), acc[i][j], 0, 0, 0); \
+    }                                                                                             \
+    if (two) {                                                                                    \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK + rd_step); \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], KGC_FRAG(Q, j, 1), acc[i][j], 0, 0, 0); \
+    }                                                                                             \
+    if (last_slice) {                                                                             \
+      float mn = acc[0][0][0];                                                                    \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+          _Pragma("unroll") for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);            \
+      if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {                                       \
+        const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
+        const int64_t tbase = (int64_t)(t_begin + ct) * BN + wn * WTN;                            \
+        constexpr int NW = (TM * TN + 3) / 4;                                                     \
+        _Pragma("unroll") for (int w = 0; w < NW; ++w) {                                          \
+          unsigned long long cm = 0ull;                                                           \
+          _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                         \
+            const int tile = w * 4 + q;                                                           \
+            if (tile < TM * TN) {                                                                 \
+              const int i = tile / TN, j = tile % TN;                                             \
+              _Pragma("unroll") for (int v = 0; v < 16; ++v)                                      \
+                if (acc[i][j][v] <= thr) cm |= 1ull << (q * 16 + v);                              \
+            }                                                                                     \
+          }                                                                                       \
+          if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;                          \
+          recheck_and_emit(cm, a.r0 + rl, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) { \
+            const int tile = w * 4 + (e >> 4), v = e & 15;                                        \
+            const int i = tile / TN, j = tile % TN;                                               \
+            hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);                     \
+            tslot = tbase + j * 32 + (src & 31);                                                  \
+          });                                                                                     \
+        }                                                                                         \
+      }                                                                                           \
+      ck = 0;                                                                                     \
+      ++ct;                                                                                       \
+    } else {                                                                                      \
+      ++ck;                                                                                       \
+    }                                                                                             \
+  } while (0)
+
+  // slices i, i + 1 in flight; every step first asks for slice i + 2 (into the set slice i - 1 has left)
+  KGC_GLOAD(q0);
+  KGC_GLOAD(q1);
+  for (int i = 0; i < total; i += 3) {
+    KGC_GLOAD(q2);
+    KGC_COMPUTE(q0);
+    KGC_GLOAD(q0);
+    if (i + 1 < total) KGC_COMPUTE(q1);
+    KGC_GLOAD(q1);
+    if (i + 2 < total) KGC_COMPUTE(q2);
+  }
+#undef KGC_GLOAD
+#undef KGC_FRAG
+#undef KGC_COMPUTE
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -56,10 +56,10 @@ PRUNE_OFF, PRUNE_ON = 1, 2
 
 
 @pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
-@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13])
+@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
 def test_c1_l2_full_parity(tile_cfg, prune):
-    if prune == PRUNE_ON and 1 <= tile_cfg <= 5:
-        pytest.skip("one-block-per-tile variants have no pruned mode")
+    if prune == PRUNE_ON and (1 <= tile_cfg <= 5 or tile_cfg >= 15):
+        pytest.skip("one-block-per-tile and barrier-free variants have no pruned mode")
     wl = workloads.generate("c1_tiny_l2")
     got, ref, rep = _check(wl.E, wl.Rv, 2, wl.delta, tile_cfg=tile_cfg, prune=prune)
     if prune == PRUNE_ON:
