@@ -129,7 +129,8 @@ def main():
         roof["frac"] = roof["achieved"] / roof["peak"]
         roof["traffic"] = None      # filled below for configurations with a committed counter measurement
         v = st["join_variant"]
-        roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_ares" if v >= 11 else "k_join_l2_stream" if v >= 6 else "k_join_l2")
+        roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_direct" if v >= 15 else "k_join_l2_ares" if v >= 11
+                          else "k_join_l2_stream" if v >= 6 else "k_join_l2")
         roof["tile_cfg"] = v
         roof["launches_per_step"] = launches
         roof["avg_launch_ms"] = ms_join / launches
@@ -146,7 +147,8 @@ def main():
     if dense is not None:
         roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((spec.name, roof["kernel"], "dense"))
         roof["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, separate runs)"
-        roof["algorithmic_bytes"] = (2.0 * (main_run["stats"]["k_padded"] + 31) // 32 * 32 * N * R + 0) if p == 2 else None
+        # every staged operand row read once: R * N head rows and N tail rows of k_padded bf16 values
+        roof["algorithmic_bytes"] = 2.0 * main_run["stats"]["k_padded"] * N * (R + 1) if p == 2 else None
     line = {
         "metric": "triple_scores_per_sec_effective",
         "value": N * N * R / (main_run["ms_per_step"] * 1e-3),

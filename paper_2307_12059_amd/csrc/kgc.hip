@@ -118,6 +118,8 @@ const TileCfg kL2Tiles[] = {
 };
 constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles: streaming, 256 x 256, 8 waves
 constexpr int kResidentL2Tile = 11;               // head-resident, 256 x 256, 8 waves (2 x 4)
+constexpr int kDirectL2Tile = 14;                 // head-resident and barrier-free (dense mode only), 8 waves (2 x 4)
+constexpr int kDirectMaxKS = 9;                   // its head tile then takes 144 of the 160 KiB of LDS
 constexpr int kNumL2Tiles = (int)(sizeof(kL2Tiles) / sizeof(kL2Tiles[0]));
 
 int check_common(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R) {
@@ -259,9 +261,13 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   // tile shape
   const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
   const int k16 = (d + kNormCols + 15) / 16;
-  // automatic choice: the head-resident kernel while its LDS tile fits (d <= 218), else the streaming one
-  int tile_id = hd->cfg.tile_cfg > 0 ? hd->cfg.tile_cfg - 1
-                : (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile);
+  // automatic choice.  Dense: the barrier-free head-resident kernel while the head tile fits in LDS with
+  // some room to spare (KS <= 9, d <= 282).  Pruned: the head-resident kernel with its candidate queue
+  // (KS <= 7, d <= 218).  Otherwise the streaming kernel.
+  int tile_id = kDefaultL2Tile;
+  if (hd->cfg.tile_cfg > 0) tile_id = hd->cfg.tile_cfg - 1;
+  else if (!prune && KS <= kDirectMaxKS) tile_id = kDirectL2Tile;
+  else if (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds) tile_id = kResidentL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
   if (p == 2 && prune && !tc.listed_kernel)
     return fail(hd, KGC_E_INVALID, "this tile variant has no pruned mode; choose a streaming variant");
