@@ -150,7 +150,7 @@ def main():
         # every staged operand row read once: R * N head rows and N tail rows of k_padded bf16 values
         roof["algorithmic_bytes"] = 2.0 * main_run["stats"]["k_padded"] * N * (R + 1) if p == 2 else None
     line = {
-        "metric": "triple_scores_per_sec_effective",
+        "metric": "triple-scores/sec (effective N\u00b2R) + MFMA util %",
         "value": N * N * R / (main_run["ms_per_step"] * 1e-3),
         "unit": "triple-scores/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -168,6 +168,9 @@ def main():
         "candidates": main_run["stats"]["candidates"],
         "phase_ms": main_run["phase_ms"],
         "roofline": roof,
+        # MFMA utilisation of the dense join tiles: algorithmic flop rate over the bf16 MFMA peak (the counter
+        # view, MFMA-busy cycles and the sustained clock, is in profiles/counters_*.txt)
+        "mfma_util_pct": 100.0 * roof["frac"] if p == 2 else None,
     }
     if dense is not None and dense is not main_run:
         line["dense"] = {"ms_per_step": dense["ms_per_step"], "value": N * N * R / (dense["ms_per_step"] * 1e-3),
