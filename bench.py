@@ -25,8 +25,8 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 KiB, factors from a plain 1 GiB copy; see profiles/traffic_*.txt).
 # Counters cannot be read from inside the timed run, so the figure is attached to the matching configuration.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2_mid_l2", "k_join_l2_direct", "dense"): 2.23e10,
-    ("c4_large_l2", "k_join_l2_direct", "dense"): 3.12e11,
+    ("c2_mid_l2", "k_join_l2_direct", "dense"): 1.07e10,
+    ("c4_large_l2", "k_join_l2_direct", "dense"): 1.60e11,
 }
 
 

@@ -472,9 +472,11 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = (int)r0; sa.RB = RB;
         sa.row_start = row_start; sa.row_count = row_count; sa.cols = cols; sa.active_rows = active_rows;
         sa.n_active = n_active; sa.cx = cx;
-        // Dense: tail tiles are cut into ranges of about kL2RangeBytes of staged B rows, so that the blocks
-        // running at the same time (consecutive head tiles of one range) keep their B rows in the 4 MiB L2 of
-        // their XCD; small problems are cut further to fill the chip.  Pruned: one block per row.
+        // Dense: tail tiles are cut into ranges of about kL2RangeBytes of staged B rows and the range is the
+        // slowest grid dimension, so that a range stays in the 4 MiB L2 of every XCD while all head tiles of
+        // all relations of the batch pass over it (the tail rows then cost almost no HBM traffic; what remains
+        // is one read of every head tile per range); small problems are cut further to fill the chip.
+        // Pruned: one block per row.
         int64_t nsplit = 1;
         if (!prune) {
           const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
@@ -491,7 +493,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
           if ((dyn_lds + tc.static_lds) * tc.blocks_per_cu > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
           KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
         }
-        const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)nsplit, (unsigned)RB);
+        const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit);
         hipLaunchKernelGGL(kern, grid, dim3(tc.threads), dyn_lds, st, sa);
       } else {
         JoinArgs ja;

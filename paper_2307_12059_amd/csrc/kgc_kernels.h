@@ -385,8 +385,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void k_join_l2(const JoinArgs a) {
 // tiles; the K slices of all those tiles form one continuous stream that is prefetched two slices
 // ahead through registers into a double-buffered LDS stage, so the global-memory latency of a slice
 // is covered by the MFMA work of the two slices before it, also across tile boundaries.
-// Tail-tile range: dense mode splits [0, nT) evenly over gridDim.y; pruned mode reads the row's list of
-// surviving tail tiles.
+// Tail-tile range: dense mode splits [0, nT) evenly over gridDim.z, the slowest grid dimension (x = head tile,
+// y = relation), so that one range of tail rows stays in the L2 caches while every head tile of every
+// relation passes over it; pruned mode reads the row's list of surviving tail tiles.
 struct JoinStreamArgs {
   const uint16_t* A;
   const uint16_t* B;
@@ -434,9 +435,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
     __syncthreads();                    // the previous row is done with the LDS buffers
   } else {
     // grid = (head tiles, tail-tile ranges, relations): blocks that run together share a tail-tile range
-    tH = (int)blockIdx.x; rl = (int)blockIdx.z;
-    t_begin = (int)(((int64_t)a.nT * blockIdx.y) / gridDim.y);
-    t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
+    tH = (int)blockIdx.x; rl = (int)blockIdx.y;
+    t_begin = (int)(((int64_t)a.nT * blockIdx.z) / gridDim.z);
+    t_end = (int)(((int64_t)a.nT * (blockIdx.z + 1)) / gridDim.z);
   }
   const int ntiles = t_end - t_begin;
   if (ntiles <= 0) break;
@@ -637,9 +638,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
     cols = a.cols;
     __syncthreads();                    // the previous row is done with the LDS buffers
   } else {
-    tH = (int)blockIdx.x; rl = (int)blockIdx.z;
-    t_begin = (int)(((int64_t)a.nT * blockIdx.y) / gridDim.y);
-    t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
+    tH = (int)blockIdx.x; rl = (int)blockIdx.y;
+    t_begin = (int)(((int64_t)a.nT * blockIdx.z) / gridDim.z);
+    t_end = (int)(((int64_t)a.nT * (blockIdx.z + 1)) / gridDim.z);
   }
   const int ntiles = t_end - t_begin;
   if (ntiles <= 0) break;
@@ -852,9 +853,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  const int tH = (int)blockIdx.x, rl = (int)blockIdx.z;
-  const int t_begin = (int)(((int64_t)a.nT * blockIdx.y) / gridDim.y);
-  const int t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
+  const int tH = (int)blockIdx.x, rl = (int)blockIdx.y;
+  const int t_begin = (int)(((int64_t)a.nT * blockIdx.z) / gridDim.z);
+  const int t_end = (int)(((int64_t)a.nT * (blockIdx.z + 1)) / gridDim.z);
   const int ntiles = t_end - t_begin;
   if (ntiles <= 0) return;
   const int64_t slice_bytes = a.Nslots * ROWB;
