@@ -40,7 +40,7 @@ struct kgc_handle {
   DevBuf slot_ent, opB, opA, normsB, normsA, counters, params;
   // pruning scratch
   DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
-  DevBuf active_rows, cnorm, gram, relu, reln;
+  DevBuf active_rows, cnorm, gram, relu, reln, asg_a, asg_b;
   GroupState* host_gstate = nullptr;           // pinned
   DevCounters* host_counters = nullptr;        // pinned
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -113,8 +113,8 @@ const TileCfg kL2Tiles[] = {
     {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 2, 4, 1, 512, false>, k_join_l2_ares<256, 256, 2, 4, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
     {256, 128, 512, nullptr, k_join_l2_ares<256, 128, 4, 2, 1, 512, false>, k_join_l2_ares<256, 128, 4, 2, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
     {128, 128, 256, nullptr, k_join_l2_ares<128, 128, 2, 2, 2, 256, false>, k_join_l2_ares<128, 128, 2, 2, 2, 256, true>, true, sizeof(BlockQueueT<256>), 2, 2},
-    {256, 256, 512, nullptr, k_join_l2_direct<2, 4>, nullptr, true, 0, 1, 0},
-    {256, 256, 512, nullptr, k_join_l2_direct<1, 8>, nullptr, true, 0, 1, 0},
+    {256, 256, 512, nullptr, k_join_l2_direct<2, 4, kEpiJoin>, nullptr, true, 0, 1, 0},
+    {256, 256, 512, nullptr, k_join_l2_direct<1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
 };
 constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles: streaming, 256 x 256, 8 waves
 constexpr int kResidentL2Tile = 11;               // head-resident, 256 x 256, 8 waves (2 x 4)
@@ -299,24 +299,62 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
     int32_t* unc_next = (int32_t*)hd->unc_b.p;
     const float radius_mult = hd->cfg.group_radius > 0.f ? hd->cfg.group_radius : 2.0f;
     const float tau = delta > 0.f ? radius_mult * delta : 0.f;
-    const int gN = grid_for(N, 256);
+    const int gN = grid_for(std::max<int64_t>(N, kPivotsPerRound), 256);
     k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
+    // L2 with a head tile that fits in LDS: the rows-against-pivots distances of every round run on the
+    // matrix pipes, as a join of all entities (heads, staged once in identity order) with the round's pivots
+    // (tails) whose epilogue keeps, per entity, the lowest pivot position within tau.  Otherwise (L1, large d)
+    // the float32 vector kernel does it.  Which member of a cluster ends up with which pivot does not touch
+    // the result: centres and radii are taken from the rows after the layout.
+    const bool mfma_assign = (p == 2) && KS <= kDirectMaxKS && delta > 0.f;
+    const int64_t Npad = (N + 255) / 256 * 256;
+    const size_t asg_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
+    if (mfma_assign) {
+      if ((rc = ensure(hd, hd->asg_a, (size_t)KS * Npad * kSliceK * 2)) ||
+          (rc = ensure(hd, hd->asg_b, (size_t)KS * kPivotsPerRound * kSliceK * 2)))
+        return rc;
+      // slot_ent is free until the layout fills it: identity order for the staging of the heads
+      k_identity_slots<<<grid_for(Npad, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Npad);
+      k_stage_operands<true><<<grid_for(Npad / kStageRows, 1), 256, asg_lds, st>>>(
+          E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Npad, KS, (uint16_t*)hd->asg_a.p, nullptr, nullptr,
+          nullptr, nullptr, 0, kStageRows);
+      KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_direct<2, 4, kEpiAssignMin>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)KS * 256 * kSliceK * 2)));
+    }
     for (int round = 0; round < kGroupRounds; ++round) {
       // sampling density of the pivots among the still uncovered entities: 1/16, 1/16, 1/8, 1/8, 1/4, 1/2
       static const int kShift[kGroupRounds] = {4, 4, 3, 3, 2, 1};
       k_round_begin<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->piv_ent.p, (unsigned long long*)hd->best.p,
-                                       kShift[round]);
-      TileDistArgs ta{};
-      ta.X = E; ta.dtypeX = dtype; ta.row_ids = unc; ta.n_rows_dev = &gs->n_unc; ta.n_rows = N;
-      ta.Y = E; ta.dtypeY = dtype; ta.col_ids = (const int32_t*)hd->piv_ent.p; ta.n_cols_dev = &gs->n_piv;
-      ta.n_cols = kPivotsPerRound;
-      ta.shift = nullptr; ta.dtype_shift = dtype; ta.r0 = 0; ta.d = d; ta.best = (unsigned long long*)hd->best.p;
-      ta.delta = tau;
-      const dim3 g((unsigned)((std::min<int64_t>(kPivotsPerRound, N) + 127) / 128), (unsigned)((N + 127) / 128), 1);
-      if (p == 2) k_tile_dist<2, kEpiAssign><<<g, 256, 0, st>>>(ta);
-      else k_tile_dist<1, kEpiAssign><<<g, 256, 0, st>>>(ta);
+                                       kShift[round], mfma_assign ? 1 : 0);
+      if (mfma_assign) {
+        k_stage_operands<false><<<kPivotsPerRound / kStageRows, 256, asg_lds, st>>>(
+            E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->piv_ent.p, kPivotsPerRound, KS, (uint16_t*)hd->asg_b.p, nullptr,
+            nullptr, nullptr, nullptr, 0, kStageRows);
+        JoinStreamArgs sa{};
+        sa.A = (const uint16_t*)hd->asg_a.p; sa.B = (const uint16_t*)hd->asg_b.p; sa.prm = nullptr; sa.Nslots = Npad;
+        sa.KS = KS; sa.k16 = k16; sa.nH = (int)(Npad / 256); sa.nT = kPivotsPerRound / 256; sa.r0 = 0; sa.RB = 1;
+        sa.tail_slots = kPivotsPerRound; sa.tail_rows_dev = &gs->n_piv;
+        // bf16 rows move a distance by at most 2^-8 (||e|| + ||pivot||); that much either way is of no concern here
+        sa.thr_value = tau * tau;
+        sa.best = (unsigned long long*)hd->best.p; sa.group_of = (const int32_t*)hd->group_of.p; sa.n_heads = N;
+        // the pivot tiles are dealt to 1, 2 or 4 blocks per head tile, enough to fill the chip
+        const int64_t nHa = Npad / 256;
+        const unsigned zsplit = nHa >= 1024 ? 1u : nHa >= 512 ? 2u : 4u;
+        hipLaunchKernelGGL((k_join_l2_direct<2, 4, kEpiAssignMin>), dim3((unsigned)nHa, 1, zsplit), dim3(512),
+                           (size_t)KS * 256 * kSliceK * 2, st, sa);
+      } else {
+        TileDistArgs ta{};
+        ta.X = E; ta.dtypeX = dtype; ta.row_ids = unc; ta.n_rows_dev = &gs->n_unc; ta.n_rows = N;
+        ta.Y = E; ta.dtypeY = dtype; ta.col_ids = (const int32_t*)hd->piv_ent.p; ta.n_cols_dev = &gs->n_piv;
+        ta.n_cols = kPivotsPerRound;
+        ta.shift = nullptr; ta.dtype_shift = dtype; ta.r0 = 0; ta.d = d; ta.best = (unsigned long long*)hd->best.p;
+        ta.delta = tau;
+        const dim3 g((unsigned)((std::min<int64_t>(kPivotsPerRound, N) + 127) / 128), (unsigned)((N + 127) / 128), 1);
+        if (p == 2) k_tile_dist<2, kEpiAssign><<<g, 256, 0, st>>>(ta);
+        else k_tile_dist<1, kEpiAssign><<<g, 256, 0, st>>>(ta);
+      }
       k_round_commit<<<gN, 256, 0, st>>>(gs, unc, (const unsigned long long*)hd->best.p, (int32_t*)hd->group_of.p,
-                                        unc_next);
+                                        unc_next, mfma_assign ? 1 : 0);
       k_round_end<<<1, 64, 0, st>>>(gs);
       std::swap(unc, unc_next);
     }
@@ -426,7 +464,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
       if (delta >= 0.f && p == 2) {
         k_rel_centre_dot<<<grid_for((n_micro + 1) * RB * 64, 256), 256, 0, st>>>(
             Rvecs, dtype, d, (int)r0, RB, (const float*)hd->cent.p, n_micro, (float*)hd->relu.p, (float*)hd->reln.p);
-        BoundL2Args ba;
+        BoundL2Args ba{};
         ba.D = (const float*)hd->gram.p; ba.u = (const float*)hd->relu.p; ba.rn = (const float*)hd->reln.p;
         ba.rad = (const float*)hd->rad.p; ba.cnorm = (const float*)hd->cnorm.p; ba.n_micro = n_micro; ba.RB = RB;
         ba.d = d; ba.delta = delta; ba.bitmap = (uint32_t*)hd->bitmap.p; ba.nH = nH; ba.words_per_row = words_per_row;
@@ -467,7 +505,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
       if (tc.stream_kernel) {
-        JoinStreamArgs sa;
+        JoinStreamArgs sa{};      // the fields a launch does not use stay zero
         sa.A = (const uint16_t*)hd->opA.p; sa.B = (const uint16_t*)hd->opB.p; sa.prm = prm; sa.Nslots = Nslots;
         sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = (int)r0; sa.RB = RB;
         sa.row_start = row_start; sa.row_count = row_count; sa.cols = cols; sa.active_rows = active_rows;
@@ -496,14 +534,14 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
         const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit);
         hipLaunchKernelGGL(kern, grid, dim3(tc.threads), dyn_lds, st, sa);
       } else {
-        JoinArgs ja;
+        JoinArgs ja{};
         ja.A = (const uint16_t*)hd->opA.p; ja.B = (const uint16_t*)hd->opB.p; ja.prm = prm;
         ja.Nslots = Nslots; ja.KS = KS; ja.k16 = k16; ja.nH = nH; ja.nT = nT; ja.r0 = (int)r0; ja.RB = RB; ja.cx = cx;
         hipLaunchKernelGGL(tc.tile_kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);
       }
       KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else {
-      JoinL1Args la;
+      JoinL1Args la{};
       la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = (int)r0; la.RB = RB;
       la.row_start = row_start; la.row_count = row_count; la.cols = cols; la.active_rows = active_rows;
       la.n_active = n_active; la.cx = cx;

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
       uint16_t o = 0;
       if (ent >= 0) {
         float v = ld_elem(E, (int64_t)ent * d + c, dtype);
-        if (IS_A) v += ld_elem(Rv, ro + c, dtype);
+        if (IS_A && Rv) v += ld_elem(Rv, ro + c, dtype);     // Rv == nullptr: the plain row (a = h)
         o = f32_to_bf16_rne(v);
       }
       tile[row * W + c] = o;
@@ -402,7 +402,16 @@ struct JoinStreamArgs {
   const uint32_t* active_rows;   // pruned mode: the rows with row_count > 0 ...
   const unsigned int* n_active;  // ... and how many there are; the grid strides over them
   RecheckCtx cx;
+  // Group assignment (k_join_l2_direct<.., kEpiAssignMin>): heads are all entities in identity order, tails
+  // the pivots of a covering round, staged in an array of their own with tail_slots rows.
+  int64_t tail_slots;                 // rows per K slice of B when it differs from Nslots (0: the same)
+  const int32_t* tail_rows_dev;       // device count of valid tail rows (tail tiles past it are skipped); may be NULL
+  float thr_value;                    // filter threshold on the squared distance when prm == NULL
+  unsigned long long* best;           // per entity: min over the pivots within reach of (pivot position << 32)
+  const int32_t* group_of;            // entities that already belong to a group (>= 0) are left alone
+  int64_t n_heads;                    // entities (head slots past it are padding)
 };
+enum { kEpiJoin = 0, kEpiAssignMin = 1 };
 
 // LISTED: the block walks tile lists (pruned mode); otherwise the grid enumerates the dense problem and the
 // kernel holds no load of the list in its inner loop (such a load would make every tile end wait for all
@@ -837,7 +846,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
 // a block drift apart, so that one wave's MFMAs cover the other's waits.  The waves that share tail columns
 // (same wn) read the same lines, mostly one after the other out of the CU's vector cache.
 // LDS: KS * 256 * 64 bytes (KS <= 9, d <= 282).  Candidates are re-scored by the owning wave.
-template <int WGM, int WGN>
+template <int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinStreamArgs a) {
   constexpr int BM = 256, BN = 256;
   constexpr int NT = WGM * WGN * 64;
@@ -854,11 +863,17 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
   const int wm = wave / WGN, wn = wave % WGN;
 
   const int tH = (int)blockIdx.x, rl = (int)blockIdx.y;
-  const int t_begin = (int)(((int64_t)a.nT * blockIdx.z) / gridDim.z);
-  const int t_end = (int)(((int64_t)a.nT * (blockIdx.z + 1)) / gridDim.z);
+  int nT = a.nT;
+  if (EPI == kEpiAssignMin && a.tail_rows_dev) {          // only the tail tiles that hold pivots of this round
+    const int used = (*a.tail_rows_dev + BN - 1) / BN;
+    nT = used < nT ? used : nT;
+  }
+  const int t_begin = (int)(((int64_t)nT * blockIdx.z) / gridDim.z);
+  const int t_end = (int)(((int64_t)nT * (blockIdx.z + 1)) / gridDim.z);
   const int ntiles = t_end - t_begin;
   if (ntiles <= 0) return;
-  const int64_t slice_bytes = a.Nslots * ROWB;
+  const int64_t slice_bytes_a = a.Nslots * ROWB;
+  const int64_t slice_bytes = (a.tail_slots ? a.tail_slots : a.Nslots) * ROWB;
 
   // ---- head tile: all K slices into LDS, once (swizzled as in the other forms) ----
   {
@@ -869,7 +884,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
     for (int ks = 0; ks < KS; ++ks) {
       uint4 t[LA];
 #pragma unroll
-      for (int i = 0; i < LA; ++i) t[i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+      for (int i = 0; i < LA; ++i) t[i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes_a + voff + (uint32_t)(i * NT * 16));
 #pragma unroll
       for (int i = 0; i < LA; ++i) *(uint4*)(&lds[ks * ASZ + st0 + i * st_step]) = t[i];
     }
@@ -911,7 +926,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
   __builtin_bit_cast(bf16x8_t, u32x4_t{Q[8 * (J) + 4 * (STEP)], Q[8 * (J) + 4 * (STEP) + 1],      \
                                        Q[8 * (J) + 4 * (STEP) + 2], Q[8 * (J) + 4 * (STEP) + 3]})
 
-  const float thr = a.prm->thr;
+  const float thr = a.prm ? a.prm->thr : a.thr_value;
   const int last_two = (a.k16 - (KS - 1) * 2) >= 2;
   int ck = 0, ct = 0;
   f32x16_t acc[TM][TN];
@@ -968,12 +983,26 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
             }                                                                                     \
           }                                                                                       \
           if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;                          \
-          recheck_and_emit(cm, a.r0 + rl, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) { \
+          auto map = [=](int e, int src, int64_t& hslot, int64_t& tslot) {                        \
             const int tile = w * 4 + (e >> 4), v = e & 15;                                        \
             const int i = tile / TN, j = tile % TN;                                               \
             hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);                     \
             tslot = tbase + j * 32 + (src & 31);                                                  \
-          });                                                                                     \
+          };                                                                                      \
+          if (EPI == kEpiJoin) {                                                                  \
+            recheck_and_emit(cm, a.r0 + rl, a.cx, map);                                           \
+          } else {                                                                                \
+            /* every lane files its own elements; the lowest pivot position within reach wins (only the */ \
+            /* position matters to the round: the low word, a distance in the float32 form, stays 0)   */ \
+            while (cm) {                                                                          \
+              const int e = (int)__builtin_ctzll(cm);                                             \
+              cm &= cm - 1ull;                                                                    \
+              int64_t hslot, tslot;                                                               \
+              map(e, lane, hslot, tslot);                                                         \
+              if (hslot < a.n_heads && a.group_of[hslot] < 0)                                     \
+                atomicMin(&a.best[hslot], (unsigned long long)(uint32_t)tslot << 32);             \
+            }                                                                                     \
+          }                                                                                       \
         }                                                                                         \
       }                                                                                           \
       ck = 0;                                                                                     \

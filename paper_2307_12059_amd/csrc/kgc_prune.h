@@ -44,25 +44,27 @@ __global__ void k_group_init(GroupState* gs, int32_t* unc, int32_t* group_of, in
 
 // Start of a round: pivots are an even-stride sample (one in 2^shift, at most kPivotsPerRound) of the
 // uncovered list; nearest-pivot records are reset.
+// `best` is indexed by the position in the uncovered list, or (by_entity) by the entity itself; the pivot
+// list is padded with -1 up to kPivotsPerRound (the grid covers max(N, kPivotsPerRound) threads).
 __global__ void k_round_begin(GroupState* gs, const int32_t* unc, int32_t* piv_ent, unsigned long long* best,
-                              int shift) {
+                              int shift, int by_entity) {
   const int n_unc = gs->n_unc;
   int n_piv = n_unc >> shift;
   n_piv = n_piv < 1 ? (n_unc > 0 ? 1 : 0) : n_piv;
   n_piv = n_piv < kPivotsPerRound ? n_piv : kPivotsPerRound;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n_piv) piv_ent[i] = unc[(int64_t)i * n_unc / n_piv];   // n_piv > 0 here
-  if (i < n_unc) best[i] = ~0ull;
+  if (i < kPivotsPerRound) piv_ent[i] = i < n_piv ? unc[(int64_t)i * n_unc / n_piv] : -1;   // n_piv > 0 where read
+  if (i < n_unc) best[by_entity ? unc[i] : i] = ~0ull;
   if (i == 0) { gs->n_piv = n_piv; gs->n_unc_next = 0; }
 }
 
 // End of a round: an uncovered entity joins the group of the pivot the assignment found within tau, if any.
 __global__ void k_round_commit(GroupState* gs, const int32_t* unc, const unsigned long long* best,
-                               int32_t* group_of, int32_t* unc_next) {
+                               int32_t* group_of, int32_t* unc_next, int by_entity) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= gs->n_unc) return;
-  const unsigned long long b = best[i];
   const int ent = unc[i];
+  const unsigned long long b = best[by_entity ? ent : i];
   if (b != ~0ull) group_of[ent] = gs->n_groups + (int)(uint32_t)(b >> 32);
   else unc_next[atomicAdd(&gs->n_unc_next, 1)] = ent;
 }
