@@ -495,7 +495,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
       n_active = &cnt->n_active;
     }
     // pruned launches stride a fixed grid over the active rows (their number is only known on the device)
-    const unsigned row_grid = (unsigned)std::min<int64_t>((int64_t)RB * nH, 4096);
+    const unsigned row_grid = (unsigned)std::min<int64_t>((int64_t)RB * nH, getenv("KGC_ROW_GRID") ? atoi(getenv("KGC_ROW_GRID")) : 4096);
     if (p == 2) {
       const int stage_grid = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 16384)
                                    : grid_for((int64_t)RB * (Nslots / kStageRows), 1);

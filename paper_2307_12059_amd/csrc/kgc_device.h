@@ -132,6 +132,88 @@ __device__ __forceinline__ double group16_exact_dist(const RecheckCtx& cx, int32
   return p2 ? sqrt(s) : s;
 }
 
+// NC candidates of one relation at once (same arithmetic per candidate as group16_exact_dist): the loads of
+// all of them are requested before any is used, so a drain step of the block-cooperative second stage pays
+// one memory round trip per 16 x 4 (float32) or 16 x 8 (bfloat16) dimensions for NC candidates.  A negative
+// h or t marks an absent candidate (its result is unused).
+template <int NC>
+__device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, const int32_t (&h)[NC], const int32_t (&t)[NC],
+                                                         int32_t r, int sub, double (&out)[NC]) {
+  const int d = cx.d;
+  const bool p2 = cx.p == 2;
+  const int64_t ro = (int64_t)r * d;
+  int64_t ho[NC], to[NC];
+  double s0[NC], s1[NC];                 // two partial sums per candidate, as in the single form
+#pragma unroll
+  for (int n = 0; n < NC; ++n) {
+    const bool ok = h[n] >= 0 && t[n] >= 0;
+    ho[n] = (int64_t)(ok ? h[n] : 0) * d;
+    to[n] = (int64_t)(ok ? t[n] : 0) * d;
+    s0[n] = 0.0; s1[n] = 0.0;
+  }
+  if (cx.dtype == KGC_F32 && (d & 3) == 0) {
+    const float4* rv = (const float4*)((const float*)cx.Rv + ro);
+    const int nch = d >> 2;
+#pragma unroll 1
+    for (int c = sub; c < nch; c += 16) {
+      const float4 rr = rv[c];
+      float4 x[NC], y[NC];
+#pragma unroll
+      for (int n = 0; n < NC; ++n) {
+        x[n] = ((const float4*)((const float*)cx.E + ho[n]))[c];
+        y[n] = ((const float4*)((const float*)cx.E + to[n]))[c];
+      }
+#pragma unroll
+      for (int n = 0; n < NC; ++n) {
+        const double q0 = ((double)x[n].x + (double)rr.x) - (double)y[n].x, q1 = ((double)x[n].y + (double)rr.y) - (double)y[n].y;
+        const double q2 = ((double)x[n].z + (double)rr.z) - (double)y[n].z, q3 = ((double)x[n].w + (double)rr.w) - (double)y[n].w;
+        s0[n] += p2 ? (q0 * q0 + q1 * q1) : (fabs(q0) + fabs(q1));
+        s1[n] += p2 ? (q2 * q2 + q3 * q3) : (fabs(q2) + fabs(q3));
+      }
+    }
+  } else if (cx.dtype == KGC_BF16 && (d & 7) == 0) {
+    const uint4* rv = (const uint4*)((const uint16_t*)cx.Rv + ro);
+    const int nch = d >> 3;
+#pragma unroll 1
+    for (int c = sub; c < nch; c += 16) {
+      const uint4 rr = rv[c];
+      uint4 x[NC], y[NC];
+#pragma unroll
+      for (int n = 0; n < NC; ++n) {
+        x[n] = ((const uint4*)((const uint16_t*)cx.E + ho[n]))[c];
+        y[n] = ((const uint4*)((const uint16_t*)cx.E + to[n]))[c];
+      }
+      const uint32_t rw[4] = {rr.x, rr.y, rr.z, rr.w};
+#pragma unroll
+      for (int n = 0; n < NC; ++n) {
+        const uint32_t xw[4] = {x[n].x, x[n].y, x[n].z, x[n].w}, yw[4] = {y[n].x, y[n].y, y[n].z, y[n].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const double xl = ((double)__uint_as_float(xw[q] << 16) + (double)__uint_as_float(rw[q] << 16)) -
+                            (double)__uint_as_float(yw[q] << 16);
+          const double xh = ((double)__uint_as_float(xw[q] & 0xffff0000u) + (double)__uint_as_float(rw[q] & 0xffff0000u)) -
+                            (double)__uint_as_float(yw[q] & 0xffff0000u);
+          s0[n] += p2 ? xl * xl : fabs(xl);
+          s1[n] += p2 ? xh * xh : fabs(xh);
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int n = 0; n < NC; ++n) out[n] = (h[n] >= 0 && t[n] >= 0) ? group16_exact_dist(cx, h[n], r, t[n], sub) : 0.0;
+    return;
+  }
+#pragma unroll
+  for (int n = 0; n < NC; ++n) {
+    double s = s0[n] + s1[n];
+    s += __shfl_xor(s, 8, 16);
+    s += __shfl_xor(s, 4, 16);
+    s += __shfl_xor(s, 2, 16);
+    s += __shfl_xor(s, 1, 16);
+    out[n] = p2 ? sqrt(s) : s;
+  }
+}
+
 // ---- second stage: exact re-scoring of filter candidates + compaction ----
 // `cm` holds, per lane, one bit for each of up to 64 accumulator elements of this lane that passed
 // the low-precision filter.  `map(e, lane, hslot, tslot)` turns (element, owning lane) into the two
@@ -194,12 +276,14 @@ struct BlockQueueT {
   unsigned int flag;       // set by any wave whose tile has candidates; read after the block barrier
   unsigned int nhits;      // hits staged in this round
   unsigned long long base; // where this round's hits go in the output (one global atomic per round)
-  unsigned long long ent[CAP];   // (hslot << 32) | tslot
+  unsigned long long ent[CAP];   // (hslot << 32) | tslot when pushed, then (head entity << 32) | tail entity (0xffffffff: padding row)
   kgc_triple hits[CAP];          // hits of this round, copied out together
 };
 using BlockQueue = BlockQueueT<512>;
 
-template <int NWAVES, int NW, typename Queue, typename MapFn>
+// DRAIN: candidates per 16-lane group and drain step (their loads are in flight together); a kernel that is
+// short of registers takes 1.
+template <int NWAVES, int NW, int DRAIN, typename Queue, typename MapFn>
 __device__ __forceinline__ void block_recheck(unsigned long long (&cm)[NW], int32_t r, const RecheckCtx& cx,
                                               Queue* q, MapFn map) {
   constexpr int kQueueCap = Queue::kCap;
@@ -238,27 +322,40 @@ __device__ __forceinline__ void block_recheck(unsigned long long (&cm)[NW], int3
     __syncthreads();
     const unsigned int qn = q->count < (unsigned)kQueueCap ? q->count : (unsigned)kQueueCap;
     const unsigned int pend = q->pending;
-    // 2. all groups drain the queue: entry e0 + 4 * wave + group, exact distance in double, compaction
-    for (unsigned int e0 = 0; e0 < qn; e0 += NWAVES * 4) {
-      const unsigned int e = e0 + (unsigned)(wave * 4 + grp);
-      bool hit = false;
-      float distf = 0.f;
-      int32_t h = -1, t = -1;
-      if (e < qn) {
-        const unsigned long long ent = q->ent[e];
-        h = cx.slot_ent[(int64_t)(uint32_t)(ent >> 32)];
-        t = cx.slot_ent[(int64_t)(uint32_t)(ent & 0xffffffffull)];
-        if (h >= 0 && t >= 0) {
-          const double dist = group16_exact_dist(cx, h, r, t, sub);
-          hit = dist <= cx.delta;
-          distf = (float)dist;
+    // 1b. slots -> entity numbers for the whole queue at once, one entry per thread, so that a drain step
+    //     has one memory round trip (the rows) instead of two in a row; -1 (padding) becomes 0xffffffff
+    for (unsigned int i = threadIdx.x; i < qn; i += NWAVES * 64) {
+      const unsigned long long ent = q->ent[i];
+      q->ent[i] = ((unsigned long long)(uint32_t)cx.slot_ent[(int64_t)(uint32_t)(ent >> 32)] << 32) |
+                  (unsigned long long)(uint32_t)cx.slot_ent[(int64_t)(uint32_t)ent];
+    }
+    __syncthreads();
+    // 2. all groups drain the queue, kDrain entries per group and step (entry e0 + 4 * wave + group and those
+    //    NWAVES * 4 further), exact distance in double, hits staged in LDS
+    constexpr int kDrain = DRAIN;
+    for (unsigned int e0 = 0; e0 < qn; e0 += NWAVES * 4 * kDrain) {
+      int32_t hh[kDrain], tt[kDrain];
+      double dd[kDrain];
+#pragma unroll
+      for (int n = 0; n < kDrain; ++n) {
+        const unsigned int e = e0 + (unsigned)(n * NWAVES * 4 + wave * 4 + grp);
+        hh[n] = -1; tt[n] = -1;
+        if (e < qn) {
+          const unsigned long long ent = q->ent[e];
+          hh[n] = (int32_t)(uint32_t)(ent >> 32);
+          tt[n] = (int32_t)(uint32_t)ent;
+          if (sub == 0) ++ncand;
         }
-        if (sub == 0) ++ncand;
       }
-      if (hit && sub == 0) {
-        kgc_triple rec;
-        rec.h = h; rec.r = r; rec.t = t; rec.dist = distf;
-        q->hits[atomicAdd(&q->nhits, 1u)] = rec;             // LDS atomic; at most one hit per entry
+      group16_exact_dist_multi<kDrain>(cx, hh, tt, r, sub, dd);
+      if (sub == 0) {
+#pragma unroll
+        for (int n = 0; n < kDrain; ++n)
+          if (hh[n] >= 0 && tt[n] >= 0 && dd[n] <= cx.delta) {
+            kgc_triple rec;
+            rec.h = hh[n]; rec.r = r; rec.t = tt[n]; rec.dist = (float)dd[n];
+            q->hits[atomicAdd(&q->nhits, 1u)] = rec;         // LDS atomic; at most one hit per entry
+          }
       }
     }
     __syncthreads();

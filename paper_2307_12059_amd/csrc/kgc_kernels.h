@@ -793,13 +793,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
         }                                                                                         \
         const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
         const int64_t tbase = (int64_t)done_tcol * BN + wn * WTN;                                 \
-        block_recheck<WGM * WGN, NW>(cm, a.r0 + rl, a.cx, &queue,                                 \
+        block_recheck<WGM * WGN, NW, 4>(cm, a.r0 + rl, a.cx, &queue,                                 \
                                      [=](int e, int src, int64_t& hslot, int64_t& tslot) {        \
           const int tile = e >> 4, v = e & 15;                                                    \
           const int i = tile / TN, j = tile % TN;                                                 \
           hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);                       \
           tslot = tbase + j * 32 + (src & 31);                                                    \
         });                                                                                       \
+        /* The accumulators are dead by now (the next tile starts from a zero C operand); writing them */ \
+        /* here says so to the compiler, which then has their 128 registers for the exact path above.  */ \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
+          _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;                    \
       }                                                                                           \
     }                                                                                             \
   } while (0)
@@ -1138,7 +1143,7 @@ __global__ __launch_bounds__(256, 3) void k_join_l1(const JoinL1Args a) {
     __syncthreads();
     if (queue.flag) {
       const int64_t hbase = (int64_t)tH * BM, tbase = (int64_t)tT * BN;
-      block_recheck<4, 1>(cm, r, a.cx, &queue, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
+      block_recheck<4, 1, 1>(cm, r, a.cx, &queue, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
         const int stid = wave * 64 + src;
         const int sx = stid & 15, sy = stid >> 4;
         const int i = e >> 3, j = e & 7;
