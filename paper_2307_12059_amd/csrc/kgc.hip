@@ -462,8 +462,14 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
       const int64_t bm_words = (int64_t)RB * nH * words_per_row;
       k_fill_u32<<<grid_for(bm_words, 256), 256, 0, st>>>((uint32_t*)hd->bitmap.p, bm_words, 0u);
       if (delta >= 0.f && p == 2) {
-        k_rel_centre_dot<<<grid_for((n_micro + 1) * RB * 64, 256), 256, 0, st>>>(
-            Rvecs, dtype, d, (int)r0, RB, (const float*)hd->cent.p, n_micro, (float*)hd->relu.p, (float*)hd->reln.p);
+        // u[rl][m] = r . c_m as a tiled product, ||r||^2 by one wave per relation
+        k_rel_centre_dot<<<grid_for((int64_t)RB * 64, 256), 256, 0, st>>>(
+            Rvecs, dtype, d, (int)r0, RB, (const float*)hd->cent.p, 0, (float*)hd->relu.p, (float*)hd->reln.p);
+        TileDistArgs td{};
+        td.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); td.dtypeX = dtype; td.n_rows = RB;
+        td.Y = hd->cent.p; td.dtypeY = KGC_F32; td.n_cols = n_micro; td.shift = nullptr; td.dtype_shift = KGC_F32;
+        td.d = d; td.matrix = (float*)hd->relu.p;
+        k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((n_micro + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(td);
         BoundL2Args ba{};
         ba.D = (const float*)hd->gram.p; ba.u = (const float*)hd->relu.p; ba.rn = (const float*)hd->reln.p;
         ba.rad = (const float*)hd->rad.p; ba.cnorm = (const float*)hd->cnorm.p; ba.n_micro = n_micro; ba.RB = RB;

@@ -184,7 +184,7 @@ __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E
 
 // ---------------------------------------------------------------------------------------------
 // Generic 128 x 128 distance tile in float32 vector arithmetic (no MFMA): rows x_i (+ shift), columns y_j,
-// dist_p(x_i + shift, y_j) for p = 1 or 2, K staged through LDS in 16-dimension slices, 8 x 8 results
+// dist_p(x_i + shift, y_j) for p = 1 or 2 (p = 0: the dot product x_i . y_j, MATRIX epilogue only), K staged through LDS in 16-dimension slices, 8 x 8 results
 // per thread.  Two epilogues:
 //   ASSIGN  first column within delta (= the group radius tau) of every row -> atomicMin on a packed
 //           (column position, distance bits) word
@@ -264,8 +264,12 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
       for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          const float x = av[i] - bv[j];
-          acc[i][j] += (P == 2) ? x * x : fabsf(x);
+          if (P == 0) {
+            acc[i][j] += av[i] * bv[j];
+          } else {
+            const float x = av[i] - bv[j];
+            acc[i][j] += (P == 2) ? x * x : fabsf(x);
+          }
         }
     }
   }
@@ -377,23 +381,20 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
   // block = 256 tail micro-tiles x kHeadChunk head micro-tiles x kRelChunk relations; the per-head and
   // per-relation scalars sit in LDS, the thread's own r.c_T values in registers, so one test costs one
   // (shared) D load per kRelChunk relations and a handful of VALU operations
-  __shared__ float uH[kRelChunk][kHeadChunk];
-  __shared__ float rnS[kRelChunk], srnS[kRelChunk];
+  __shared__ float aH[kHeadChunk][kRelChunk];       // 2 r.c_H + ||r||^2 per (head micro-tile, relation)
+  __shared__ float srnS[kRelChunk];
   __shared__ float radH[kHeadChunk], cnH[kHeadChunk];
   const int tid = threadIdx.x;
   const int64_t mT = (int64_t)blockIdx.x * blockDim.x + tid;
   const int64_t mH0 = (int64_t)blockIdx.y * kHeadChunk;
   const int rl0 = (int)blockIdx.z * kRelChunk;
   {
-    const int q = tid / kHeadChunk, hq = tid % kHeadChunk;      // 256 threads = kRelChunk x kHeadChunk
+    const int hq = tid / kRelChunk, q = tid % kRelChunk;        // 256 threads = kHeadChunk x kRelChunk
     const int rl = rl0 + q;
     const int64_t mH = mH0 + hq;
-    uH[q][hq] = (rl < a.RB && mH < a.n_micro) ? a.u[(int64_t)rl * a.n_micro + mH] : 0.f;
-    if (tid < kRelChunk) {
-      const float v = (rl0 + tid < a.RB) ? a.rn[rl0 + tid] : 0.f;
-      rnS[tid] = v;
-      srnS[tid] = sqrtf(v);
-    }
+    const float rnq = rl < a.RB ? a.rn[rl] : 0.f;
+    aH[hq][q] = (rl < a.RB && mH < a.n_micro) ? 2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f) : 0.f;
+    if (tid < kRelChunk) srnS[tid] = sqrtf((rl0 + tid < a.RB) ? a.rn[rl0 + tid] : 0.f);
     if (tid < kHeadChunk) {
       const int64_t m = mH0 + tid;
       radH[tid] = m < a.n_micro ? a.rad[m] : -1.f;
@@ -405,27 +406,34 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
   const float rT = a.rad[mT];
   if (rT < 0.f) return;                                          // empty micro-tile
   const float cT = a.cnorm[mT];
-  float uT[kRelChunk];
+  // dist^2 <= lim + ek sqrt(rn)   <=>   (2 u_H + rn) - 2 u_T - ek sqrt(rn) <= lim - D: the left side needs one
+  // subtraction and one fused multiply-add per relation, the right side is formed once per micro-tile pair.
+  // The four extra roundings of this order (each at most 2^-24 of |2 u_H + rn|, |2 u_T| or D) are paid for
+  // on the keeping side: 4 more units in the (d + 8) factor of ek, 2.4e-7 of rn and of D.
+  float bT[kRelChunk];
   const int nrel = a.RB - rl0 < kRelChunk ? a.RB - rl0 : kRelChunk;
 #pragma unroll
-  for (int q = 0; q < kRelChunk; ++q) uT[q] = q < nrel ? a.u[(int64_t)(rl0 + q) * a.n_micro + mT] : 0.f;
+  for (int q = 0; q < kRelChunk; ++q) bT[q] = q < nrel ? 2.f * a.u[(int64_t)(rl0 + q) * a.n_micro + mT] : -3e38f;
   const int tT = (int)(mT / a.micro_per_bn);
   const float dsl = a.delta * (1.f + kBoundSlack);
-  const float kk = 2.f * (float)(a.d + 8) * 6e-8f;
+  const float kk = 2.f * (float)(a.d + 12) * 6e-8f;
   for (int hq = 0; hq < kHeadChunk; ++hq) {
     const float rH = radH[hq];
     if (rH < 0.f) continue;                                      // empty or past the end
     const int64_t mH = mH0 + hq;
     const float D = a.D[mH * a.n_micro + mT];
     const float reach = dsl + rH + rT;
-    const float lim = reach * reach * (1.f + kBoundSlack) + D * 9.6e-7f;
+    const float rhs = reach * reach * (1.f + kBoundSlack) + D * 1.2e-6f - D;
     const float ek = kk * (cnH[hq] + cT);
     const int tH = (int)(mH / a.micro_per_bm);
+    uint32_t keep = 0u;
 #pragma unroll
-    for (int q = 0; q < kRelChunk; ++q) {
-      const float dist2 = D + 2.f * (uH[q][hq] - uT[q]) + rnS[q];
-      if (q < nrel && dist2 <= lim + ek * srnS[q])
-        atomicOr(&a.bitmap[((int64_t)(rl0 + q) * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
+    for (int q = 0; q < kRelChunk; ++q)
+      keep |= (aH[hq][q] - bT[q] - ek * srnS[q] <= rhs) ? (1u << q) : 0u;     // past the batch: bT = -3e38 never passes
+    while (keep) {
+      const int q = __builtin_ctz(keep);
+      keep &= keep - 1u;
+      atomicOr(&a.bitmap[((int64_t)(rl0 + q) * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
     }
   }
 }
