@@ -113,13 +113,16 @@ const TileCfg kL2Tiles[] = {
     {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 2, 4, 1, 512, false>, k_join_l2_ares<256, 256, 2, 4, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
     {256, 128, 512, nullptr, k_join_l2_ares<256, 128, 4, 2, 1, 512, false>, k_join_l2_ares<256, 128, 4, 2, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
     {128, 128, 256, nullptr, k_join_l2_ares<128, 128, 2, 2, 2, 256, false>, k_join_l2_ares<128, 128, 2, 2, 2, 256, true>, true, sizeof(BlockQueueT<256>), 2, 2},
-    {256, 256, 512, nullptr, k_join_l2_direct<2, 4, kEpiJoin>, nullptr, true, 0, 1, 0},
-    {256, 256, 512, nullptr, k_join_l2_direct<1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
+    {256, 256, 512, nullptr, k_join_l2_direct<256, 2, 4, kEpiJoin>, nullptr, true, 0, 1, 0},
+    {256, 256, 512, nullptr, k_join_l2_direct<256, 1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
+    {128, 256, 512, nullptr, k_join_l2_direct<128, 1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
 };
 constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles: streaming, 256 x 256, 8 waves
 constexpr int kResidentL2Tile = 11;               // head-resident, 256 x 256, 8 waves (2 x 4)
 constexpr int kDirectL2Tile = 14;                 // head-resident and barrier-free (dense mode only), 8 waves (2 x 4)
 constexpr int kDirectMaxKS = 9;                   // its head tile then takes 144 of the 160 KiB of LDS
+constexpr int kDirectHalfL2Tile = 16;             // the same with a 128-row head tile (wave tile 128 x 32), for larger d
+constexpr int kDirectHalfMaxKS = 19;              // 152 KiB
 constexpr int kNumL2Tiles = (int)(sizeof(kL2Tiles) / sizeof(kL2Tiles[0]));
 
 int check_common(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R) {
@@ -262,11 +265,12 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
   const int k16 = (d + kNormCols + 15) / 16;
   // automatic choice.  Dense: the barrier-free head-resident kernel while the head tile fits in LDS with
-  // some room to spare (KS <= 9, d <= 282).  Pruned: the head-resident kernel with its candidate queue
+  // some room to spare (256 rows for KS <= 9, d <= 282; 128 rows for KS <= 19, d <= 602).  Pruned: the head-resident kernel with its candidate queue
   // (KS <= 7, d <= 218).  Otherwise the streaming kernel.
   int tile_id = kDefaultL2Tile;
   if (hd->cfg.tile_cfg > 0) tile_id = hd->cfg.tile_cfg - 1;
   else if (!prune && KS <= kDirectMaxKS) tile_id = kDirectL2Tile;
+  else if (!prune && KS <= kDirectHalfMaxKS) tile_id = kDirectHalfL2Tile;
   else if (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds) tile_id = kResidentL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
   if (p == 2 && prune && !tc.listed_kernel)
@@ -306,7 +310,10 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
     // (tails) whose epilogue keeps, per entity, the lowest pivot position within tau.  Otherwise (L1, large d)
     // the float32 vector kernel does it.  Which member of a cluster ends up with which pivot does not touch
     // the result: centres and radii are taken from the rows after the layout.
-    const bool mfma_assign = (p == 2) && KS <= kDirectMaxKS && delta > 0.f;
+    const bool mfma_assign = (p == 2) && KS <= kDirectHalfMaxKS && delta > 0.f;
+    const int abm = KS <= kDirectMaxKS ? 256 : 128;           // head tile height of the assignment kernel
+    void (*assign_kernel)(const JoinStreamArgs) =
+        abm == 256 ? k_join_l2_direct<256, 2, 4, kEpiAssignMin> : k_join_l2_direct<128, 1, 8, kEpiAssignMin>;
     const int64_t Npad = (N + 255) / 256 * 256;
     const size_t asg_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
     if (mfma_assign) {
@@ -318,8 +325,8 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
       k_stage_operands<true><<<grid_for(Npad / kStageRows, 1), 256, asg_lds, st>>>(
           E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Npad, KS, (uint16_t*)hd->asg_a.p, nullptr, nullptr,
           nullptr, nullptr, 0, kStageRows);
-      KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_direct<2, 4, kEpiAssignMin>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)KS * 256 * kSliceK * 2)));
+      KGC_HIP(hd, hipFuncSetAttribute((const void*)assign_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)((size_t)KS * abm * kSliceK * 2)));
     }
     for (int round = 0; round < kGroupRounds; ++round) {
       // sampling density of the pivots among the still uncovered entities: 1/16, 1/16, 1/8, 1/8, 1/4, 1/2
@@ -332,16 +339,15 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
             nullptr, nullptr, nullptr, 0, kStageRows);
         JoinStreamArgs sa{};
         sa.A = (const uint16_t*)hd->asg_a.p; sa.B = (const uint16_t*)hd->asg_b.p; sa.prm = nullptr; sa.Nslots = Npad;
-        sa.KS = KS; sa.k16 = k16; sa.nH = (int)(Npad / 256); sa.nT = kPivotsPerRound / 256; sa.r0 = 0; sa.RB = 1;
+        sa.KS = KS; sa.k16 = k16; sa.nH = (int)(Npad / abm); sa.nT = kPivotsPerRound / 256; sa.r0 = 0; sa.RB = 1;
         sa.tail_slots = kPivotsPerRound; sa.tail_rows_dev = &gs->n_piv;
         // bf16 rows move a distance by at most 2^-8 (||e|| + ||pivot||); that much either way is of no concern here
         sa.thr_value = tau * tau;
         sa.best = (unsigned long long*)hd->best.p; sa.group_of = (const int32_t*)hd->group_of.p; sa.n_heads = N;
         // the pivot tiles are dealt to 1, 2 or 4 blocks per head tile, enough to fill the chip
-        const int64_t nHa = Npad / 256;
+        const int64_t nHa = Npad / abm;
         const unsigned zsplit = nHa >= 1024 ? 1u : nHa >= 512 ? 2u : 4u;
-        hipLaunchKernelGGL((k_join_l2_direct<2, 4, kEpiAssignMin>), dim3((unsigned)nHa, 1, zsplit), dim3(512),
-                           (size_t)KS * 256 * kSliceK * 2, st, sa);
+        hipLaunchKernelGGL(assign_kernel, dim3((unsigned)nHa, 1, zsplit), dim3(512), (size_t)KS * abm * kSliceK * 2, st, sa);
       } else {
         TileDistArgs ta{};
         ta.X = E; ta.dtypeX = dtype; ta.row_ids = unc; ta.n_rows_dev = &gs->n_unc; ta.n_rows = N;

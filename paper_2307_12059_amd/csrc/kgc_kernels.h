@@ -850,10 +850,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
 // waves, so it holds no barrier and no LDS store: the LDS only serves the head fragments, and the waves of
 // a block drift apart, so that one wave's MFMAs cover the other's waits.  The waves that share tail columns
 // (same wn) read the same lines, mostly one after the other out of the CU's vector cache.
-// LDS: KS * 256 * 64 bytes (KS <= 9, d <= 282).  Candidates are re-scored by the owning wave.
-template <int WGM, int WGN, int EPI>
+// LDS: KS * BM * 64 bytes: BM = 256 up to KS = 9 (d <= 282), BM = 128 up to KS = 19 (d <= 602).  In the join
+// form (EPI = kEpiJoin) candidates are re-scored by the owning wave; kEpiAssignMin is the epilogue of the
+// group assignment (see JoinStreamArgs).
+template <int BM, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinStreamArgs a) {
-  constexpr int BM = 256, BN = 256;
+  constexpr int BN = 256;
   constexpr int NT = WGM * WGN * 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;

@@ -56,7 +56,7 @@ PRUNE_OFF, PRUNE_ON = 1, 2
 
 
 @pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
-@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
+@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17])
 def test_c1_l2_full_parity(tile_cfg, prune):
     if prune == PRUNE_ON and (1 <= tile_cfg <= 5 or tile_cfg >= 15):
         pytest.skip("one-block-per-tile and barrier-free variants have no pruned mode")
@@ -84,7 +84,8 @@ def test_c1_l1_full_parity(prune):
 @pytest.mark.parametrize("p", [1, 2])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("N,R,d", [(300, 3, 37), (257, 2, 200), (129, 1, 7), (1, 1, 1), (700, 5, 122),
-                                   (600, 3, 300), (300, 2, 960), (520, 2, 218), (520, 2, 219)])
+                                   (600, 3, 300), (300, 2, 960), (520, 2, 218), (520, 2, 219), (400, 2, 282),
+                                   (400, 2, 283), (520, 2, 602), (520, 2, 603)])
 def test_ragged_shapes(p, dtype, N, R, d, prune):
     g = np.random.default_rng(N * 1000 + d)
     cent = g.standard_normal((4, d))
