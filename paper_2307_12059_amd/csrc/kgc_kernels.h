@@ -425,11 +425,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
   constexpr int ASZ = BM * kSliceK, BSZ = BN * kSliceK;      // elements per LDS buffer (64-byte rows, swizzled)
   static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
 
+  __shared__ BlockQueueT<(LISTED ? 512 : 1)> queue;          // pruned mode: candidates are re-scored by the whole block
   __shared__ __attribute__((aligned(16))) uint16_t As[2 * ASZ];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[2 * BSZ];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
+  if (LISTED && tid == 0) { queue.count = 0u; queue.pending = 0u; queue.flag = 0u; queue.nhits = 0u; }   // published by the first barrier
 
   // pruned mode: the grid strides over the rows (relation, head tile) that still have tail tiles
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
@@ -574,11 +576,42 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);
-    if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {
-      // MFMA 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
-      const int64_t hbase = (int64_t)tH * BM + wm * WTM;
-      const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;
-      constexpr int NW = (TM * TN + 3) / 4;
+    const bool has = __builtin_amdgcn_ballot_w64(mn <= thr) != 0ull;
+    // MFMA 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
+    const int64_t hbase = (int64_t)tH * BM + wm * WTM;
+    const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;
+    constexpr int NW = (TM * TN + 3) / 4;
+    if constexpr (LISTED) {
+      // Surviving tiles hold their hits in clusters: the block re-scores them together (one output atomic per
+      // round instead of one per wave step).  The decision to enter is made block-uniform through queue.flag.
+      if (has && lane == 0) queue.flag = 1u;
+      __syncthreads();
+      if (queue.flag) {
+        unsigned long long cm[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          cm[w] = 0ull;
+          if (has) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int tile = w * 4 + q;
+              if (tile < TM * TN) {
+                const int i = tile / TN, j = tile % TN;
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                  if (acc[i][j][v] <= thr) cm[w] |= 1ull << (q * 16 + v);
+              }
+            }
+          }
+        }
+        block_recheck<WGM * WGN, NW, 2>(cm, a.r0 + rl, a.cx, &queue, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
+          const int tile = e >> 4, v = e & 15;
+          const int i = tile / TN, j = tile % TN;
+          hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);
+          tslot = tbase + j * 32 + (src & 31);
+        });
+      }
+    } else if (has) {
 #pragma unroll
       for (int w = 0; w < NW; ++w) {
         unsigned long long cm = 0ull;
