@@ -59,7 +59,9 @@ typedef struct {
     void*   stream;           /* hipStream_t to enqueue on; NULL = the default stream */
     float   group_radius;     /* pruning only: radius of entity groups as a multiple of delta; 0 = 2.0 */
     int32_t range_kib;        /* dense L2 join: KiB of staged tail rows one block walks (L2 blocking); 0 = automatic */
-    int32_t reserved[4];      /* must be zero */
+    int32_t factorised;       /* 1: dense L2 joins with d <= 282 use the relation-factorised kernel (one MFMA tile
+                                 ||h - t||^2 per tile pair, then vector arithmetic per relation); same result set */
+    int32_t reserved[3];      /* must be zero */
 } kgc_config;
 
 /* Counters and timings of the last kgc_join on a handle. */
@@ -80,7 +82,8 @@ typedef struct {
     int32_t  tile_m, tile_n;    /* tile shape used (heads x tails) */
     int32_t  k_padded;          /* contraction length after appending the norm columns and padding (L2) */
     int32_t  relation_batches;
-    int32_t  join_variant;      /* which join kernel ran: 0 = L1 (VALU); for L2 the tile_cfg number that was used */
+    int32_t  join_variant;      /* which join kernel ran: 0 = L1 (VALU); for L2 the tile_cfg number that was used,
+                                   100 = the relation-factorised kernel */
     int32_t  reserved;
 } kgc_stats;
 

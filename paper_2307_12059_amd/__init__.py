@@ -33,7 +33,8 @@ class kgc_triple(ctypes.Structure):
 class kgc_config(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("max_d", ctypes.c_int32), ("prune", ctypes.c_int32),
                 ("tile_cfg", ctypes.c_int32), ("workspace_bytes", ctypes.c_int64), ("stream", ctypes.c_void_p),
-                ("group_radius", ctypes.c_float), ("range_kib", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+                ("group_radius", ctypes.c_float), ("range_kib", ctypes.c_int32), ("factorised", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 3)]
 
 
 class kgc_stats(ctypes.Structure):
@@ -137,7 +138,8 @@ class Join:
     """
 
     def __init__(self, dtype: str = "f32", prune: int = KGC_PRUNE_AUTO, tile_cfg: int = 0, max_d: int = 0,
-                 workspace_bytes: int = 0, group_radius: float = 0.0, range_kib: int = 0):
+                 workspace_bytes: int = 0, group_radius: float = 0.0, range_kib: int = 0,
+                 factorised: bool = False):
         import torch
 
         if not torch.cuda.is_available():
@@ -150,6 +152,7 @@ class Join:
         cfg.workspace_bytes = workspace_bytes
         cfg.group_radius = group_radius
         cfg.range_kib = range_kib
+        cfg.factorised = 1 if factorised else 0
         cfg.stream = torch.cuda.current_stream().cuda_stream
         rc, h = kgc_create(cfg)
         if rc != KGC_OK:

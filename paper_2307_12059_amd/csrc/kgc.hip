@@ -40,7 +40,7 @@ struct kgc_handle {
   DevBuf slot_ent, opB, opA, normsB, normsA, counters, params;
   // pruning scratch
   DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
-  DevBuf active_rows, cnorm, gram, relu, reln, asg_a, asg_b;
+  DevBuf active_rows, cnorm, gram, relu, reln, asg_a, asg_b, limr;
   GroupState* host_gstate = nullptr;           // pinned
   DevCounters* host_counters = nullptr;        // pinned
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -155,7 +155,7 @@ int kgc_create(const kgc_config* cfg, kgc_handle** out) {
   if (c.prune < KGC_PRUNE_AUTO || c.prune > KGC_PRUNE_ON) return KGC_E_INVALID;
   if (c.max_d < 0 || c.max_d > kMaxD || c.workspace_bytes < 0 || c.tile_cfg < 0 || c.tile_cfg > kNumL2Tiles)
     return KGC_E_INVALID;
-  if (!(c.group_radius >= 0.f) || c.range_kib < 0) return KGC_E_INVALID;
+  if (!(c.group_radius >= 0.f) || c.range_kib < 0 || c.factorised < 0 || c.factorised > 1) return KGC_E_INVALID;
   for (int v : c.reserved)
     if (v != 0) return KGC_E_INVALID;
   int ndev = 0;
@@ -267,8 +267,11 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   // automatic choice.  Dense: the barrier-free head-resident kernel while the head tile fits in LDS with
   // some room to spare (256 rows for KS <= 9, d <= 282; 128 rows for KS <= 19, d <= 602).  Pruned: the head-resident kernel with its candidate queue
   // (KS <= 7, d <= 218).  Otherwise the streaming kernel.
+  // the relation-factorised form (optional, dense L2 only, head tile in LDS) has one tile shape of its own
+  const bool fact = hd->cfg.factorised != 0 && p == 2 && !prune && KS <= kDirectMaxKS;
   int tile_id = kDefaultL2Tile;
-  if (hd->cfg.tile_cfg > 0) tile_id = hd->cfg.tile_cfg - 1;
+  if (fact) tile_id = kDirectL2Tile;
+  else if (hd->cfg.tile_cfg > 0) tile_id = hd->cfg.tile_cfg - 1;
   else if (!prune && KS <= kDirectMaxKS) tile_id = kDirectL2Tile;
   else if (!prune && KS <= kDirectHalfMaxKS) tile_id = kDirectHalfL2Tile;
   else if (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds) tile_id = kResidentL2Tile;
@@ -393,15 +396,19 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   const int64_t ws = hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
   const size_t opA_per_rel = (p == 2) ? (size_t)KS * Nslots * kSliceK * 2 : 0;
   int64_t RBmax = R;
-  if (p == 2) RBmax = std::max<int64_t>(1, std::min<int64_t>(R, ws / (int64_t)(opA_per_rel + Nslots * 4)));
+  if (p == 2 && !fact) RBmax = std::max<int64_t>(1, std::min<int64_t>(R, ws / (int64_t)(opA_per_rel + Nslots * 4)));
+  if (fact) RBmax = std::max<int64_t>(1, std::min<int64_t>(R, ws / (int64_t)(Nslots * 4)));       // u[r][slot]
   if (prune) RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, kMaxTileList / tiles_per_rel));
   RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, 65535));
   if (prune && tiles_per_rel > kMaxTileList) return fail(hd, KGC_E_INVALID, "N too large for the pruned tile list");
 
   if (p == 2) {
     if ((rc = ensure(hd, hd->opB, (size_t)KS * Nslots * kSliceK * 2)) ||
-        (rc = ensure(hd, hd->opA, opA_per_rel * (size_t)RBmax)) || (rc = ensure(hd, hd->normsB, Nslots * 4)) ||
-        (rc = ensure(hd, hd->normsA, (size_t)RBmax * Nslots * 4)))
+        (rc = ensure(hd, hd->opA, opA_per_rel * (size_t)(fact ? 1 : RBmax))) || (rc = ensure(hd, hd->normsB, Nslots * 4)) ||
+        (rc = ensure(hd, hd->normsA, (size_t)(fact ? 1 : RBmax) * Nslots * 4)))
+      return rc;
+    if (fact && ((rc = ensure(hd, hd->relu, (size_t)RBmax * Nslots * 4)) || (rc = ensure(hd, hd->reln, RBmax * 4)) ||
+                 (rc = ensure(hd, hd->limr, RBmax * 4))))
       return rc;
   }
   if (prune) {
@@ -448,6 +455,10 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   if (p == 2) {
     k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
         E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b, nullptr, nullptr, 0, kStageRows);
+    if (fact)     // the head side of the factorised form carries no relation: the plain rows, once
+      k_stage_operands<true><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
+          E, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p, cnt->max_a, nullptr,
+          nullptr, 0, kStageRows);
   } else {
     k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(E, N, d, dtype, cnt->max_a);
     k_row_l1_max<<<grid_for((int64_t)R * 32, 256), 256, 0, st>>>(Rvecs, R, d, dtype, cnt->max_b);
@@ -507,8 +518,37 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
       n_active = &cnt->n_active;
     }
     // pruned launches stride a fixed grid over the active rows (their number is only known on the device)
-    const unsigned row_grid = (unsigned)std::min<int64_t>((int64_t)RB * nH, getenv("KGC_ROW_GRID") ? atoi(getenv("KGC_ROW_GRID")) : 4096);
-    if (p == 2) {
+    const unsigned row_grid = (unsigned)std::min<int64_t>((int64_t)RB * nH, 4096);
+    if (fact) {
+      // u[rl][slot] = r . e for the batch (tiled float32 product; padding slots stay 0), ||r||^2, thresholds
+      k_fill_u32<<<grid_for((int64_t)RB * Nslots, 256), 256, 0, st>>>((uint32_t*)hd->relu.p, (int64_t)RB * Nslots, 0u);
+      TileDistArgs td{};
+      td.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); td.dtypeX = dtype; td.n_rows = RB;
+      td.Y = E; td.dtypeY = dtype; td.col_ids = slot_ent; td.n_cols = Nslots; td.shift = nullptr; td.dtype_shift = dtype;
+      td.d = d; td.matrix = (float*)hd->relu.p;
+      k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((Nslots + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(td);
+      k_rel_centre_dot<<<grid_for((int64_t)RB * 64, 256), 256, 0, st>>>(Rvecs, dtype, d, (int)r0, RB, nullptr, 0,
+                                                                     (float*)hd->relu.p, (float*)hd->reln.p);
+      k_fact_params<<<grid_for(RB, 256), 256, 0, st>>>(cnt, (const float*)hd->reln.p, RB, delta, dtype, d, KS * kSliceK,
+                                                      (float*)hd->limr.p);
+      KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
+      JoinFactArgs fa{};
+      fa.A = (const uint16_t*)hd->opA.p; fa.B = (const uint16_t*)hd->opB.p; fa.u = (const float*)hd->relu.p;
+      fa.limr = (const float*)hd->limr.p; fa.Nslots = Nslots; fa.KS = KS; fa.k16 = k16; fa.nH = nH; fa.nT = nT;
+      fa.r0 = (int)r0; fa.RB = RB; fa.cx = cx;
+      const size_t head_bytes = (size_t)KS * 256 * kSliceK * 2;
+      fa.rc = (int)std::max<size_t>(1, std::min<size_t>(64, (kMaxLds - head_bytes) / (256 * 4)));
+      const size_t dyn_lds = head_bytes + (size_t)fa.rc * 256 * 4;
+      // tail tiles in ranges of about 3 MiB of staged rows (they stay in L2 while the head tiles pass), cut
+      // further when there are too few head tiles to fill the chip
+      const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
+      int64_t nsplit = (nT * tile_bytes + kL2RangeBytesResident - 1) / kL2RangeBytesResident;
+      nsplit = std::max<int64_t>(nsplit, (1024 + nH - 1) / nH);
+      nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
+      KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_fact<2, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
+      hipLaunchKernelGGL((k_join_l2_fact<2, 4>), dim3((unsigned)nH, (unsigned)nsplit, 1), dim3(512), dyn_lds, st, fa);
+      KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
+    } else if (p == 2) {
       const int stage_grid = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 16384)
                                    : grid_for((int64_t)RB * (Nslots / kStageRows), 1);
       k_stage_operands<true><<<stage_grid, 256, stage_lds, st>>>(
@@ -580,7 +620,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   s.tile_m = BM; s.tile_n = BN;
   s.k_padded = (p == 2) ? k16 * 16 : d;
   s.relation_batches = nbatch;
-  s.join_variant = (p == 2) ? tile_id + 1 : 0;
+  s.join_variant = (p == 2) ? (fact ? 100 : tile_id + 1) : 0;
   // phase times from the events: [ev0 grouping ev3 | summaries + B staging ev1 | per batch: bound test + A staging | join]
   float ms = 0.f, ms_group = 0.f, ms_between = 0.f;
   (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);

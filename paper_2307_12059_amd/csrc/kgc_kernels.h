@@ -1069,6 +1069,220 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
 }
 
 // ---------------------------------------------------------------------------------------------
+// Relation-factorised dense L2 join (optional mode).  For the TransE distance of Section 4.3,
+//     ||h + r - t||^2 = ||h - t||^2 + 2 r.h - 2 r.t + ||r||^2,
+// and the only part that needs a d-long contraction per (h, t) pair, ||h - t||^2, does not depend on the
+// relation (the observation Section 5.2 makes for the tail side, taken one step further).  One block keeps
+// a 256-row head tile in LDS, forms the 256 x 256 tile G = ||h~ - t~||^2 ONCE with the matrix pipes (plain
+// entity rows on both sides, same augmented-K operands as the other forms), and then walks the relations of
+// the batch with vector arithmetic only: per relation and element one addition (G + 2 r.h) and half a
+// three-way minimum, the result compared against lim_r + 2 r.t per tail column.  The products r.e are a
+// float32 matrix u[r][slot] made beforehand by a tiled kernel.  Elements that pass go to the same exact
+// double-precision re-scoring as everywhere else, so the result set is unchanged.
+// Filter threshold: see k_fact_params.  LDS: the head tile (KS * 16 KiB) and 2 r.h of `rc` relations at a
+// time (rc KiB).
+struct JoinFactArgs {
+  const uint16_t* A;         // staged head operands of the plain entity rows: [KS][Nslots][32]
+  const uint16_t* B;         // staged tail operands: [KS][Nslots][32]
+  const float* u;            // [RB][Nslots] r . e (float32, from the caller's rows)
+  const float* limr;         // [RB] threshold on G + 2 r.h - 2 r.t, i.e. thr_r - ||r||^2
+  int64_t Nslots;
+  int KS, k16;
+  int nH, nT;
+  int r0, RB;
+  int rc;                    // relations per LDS chunk
+  RecheckCtx cx;
+};
+
+template <int WGM, int WGN>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_fact(const JoinFactArgs a) {
+  constexpr int BM = 256, BN = 256;
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int LA = (BM * 4) / NT;
+  constexpr int ASZ = BM * kSliceK;
+  constexpr int ROWB = kSliceK * 2;
+  static_assert(LA * NT == BM * 4, "tile rows must divide over the threads");
+
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [KS][BM][32] head slices, then float uh[rc][BM]
+  const int KS = a.KS;
+  float* uh = (float*)(lds + (size_t)KS * ASZ);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  const int tH = (int)blockIdx.x;
+  const int t_begin = (int)(((int64_t)a.nT * blockIdx.y) / gridDim.y);
+  const int t_end = (int)(((int64_t)a.nT * (blockIdx.y + 1)) / gridDim.y);
+  if (t_end <= t_begin) return;
+  const int64_t slice_bytes = a.Nslots * ROWB;
+
+  // ---- head tile: all K slices into LDS, once ----
+  {
+    const char* Abase = (const char*)a.A + (int64_t)tH * BM * ROWB;
+    const uint32_t voff = (uint32_t)tid * 16u;
+    const int st0 = (tid >> 2) * kSliceK + (((tid & 3) ^ lds_swizzle(tid >> 2)) * 8);
+    constexpr int st_step = (NT / 4) * kSliceK;
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 t[LA];
+#pragma unroll
+      for (int i = 0; i < LA; ++i) t[i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+#pragma unroll
+      for (int i = 0; i < LA; ++i) *(uint4*)(&lds[ks * ASZ + st0 + i * st_step]) = t[i];
+    }
+  }
+  __syncthreads();
+
+  const int rsw = lds_swizzle(lane & 31);
+  const int rd_a = (wm * WTM + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
+  const int rd_step = (((lane >> 5) ^ rsw) & 2) ? -16 : 16;
+  const uint32_t boff = (uint32_t)((wn * WTN + (lane & 31)) * ROWB + (lane >> 5) * 16);
+  const int last_two = (a.k16 - (KS - 1) * 2) >= 2;
+  // this lane's rows inside a 32-row block: 8 * (v / 4) + 4 * (lane / 32) + (v % 4); its column: lane % 32
+  const int urow = wm * WTM + 4 * (lane >> 5);
+
+  for (int tT = t_begin; tT < t_end; ++tT) {
+    // ---- G = ||h~ - t~||^2 for the 256 x 256 tile: tail fragments straight from the staged array ----
+    f32x16_t acc[TM][TN];
+    const char* pB = (const char*)a.B + (int64_t)tT * BN * ROWB + boff;
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint16_t* Ac = lds + ks * ASZ + rd_a;
+      const bool two = ks < KS - 1 || last_two;
+      bf16x8_t fb0[TN], fb1[TN], fa[TM];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        fb0[j] = *(const bf16x8_t*)(pB + j * 32 * ROWB);
+        fb1[j] = *(const bf16x8_t*)(pB + j * 32 * ROWB + 32);
+      }
+      pB += slice_bytes;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK);
+      if (ks == 0) {
+        const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb0[j], zero16, 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb0[j], acc[i][j], 0, 0, 0);
+      }
+      if (two) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK + rd_step);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb1[j], acc[i][j], 0, 0, 0);
+      }
+    }
+
+    // ---- the relations of the batch, rc at a time: 2 r.h of the head rows through LDS ----
+    const int64_t tcol0 = (int64_t)tT * BN + wn * WTN + (lane & 31);     // this lane's column of block j: + 32 j
+    for (int rl0 = 0; rl0 < a.RB; rl0 += a.rc) {
+      const int nr = a.RB - rl0 < a.rc ? a.RB - rl0 : a.rc;
+      __syncthreads();                                                    // the previous chunk has been read
+      for (int e = tid; e < nr * BM; e += NT) {
+        const int q = e / BM, row = e - q * BM;
+        uh[q * BM + row] = 2.f * a.u[(int64_t)(rl0 + q) * a.Nslots + (int64_t)tH * BM + row];
+      }
+      __syncthreads();
+      for (int q = 0; q < nr; ++q) {
+        const int rl = rl0 + q;
+        float lim[TN], mn[TN];
+        const float limr = a.limr[rl];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          lim[j] = limr + 2.f * a.u[(int64_t)rl * a.Nslots + tcol0 + 32 * j];
+          mn[j] = 3e38f;
+        }
+        const float* uq = uh + q * BM + urow;
+        // per element one addition and half a three-way minimum; the 2 r.h values of this lane's rows come
+        // from LDS, four rows per read (two addresses per wave)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int vg = 0; vg < 4; ++vg) {
+            const float4 hh = *(const float4*)(uq + i * 32 + 8 * vg);      // rows v = 4 vg .. 4 vg + 3 of block i
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              mn[j] = fminf(fminf(mn[j], acc[i][j][4 * vg + 0] + hh.x), acc[i][j][4 * vg + 1] + hh.y);
+              mn[j] = fminf(fminf(mn[j], acc[i][j][4 * vg + 2] + hh.z), acc[i][j][4 * vg + 3] + hh.w);
+            }
+          }
+        bool any = false;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) any |= mn[j] <= lim[j];
+        if (__builtin_amdgcn_ballot_w64(any) == 0ull) continue;
+        // rare: the elements of this relation that pass, then the exact path.  MFMA 32x32 accumulator layout:
+        // register v of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
+        const int64_t hbase = (int64_t)tH * BM + wm * WTM;
+        const int64_t tbase = (int64_t)tT * BN + wn * WTN;
+        constexpr int NW = (TM * TN + 3) / 4;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          unsigned long long cm = 0ull;
+#pragma unroll
+          for (int qq = 0; qq < 4; ++qq) {
+            const int tile = w * 4 + qq;
+            if (tile < TM * TN) {
+              const int i = tile / TN, j = tile % TN;
+#pragma unroll
+              for (int v = 0; v < 16; ++v)
+                if (acc[i][j][v] + uq[i * 32 + 8 * (v >> 2) + (v & 3)] <= lim[j]) cm |= 1ull << (qq * 16 + v);
+            }
+          }
+          if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;
+          recheck_and_emit(cm, a.r0 + rl, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
+            const int tile = w * 4 + (e >> 4), v = e & 15;
+            const int i = tile / TN, j = tile % TN;
+            hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);
+            tslot = tbase + j * 32 + (src & 31);
+          });
+        }
+      }
+    }
+  }
+}
+
+// Per-relation filter thresholds of the factorised join: limr[rl] = thr_r - ||r||^2, where a true hit has
+//     G + 2 r.h - 2 r.t + ||r||^2 <= thr_r = delta^2 + m (2 (delta + ||r||) + m) + e_acc + e_u:
+// G is taken on bf16-rounded rows, which moves ||h - t|| by at most m = 2^-8 1.01 (max||h~|| + max||t~||)
+// (m = 0 for bf16 storage, where rounding changes nothing), and ||h - t|| <= delta + ||r|| for a hit, hence the
+// first term; e_acc bounds the float32 accumulation of G as in k_join_params; e_u bounds the float32 error of
+// the two products (d + 8) 2^-24 ||r|| ||e|| each, doubled, and of the final sums.
+__global__ __launch_bounds__(256) void k_fact_params(const DevCounters* cnt, const float* __restrict__ rn, int RB, float delta,
+                                                     int dtype, int d, int kp, float* __restrict__ limr) {
+  __shared__ float sm[2];
+  if (threadIdx.x < 64) {
+    float ma = 0.f, mb = 0.f;
+    for (int i = threadIdx.x; i < 1024; i += 64) {
+      ma = fmaxf(ma, __uint_as_float(cnt->max_a[i]));
+      mb = fmaxf(mb, __uint_as_float(cnt->max_b[i]));
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+      ma = fmaxf(ma, __shfl_xor(ma, off, 64));
+      mb = fmaxf(mb, __shfl_xor(mb, off, 64));
+    }
+    if (threadIdx.x == 0) { sm[0] = ma; sm[1] = mb; }
+  }
+  __syncthreads();
+  const float ma = sm[0], mb = sm[1];
+  const int rl = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (rl >= RB) return;
+  if (delta < 0.f) { limr[rl] = -3e38f; return; }
+  const float na = sqrtf(ma) * 1.01f, nb = sqrtf(mb) * 1.01f;
+  const float m = dtype == KGC_BF16 ? 0.f : (1.01f / 256.f) * (na + nb);
+  const float rnorm = sqrtf(rn[rl]) * 1.0001f;
+  const float eacc = (float)(kp + 16) * 1.2e-7f * 2.f * (ma + mb);
+  const float eu = 4.f * (float)(d + 12) * 6e-8f * rnorm * (na + nb) + 1e-6f * (rn[rl] + ma + mb);
+  const float thr = (delta * delta + m * (2.f * (delta + rnorm) + m) + eacc + eu) * (1.f + 1e-6f);
+  limr[rl] = thr - rn[rl];
+}
+
+// ---------------------------------------------------------------------------------------------
 struct JoinL1Args {
   const JoinParams* prm;
   int64_t Nslots;

@@ -181,3 +181,46 @@ def test_kernel1_norms(dtype):
     np.testing.assert_allclose(nA.cpu().numpy(), refA, rtol=2e-6)
     # zero pivot (Section 4.5): sqrt(nB) is distB up to the bf16 rounding of the operand
     np.testing.assert_allclose(np.sqrt(nB.cpu().numpy()), np.linalg.norm(E.astype(np.float64), axis=1), rtol=5e-3)
+
+
+# ---- relation-factorised dense L2 join (optional mode): same result set as every other path ----
+def test_factorised_hand_case():
+    for delta, count in ((1.0, 7), (5.0, 15)):
+        got, ref, rep = _check(E3, R2, 2, delta, prune=PRUNE_OFF, factorised=True)
+        assert got["count"] == count == ref["count"]
+        assert got["stats"]["join_variant"] == 100
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_factorised_c1_parity(dtype):
+    wl = workloads.generate("c1_tiny_l2")
+    E, Rv = wl.E, wl.Rv
+    if dtype == "bf16":
+        E = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(E))
+        Rv = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(Rv))
+    got, ref, rep = _check(E, Rv, 2, wl.delta, dtype=dtype, prune=PRUNE_OFF, factorised=True)
+    assert got["stats"]["join_variant"] == 100
+    assert rep["only_gpu_in_band"] == 0 and rep["only_oracle_in_band"] == 0
+    if dtype == "f32":
+        assert ref["count"] == 3640
+    # the filter is conservative (no hit lost) and not absurdly loose
+    assert got["stats"]["candidates"] >= got["count"]
+    assert got["stats"]["candidates"] <= 50 * max(1, got["count"])
+
+
+@pytest.mark.parametrize("N,R,d", [(300, 3, 37), (257, 70, 200), (129, 1, 7), (1, 1, 1), (700, 5, 122), (400, 2, 282),
+                                   (400, 2, 283)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_factorised_ragged_shapes(dtype, N, R, d):
+    g = np.random.default_rng(N * 1000 + d + 7)
+    cent = g.standard_normal((4, d))
+    E = (cent[g.integers(0, 4, N)] + 0.1 * g.standard_normal((N, d))).astype(np.float32)
+    Rv = (cent[g.integers(0, 4, R)] - cent[g.integers(0, 4, R)] + 0.02 * g.standard_normal((R, d))).astype(np.float32)
+    if dtype == "bf16":
+        E = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(E))
+        Rv = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(Rv))
+    delta = 0.1 * np.sqrt(2.0 * d) * 1.05
+    got, ref, rep = _check(E, Rv, 2, float(np.float32(delta)), dtype=dtype, prune=PRUNE_OFF, factorised=True)
+    # d = 283 does not fit the head-resident tile: the library then takes its ordinary dense kernel
+    assert got["stats"]["join_variant"] == (100 if d <= 282 else 17)
+    assert rep["only_gpu_in_band"] == 0 and rep["only_oracle_in_band"] == 0
