@@ -63,6 +63,8 @@ def main():
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--also-dense", type=int, default=3, help="extra dense (prune off) steps reported beside a pruned run")
+    ap.add_argument("--also-factorised", type=int, default=3,
+                    help="extra dense steps through the optional relation-factorised kernel (L2, d <= 282), reported beside")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -101,8 +103,9 @@ def main():
     cap = int(4 * spec.selectivity * spec.n_triples) + 4096
     out = torch.empty((cap, 4), dtype=torch.int32, device="cuda")
 
-    def run(prune, steps, warmup):
-        j = kgc.Join(dtype=spec.storage, prune=kgc.KGC_PRUNE_ON if prune else kgc.KGC_PRUNE_OFF, tile_cfg=args.tile)
+    def run(prune, steps, warmup, factorised=False):
+        j = kgc.Join(dtype=spec.storage, prune=kgc.KGC_PRUNE_ON if prune else kgc.KGC_PRUNE_OFF, tile_cfg=args.tile,
+                     factorised=factorised)
         res = None
         for _ in range(warmup):
             res = j.join(E, Rv, p, wl.delta, cap, out=out, fetch=False)
@@ -120,7 +123,13 @@ def main():
         launches = max(1, st["join_launches"])
         ms_join = acc["ms_join"] / steps
         work = 2.0 * d * st["pairs_evaluated"]                 # flop (L2) or lane-ops (L1) of the join kernel per step
-        if p == 2:
+        if st["join_variant"] == 100:
+            # relation-factorised kernel: the matrix work is 1/R of the per-relation form and the time goes into
+            # vector arithmetic, 2 lane-ops per evaluated triple (one addition, one comparison)
+            work = 2.0 * st["pairs_evaluated"]
+            roof = {"bound": "alu", "achieved": work / (ms_join * 1e-3) / 1e12 if ms_join > 0 else 0.0,
+                    "peak": PEAK_VALU_TLANEOPS, "unit": "Tlane-op/s"}
+        elif p == 2:
             roof = {"bound": "mfma", "achieved": work / (ms_join * 1e-3) / 1e12 if ms_join > 0 else 0.0,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
         else:
@@ -129,7 +138,7 @@ def main():
         roof["frac"] = roof["achieved"] / roof["peak"]
         roof["traffic"] = None      # filled below for configurations with a committed counter measurement
         v = st["join_variant"]
-        roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_direct" if v >= 15 else "k_join_l2_ares" if v >= 11
+        roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_fact" if v == 100 else "k_join_l2_direct" if v >= 15 else "k_join_l2_ares" if v >= 11
                           else "k_join_l2_stream" if v >= 6 else "k_join_l2")
         roof["tile_cfg"] = v
         roof["launches_per_step"] = launches
@@ -177,6 +186,11 @@ def main():
                          "hits": dense["count"], "phase_ms": dense["phase_ms"],
                          "speedup_prune_on_vs_off": dense["ms_per_step"] / main_run["ms_per_step"]}
         assert dense["count"] == main_run["count"], "pruned and dense runs disagree on the number of hits"
+    if p == 2 and d <= 282 and args.also_factorised > 0:
+        fr = run(False, args.also_factorised, 1, factorised=True)
+        assert fr["count"] == main_run["count"], "factorised and main runs disagree on the number of hits"
+        line["dense_factorised"] = {"ms_per_step": fr["ms_per_step"], "value": N * N * R / (fr["ms_per_step"] * 1e-3),
+                                    "hits": fr["count"], "phase_ms": fr["phase_ms"], "roofline": fr["roofline"]}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(line))
