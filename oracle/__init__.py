@@ -57,6 +57,10 @@ def _load():
                                   ip, ip, ip, dp, lp]
         lib.kgco_dist_triples.restype = None
         lib.kgco_dist_triples.argtypes = [dp, ctypes.c_int32, dp, ctypes.c_int32, ip, ip, ip, ctypes.c_int64, dp]
+        lib.kgco_top1.restype = ctypes.c_int32
+        lib.kgco_top1.argtypes = [dp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                  ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
+                                  ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)]
         lib.kgco_compute_range.restype = None
         lib.kgco_compute_range.argtypes = [dp, ctypes.c_int64, dp, ctypes.c_int64, ctypes.c_double,
                                            ctypes.c_int32, lp, lp]
@@ -141,6 +145,28 @@ def dist_triples(E, Rv, p: int, h, r, t) -> np.ndarray:
                           _ptr(h, ctypes.c_int32), _ptr(r, ctypes.c_int32), _ptr(t, ctypes.c_int32), n,
                           _ptr(out, ctypes.c_double))
     return out
+
+
+def top1(E, Rv, p: int, exclude_self: bool = False):
+    """The smallest ||E[h] + Rv[r] - E[t]||_p over all triples (the top-1 score of Section 3.3), optionally
+    without the self pairs h == t.  Returns a dict h, r, t, dist, or None when no triple is eligible.
+    Among equal distances the smallest (r, h, t) is returned."""
+    lib = _load()
+    E64, R64 = _f64(E), _f64(Rv)
+    if int(p) not in (1, 2):
+        raise ValueError("p must be 1 or 2")
+    if E64.ndim != 2 or R64.ndim != 2 or (E64.shape[0] and R64.shape[0] and E64.shape[1] != R64.shape[1]):
+        raise ValueError("E and Rv must be 2-D with one dimension d")
+    h, r, t = ctypes.c_int32(-1), ctypes.c_int32(-1), ctypes.c_int32(-1)
+    dist = ctypes.c_double(0.0)
+    rc = lib.kgco_top1(_ptr(E64, ctypes.c_double), E64.shape[0], E64.shape[1] if E64.shape[0] else R64.shape[1],
+                       _ptr(R64, ctypes.c_double), R64.shape[0], int(p), 1 if exclude_self else 0,
+                       ctypes.byref(h), ctypes.byref(r), ctypes.byref(t), ctypes.byref(dist))
+    if rc < 0:
+        raise ValueError("bad argument")
+    if rc == 0:
+        return None
+    return {"h": h.value, "r": r.value, "t": t.value, "dist": dist.value}
 
 
 def compute_range(sa, sb, eps: float, impl: str = "two_pointer"):

@@ -158,6 +158,47 @@ void kgco_dist_triples(const double *E, int32_t d, const double *Rv, int32_t p, 
         out[k] = triple_dist(E + (int64_t)h[k] * d, Rv + (int64_t)r[k] * d, E + (int64_t)t[k] * d, d, p);
 }
 
+/* ---- top-1: the smallest distance over all triples (the "top-1 score" of Section 3.3), optionally
+ * leaving out the self pairs h == t (the paper's "top-1 score except self-edges").  Plain triple loop,
+ * every distance summed in full.  Among equal distances the smallest (r, h, t) wins.  Returns 1 and fills
+ * the outputs, or 0 when no triple is eligible (N == 0, R == 0, or exclude_self with N == 1), or -1 on a
+ * bad argument. */
+int32_t kgco_top1(const double *E, int64_t N, int32_t d, const double *Rv, int32_t R, int32_t p, int32_t exclude_self,
+                  int32_t *oh, int32_t *or_, int32_t *ot, double *od)
+{
+    if ((p != 1 && p != 2) || N < 0 || R < 0 || d < 0) return -1;
+    int found = 0;
+    double best = INFINITY;
+    int32_t bh = -1, br = -1, bt = -1;
+#pragma omp parallel
+    {
+        int lfound = 0;
+        double lbest = INFINITY;
+        int32_t lh = -1, lr = -1, lt = -1;
+#pragma omp for schedule(static) collapse(2) nowait
+        for (int32_t r = 0; r < R; ++r)
+            for (int64_t h = 0; h < N; ++h)
+                for (int64_t t = 0; t < N; ++t) {
+                    if (exclude_self && h == t) continue;
+                    double v = triple_dist(E + h * d, Rv + (int64_t)r * d, E + t * d, d, p);
+                    /* within a thread (r, h, t) ascends, so '<' keeps the first of equal distances */
+                    if (!lfound || v < lbest) { lfound = 1; lbest = v; lh = (int32_t)h; lr = r; lt = (int32_t)t; }
+                }
+#pragma omp critical
+        {
+            if (lfound) {
+                int better = !found || lbest < best;
+                if (!better && lbest == best)
+                    better = (lr < br) || (lr == br && (lh < bh || (lh == bh && lt < bt)));
+                if (better) { found = 1; best = lbest; bh = lh; br = lr; bt = lt; }
+            }
+        }
+    }
+    if (!found) return 0;
+    *oh = bh; *or_ = br; *ot = bt; *od = best;
+    return 1;
+}
+
 /* ---- the join ----
  * E[N][d], Rv[R][d] row-major doubles.  pivot: d doubles or NULL for the zero vector (mode 2).
  * range_impl: see kgco_compute_range (mode 2).  Writes min(total, cap) hits to oh/or_/ot/od in an

@@ -250,3 +250,56 @@ def test_bad_arguments():
         oracle.dist_triples(E3, R2, 2, [3], [0], [0])
     assert oracle.join(np.zeros((0, 2)), R2, 2, 1.0)["count"] == 0
     assert oracle.join(E3, np.zeros((0, 2)), 2, 1.0)["count"] == 0
+
+
+# ---- top-1 score (Section 3.3): the minimum of the triple distance, with and without self pairs ----
+def test_top1_hand_case():
+    # E3 = {(0,0), (3,4), (1,0)}, R2 = {(3,4), (0,0)}: (h=0, r=0, t=1) has distance 0 and is the smallest (r, h, t)
+    # among the zero-distance triples (the others are the self pairs under the zero relation r=1)
+    E = np.array([[0.0, 0.0], [3.0, 4.0], [1.0, 0.0]])
+    R = np.array([[3.0, 4.0], [0.0, 0.0]])
+    for p in (1, 2):
+        a = oracle.top1(E, R, p)
+        assert (a["r"], a["h"], a["t"]) == (0, 0, 1) and a["dist"] == 0.0
+        b = oracle.top1(E, R, p, exclude_self=True)
+        assert (b["r"], b["h"], b["t"]) == (0, 0, 1) and b["dist"] == 0.0
+    # only the zero relation: every self pair has distance 0; without them the closest pair is (0,0)-(1,0)
+    Z = np.zeros((1, 2))
+    a = oracle.top1(E, Z, 2)
+    assert (a["r"], a["h"], a["t"], a["dist"]) == (0, 0, 0, 0.0)
+    b = oracle.top1(E, Z, 2, exclude_self=True)
+    assert (b["r"], b["h"], b["t"], b["dist"]) == (0, 0, 2, 1.0)
+    b1 = oracle.top1(E, Z, 1, exclude_self=True)
+    assert (b1["h"], b1["t"], b1["dist"]) == (0, 2, 1.0)
+
+
+def test_top1_against_cdist_and_join():
+    from scipy.spatial.distance import cdist
+    g = np.random.default_rng(77)
+    E = g.standard_normal((60, 9)); R = g.standard_normal((4, 9)) * 0.3
+    for p, metric in ((2, "euclidean"), (1, "cityblock")):
+        D = np.stack([cdist(E + R[r], E, metric) for r in range(R.shape[0])])       # [r][h][t]
+        for excl in (False, True):
+            Dm = D.copy()
+            if excl:
+                for r in range(R.shape[0]):
+                    np.fill_diagonal(Dm[r], np.inf)
+            r, h, t = np.unravel_index(np.argmin(Dm), Dm.shape)
+            a = oracle.top1(E, R, p, exclude_self=excl)
+            assert (a["r"], a["h"], a["t"]) == (r, h, t)
+            assert abs(a["dist"] - Dm[r, h, t]) <= 1e-12 * max(1.0, Dm[r, h, t])
+            # the join sees it the same way: nothing below the top-1 distance, the top-1 triple at it
+            if not excl:
+                below = oracle.join(E, R, p, np.nextafter(a["dist"], -np.inf), mode="brute")
+                assert below["count"] == 0
+                at = oracle.join(E, R, p, a["dist"], mode="brute")
+                assert at["count"] >= 1 and (a["h"], a["r"], a["t"]) in set(zip(at["h"], at["r"], at["t"]))
+
+
+def test_top1_degenerate():
+    E1 = np.ones((1, 3)); R = np.ones((2, 3))
+    assert oracle.top1(E1, R, 2, exclude_self=True) is None          # one entity: only self pairs exist
+    a = oracle.top1(E1, R, 2)
+    assert (a["h"], a["t"]) == (0, 0) and abs(a["dist"] - np.sqrt(3.0)) < 1e-15
+    assert oracle.top1(np.zeros((0, 3)), R, 2) is None
+    assert oracle.top1(E1, np.zeros((0, 3)), 1) is None
