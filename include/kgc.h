@@ -120,6 +120,17 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
 int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R,
               float* nB, float* nA);
 
+/* The top-1 score of Section 3.3: the triple with the smallest dist_3(h, r, t) over E x R x E, or, with
+ * exclude_self != 0, over the triples with h != t (the paper's "top-1 score except self-edges").
+ *   out   receives the triple and its distance (host).  h = r = t = -1 and dist = +inf when no triple is
+ *         eligible (N == 0, R == 0, or exclude_self with N == 1): that is KGC_OK, not an error.
+ * Same E / Rvecs / p conventions and error codes as kgc_join.  Found by joins with a shrinking threshold,
+ * starting from the smallest of 65,536 sampled triples; the handle's pruning setting applies.  Among triples
+ * whose distances agree to float precision the smallest (r, h, t) is returned.  Synchronises the stream a
+ * few times. */
+int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+             int32_t exclude_self, kgc_triple* out);
+
 /* Copy the statistics of the last kgc_join into *out (host). */
 int kgc_get_stats(const kgc_handle* hd, kgc_stats* out);
 

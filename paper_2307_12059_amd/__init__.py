@@ -23,7 +23,8 @@ KGC_PRUNE_AUTO, KGC_PRUNE_OFF, KGC_PRUNE_ON = 0, 1, 2
 KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
-EXPORTS = ["kgc_create", "kgc_join", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy", "kgc_version"]
+EXPORTS = ["kgc_create", "kgc_join", "kgc_top1", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
+           "kgc_version"]
 
 
 class kgc_triple(ctypes.Structure):
@@ -72,6 +73,9 @@ def load_library():
     lib.kgc_join.restype = ctypes.c_int
     lib.kgc_join.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
                              ctypes.c_float, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64)]
+    lib.kgc_top1.restype = ctypes.c_int
+    lib.kgc_top1.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                             ctypes.POINTER(kgc_triple)]
     lib.kgc_norms.restype = ctypes.c_int
     lib.kgc_norms.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
     lib.kgc_get_stats.restype = ctypes.c_int
@@ -121,6 +125,14 @@ def kgc_join(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, del
     rc = load_library().kgc_join(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
                                  ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap, ctypes.byref(count))
     return rc, int(count.value)
+
+
+def kgc_top1(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, exclude_self: bool):
+    """Raw call on device addresses.  Returns (code, kgc_triple)."""
+    out = kgc_triple()
+    rc = load_library().kgc_top1(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
+                                 1 if exclude_self else 0, ctypes.byref(out))
+    return rc, out
 
 
 def kgc_norms(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, nB_ptr: int, nA_ptr: int) -> int:
@@ -198,6 +210,16 @@ class Join:
             res.update({"h": host[:, 0].copy(), "r": host[:, 1].copy(), "t": host[:, 2].copy(),
                         "dist": host[:, 3].copy().view("float32")})
         return res
+
+    def top1(self, E, Rv, p: int, exclude_self: bool = False):
+        """The triple with the smallest distance (None when no triple is eligible): dict h, r, t, dist."""
+        self._check(E, Rv)
+        rc, rec = kgc_top1(self.handle, E.data_ptr(), E.shape[0], E.shape[1], Rv.data_ptr(), Rv.shape[0], p, exclude_self)
+        if rc < 0:
+            raise RuntimeError(f"kgc_top1 failed with code {rc}: {kgc_last_error(self.handle)}")
+        if rec.h < 0:
+            return None
+        return {"h": int(rec.h), "r": int(rec.r), "t": int(rec.t), "dist": float(rec.dist)}
 
     def norms(self, E, Rv, want_nA: bool = True):
         torch = self._torch

@@ -41,6 +41,9 @@ struct kgc_handle {
   // pruning scratch
   DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
   DevBuf active_rows, cnorm, gram, relu, reln, asg_a, asg_b, limr;
+  DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
+  DevBuf top1_a, top1_b, top1_pick;            // ... and the operands / entity samples of its sub-sampled dense pass
+  int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
   GroupState* host_gstate = nullptr;           // pinned
   DevCounters* host_counters = nullptr;        // pinned
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -197,6 +200,116 @@ void kgc_destroy(kgc_handle* h) {
 }
 
 const char* kgc_last_error(const kgc_handle* h) { return h ? h->err.c_str() : "null handle"; }
+
+int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+             int32_t exclude_self, kgc_triple* out) {
+  if (!hd) return KGC_E_INVALID;
+  if (!out) return fail(hd, KGC_E_INVALID, "out is NULL");
+  out->h = out->r = out->t = -1;
+  out->dist = INFINITY;
+  int rc = check_common(hd, E, N, d, Rvecs, R);
+  if (rc != KGC_OK) return rc;
+  if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
+  if (N == 0 || R == 0 || (exclude_self && N < 2)) return KGC_OK;          // no eligible triple
+  hipStream_t st = hd->stream;
+  constexpr uint64_t kCap = 1u << 20;
+  if ((rc = ensure(hd, hd->top1_buf, kCap * sizeof(kgc_triple))) || (rc = ensure(hd, hd->top1_state, sizeof(Top1State))) ||
+      (rc = ensure(hd, hd->counters, sizeof(DevCounters))))
+    return rc;
+  Top1State* ts = (Top1State*)hd->top1_state.p;
+  Top1State host{};
+  RecheckCtx cx{};
+  cx.E = E; cx.Rv = Rvecs; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
+
+  // 1. an upper bound of the answer: the smallest of 65,536 sampled eligible triples
+  const int n_sample = 1 << 16;
+  k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)ts, sizeof(Top1State) / 4, 0xffffffffu);
+  k_top1_sample<<<grid_for((int64_t)n_sample * 16, 256), 256, 0, st>>>(cx, N, R, n_sample, exclude_self ? 1 : 0, ts);
+  KGC_HIP(hd, hipMemcpyAsync(&host, ts, sizeof(Top1State), hipMemcpyDeviceToHost, st));
+  KGC_HIP(hd, hipStreamSynchronize(st));
+  double bound;
+  std::memcpy(&bound, &host.sample_min, sizeof(double));
+  if (!(bound >= 0.0) || std::isinf(bound)) return fail(hd, KGC_E_INVALID, "non-finite distances: E or Rvecs hold non-finite values");
+  const double sample_bound = bound;
+
+  // 1b. (L2, head tile fits in LDS, enough entities)  A random triple is almost never a close one, so the
+  //     sampled bound is usually far above the answer, where a join prunes nothing.  A dense pass over a
+  //     sub-sample -- up to 8,192 heads x 8,192 other tails x the first 32 relations, the barrier-free kernel
+  //     with an epilogue that keeps only the smallest squared distance -- costs about a millisecond and
+  //     usually lands within a few tens of percent of the answer.
+  const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
+  if (p == 2 && KS <= kDirectMaxKS && N >= 1024) {
+    const int m = (int)std::min<int64_t>(8192, (N / 2) / 256 * 256);
+    const int Rs = (int)std::min<int32_t>(R, 32);
+    const int k16 = (d + kNormCols + 15) / 16;
+    const size_t op_rows = (size_t)KS * m * kSliceK * 2;
+    if ((rc = ensure(hd, hd->top1_pick, (size_t)2 * m * 4)) || (rc = ensure(hd, hd->top1_b, op_rows)) ||
+        (rc = ensure(hd, hd->top1_a, op_rows * Rs)))
+      return rc;
+    DevCounters* cnt = (DevCounters*)hd->counters.p;
+    int32_t* heads = (int32_t*)hd->top1_pick.p;
+    int32_t* tails = heads + m;
+    const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
+    k_fill_u32<<<grid_for(sizeof(DevCounters) / 4, 256), 256, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
+    k_top1_pick<<<grid_for(m, 256), 256, 0, st>>>(N, m, heads, tails);
+    k_stage_operands<false><<<m / kStageRows, 256, stage_lds, st>>>(E, Rvecs, hd->cfg.dtype, d, 0, 1, tails, m, KS,
+                                                               (uint16_t*)hd->top1_b.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
+                                                               kStageRows);
+    k_stage_operands<true><<<grid_for((int64_t)Rs * (m / kStageRows), 1), 256, stage_lds, st>>>(
+        E, Rvecs, hd->cfg.dtype, d, 0, Rs, heads, m, KS, (uint16_t*)hd->top1_a.p, nullptr, cnt->max_a, nullptr, nullptr, 0,
+        kStageRows);
+    JoinStreamArgs sa{};
+    sa.A = (const uint16_t*)hd->top1_a.p; sa.B = (const uint16_t*)hd->top1_b.p; sa.prm = nullptr; sa.Nslots = m;
+    sa.KS = KS; sa.k16 = k16; sa.nH = m / 256; sa.nT = m / 256; sa.r0 = 0; sa.RB = Rs; sa.thr_value = 0.f;
+    sa.best = &ts->sub_min;
+    const size_t dyn_lds = (size_t)KS * 256 * kSliceK * 2;
+    KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_direct<256, 2, 4, kEpiMinDist>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
+    hipLaunchKernelGGL((k_join_l2_direct<256, 2, 4, kEpiMinDist>), dim3((unsigned)(m / 256), (unsigned)Rs, 1), dim3(512), dyn_lds,
+                       st, sa);
+    k_top1_bound<<<1, 64, 0, st>>>(cnt, hd->cfg.dtype, KS * kSliceK, ts);
+    KGC_HIP(hd, hipMemcpyAsync(&host, ts, sizeof(Top1State), hipMemcpyDeviceToHost, st));
+    KGC_HIP(hd, hipStreamSynchronize(st));
+    if (host.sub_bound >= 0.0 && host.sub_bound < bound) bound = host.sub_bound;
+  }
+
+  // 2. Joins with a shrinking threshold: every triple at or below the bound comes back; if there are more
+  //    than the buffer holds, the smallest distance among those that did come back is the next bound.  The
+  //    bound of step 1b rests on an error analysis instead of an exact distance; should a join at it come
+  //    back empty, the search falls back to the sampled bound, whose triple is known to qualify.
+  hd->no_self = exclude_self ? 1 : 0;
+  int rounds = 0;
+  for (;; ++rounds) {
+    float delta = (float)bound;
+    if ((double)delta < bound) delta = std::nextafterf(delta, INFINITY);    // the bounding triple must qualify
+    uint64_t count = 0;
+    rc = kgc_join(hd, E, N, d, Rvecs, R, p, delta, (kgc_triple*)hd->top1_buf.p, kCap, &count);
+    if (rc < 0) { hd->no_self = 0; return rc; }
+    if (count == 0) {
+      if (bound < sample_bound) { bound = sample_bound; continue; }
+      hd->no_self = 0;
+      return fail(hd, KGC_E_HIP, "top-1 search lost its bounding triple");
+    }
+    DevCounters* cnt = (DevCounters*)hd->counters.p;
+    k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)ts, sizeof(Top1State) / 4, 0xffffffffu);
+    k_top1_min<<<256, 256, 0, st>>>((const kgc_triple*)hd->top1_buf.p, &cnt->hits, kCap, 0, ts);
+    k_top1_min<<<256, 256, 0, st>>>((const kgc_triple*)hd->top1_buf.p, &cnt->hits, kCap, 1, ts);
+    k_top1_exact<<<1, 64, 0, st>>>(cx, ts);
+    KGC_HIP(hd, hipMemcpyAsync(&host, ts, sizeof(Top1State), hipMemcpyDeviceToHost, st));
+    KGC_HIP(hd, hipStreamSynchronize(st));
+    if (rc == KGC_OK) break;                                // everything at or below the bound was seen
+    // overflow: the buffer holds a subset; its minimum bounds the answer from above.  When that does not
+    // lower the bound any more (a mass of equal distances), any of them is a smallest distance.
+    if (!(host.dist < bound) || rounds >= 40) break;
+    bound = host.dist;
+  }
+  hd->no_self = 0;
+  out->r = (int32_t)(uint32_t)(host.key_dr & 0xffffffffull);
+  out->h = (int32_t)(uint32_t)(host.key_ht >> 32);
+  out->t = (int32_t)(uint32_t)(host.key_ht & 0xffffffffull);
+  out->dist = (float)host.dist;
+  return KGC_OK;
+}
 
 int kgc_get_stats(const kgc_handle* h, kgc_stats* out) {
   if (!h || !out) return KGC_E_INVALID;
@@ -432,7 +545,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
 
   RecheckCtx cx;
   cx.E = E; cx.Rv = Rvecs; cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
-  cx.delta = (double)delta; cx.out = out_triples; cx.cap = cap;
+  cx.delta = (double)delta; cx.out = out_triples; cx.cap = cap; cx.no_self = hd->no_self;
   cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates;
 
   KGC_HIP(hd, hipEventRecord(hd->ev[3], st));     // end of grouping

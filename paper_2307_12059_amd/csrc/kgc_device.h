@@ -72,6 +72,7 @@ struct RecheckCtx {
   unsigned long long cap;
   unsigned long long* hit_counter;
   unsigned long long* cand_counter;
+  int no_self;               // 1: candidates with h == t are dropped (the top-1 search without self pairs)
 };
 
 // Exact score of one triple by a 16-lane group (the TransE distance of Section 4.3 in double):
@@ -146,7 +147,7 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
   double s0[NC], s1[NC];                 // two partial sums per candidate, as in the single form
 #pragma unroll
   for (int n = 0; n < NC; ++n) {
-    const bool ok = h[n] >= 0 && t[n] >= 0;
+    const bool ok = h[n] >= 0 && t[n] >= 0;      // an absent candidate reads row 0 and its result is ignored
     ho[n] = (int64_t)(ok ? h[n] : 0) * d;
     to[n] = (int64_t)(ok ? t[n] : 0) * d;
     s0[n] = 0.0; s1[n] = 0.0;
@@ -246,7 +247,7 @@ __device__ __forceinline__ void recheck_and_emit(unsigned long long cm, int32_t 
       map(e, src, hslot, tslot);
       h = cx.slot_ent[hslot];
       t = cx.slot_ent[tslot];
-      if (h >= 0 && t >= 0) {
+      if (h >= 0 && t >= 0 && !(cx.no_self && h == t)) {
         const double dist = group16_exact_dist(cx, h, r, t, sub);
         hit = dist <= cx.delta;
         distf = (float)dist;
@@ -351,7 +352,7 @@ __device__ __forceinline__ void block_recheck(unsigned long long (&cm)[NW], int3
       if (sub == 0) {
 #pragma unroll
         for (int n = 0; n < kDrain; ++n)
-          if (hh[n] >= 0 && tt[n] >= 0 && dd[n] <= cx.delta) {
+          if (hh[n] >= 0 && tt[n] >= 0 && !(cx.no_self && hh[n] == tt[n]) && dd[n] <= cx.delta) {
             kgc_triple rec;
             rec.h = hh[n]; rec.r = r; rec.t = tt[n]; rec.dist = (float)dd[n];
             q->hits[atomicAdd(&q->nhits, 1u)] = rec;         // LDS atomic; at most one hit per entry

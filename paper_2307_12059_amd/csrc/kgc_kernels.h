@@ -407,11 +407,12 @@ struct JoinStreamArgs {
   int64_t tail_slots;                 // rows per K slice of B when it differs from Nslots (0: the same)
   const int32_t* tail_rows_dev;       // device count of valid tail rows (tail tiles past it are skipped); may be NULL
   float thr_value;                    // filter threshold on the squared distance when prm == NULL
-  unsigned long long* best;           // per entity: min over the pivots within reach of (pivot position << 32)
+  unsigned long long* best;           // kEpiAssignMin: per entity, min over the pivots within reach of (pivot position << 32);
+                                      // kEpiMinDist: one word, min over all scored pairs of the float bits of the squared distance
   const int32_t* group_of;            // entities that already belong to a group (>= 0) are left alone
   int64_t n_heads;                    // entities (head slots past it are padding)
 };
-enum { kEpiJoin = 0, kEpiAssignMin = 1 };
+enum { kEpiJoin = 0, kEpiAssignMin = 1, kEpiMinDist = 2 };
 
 // LISTED: the block walks tile lists (pruned mode); otherwise the grid enumerates the dense problem and the
 // kernel holds no load of the list in its inner loop (such a load would make every tile end wait for all
@@ -967,6 +968,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
                                        Q[8 * (J) + 4 * (STEP) + 2], Q[8 * (J) + 4 * (STEP) + 3]})
 
   const float thr = a.prm ? a.prm->thr : a.thr_value;
+  float run_min = 3e38f;                                   // kEpiMinDist
   const int last_two = (a.k16 - (KS - 1) * 2) >= 2;
   int ck = 0, ct = 0;
   f32x16_t acc[TM][TN];
@@ -1008,7 +1010,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
       _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
         _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
           _Pragma("unroll") for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);            \
-      if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {                                       \
+      if (EPI == kEpiMinDist) {                                                                   \
+        run_min = fminf(run_min, mn);        /* only the smallest squared distance is wanted */    \
+      } else if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {                                \
         const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
         const int64_t tbase = (int64_t)(t_begin + ct) * BN + wn * WTN;                            \
         constexpr int NW = (TM * TN + 3) / 4;                                                     \
@@ -1066,6 +1070,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
 #undef KGC_GLOAD
 #undef KGC_FRAG
 #undef KGC_COMPUTE
+  if (EPI == kEpiMinDist) {
+    for (int off = 32; off > 0; off >>= 1) run_min = fminf(run_min, __shfl_xor(run_min, off, 64));
+    if (lane == 0) atomicMin(a.best, (unsigned long long)__float_as_uint(fmaxf(run_min, 0.f)));   // non-negative floats order like their bits
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1280,6 +1288,102 @@ __global__ __launch_bounds__(256) void k_fact_params(const DevCounters* cnt, con
   const float eu = 4.f * (float)(d + 12) * 6e-8f * rnorm * (na + nb) + 1e-6f * (rn[rl] + ma + mb);
   const float thr = (delta * delta + m * (2.f * (delta + rnorm) + m) + eacc + eu) * (1.f + 1e-6f);
   limr[rl] = thr - rn[rl];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Top-1 search (the smallest triple distance, Section 3.3).  Three small kernels around the join:
+//   k_top1_sample  exact distances of `n` pseudo-random triples (one per 16-lane group), minimum by atomicMin
+//                  on the bits of the non-negative double: an upper bound of the top-1 distance to start from;
+//   k_top1_min     over the records a join returned: pass 0 the minimum of (distance bits << 32 | r), pass 1,
+//                  among the records that attain it, the minimum of (h << 32 | t);
+//   k_top1_exact   the double-precision distance of the chosen triple.
+struct Top1State {
+  unsigned long long sample_min;   // bits of a double
+  unsigned long long key_dr;       // (float distance bits << 32) | r
+  unsigned long long key_ht;       // (h << 32) | t
+  double dist;                     // exact distance of (key_ht, r of key_dr)
+  unsigned long long sub_min;      // float bits of the smallest squared distance the sub-sampled dense pass saw
+  double sub_bound;                // the distance bound that follows from it
+};
+
+__device__ __forceinline__ uint32_t top1_hash(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
+__global__ __launch_bounds__(256) void k_top1_sample(RecheckCtx cx, int64_t N, int R, int n, int no_self, Top1State* st) {
+  const int64_t g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+  const int sub = threadIdx.x & 15;
+  if (g >= n) return;                                   // whole 16-lane groups leave together
+  const uint32_t a = top1_hash((uint32_t)g * 3u + 1u), b = top1_hash((uint32_t)g * 3u + 2u), c = top1_hash((uint32_t)g * 3u + 3u);
+  const int32_t h = (int32_t)(((uint64_t)a * (uint64_t)N) >> 32);
+  int32_t t = (int32_t)(((uint64_t)b * (uint64_t)N) >> 32);
+  const int32_t r = (int32_t)(((uint64_t)c * (uint64_t)R) >> 32);
+  if (no_self && t == h) t = (t + 1 == N) ? 0 : t + 1;  // N >= 2 is checked on the host
+  const double dist = group16_exact_dist(cx, h, r, t, sub);
+  if (sub == 0) atomicMin(&st->sample_min, (unsigned long long)__double_as_longlong(dist));
+}
+
+__global__ __launch_bounds__(256) void k_top1_min(const kgc_triple* __restrict__ rec, const unsigned long long* __restrict__ count,
+                                                  unsigned long long cap, int pass, Top1State* st) {
+  const unsigned long long n = *count < cap ? *count : cap;
+  unsigned long long best = ~0ull;
+  const unsigned long long want = st->key_dr;           // pass 1: written by pass 0, an earlier launch
+  for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (unsigned long long)gridDim.x * blockDim.x) {
+    const kgc_triple x = rec[i];
+    const unsigned long long kdr = ((unsigned long long)__float_as_uint(x.dist) << 32) | (uint32_t)x.r;
+    if (pass == 0) best = kdr < best ? kdr : best;
+    else if (kdr == want) {
+      const unsigned long long kht = ((unsigned long long)(uint32_t)x.h << 32) | (uint32_t)x.t;
+      best = kht < best ? kht : best;
+    }
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)(best & 0xffffffffull), off, 64);
+    const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(best >> 32), off, 64);
+    const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+    best = o < best ? o : best;
+  }
+  if ((threadIdx.x & 63) == 0 && best != ~0ull) atomicMin(pass == 0 ? &st->key_dr : &st->key_ht, best);
+}
+
+// Disjoint head and tail samples for the sub-sampled dense pass: 2 m entities evenly spread over [0, N),
+// even positions to the heads, odd positions to the tails (so the pass scores no self pair); N >= 2 m.
+__global__ void k_top1_pick(int64_t N, int m, int32_t* heads, int32_t* tails) {
+  const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (i >= m) return;
+  heads[i] = (int32_t)(((int64_t)(2 * i) * N) / (2 * (int64_t)m));
+  tails[i] = (int32_t)(((int64_t)(2 * i + 1) * N) / (2 * (int64_t)m));
+}
+
+// The smallest squared distance of the sub-sampled pass is taken on bf16-rounded rows with float32
+// accumulation; the true distance of that pair is at most sqrt(D + e_acc) + m (same m and e_acc as the join's
+// filter threshold, see k_join_params), which bounds the top-1 distance from above.
+__global__ __launch_bounds__(64) void k_top1_bound(const DevCounters* cnt, int dtype, int kp, Top1State* st) {
+  float ma = 0.f, mb = 0.f;
+  for (int i = threadIdx.x; i < 1024; i += 64) {
+    ma = fmaxf(ma, __uint_as_float(cnt->max_a[i]));
+    mb = fmaxf(mb, __uint_as_float(cnt->max_b[i]));
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    ma = fmaxf(ma, __shfl_xor(ma, off, 64));
+    mb = fmaxf(mb, __shfl_xor(mb, off, 64));
+  }
+  if (threadIdx.x != 0) return;
+  const float D = __uint_as_float((uint32_t)st->sub_min);
+  const float u = 1.01f / 256.f;
+  const float m = u * (sqrtf(ma) * 1.01f + (dtype == KGC_BF16 ? 0.f : sqrtf(mb) * 1.01f));
+  const float eacc = (float)(kp + 16) * 1.2e-7f * 2.f * (ma + mb);
+  st->sub_bound = ((double)sqrtf(D + eacc) + (double)m) * (1.0 + 1e-5);
+}
+
+__global__ __launch_bounds__(64) void k_top1_exact(RecheckCtx cx, Top1State* st) {
+  const int sub = threadIdx.x & 15;
+  const int32_t r = (int32_t)(uint32_t)(st->key_dr & 0xffffffffull);
+  const int32_t h = (int32_t)(uint32_t)(st->key_ht >> 32), t = (int32_t)(uint32_t)(st->key_ht & 0xffffffffull);
+  const double dist = group16_exact_dist(cx, h, r, t, sub);
+  if (threadIdx.x == 0) st->dist = dist;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -120,3 +120,38 @@ def test_c4_large_l2_fullsize():
 def test_c5_scale_l2_fullsize():
     # 10^15 triples: pruned mode only; recall is verified on the subsample only, precision on every emitted triple
     _fullsize_checks("c5_scale_l2", n_rel=10, max_entities=5000, modes=["prune"])
+
+
+@pytest.mark.parametrize("name", ["c2_mid_l2", "c4_large_l2"])
+def test_top1_fullsize(name):
+    """Top-1 at full size: it must be the smallest distance of the (oracle-verified) join result at the stored
+    threshold, which is known to be non-empty, and its triple must attain it in the oracle's arithmetic."""
+    import time
+
+    import torch
+
+    import paper_2307_12059_amd as kgc
+    wl = workloads.generate(name)
+    spec = wl.spec
+    if spec.storage == "bf16":
+        E = torch.from_numpy(wl.E_bits.view(np.int16)).cuda().view(torch.bfloat16)
+        Rv = torch.from_numpy(wl.Rv_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        E = torch.from_numpy(wl.E).cuda(); Rv = torch.from_numpy(wl.Rv).cuda()
+    j = kgc.Join(dtype=spec.storage, prune=kgc.KGC_PRUNE_ON)
+    try:
+        full = j.join(E, Rv, spec.p, wl.delta, int(6 * spec.selectivity * spec.n_triples) + 4096)
+        for excl in (False, True):
+            t0 = time.perf_counter()
+            got = j.top1(E, Rv, spec.p, excl)
+            ms = (time.perf_counter() - t0) * 1e3
+            m = (full["h"] != full["t"]) if excl else np.ones(full["h"].size, bool)
+            assert m.any()
+            dref = oracle.dist_triples(wl.E, wl.Rv, spec.p, full["h"][m], full["r"][m], full["t"][m])
+            best = float(dref.min())
+            dg = oracle.dist_triples(wl.E, wl.Rv, spec.p, [got["h"]], [got["r"]], [got["t"]])[0]
+            print(f"[{name}] top-1 exclude_self={excl}: {got} in {ms:.1f} ms; oracle min over the join result {best:.7f}", flush=True)
+            assert abs(dg - best) <= 1e-6 * best and abs(got["dist"] - best) <= 1e-6 * best
+            assert not excl or got["h"] != got["t"]
+    finally:
+        j.close()

@@ -224,3 +224,68 @@ def test_factorised_ragged_shapes(dtype, N, R, d):
     # d = 283 does not fit the head-resident tile: the library then takes its ordinary dense kernel
     assert got["stats"]["join_variant"] == (100 if d <= 282 else 17)
     assert rep["only_gpu_in_band"] == 0 and rep["only_oracle_in_band"] == 0
+
+
+# ---- top-1 score (Section 3.3): smallest triple distance, with and without self pairs ----
+def _top1(E, Rv, p, exclude_self, dtype="f32", **kw):
+    import paper_2307_12059_amd as kgc
+    j = kgc.Join(dtype=dtype, **kw)
+    try:
+        return j.top1(_dev(E, dtype), _dev(Rv, dtype), p, exclude_self)
+    finally:
+        j.close()
+
+
+def _check_top1(E, Rv, p, exclude_self, dtype="f32", **kw):
+    ref = oracle.top1(E, Rv, p, exclude_self)
+    got = _top1(E, Rv, p, exclude_self, dtype=dtype, **kw)
+    if ref is None:
+        assert got is None
+        return got, ref
+    assert got is not None
+    # the distance is unique; the triple is checked to attain it (several triples may tie within float precision)
+    tol = max(1e-6 * ref["dist"], 1e-6)
+    assert abs(got["dist"] - ref["dist"]) <= tol
+    dg = oracle.dist_triples(E, Rv, p, [got["h"]], [got["r"]], [got["t"]])[0]
+    assert abs(dg - ref["dist"]) <= tol
+    if exclude_self:
+        assert got["h"] != got["t"]
+    return got, ref
+
+
+def test_top1_hand_case():
+    Z = np.zeros((1, 2), np.float32)
+    for p in (1, 2):
+        for prune in (PRUNE_OFF, PRUNE_ON):
+            got, ref = _check_top1(E3, R2, p, False, prune=prune)
+            assert (got["r"], got["h"], got["t"]) == (0, 0, 1) == (ref["r"], ref["h"], ref["t"])
+            got, ref = _check_top1(E3, R2, p, True, prune=prune)
+            assert (got["r"], got["h"], got["t"]) == (0, 0, 1)
+            got, ref = _check_top1(E3, Z, p, False, prune=prune)
+            assert (got["r"], got["h"], got["t"], got["dist"]) == (0, 0, 0, 0.0)
+            got, ref = _check_top1(E3, Z, p, True, prune=prune)
+            assert (got["r"], got["h"], got["t"], got["dist"]) == (0, 0, 2, 1.0)
+    assert _top1(E3[:1], R2, 2, True) is None                       # one entity: only self pairs
+    one = _top1(E3[:1], R2, 2, False)                               # the self pair under the zero relation
+    assert (one["r"], one["h"], one["t"], one["dist"]) == (1, 0, 0, 0.0)
+    assert _top1(E3[:1], R2[:1], 2, False)["dist"] == pytest.approx(5.0)
+
+
+@pytest.mark.parametrize("exclude_self", [False, True])
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
+@pytest.mark.parametrize("p", [1, 2])
+def test_top1_c1(p, prune, exclude_self):
+    wl = workloads.generate("c1_tiny_l2")
+    _check_top1(wl.E, wl.Rv, p, exclude_self, prune=prune)
+
+
+@pytest.mark.parametrize("exclude_self", [False, True])
+def test_top1_with_self_edges_and_overflow(exclude_self):
+    # a zero relation makes every self pair a zero-distance triple; duplicated rows make far more than the
+    # inner buffer of 2^20 records qualify at the first threshold, so the search has to shrink it
+    g = np.random.default_rng(5)
+    base = g.standard_normal((40, 16)).astype(np.float32)
+    E = np.repeat(base, 60, axis=0)                                   # 2400 rows, 60 copies of each
+    Rv = np.concatenate([np.zeros((1, 16), np.float32), g.standard_normal((2, 16)).astype(np.float32)])
+    got, ref = _check_top1(E, Rv, 2, exclude_self, prune=PRUNE_ON)
+    assert ref["dist"] == 0.0 and got["dist"] == 0.0
