@@ -120,6 +120,15 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
 int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R,
               float* nB, float* nA);
 
+/* The same join restricted to the relations r_begin <= r < r_end (0 <= r_begin <= r_end <= R); r in the
+ * records is still the row number in Rvecs.  The join over [0, R) is the disjoint union of the joins over
+ * any partition of [0, R) into ranges, which lets a caller bound the output of one call (a range whose
+ * result overflows cap can be split and run again) and drain a result larger than its buffer range by
+ * range -- the relation-wise form of the partition-based join of Section 4.7.  kgc_join is this call with
+ * the range [0, R).  An empty range yields *count == 0. */
+int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                   float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
+
 /* The top-1 score of Section 3.3: the triple with the smallest dist_3(h, r, t) over E x R x E, or, with
  * exclude_self != 0, over the triples with h != t (the paper's "top-1 score except self-edges").
  *   out   receives the triple and its distance (host).  h = r = t = -1 and dist = +inf when no triple is

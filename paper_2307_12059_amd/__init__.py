@@ -23,7 +23,7 @@ KGC_PRUNE_AUTO, KGC_PRUNE_OFF, KGC_PRUNE_ON = 0, 1, 2
 KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
-EXPORTS = ["kgc_create", "kgc_join", "kgc_top1", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
+EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_top1", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
            "kgc_version"]
 
 
@@ -73,6 +73,10 @@ def load_library():
     lib.kgc_join.restype = ctypes.c_int
     lib.kgc_join.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
                              ctypes.c_float, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64)]
+    lib.kgc_join_range.restype = ctypes.c_int
+    lib.kgc_join_range.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
+                                   ctypes.c_float, ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_uint64,
+                                   ctypes.POINTER(ctypes.c_uint64)]
     lib.kgc_top1.restype = ctypes.c_int
     lib.kgc_top1.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                              ctypes.POINTER(kgc_triple)]
@@ -124,6 +128,16 @@ def kgc_join(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, del
     count = ctypes.c_uint64(0)
     rc = load_library().kgc_join(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
                                  ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap, ctypes.byref(count))
+    return rc, int(count.value)
+
+
+def kgc_join_range(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, delta: float, r_begin: int,
+                   r_end: int, out_ptr: int, cap: int):
+    """Raw call on device addresses, relations r_begin <= r < r_end only.  Returns (code, count)."""
+    count = ctypes.c_uint64(0)
+    rc = load_library().kgc_join_range(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R,
+                                       p, ctypes.c_float(delta), r_begin, r_end, ctypes.c_void_p(out_ptr), cap,
+                                       ctypes.byref(count))
     return rc, int(count.value)
 
 
@@ -193,14 +207,19 @@ class Join:
         if E.shape[0] and Rv.shape[0] and E.shape[1] != Rv.shape[1]:
             raise ValueError("E and Rv must share d")
 
-    def join(self, E, Rv, p: int, delta: float, cap: int, out=None, fetch: bool = True) -> dict:
+    def join(self, E, Rv, p: int, delta: float, cap: int, out=None, fetch: bool = True, r_range=None) -> dict:
+        """``r_range = (r_begin, r_end)`` restricts the join to those relations (kgc_join_range)."""
         torch = self._torch
         self._check(E, Rv)
         N, d = E.shape[0], (E.shape[1] if E.shape[0] else Rv.shape[1])
         R = Rv.shape[0]
         if out is None:
             out = torch.empty((max(cap, 1), 4), dtype=torch.int32, device=E.device)
-        rc, count = kgc_join(self.handle, E.data_ptr(), N, d, Rv.data_ptr(), R, p, float(delta), out.data_ptr(), cap)
+        if r_range is None:
+            rc, count = kgc_join(self.handle, E.data_ptr(), N, d, Rv.data_ptr(), R, p, float(delta), out.data_ptr(), cap)
+        else:
+            rc, count = kgc_join_range(self.handle, E.data_ptr(), N, d, Rv.data_ptr(), R, p, float(delta),
+                                       int(r_range[0]), int(r_range[1]), out.data_ptr(), cap)
         if rc < 0:
             raise RuntimeError(f"kgc_join failed with code {rc}: {kgc_last_error(self.handle)}")
         res = {"code": rc, "count": count, "stats": kgc_get_stats(self.handle), "out": out}

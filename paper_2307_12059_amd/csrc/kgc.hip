@@ -356,19 +356,26 @@ int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* R
 
 int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
              float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count) {
+  return kgc_join_range(hd, E, N, d, Rvecs, R, p, delta, 0, R, out_triples, cap, count);
+}
+
+int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                   float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count) {
   if (!hd) return KGC_E_INVALID;
   if (!count) return fail(hd, KGC_E_INVALID, "count is NULL");
   *count = 0;
   int rc = check_common(hd, E, N, d, Rvecs, R);
   if (rc != KGC_OK) return rc;
+  if (r_begin < 0 || r_end < r_begin || r_end > R) return fail(hd, KGC_E_INVALID, "relation range outside [0, R]");
+  const int64_t Rn = (int64_t)r_end - r_begin;          // relations of this call
   if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
   if (std::isnan(delta)) return fail(hd, KGC_E_INVALID, "delta is NaN");
   if (cap > 0 && !out_triples) return fail(hd, KGC_E_INVALID, "out_triples is NULL with cap > 0");
   if ((uintptr_t)out_triples % 16) return fail(hd, KGC_E_INVALID, "out_triples must be 16-byte aligned");
   hd->err.clear();
   hd->stats = kgc_stats{};
-  hd->stats.triples_total = (uint64_t)N * (uint64_t)N * (uint64_t)R;
-  if (N == 0 || R == 0) return KGC_OK;
+  hd->stats.triples_total = (uint64_t)N * (uint64_t)N * (uint64_t)Rn;
+  if (N == 0 || Rn == 0) return KGC_OK;
 
   hipStream_t st = hd->stream;
   const int dtype = hd->cfg.dtype;
@@ -508,9 +515,9 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   // ---- relation batches: staged A operands (L2) and the tile lists (pruning) must fit the workspace ----
   const int64_t ws = hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
   const size_t opA_per_rel = (p == 2) ? (size_t)KS * Nslots * kSliceK * 2 : 0;
-  int64_t RBmax = R;
-  if (p == 2 && !fact) RBmax = std::max<int64_t>(1, std::min<int64_t>(R, ws / (int64_t)(opA_per_rel + Nslots * 4)));
-  if (fact) RBmax = std::max<int64_t>(1, std::min<int64_t>(R, ws / (int64_t)(Nslots * 4)));       // u[r][slot]
+  int64_t RBmax = Rn;
+  if (p == 2 && !fact) RBmax = std::max<int64_t>(1, std::min<int64_t>(Rn, ws / (int64_t)(opA_per_rel + Nslots * 4)));
+  if (fact) RBmax = std::max<int64_t>(1, std::min<int64_t>(Rn, ws / (int64_t)(Nslots * 4)));      // u[r][slot]
   if (prune) RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, kMaxTileList / tiles_per_rel));
   RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, 65535));
   if (prune && tiles_per_rel > kMaxTileList) return fail(hd, KGC_E_INVALID, "N too large for the pruned tile list");
@@ -536,7 +543,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
                    (rc = ensure(hd, hd->relu, (size_t)RBmax * n_micro * 4)) || (rc = ensure(hd, hd->reln, RBmax * 4))))
       return rc;
   }
-  const int nbatch = (int)((R + RBmax - 1) / RBmax);
+  const int nbatch = (int)((Rn + RBmax - 1) / RBmax);
   while ((int)hd->join_ev.size() < 2 * nbatch) {
     hipEvent_t e;
     KGC_HIP(hd, hipEventCreate(&e));
@@ -580,8 +587,8 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   KGC_HIP(hd, hipEventRecord(hd->ev[1], st));
 
   int b = 0;
-  for (int64_t r0 = 0; r0 < R; r0 += RBmax, ++b) {
-    const int RB = (int)std::min<int64_t>(RBmax, R - r0);
+  for (int64_t r0 = r_begin; r0 < r_end; r0 += RBmax, ++b) {
+    const int RB = (int)std::min<int64_t>(RBmax, r_end - r0);
     const uint32_t* row_start = nullptr;
     const uint32_t* row_count = nullptr;
     const uint32_t* cols = nullptr;
@@ -725,7 +732,7 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   kgc_stats& s = hd->stats;
   s.emitted = hd->host_counters->hits;
   s.candidates = hd->host_counters->candidates;
-  s.tiles_total = (uint64_t)tiles_per_rel * (uint64_t)R;
+  s.tiles_total = (uint64_t)tiles_per_rel * (uint64_t)Rn;
   s.tiles_evaluated = prune ? hd->host_counters->tiles : s.tiles_total;
   s.tiles_pruned = s.tiles_total - s.tiles_evaluated;
   s.pairs_evaluated = prune ? s.tiles_evaluated * (uint64_t)BM * (uint64_t)BN : s.triples_total;

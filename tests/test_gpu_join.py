@@ -289,3 +289,36 @@ def test_top1_with_self_edges_and_overflow(exclude_self):
     Rv = np.concatenate([np.zeros((1, 16), np.float32), g.standard_normal((2, 16)).astype(np.float32)])
     got, ref = _check_top1(E, Rv, 2, exclude_self, prune=PRUNE_ON)
     assert ref["dist"] == 0.0 and got["dist"] == 0.0
+
+
+# ---- relation ranges (the relation-wise partition of Section 4.7): the union of the parts is the whole ----
+@pytest.mark.parametrize("mode", ["dense", "prune", "factorised", "l1"])
+def test_join_range_partition(mode):
+    import paper_2307_12059_amd as kgc
+    wl = workloads.generate("c1_tiny_l2")
+    p = 1 if mode == "l1" else 2
+    delta = wl.delta if p == 2 else 2.6
+    ref = oracle.join(wl.E, wl.Rv, p, delta, mode="abandon")
+    assert ref["count"] > 0
+    j = kgc.Join(prune=PRUNE_ON if mode in ("prune", "l1") else PRUNE_OFF, factorised=(mode == "factorised"))
+    try:
+        Ed, Rd = _dev(wl.E, "f32"), _dev(wl.Rv, "f32")
+        R = wl.Rv.shape[0]
+        parts = []
+        for lo, hi in ((0, 3), (3, 3), (3, 4), (4, R)):              # an empty range among them
+            got = j.join(Ed, Rd, p, delta, 1 << 16, r_range=(lo, hi))
+            assert got["code"] == 0
+            assert np.all((got["r"] >= lo) & (got["r"] < hi))
+            assert got["count"] == int(np.sum((ref["r"] >= lo) & (ref["r"] < hi)))
+            assert got["stats"]["triples_total"] == wl.E.shape[0] ** 2 * (hi - lo)
+            parts.append(got)
+        merged = {k: np.concatenate([g[k] for g in parts]) for k in ("h", "r", "t", "dist")}
+        rep = parity.compare(merged, ref, wl.E, wl.Rv, p, delta, wl.E.shape[0])
+        assert rep["gpu_count"] == ref["count"] and rep["only_gpu_in_band"] == 0 and rep["only_oracle_in_band"] == 0
+        # a range whose result does not fit reports the overflow with the true count of the range
+        small = j.join(Ed, Rd, p, delta, 8, r_range=(0, R))
+        assert small["code"] == 1 and small["count"] == ref["count"]
+        with pytest.raises(RuntimeError):
+            j.join(Ed, Rd, p, delta, 8, r_range=(2, R + 1))
+    finally:
+        j.close()
