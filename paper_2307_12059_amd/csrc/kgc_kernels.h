@@ -1197,29 +1197,41 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_fact(const JoinFac
         uh[q * BM + row] = 2.f * a.u[(int64_t)(rl0 + q) * a.Nslots + (int64_t)tH * BM + row];
       }
       __syncthreads();
+      // the per-column part of the threshold (lim_r + 2 r.t) is fetched one relation ahead of its use
+      float nlimr = a.limr[rl0], nut[TN];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) nut[j] = a.u[(int64_t)rl0 * a.Nslots + tcol0 + 32 * j];
       for (int q = 0; q < nr; ++q) {
         const int rl = rl0 + q;
         float lim[TN], mn[TN];
-        const float limr = a.limr[rl];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          lim[j] = limr + 2.f * a.u[(int64_t)rl * a.Nslots + tcol0 + 32 * j];
+          lim[j] = nlimr + 2.f * nut[j];
           mn[j] = 3e38f;
+        }
+        {
+          const int rn = q + 1 < nr ? rl + 1 : rl;              // the last one re-reads itself
+          nlimr = a.limr[rn];
+#pragma unroll
+          for (int j = 0; j < TN; ++j) nut[j] = a.u[(int64_t)rn * a.Nslots + tcol0 + 32 * j];
         }
         const float* uq = uh + q * BM + urow;
         // per element one addition and half a three-way minimum; the 2 r.h values of this lane's rows come
-        // from LDS, four rows per read (two addresses per wave)
+        // from LDS, four rows per read (two addresses per wave), two reads ahead of their use
+        constexpr int NH4 = TM * 4;
+        float4 hq0 = *(const float4*)(uq), hq1 = *(const float4*)(uq + 8);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int k = 0; k < NH4; ++k) {
+          const int i = k >> 2, vg = k & 3;                          // rows v = 4 vg .. 4 vg + 3 of block i
+          const float4 hh = hq0;
+          hq0 = hq1;
+          if (k + 2 < NH4) hq1 = *(const float4*)(uq + ((k + 2) >> 2) * 32 + 8 * ((k + 2) & 3));
 #pragma unroll
-          for (int vg = 0; vg < 4; ++vg) {
-            const float4 hh = *(const float4*)(uq + i * 32 + 8 * vg);      // rows v = 4 vg .. 4 vg + 3 of block i
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-              mn[j] = fminf(fminf(mn[j], acc[i][j][4 * vg + 0] + hh.x), acc[i][j][4 * vg + 1] + hh.y);
-              mn[j] = fminf(fminf(mn[j], acc[i][j][4 * vg + 2] + hh.z), acc[i][j][4 * vg + 3] + hh.w);
-            }
+          for (int j = 0; j < TN; ++j) {
+            mn[j] = fminf(fminf(mn[j], acc[i][j][4 * vg + 0] + hh.x), acc[i][j][4 * vg + 1] + hh.y);
+            mn[j] = fminf(fminf(mn[j], acc[i][j][4 * vg + 2] + hh.z), acc[i][j][4 * vg + 3] + hh.w);
           }
+        }
         bool any = false;
 #pragma unroll
         for (int j = 0; j < TN; ++j) any |= mn[j] <= lim[j];
