@@ -54,7 +54,13 @@ typedef struct {
     int32_t dtype;            /* KGC_F32 (default) or KGC_BF16: element type of E and Rv */
     int32_t max_d;            /* largest d this handle accepts; 0 = 960 (the compiled limit) */
     int32_t prune;            /* KGC_PRUNE_* */
-    int32_t tile_cfg;         /* 0 = automatic choice of the join kernel's tile shape; >0 selects a variant */
+    int32_t tile_cfg;         /* 0 = automatic choice of the L2 join kernel; > 0 forces a variant (for measurements):
+                                 1-5   one block per tile pair, 128/256-row tiles (dense mode only)
+                                 6-10  streaming: a block walks tail tiles, head and tail slices through LDS (any d)
+                                 11-14 head tile resident in LDS, tail slices through LDS (d <= 218; pruned default 12)
+                                 15-17 head tile resident, tail fragments straight to registers, no barrier in the
+                                       loop (dense mode only; 15-16: d <= 282, dense default 15; 17: d <= 602)
+                                 A variant that cannot run the request (pruned mode, d) fails with KGC_E_INVALID. */
     int64_t workspace_bytes;  /* cap on scratch held for staged operands; 0 = 16 GiB.  Larger joins run in relation batches */
     void*   stream;           /* hipStream_t to enqueue on; NULL = the default stream */
     float   group_radius;     /* pruning only: radius of entity groups as a multiple of delta; 0 = 2.0 */
