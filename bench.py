@@ -150,7 +150,12 @@ def main():
     # The join kernel's roofline is measured where every tile goes through it: the dense (prune off) mode, the
     # analogue of the paper's naive GPU approach.  When the timed run is the pruned one, a few dense steps are
     # run in the same invocation for it.
-    dense = main_run if args.prune == "off" else (run(False, args.also_dense, 1) if args.also_dense > 0 else None)
+    # (a dense pass over the 1e15-triple workload would take minutes per step: the extra legs are only run when
+    # their estimated cost is a few seconds)
+    est_dense_s = 2.0 * d * N * N * R / (1.0e15 if p == 2 else 3.5e13)
+    est_fact_s = 1.5 * N * N * R / 3.0e13
+    want_dense = args.also_dense > 0 and est_dense_s * (args.also_dense + 1) <= 20.0
+    dense = main_run if args.prune == "off" else (run(False, args.also_dense, 1) if want_dense else None)
     roof = dict((dense or main_run)["roofline"])
     roof["measured_in"] = "dense (prune off) steps of this invocation" if dense is not None else "the timed (pruned) steps"
     if dense is not None:
@@ -186,7 +191,7 @@ def main():
                          "hits": dense["count"], "phase_ms": dense["phase_ms"],
                          "speedup_prune_on_vs_off": dense["ms_per_step"] / main_run["ms_per_step"]}
         assert dense["count"] == main_run["count"], "pruned and dense runs disagree on the number of hits"
-    if p == 2 and d <= 282 and args.also_factorised > 0:
+    if p == 2 and d <= 282 and args.also_factorised > 0 and est_fact_s * (args.also_factorised + 1) <= 20.0:
         fr = run(False, args.also_factorised, 1, factorised=True)
         assert fr["count"] == main_run["count"], "factorised and main runs disagree on the number of hits"
         line["dense_factorised"] = {"ms_per_step": fr["ms_per_step"], "value": N * N * R / (fr["ms_per_step"] * 1e-3),
