@@ -57,6 +57,9 @@ def _load():
                                   ip, ip, ip, dp, lp]
         lib.kgco_dist_triples.restype = None
         lib.kgco_dist_triples.argtypes = [dp, ctypes.c_int32, dp, ctypes.c_int32, ip, ip, ip, ctypes.c_int64, dp]
+        lib.kgco_join_ab.restype = ctypes.c_int64
+        lib.kgco_join_ab.argtypes = [dp, dp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.c_double, ctypes.c_int64, ip, ip, ip, dp]
         lib.kgco_top1.restype = ctypes.c_int32
         lib.kgco_top1.argtypes = [dp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                   ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
@@ -124,6 +127,36 @@ def join(E, Rv, p: int, delta: float, mode: str = "brute", pivot=None, range_imp
     order = np.lexsort((ot, oh, orr))
     return {"h": oh[order], "r": orr[order], "t": ot[order], "dist": od[order], "count": n,
             "evaluated": int(ev.value)}
+
+
+def join_ab(A, B, p: int, delta: float, cap: Optional[int] = None) -> dict:
+    """The join on connector outputs supplied by the caller (Section 4.3): all (h, r, t) with
+    ||A[r][h] - B[r][t]||_p <= delta.  ``A`` is R x N x d; ``B`` is R x N x d, or 1 x N x d (or N x d) when
+    connector_2 does not depend on the relation.  Same result convention as ``join``."""
+    lib = _load()
+    A64, B64 = _f64(A), _f64(B)
+    if B64.ndim == 2:
+        B64 = B64[None]
+    if A64.ndim != 3 or B64.ndim != 3 or A64.shape[1:] != B64.shape[1:] or B64.shape[0] not in (1, A64.shape[0]):
+        raise ValueError("A must be R x N x d and B must be R x N x d or 1 x N x d")
+    R, N, d = A64.shape
+    per_rel = 1 if (B64.shape[0] == R and R > 1) else 0
+    cap = int(cap) if cap is not None else 1 << 20
+    while True:
+        oh = np.empty(cap, np.int32); orr = np.empty(cap, np.int32); ot = np.empty(cap, np.int32)
+        od = np.empty(cap, np.float64)
+        total = lib.kgco_join_ab(_ptr(A64, ctypes.c_double), _ptr(B64, ctypes.c_double), N, d, R, per_rel, int(p),
+                                 float(delta), cap, _ptr(oh, ctypes.c_int32), _ptr(orr, ctypes.c_int32),
+                                 _ptr(ot, ctypes.c_int32), _ptr(od, ctypes.c_double))
+        if total < 0:
+            raise ValueError("oracle rejected its arguments (p must be 1 or 2)")
+        if total <= cap:
+            break
+        cap = int(total)
+    n = int(total)
+    oh, orr, ot, od = oh[:n], orr[:n], ot[:n], od[:n]
+    order = np.lexsort((ot, oh, orr))
+    return {"h": oh[order], "r": orr[order], "t": ot[order], "dist": od[order], "count": n}
 
 
 def dist_triples(E, Rv, p: int, h, r, t) -> np.ndarray:

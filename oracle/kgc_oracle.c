@@ -158,6 +158,31 @@ void kgco_dist_triples(const double *E, int32_t d, const double *Rv, int32_t p, 
         out[k] = triple_dist(E + (int64_t)h[k] * d, Rv + (int64_t)r[k] * d, E + (int64_t)t[k] * d, d, p);
 }
 
+/* ---- the join in its general form (Section 4.3): the caller supplies the connector outputs ----
+ * A[R][N][d] holds a_{r,h} = connector_1(h, r); B[RB][N][d] holds b_{r,t} = connector_2(t, r), with RB = R when
+ * connector_2 depends on the relation (b_per_rel != 0) and RB = 1 when it does not (TransE: b = t).  All
+ * (h, r, t) with dist(a_{r,h}, b_{r,t}) = ||a - b||_p <= delta, by the plain triple loop in double, every
+ * distance summed in full, dimensions ascending.  Same output convention as kgco_join. */
+int64_t kgco_join_ab(const double *A, const double *B, int64_t N, int32_t d, int32_t R, int32_t b_per_rel, int32_t p,
+                     double delta, int64_t cap, int32_t *oh, int32_t *or_, int32_t *ot, double *od)
+{
+    if ((p != 1 && p != 2) || N < 0 || R < 0 || d < 0) return -1;
+    int64_t total = 0;
+    for (int32_t r = 0; r < R; ++r) {
+        const double *Ar = A + (int64_t)r * N * d;
+        const double *Br = B + (b_per_rel ? (int64_t)r * N * d : 0);
+        for (int64_t h = 0; h < N; ++h)
+            for (int64_t t = 0; t < N; ++t) {
+                double v = metric_dist(Ar + h * d, Br + t * d, d, p);
+                if (v <= delta) {
+                    if (total < cap) { oh[total] = (int32_t)h; or_[total] = r; ot[total] = (int32_t)t; od[total] = v; }
+                    ++total;
+                }
+            }
+    }
+    return total;
+}
+
 /* ---- top-1: the smallest distance over all triples (the "top-1 score" of Section 3.3), optionally
  * leaving out the self pairs h == t (the paper's "top-1 score except self-edges").  Plain triple loop,
  * every distance summed in full.  Among equal distances the smallest (r, h, t) wins.  Returns 1 and fills

@@ -303,3 +303,36 @@ def test_top1_degenerate():
     assert (a["h"], a["t"]) == (0, 0) and abs(a["dist"] - np.sqrt(3.0)) < 1e-15
     assert oracle.top1(np.zeros((0, 3)), R, 2) is None
     assert oracle.top1(E1, np.zeros((0, 3)), 1) is None
+
+
+# ---- general form of Section 4.3: connector outputs supplied by the caller ----
+def test_join_ab_reduces_to_transe_and_cdist():
+    from scipy.spatial.distance import cdist
+    g = np.random.default_rng(11)
+    E = g.standard_normal((50, 7)); R = g.standard_normal((3, 7)) * 0.4
+    A = E[None, :, :] + R[:, None, :]                   # connector_1(h, r) = h + r, connector_2(t, r) = t
+    for p, metric, delta in ((2, "euclidean", 2.2), (1, "cityblock", 5.0)):
+        ref = oracle.join(E, R, p, delta, mode="brute")
+        assert ref["count"] > 0
+        for B in (E, E[None], np.broadcast_to(E, (3, 50, 7)).copy()):
+            got = oracle.join_ab(A, B, p, delta)
+            assert got["count"] == ref["count"]
+            assert np.array_equal(got["h"], ref["h"]) and np.array_equal(got["r"], ref["r"]) and np.array_equal(got["t"], ref["t"])
+            # (h + r) - t and a - t differ by the rounding of a = h + r only
+            assert np.allclose(got["dist"], ref["dist"], rtol=1e-13, atol=1e-13)
+    # relation-dependent connector on both sides (SE-like: a = W1_r h, b = W2_r t), against scipy
+    W1 = g.standard_normal((3, 7, 7)) * 0.3; W2 = g.standard_normal((3, 7, 7)) * 0.3
+    A = np.einsum("rij,nj->rni", W1, E); B = np.einsum("rij,nj->rni", W2, E)
+    for p, metric in ((2, "euclidean"), (1, "cityblock")):
+        D = np.stack([cdist(A[r], B[r], metric) for r in range(3)])
+        delta = float(np.quantile(D, 0.02))
+        got = oracle.join_ab(A, B, p, delta)
+        rr, hh, tt = np.nonzero(D <= delta)
+        assert got["count"] == rr.size > 0
+        assert np.array_equal(got["r"], rr) and np.array_equal(got["h"], hh) and np.array_equal(got["t"], tt)
+        assert np.allclose(got["dist"], D[rr, hh, tt], rtol=1e-13)
+    # a swapped relation index on the B side would show here: B differs per relation
+    d2 = float(np.quantile(np.stack([cdist(A[r], B[r]) for r in range(3)]), 0.02))
+    straight = oracle.join_ab(A, B, 2, d2)
+    swapped = oracle.join_ab(A, B[::-1].copy(), 2, d2)
+    assert not (swapped["count"] == straight["count"] and np.array_equal(swapped["h"], straight["h"]))
