@@ -135,6 +135,19 @@ int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* R
 int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
                    float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
 
+/* The join in its general form (Section 4.3): for a model that is "transformable to a metric space" the
+ * caller supplies the connector outputs and the library joins them under dist(a, b) = ||a - b||_p:
+ *   A   R x N x d   a_{r,h} = connector_1(h, r), row-major, contiguous, of the handle's dtype          (device)
+ *   B   N x d when b_per_relation == 0 (connector_2 does not depend on r; TransE: b = t), else R x N x d
+ *       with b_{r,t} = connector_2(t, r)                                                               (device)
+ * finds every (h, r, t) with ||A[r][h] - B[r or 0][t]||_p <= delta.  TransE is A[r][h] = E[h] + Rv[r], B = E; the
+ * structured-embedding model of the same section is A[r] = E W1_r^T, B[r] = E W2_r^T with p = 1.  Output, count,
+ * overflow and error conventions are those of kgc_join; the exact stage scores (double)a - (double)b.  Every
+ * relation runs through the dense join kernels (one launch per relation); the handle's pruning setting is not
+ * used, since the grouping of kgc_join relies on connector_1 being a translation. */
+int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t d, int32_t R, int32_t b_per_relation,
+                int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
+
 /* The top-1 score of Section 3.3: the triple with the smallest dist_3(h, r, t) over E x R x E, or, with
  * exclude_self != 0, over the triples with h != t (the paper's "top-1 score except self-edges").
  *   out   receives the triple and its distance (host).  h = r = t = -1 and dist = +inf when no triple is

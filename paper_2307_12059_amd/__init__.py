@@ -23,7 +23,7 @@ KGC_PRUNE_AUTO, KGC_PRUNE_OFF, KGC_PRUNE_ON = 0, 1, 2
 KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
-EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_top1", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
+EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_top1", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
            "kgc_version"]
 
 
@@ -77,6 +77,9 @@ def load_library():
     lib.kgc_join_range.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
                                    ctypes.c_float, ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_uint64,
                                    ctypes.POINTER(ctypes.c_uint64)]
+    lib.kgc_join_ab.restype = ctypes.c_int
+    lib.kgc_join_ab.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                ctypes.c_float, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64)]
     lib.kgc_top1.restype = ctypes.c_int
     lib.kgc_top1.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                              ctypes.POINTER(kgc_triple)]
@@ -138,6 +141,16 @@ def kgc_join_range(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: in
     rc = load_library().kgc_join_range(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R,
                                        p, ctypes.c_float(delta), r_begin, r_end, ctypes.c_void_p(out_ptr), cap,
                                        ctypes.byref(count))
+    return rc, int(count.value)
+
+
+def kgc_join_ab(handle, A_ptr: int, B_ptr: int, N: int, d: int, R: int, b_per_relation: bool, p: int, delta: float,
+                out_ptr: int, cap: int):
+    """Raw call on device addresses: the join on caller-supplied connector outputs.  Returns (code, count)."""
+    count = ctypes.c_uint64(0)
+    rc = load_library().kgc_join_ab(ctypes.c_void_p(handle), ctypes.c_void_p(A_ptr), ctypes.c_void_p(B_ptr), N, d, R,
+                                    1 if b_per_relation else 0, p, ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap,
+                                    ctypes.byref(count))
     return rc, int(count.value)
 
 
@@ -229,6 +242,26 @@ class Join:
             res.update({"h": host[:, 0].copy(), "r": host[:, 1].copy(), "t": host[:, 2].copy(),
                         "dist": host[:, 3].copy().view("float32")})
         return res
+
+    def join_ab(self, A, B, p: int, delta: float, cap: int) -> dict:
+        """The general form: ``A`` is R x N x d, ``B`` is N x d (shared) or R x N x d (per relation)."""
+        torch = self._torch
+        if A.dim() != 3 or B.dim() not in (2, 3) or not A.is_contiguous() or not B.is_contiguous():
+            raise ValueError("A must be R x N x d and B N x d or R x N x d, contiguous")
+        if A.dtype != B.dtype or A.dtype != (torch.float32 if self.dtype == "f32" else torch.bfloat16) or not A.is_cuda or not B.is_cuda:
+            raise ValueError("A and B must be CUDA tensors of the handle's dtype")
+        R, N, d = A.shape
+        per_rel = B.dim() == 3
+        if tuple(B.shape[-2:]) != (N, d) or (per_rel and B.shape[0] != R):
+            raise ValueError("B does not match A")
+        out = torch.empty((max(cap, 1), 4), dtype=torch.int32, device=A.device)
+        rc, count = kgc_join_ab(self.handle, A.data_ptr(), B.data_ptr(), N, d, R, per_rel, p, float(delta), out.data_ptr(), cap)
+        if rc < 0:
+            raise RuntimeError(f"kgc_join_ab failed with code {rc}: {kgc_last_error(self.handle)}")
+        n = min(count, cap)
+        host = out[:n].cpu().numpy()
+        return {"code": rc, "count": count, "stats": kgc_get_stats(self.handle), "h": host[:, 0].copy(),
+                "r": host[:, 1].copy(), "t": host[:, 2].copy(), "dist": host[:, 3].copy().view("float32")}
 
     def top1(self, E, Rv, p: int, exclude_self: bool = False):
         """The triple with the smallest distance (None when no triple is eligible): dict h, r, t, dist."""

@@ -42,6 +42,7 @@ struct kgc_handle {
   DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
   DevBuf active_rows, cnorm, gram, relu, reln, asg_a, asg_b, limr;
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
+  DevBuf zero_row;                             // kgc_join_ab: the relation vector every relation reads (zeros)
   DevBuf top1_a, top1_b, top1_pick;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
   GroupState* host_gstate = nullptr;           // pinned
@@ -201,6 +202,121 @@ void kgc_destroy(kgc_handle* h) {
 
 const char* kgc_last_error(const kgc_handle* h) { return h ? h->err.c_str() : "null handle"; }
 
+int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t d, int32_t R, int32_t b_per_relation,
+                int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count) {
+  if (!hd) return KGC_E_INVALID;
+  if (!count) return fail(hd, KGC_E_INVALID, "count is NULL");
+  *count = 0;
+  int rc = check_common(hd, A, N, d, B, R);
+  if (rc != KGC_OK) return rc;
+  if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
+  if (std::isnan(delta)) return fail(hd, KGC_E_INVALID, "delta is NaN");
+  if (cap > 0 && !out_triples) return fail(hd, KGC_E_INVALID, "out_triples is NULL with cap > 0");
+  if ((uintptr_t)out_triples % 16) return fail(hd, KGC_E_INVALID, "out_triples must be 16-byte aligned");
+  hd->err.clear();
+  hd->stats = kgc_stats{};
+  hd->stats.triples_total = (uint64_t)N * (uint64_t)N * (uint64_t)R;
+  if (N == 0 || R == 0) return KGC_OK;
+
+  hipStream_t st = hd->stream;
+  const int dtype = hd->cfg.dtype;
+  const size_t esz = dtype == KGC_BF16 ? 2 : 4;
+  const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
+  const int k16 = (d + kNormCols + 15) / 16;
+  // the dense kernels of kgc_join, one relation per launch (the tail side may change with the relation)
+  const int tile_id = KS <= kDirectMaxKS ? kDirectL2Tile : KS <= kDirectHalfMaxKS ? kDirectHalfL2Tile : kDefaultL2Tile;
+  const TileCfg tc = kL2Tiles[tile_id];
+  const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
+  const int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
+  const int nH = (int)(Nslots / BM), nT = (int)(Nslots / BN);
+  if (nH > 65535 && p == 1) return fail(hd, KGC_E_INVALID, "N too large for one launch grid");
+  const size_t op_bytes = (size_t)KS * Nslots * kSliceK * 2;
+  if ((rc = ensure(hd, hd->counters, sizeof(DevCounters))) || (rc = ensure(hd, hd->params, sizeof(JoinParams))) ||
+      (rc = ensure(hd, hd->slot_ent, Nslots * 4)) || (rc = ensure(hd, hd->zero_row, (size_t)d * 4)))
+    return rc;
+  if (p == 2 && ((rc = ensure(hd, hd->opA, op_bytes)) || (rc = ensure(hd, hd->opB, op_bytes)))) return rc;
+  DevCounters* cnt = (DevCounters*)hd->counters.p;
+  JoinParams* prm = (JoinParams*)hd->params.p;
+  const int32_t* slot_ent = (const int32_t*)hd->slot_ent.p;
+  while (hd->join_ev.size() < 2) {
+    hipEvent_t e;
+    KGC_HIP(hd, hipEventCreate(&e));
+    hd->join_ev.push_back(e);
+  }
+  KGC_HIP(hd, hipEventRecord(hd->ev[0], st));
+  k_fill_u32<<<grid_for(sizeof(DevCounters) / 4, 256), 256, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
+  k_fill_u32<<<grid_for(d, 256), 256, 0, st>>>((uint32_t*)hd->zero_row.p, d, 0u);
+  k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
+  KGC_HIP(hd, hipEventRecord(hd->join_ev[0], st));
+
+  RecheckCtx cx{};
+  cx.Rv = hd->zero_row.p; cx.rstride = 0;             // the head rows already are connector_1(h, r)
+  cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p; cx.delta = (double)delta;
+  cx.out = out_triples; cx.cap = cap; cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates; cx.no_self = 0;
+  const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
+  size_t dyn_lds = 0;
+  int64_t nsplit = 1;
+  if (p == 2) {
+    if (tc.head_resident) {
+      dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
+      KGC_HIP(hd, hipFuncSetAttribute((const void*)tc.stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
+    }
+    const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
+    const int64_t range_bytes = tc.head_resident ? kL2RangeBytesResident : kL2RangeBytes;
+    nsplit = (nT * tile_bytes + range_bytes - 1) / range_bytes;
+    nsplit = std::max<int64_t>(nsplit, (2048 + nH - 1) / nH);
+    nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
+  }
+  for (int32_t r = 0; r < R; ++r) {
+    const char* Ar = (const char*)A + (size_t)r * N * d * esz;
+    const char* Br = (const char*)B + (b_per_relation ? (size_t)r * N * d * esz : 0);
+    cx.E = Ar; cx.Et = Br;
+    if (p == 2) {
+      if (r == 0 || b_per_relation)
+        k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
+            Br, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
+            kStageRows);
+      k_stage_operands<true><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
+          Ar, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, nullptr, cnt->max_a, nullptr, nullptr, 0,
+          kStageRows);
+      // the maxima only grow from relation to relation: the filter threshold stays on the safe side
+      k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
+      JoinStreamArgs sa{};
+      sa.A = (const uint16_t*)hd->opA.p; sa.B = (const uint16_t*)hd->opB.p; sa.prm = prm; sa.Nslots = Nslots;
+      sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = r; sa.RB = 1; sa.cx = cx;
+      hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, 1, (unsigned)nsplit), dim3(tc.threads), dyn_lds, st, sa);
+    } else {
+      k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(Ar, N, d, dtype, cnt->max_a);
+      if (r == 0 || b_per_relation) k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(Br, N, d, dtype, cnt->max_b);
+      k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, 0);
+      JoinL1Args la{};
+      la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = r; la.RB = 1; la.cx = cx;
+      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)nT, (unsigned)nH, 1), dim3(256), 0, st, la);
+    }
+    hd->stats.join_launches++;
+  }
+  KGC_HIP(hd, hipEventRecord(hd->join_ev[1], st));
+  KGC_HIP(hd, hipGetLastError());
+  KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 48, hipMemcpyDeviceToHost, st));
+  KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
+  KGC_HIP(hd, hipStreamSynchronize(st));
+
+  kgc_stats& s = hd->stats;
+  s.emitted = hd->host_counters->hits;
+  s.candidates = hd->host_counters->candidates;
+  s.tiles_total = s.tiles_evaluated = (uint64_t)nH * (uint64_t)nT * (uint64_t)R;
+  s.pairs_evaluated = s.triples_total;
+  s.tile_m = BM; s.tile_n = BN;
+  s.k_padded = (p == 2) ? k16 * 16 : d;
+  s.relation_batches = R;
+  s.join_variant = (p == 2) ? tile_id + 1 : 0;
+  (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);
+  (void)hipEventElapsedTime(&s.ms_join, hd->join_ev[0], hd->join_ev[1]);   // staging of each relation included
+  s.ms_precompute = s.ms_total - s.ms_join;
+  *count = s.emitted;
+  return s.emitted > cap ? KGC_OVERFLOW : KGC_OK;
+}
+
 int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
              int32_t exclude_self, kgc_triple* out) {
   if (!hd) return KGC_E_INVALID;
@@ -219,7 +335,7 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   Top1State* ts = (Top1State*)hd->top1_state.p;
   Top1State host{};
   RecheckCtx cx{};
-  cx.E = E; cx.Rv = Rvecs; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
 
   // 1. an upper bound of the answer: the smallest of 65,536 sampled eligible triples
   const int n_sample = 1 << 16;
@@ -551,7 +667,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   }
 
   RecheckCtx cx;
-  cx.E = E; cx.Rv = Rvecs; cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
   cx.delta = (double)delta; cx.out = out_triples; cx.cap = cap; cx.no_self = hd->no_self;
   cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates;
 

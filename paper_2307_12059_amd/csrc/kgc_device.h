@@ -61,8 +61,11 @@ __device__ __forceinline__ void wave_append(bool pred, int32_t h, int32_t r, int
 
 // What the second stage needs to re-score a candidate from the caller's arrays.
 struct RecheckCtx {
-  const void* E;
+  const void* E;             // rows of the head side: x = (E[h] + Rv[r]) - Et[t]
+  const void* Et;            // rows of the tail side (the same array as E for the TransE join)
   const void* Rv;
+  int64_t rstride;           // elements between relation vectors: d, or 0 when every relation reads row 0 of Rv
+                             // (the general form, whose head rows already are connector_1(h, r): Rv is a zero row)
   const int32_t* slot_ent;   // slot -> entity row, -1 for padding
   int dtype;
   int d;
@@ -82,12 +85,12 @@ struct RecheckCtx {
 // rather than one per dimension.
 __device__ __forceinline__ double group16_exact_dist(const RecheckCtx& cx, int32_t h, int32_t r, int32_t t, int sub) {
   const int d = cx.d;
-  const int64_t ho = (int64_t)h * d, to = (int64_t)t * d, ro = (int64_t)r * d;
+  const int64_t ho = (int64_t)h * d, to = (int64_t)t * d, ro = (int64_t)r * cx.rstride;
   double s0 = 0.0, s1 = 0.0;
   const bool p2 = cx.p == 2;
   if (cx.dtype == KGC_F32 && (d & 3) == 0) {
     const float4* eh = (const float4*)((const float*)cx.E + ho);
-    const float4* et = (const float4*)((const float*)cx.E + to);
+    const float4* et = (const float4*)((const float*)cx.Et + to);
     const float4* rv = (const float4*)((const float*)cx.Rv + ro);
     const int nch = d >> 2;
 #pragma unroll 1
@@ -100,7 +103,7 @@ __device__ __forceinline__ double group16_exact_dist(const RecheckCtx& cx, int32
     }
   } else if (cx.dtype == KGC_BF16 && (d & 7) == 0) {
     const uint4* eh = (const uint4*)((const uint16_t*)cx.E + ho);
-    const uint4* et = (const uint4*)((const uint16_t*)cx.E + to);
+    const uint4* et = (const uint4*)((const uint16_t*)cx.Et + to);
     const uint4* rv = (const uint4*)((const uint16_t*)cx.Rv + ro);
     const int nch = d >> 3;
 #pragma unroll 1
@@ -121,7 +124,7 @@ __device__ __forceinline__ double group16_exact_dist(const RecheckCtx& cx, int32
 #pragma unroll 1
     for (int k = sub; k < d; k += 16) {
       const double x = ((double)ld_elem(cx.E, ho + k, cx.dtype) + (double)ld_elem(cx.Rv, ro + k, cx.dtype)) -
-                       (double)ld_elem(cx.E, to + k, cx.dtype);
+                       (double)ld_elem(cx.Et, to + k, cx.dtype);
       s0 += p2 ? x * x : fabs(x);
     }
   }
@@ -142,7 +145,7 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
                                                          int32_t r, int sub, double (&out)[NC]) {
   const int d = cx.d;
   const bool p2 = cx.p == 2;
-  const int64_t ro = (int64_t)r * d;
+  const int64_t ro = (int64_t)r * cx.rstride;
   int64_t ho[NC], to[NC];
   double s0[NC], s1[NC];                 // two partial sums per candidate, as in the single form
 #pragma unroll
@@ -162,7 +165,7 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
 #pragma unroll
       for (int n = 0; n < NC; ++n) {
         x[n] = ((const float4*)((const float*)cx.E + ho[n]))[c];
-        y[n] = ((const float4*)((const float*)cx.E + to[n]))[c];
+        y[n] = ((const float4*)((const float*)cx.Et + to[n]))[c];
       }
 #pragma unroll
       for (int n = 0; n < NC; ++n) {
@@ -182,7 +185,7 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
 #pragma unroll
       for (int n = 0; n < NC; ++n) {
         x[n] = ((const uint4*)((const uint16_t*)cx.E + ho[n]))[c];
-        y[n] = ((const uint4*)((const uint16_t*)cx.E + to[n]))[c];
+        y[n] = ((const uint4*)((const uint16_t*)cx.Et + to[n]))[c];
       }
       const uint32_t rw[4] = {rr.x, rr.y, rr.z, rr.w};
 #pragma unroll

@@ -1448,7 +1448,7 @@ __global__ __launch_bounds__(256, 3) void k_join_l1(const JoinL1Args a) {
   const int tx = tid & 15, ty = tid >> 4;
   // staging assignment: thread -> (row = tid / 2, eight dimensions starting at (tid % 2) * 8)
   const int srow = tid >> 1, sk0 = (tid & 1) * 8;
-  const int64_t ro = (int64_t)r * d;
+  const int64_t ro = (int64_t)r * a.cx.rstride;
   if (tid < BM) hent[tid] = a.cx.slot_ent[(int64_t)tH * BM + tid];
 
 #pragma unroll 1
@@ -1473,7 +1473,7 @@ __global__ __launch_bounds__(256, 3) void k_join_l1(const JoinL1Args a) {
         const int k = k0 + sk0 + q;
         const bool in = k < d;
         va[q] = in ? ld_elem(a.cx.E, ho + k, dtype) + ld_elem(a.cx.Rv, ro + k, dtype) : 0.f;
-        vb[q] = in ? ld_elem(a.cx.E, to + k, dtype) : 0.f;
+        vb[q] = in ? ld_elem(a.cx.Et, to + k, dtype) : 0.f;
       }
       __syncthreads();                      // previous slice fully consumed
 #pragma unroll

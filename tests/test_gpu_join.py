@@ -322,3 +322,83 @@ def test_join_range_partition(mode):
             j.join(Ed, Rd, p, delta, 8, r_range=(2, R + 1))
     finally:
         j.close()
+
+
+# ---- general form of Section 4.3: connector outputs supplied by the caller (kgc_join_ab) ----
+def _run_ab(A, B, p, delta, cap, dtype="f32"):
+    import paper_2307_12059_amd as kgc
+    torch = _torch()
+    def dev(x):
+        t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+        return t.to(torch.bfloat16).contiguous() if dtype == "bf16" else t
+    j = kgc.Join(dtype=dtype)
+    try:
+        return j.join_ab(dev(A), dev(B), p, delta, cap)
+    finally:
+        j.close()
+
+
+def _compare_ab(got, ref, A, B, p, delta, N):
+    """Set equality outside the boundary band, distances to 1e-4 (the TransE comparison on (r, h, t) keys)."""
+    per_rel = B.ndim == 3
+    def dist(h, r, t):
+        x = A[r, h].astype(np.float64) - (B[r, t] if per_rel else B[t]).astype(np.float64)
+        return np.sqrt((x * x).sum(-1)) if p == 2 else np.abs(x).sum(-1)
+    gk = (got["r"].astype(np.int64) * N + got["h"]) * N + got["t"]
+    rk = (ref["r"].astype(np.int64) * N + ref["h"]) * N + ref["t"]
+    assert np.unique(gk).size == gk.size
+    tol = parity.BAND * abs(delta)
+    only_g, only_r = ~np.isin(gk, rk), ~np.isin(rk, gk)
+    if only_g.any():
+        dg = dist(got["h"][only_g], got["r"][only_g], got["t"][only_g])
+        assert np.all(np.abs(dg - delta) <= tol), "GPU triples outside the oracle set and outside the band"
+    assert np.all(np.abs(ref["dist"][only_r] - delta) <= tol), "oracle triples missing outside the band"
+    go, ro = np.argsort(gk), np.argsort(rk)
+    cg, cr = np.isin(gk[go], rk), np.isin(rk[ro], gk)
+    dg, dr = got["dist"][go][cg].astype(np.float64), ref["dist"][ro][cr]
+    assert np.all(np.abs(dg - dr) <= np.maximum(parity.DIST_RTOL * np.abs(dr), parity.DIST_ATOL))
+    return int(only_g.sum()), int(only_r.sum())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("p", [1, 2])
+@pytest.mark.parametrize("N,R,d", [(300, 3, 37), (520, 2, 200), (260, 2, 300), (200, 2, 700)])
+def test_join_ab_structured_embedding(p, dtype, N, R, d):
+    """Relation-dependent connectors on both sides (the structured-embedding model of Section 4.3)."""
+    g = np.random.default_rng(N + d + p)
+    cent = g.standard_normal((4, d))
+    E = (cent[g.integers(0, 4, N)] + 0.1 * g.standard_normal((N, d))).astype(np.float32)
+    W1 = (np.eye(d) + 0.05 * g.standard_normal((R, d, d)) / np.sqrt(d)).astype(np.float32)
+    W2 = (np.eye(d) + 0.05 * g.standard_normal((R, d, d)) / np.sqrt(d)).astype(np.float32)
+    A = np.einsum("rij,nj->rni", W1, E).astype(np.float32)
+    B = np.einsum("rij,nj->rni", W2, E).astype(np.float32)
+    if dtype == "bf16":
+        A = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(A)).reshape(A.shape)
+        B = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(B)).reshape(B.shape)
+    # a threshold that keeps pairs of one cluster, about 1 % of all
+    probe = np.sqrt(((A[0, :64, None, :] - B[0, None, :64, :]) ** 2).sum(-1)) if p == 2 else np.abs(A[0, :64, None, :] - B[0, None, :64, :]).sum(-1)
+    delta = float(np.float32(np.quantile(probe, 0.05)))
+    ref = oracle.join_ab(A, B, p, delta)
+    assert ref["count"] > 0
+    got = _run_ab(A, B, p, delta, max(1024, 2 * ref["count"]), dtype=dtype)
+    assert got["code"] == 0
+    _compare_ab(got, ref, A, B, p, delta, N)
+    assert got["stats"]["join_variant"] == (0 if p == 1 else 15 if d <= 282 else 17 if d <= 602 else 9)
+
+
+@pytest.mark.parametrize("p", [1, 2])
+def test_join_ab_is_transe_on_its_connectors(p):
+    """A[r][h] = E[h] + Rv[r] (formed in float32), B = E shared: the same triples as kgc_join up to the rounding of A."""
+    wl = workloads.generate("c1_tiny_l2")
+    delta = wl.delta if p == 2 else 2.6
+    A = (wl.E[None, :, :] + wl.Rv[:, None, :]).astype(np.float32)
+    ref = oracle.join_ab(A, wl.E, p, delta)
+    got = _run_ab(A, wl.E, p, delta, max(1024, 2 * ref["count"]))
+    assert got["code"] == 0 and ref["count"] > 0
+    _compare_ab(got, ref, A, wl.E, p, delta, wl.E.shape[0])
+    base = oracle.join(wl.E, wl.Rv, p, delta, mode="abandon")
+    assert abs(got["count"] - base["count"]) <= 5
+    # overflow and empty inputs follow kgc_join's conventions
+    small = _run_ab(A, wl.E, p, delta, 8)
+    assert small["code"] == 1 and small["count"] == got["count"]
+    assert _run_ab(A, wl.E, p, -1.0, 8)["count"] == 0
