@@ -234,7 +234,6 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   if ((rc = ensure(hd, hd->counters, sizeof(DevCounters))) || (rc = ensure(hd, hd->params, sizeof(JoinParams))) ||
       (rc = ensure(hd, hd->slot_ent, Nslots * 4)) || (rc = ensure(hd, hd->zero_row, (size_t)d * 4)))
     return rc;
-  if (p == 2 && ((rc = ensure(hd, hd->opA, op_bytes)) || (rc = ensure(hd, hd->opB, op_bytes)))) return rc;
   DevCounters* cnt = (DevCounters*)hd->counters.p;
   JoinParams* prm = (JoinParams*)hd->params.p;
   const int32_t* slot_ent = (const int32_t*)hd->slot_ent.p;
@@ -250,48 +249,63 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   KGC_HIP(hd, hipEventRecord(hd->join_ev[0], st));
 
   RecheckCtx cx{};
+  cx.E = A; cx.Et = B; cx.hstride = (int64_t)N * d; cx.tstride = b_per_relation ? (int64_t)N * d : 0;
   cx.Rv = hd->zero_row.p; cx.rstride = 0;             // the head rows already are connector_1(h, r)
   cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p; cx.delta = (double)delta;
   cx.out = out_triples; cx.cap = cap; cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates; cx.no_self = 0;
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
+  // relation batches: the staged operands of a batch must fit the workspace
+  const int64_t ws = hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
+  int64_t RBmax = std::min<int64_t>(R, 65535);
+  if (p == 2) RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, ws / (int64_t)(op_bytes * (b_per_relation ? 2 : 1))));
+  if (p == 2 && ((rc = ensure(hd, hd->opA, op_bytes * (size_t)RBmax)) ||
+                 (rc = ensure(hd, hd->opB, op_bytes * (size_t)(b_per_relation ? RBmax : 1)))))
+    return rc;
   size_t dyn_lds = 0;
   int64_t nsplit = 1;
-  if (p == 2) {
-    if (tc.head_resident) {
-      dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
-      KGC_HIP(hd, hipFuncSetAttribute((const void*)tc.stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
-    }
-    const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
-    const int64_t range_bytes = tc.head_resident ? kL2RangeBytesResident : kL2RangeBytes;
-    nsplit = (nT * tile_bytes + range_bytes - 1) / range_bytes;
-    nsplit = std::max<int64_t>(nsplit, (2048 + nH - 1) / nH);
-    nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
-  }
-  for (int32_t r = 0; r < R; ++r) {
-    const char* Ar = (const char*)A + (size_t)r * N * d * esz;
-    const char* Br = (const char*)B + (b_per_relation ? (size_t)r * N * d * esz : 0);
-    cx.E = Ar; cx.Et = Br;
+  int nbatch = 0;
+  for (int64_t r0 = 0; r0 < R; r0 += RBmax, ++nbatch) {
+    const int RB = (int)std::min<int64_t>(RBmax, R - r0);
     if (p == 2) {
-      if (r == 0 || b_per_relation)
+      const int stage_grid = grid_for((int64_t)RB * (Nslots / kStageRows), 1);
+      if (b_per_relation)
+        k_stage_operands<false><<<stage_grid, 256, stage_lds, st>>>(B, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
+                                                                  (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
+                                                                  kStageRows, (int64_t)N * d);
+      else if (r0 == 0)
         k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
-            Br, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
-            kStageRows);
-      k_stage_operands<true><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
-          Ar, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, nullptr, cnt->max_a, nullptr, nullptr, 0,
-          kStageRows);
-      // the maxima only grow from relation to relation: the filter threshold stays on the safe side
+            B, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
+            kStageRows, 0);
+      k_stage_operands<true><<<stage_grid, 256, stage_lds, st>>>(A, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
+                                                               (uint16_t*)hd->opA.p, nullptr, cnt->max_a, nullptr, nullptr, 0,
+                                                               kStageRows, (int64_t)N * d);
+      // the maxima only grow from batch to batch: the filter threshold stays on the safe side
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
+      if (tc.head_resident) {
+        dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
+        KGC_HIP(hd, hipFuncSetAttribute((const void*)tc.stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
+      }
+      const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
+      const int64_t range_bytes = tc.head_resident ? kL2RangeBytesResident : kL2RangeBytes;
+      nsplit = (nT * tile_bytes + range_bytes - 1) / range_bytes;
+      nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
+      nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
       JoinStreamArgs sa{};
       sa.A = (const uint16_t*)hd->opA.p; sa.B = (const uint16_t*)hd->opB.p; sa.prm = prm; sa.Nslots = Nslots;
-      sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = r; sa.RB = 1; sa.cx = cx;
-      hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, 1, (unsigned)nsplit), dim3(tc.threads), dyn_lds, st, sa);
+      sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = (int)r0; sa.RB = RB; sa.b_per_rel = b_per_relation ? 1 : 0;
+      sa.cx = cx;
+      hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit), dim3(tc.threads), dyn_lds, st, sa);
     } else {
-      k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(Ar, N, d, dtype, cnt->max_a);
-      if (r == 0 || b_per_relation) k_row_l1_max<<<grid_for(N * 32, 256), 256, 0, st>>>(Br, N, d, dtype, cnt->max_b);
+      k_row_l1_max<<<grid_for((int64_t)RB * N * 32, 256), 256, 0, st>>>((const char*)A + (size_t)r0 * N * d * esz, (int64_t)RB * N, d,
+                                                                    dtype, cnt->max_a);
+      if (b_per_relation || r0 == 0)
+        k_row_l1_max<<<grid_for((int64_t)(b_per_relation ? RB : 1) * N * 32, 256), 256, 0, st>>>(
+            (const char*)B + (b_per_relation ? (size_t)r0 * N * d * esz : 0), (int64_t)(b_per_relation ? RB : 1) * N, d, dtype,
+            cnt->max_b);
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, 0);
       JoinL1Args la{};
-      la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = r; la.RB = 1; la.cx = cx;
-      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)nT, (unsigned)nH, 1), dim3(256), 0, st, la);
+      la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = (int)r0; la.RB = RB; la.cx = cx;
+      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(256), 0, st, la);
     }
     hd->stats.join_launches++;
   }
@@ -308,10 +322,10 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   s.pairs_evaluated = s.triples_total;
   s.tile_m = BM; s.tile_n = BN;
   s.k_padded = (p == 2) ? k16 * 16 : d;
-  s.relation_batches = R;
+  s.relation_batches = nbatch;
   s.join_variant = (p == 2) ? tile_id + 1 : 0;
   (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);
-  (void)hipEventElapsedTime(&s.ms_join, hd->join_ev[0], hd->join_ev[1]);   // staging of each relation included
+  (void)hipEventElapsedTime(&s.ms_join, hd->join_ev[0], hd->join_ev[1]);   // staging of each batch included
   s.ms_precompute = s.ms_total - s.ms_join;
   *count = s.emitted;
   return s.emitted > cap ? KGC_OVERFLOW : KGC_OK;
@@ -335,7 +349,7 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   Top1State* ts = (Top1State*)hd->top1_state.p;
   Top1State host{};
   RecheckCtx cx{};
-  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
 
   // 1. an upper bound of the answer: the smallest of 65,536 sampled eligible triples
   const int n_sample = 1 << 16;
@@ -667,7 +681,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   }
 
   RecheckCtx cx;
-  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
   cx.delta = (double)delta; cx.out = out_triples; cx.cap = cap; cx.no_self = hd->no_self;
   cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates;
 

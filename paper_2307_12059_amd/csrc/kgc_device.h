@@ -64,6 +64,8 @@ struct RecheckCtx {
   const void* E;             // rows of the head side: x = (E[h] + Rv[r]) - Et[t]
   const void* Et;            // rows of the tail side (the same array as E for the TransE join)
   const void* Rv;
+  int64_t hstride, tstride;  // elements between the head / tail rows of consecutive relations: 0 for the TransE join
+                             // (one entity array), N * d for per-relation connector outputs
   int64_t rstride;           // elements between relation vectors: d, or 0 when every relation reads row 0 of Rv
                              // (the general form, whose head rows already are connector_1(h, r): Rv is a zero row)
   const int32_t* slot_ent;   // slot -> entity row, -1 for padding
@@ -85,7 +87,8 @@ struct RecheckCtx {
 // rather than one per dimension.
 __device__ __forceinline__ double group16_exact_dist(const RecheckCtx& cx, int32_t h, int32_t r, int32_t t, int sub) {
   const int d = cx.d;
-  const int64_t ho = (int64_t)h * d, to = (int64_t)t * d, ro = (int64_t)r * cx.rstride;
+  const int64_t ho = (int64_t)r * cx.hstride + (int64_t)h * d, to = (int64_t)r * cx.tstride + (int64_t)t * d,
+                ro = (int64_t)r * cx.rstride;
   double s0 = 0.0, s1 = 0.0;
   const bool p2 = cx.p == 2;
   if (cx.dtype == KGC_F32 && (d & 3) == 0) {
@@ -151,8 +154,8 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
 #pragma unroll
   for (int n = 0; n < NC; ++n) {
     const bool ok = h[n] >= 0 && t[n] >= 0;      // an absent candidate reads row 0 and its result is ignored
-    ho[n] = (int64_t)(ok ? h[n] : 0) * d;
-    to[n] = (int64_t)(ok ? t[n] : 0) * d;
+    ho[n] = (int64_t)r * cx.hstride + (int64_t)(ok ? h[n] : 0) * d;
+    to[n] = (int64_t)r * cx.tstride + (int64_t)(ok ? t[n] : 0) * d;
     s0[n] = 0.0; s1[n] = 0.0;
   }
   if (cx.dtype == KGC_F32 && (d & 3) == 0) {

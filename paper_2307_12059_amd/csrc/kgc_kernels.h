@@ -77,7 +77,8 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
                                                         uint16_t* __restrict__ out, float* __restrict__ norms,
                                                         unsigned int* __restrict__ max_slots,
                                                         const uint32_t* __restrict__ active_rows,
-                                                        const unsigned int* __restrict__ n_active, int nH, int bm) {
+                                                        const unsigned int* __restrict__ n_active, int nH, int bm,
+                                                        int64_t rel_stride = 0) {
   extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [kStageRows][KS * 32 + 8]
   __shared__ int32_t ents[kStageRows];
   __shared__ float wmax[4];
@@ -104,12 +105,13 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
     if (tid < kStageRows) ents[tid] = slot_ent[slot0 + tid];
     __syncthreads();
     const int64_t ro = (int64_t)(r0 + rl) * d;
+    const int64_t eo = (int64_t)(r0 + rl) * rel_stride;       // per-relation source rows (0: one array for all)
     for (int e = tid; e < kStageRows * d; e += 256) {
       const int row = e / d, c = e - row * d;
       const int ent = ents[row];
       uint16_t o = 0;
       if (ent >= 0) {
-        float v = ld_elem(E, (int64_t)ent * d + c, dtype);
+        float v = ld_elem(E, eo + (int64_t)ent * d + c, dtype);
         if (IS_A && Rv) v += ld_elem(Rv, ro + c, dtype);     // Rv == nullptr: the plain row (a = h)
         o = f32_to_bf16_rne(v);
       }
@@ -404,6 +406,7 @@ struct JoinStreamArgs {
   RecheckCtx cx;
   // Group assignment (k_join_l2_direct<.., kEpiAssignMin>): heads are all entities in identity order, tails
   // the pivots of a covering round, staged in an array of their own with tail_slots rows.
+  int b_per_rel;                      // 1: the tail operands are staged per relation, [RB][KS][Nslots][32] like A
   int64_t tail_slots;                 // rows per K slice of B when it differs from Nslots (0: the same)
   const int32_t* tail_rows_dev;       // device count of valid tail rows (tail tiles past it are skipped); may be NULL
   float thr_value;                    // filter threshold on the squared distance when prm == NULL
@@ -459,7 +462,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
   // per-thread byte offset inside a tile slice; uniform bases are kept apart so they can live in SGPRs
   const uint32_t voff = (uint32_t)tid * 16u;
   const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * (kSliceK * 2);
-  const char* Bbase = (const char*)a.B;
+  const char* Bbase = (const char*)a.B + (a.b_per_rel ? (int64_t)rl * KS * a.Nslots * (kSliceK * 2) : 0);
   int tcol = cols ? (int)cols[t_begin] : t_begin;
   const char* pA = Abase;                                            // slice being prefetched
   const char* pB = Bbase + (int64_t)tcol * BN * (kSliceK * 2);
@@ -690,7 +693,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
   const int64_t slice_bytes = a.Nslots * kSliceK * 2;
   const uint32_t voff = (uint32_t)tid * 16u;
   const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * (kSliceK * 2);
-  const char* Bbase = (const char*)a.B;
+  const char* Bbase = (const char*)a.B + (a.b_per_rel ? (int64_t)rl * KS * a.Nslots * (kSliceK * 2) : 0);
   int tcol = cols ? (int)cols[t_begin] : t_begin;
   const char* pB = Bbase + (int64_t)tcol * BN * (kSliceK * 2);
 
@@ -937,7 +940,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
   const int rd_step = (((lane >> 5) ^ rsw) & 2) ? -16 : 16;
 
   // tail fragments of this lane: row (lane % 32) of each 32-row group of the wave's columns
-  const char* Bw = (const char*)a.B + ((int64_t)wn * WTN + (lane & 31)) * ROWB + (lane >> 5) * 16;
+  const char* Bw = (const char*)a.B + (a.b_per_rel ? (int64_t)rl * KS * a.Nslots * ROWB : 0) +
+                   ((int64_t)wn * WTN + (lane & 31)) * ROWB + (lane >> 5) * 16;
   const char* pB = Bw + (int64_t)t_begin * BN * ROWB;
   const int total = ntiles * KS;
   int pf_k = 0, pf_t = 0, pf_i = 0;
@@ -1463,7 +1467,8 @@ __global__ __launch_bounds__(256, 3) void k_join_l1(const JoinL1Args a) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
     const int he = hent[srow], te = tent[srow];
-    const int64_t ho = (int64_t)(he < 0 ? 0 : he) * d, to = (int64_t)(te < 0 ? 0 : te) * d;
+    const int64_t ho = (int64_t)r * a.cx.hstride + (int64_t)(he < 0 ? 0 : he) * d,
+                  to = (int64_t)r * a.cx.tstride + (int64_t)(te < 0 ? 0 : te) * d;
 
 #pragma unroll 1
     for (int k0 = 0; k0 < d; k0 += BK) {
