@@ -19,6 +19,7 @@ namespace {
 constexpr int kMaxD = 960;                      // keeps kernel 1's LDS tile under 64 KiB
 constexpr int64_t kSlotAlign = 256;            // rows are padded to a multiple of the largest tile
 constexpr int64_t kDefaultWorkspace = 16ll << 30;
+constexpr size_t kBoundPairCap = 8u << 20;      // surviving (relation, unit, unit) entries of one batch kept in the list
 constexpr int64_t kL2RangeBytes = 1ll << 20;
 constexpr int64_t kL2RangeBytesResident = 3ll << 20;   // head-resident blocks leave the whole L2 to the tail rows
 constexpr size_t kMaxLds = 160 * 1024;         // LDS per workgroup on gfx950
@@ -42,6 +43,7 @@ struct kgc_handle {
   DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
   DevBuf active_rows, cnorm, gram, relu, reln, asg_a, asg_b, limr;
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
+  DevBuf unit_first, unit_n, cent_u, rad_u, cnorm_u, gram_u, relu_u, pair_list, pair_count;   // two-level bound test
   DevBuf zero_row;                             // kgc_join_ab: the relation vector every relation reads (zeros)
   DevBuf top1_a, top1_b, top1_pick;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
@@ -541,6 +543,8 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   // ---- row order: identity, or entities grouped around local pivots (pruning) ----
   int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
   uint64_t n_groups = 0;
+  UnitTable ut{};                 // two-level bound test: filled after the layout
+  bool use_units = false;
   if (prune) {
     // worst case: every group of kSmallGroup rows is padded to a micro-tile
     const int64_t max_padded_groups = std::min<int64_t>(kMaxGroups, N / kSmallGroup + 1);
@@ -549,7 +553,8 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         (rc = ensure(hd, hd->unc_a, N * 4)) || (rc = ensure(hd, hd->unc_b, N * 4)) ||
         (rc = ensure(hd, hd->group_of, N * 4)) || (rc = ensure(hd, hd->piv_ent, kPivotsPerRound * 4)) ||
         (rc = ensure(hd, hd->best, N * 8)) || (rc = ensure(hd, hd->gsize, kMaxGroups * 4)) ||
-        (rc = ensure(hd, hd->goff, kMaxGroups * 4)) || (rc = ensure(hd, hd->gfill, kMaxGroups * 4)))
+        (rc = ensure(hd, hd->goff, kMaxGroups * 4)) || (rc = ensure(hd, hd->gfill, kMaxGroups * 4)) ||
+        (rc = ensure(hd, hd->unit_first, kMaxGroups * 4)) || (rc = ensure(hd, hd->unit_n, kMaxGroups * 4)))
       return rc;
     GroupState* gs = (GroupState*)hd->gstate.p;
     int32_t* unc = (int32_t*)hd->unc_a.p;
@@ -621,7 +626,8 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gfill.p, kMaxGroups, 0u);
     k_fill_u32<<<grid_for(slots_cap, 256), 256, 0, st>>>((uint32_t*)hd->slot_ent.p, slots_cap, 0xffffffffu);
     k_group_hist<<<gN, 256, 0, st>>>((const int32_t*)hd->group_of.p, N, (int32_t*)hd->gsize.p);
-    k_group_layout<<<1, 1024, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign);
+    k_group_layout<<<1, 1024, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign,
+                                       (int32_t*)hd->unit_first.p, (int32_t*)hd->unit_n.p);
     k_scatter_slots<<<gN, 256, 0, st>>>(gs, (const int32_t*)hd->group_of.p, (const int32_t*)hd->goff.p,
                                        (int32_t*)hd->gfill.p, N, (int32_t*)hd->slot_ent.p);
     KGC_HIP(hd, hipGetLastError());
@@ -631,6 +637,12 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     Nslots = hd->host_gstate->n_slots;
     n_groups = (uint64_t)hd->host_gstate->n_groups;
     if (Nslots < N || Nslots > slots_cap || Nslots % kSlotAlign) return fail(hd, KGC_E_HIP, "group layout out of range");
+    ut.first = (const int32_t*)hd->unit_first.p; ut.n = (const int32_t*)hd->unit_n.p;
+    ut.n_big = hd->host_gstate->n_big;
+    ut.tail_first = hd->host_gstate->tail_base / kMicro;
+    ut.n_units = ut.n_big + (int)(Nslots / kMicro) - ut.tail_first;
+    if (ut.n_big < 0 || ut.n_big > kMaxGroups || ut.tail_first < 0 || ut.tail_first > Nslots / kMicro)
+      return fail(hd, KGC_E_HIP, "unit table out of range");
   } else {
     if ((rc = ensure(hd, hd->slot_ent, Nslots * 4))) return rc;
     k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
@@ -672,6 +684,14 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     if (p == 2 && ((rc = ensure(hd, hd->gram, (size_t)n_micro * n_micro * 4)) ||
                    (rc = ensure(hd, hd->relu, (size_t)RBmax * n_micro * 4)) || (rc = ensure(hd, hd->reln, RBmax * 4))))
       return rc;
+    // the two-level test pays when the units are clearly fewer than the micro-tiles (groups of several micro-tiles)
+    use_units = p == 2 && delta >= 0.f && ut.n_units > 0 && ut.n_units < (1 << 24) && (int64_t)ut.n_units * 10 <= n_micro * 6;
+    if (use_units && ((rc = ensure(hd, hd->cent_u, (size_t)ut.n_units * d * 4)) || (rc = ensure(hd, hd->rad_u, (size_t)ut.n_units * 4)) ||
+                      (rc = ensure(hd, hd->cnorm_u, (size_t)ut.n_units * 4)) ||
+                      (rc = ensure(hd, hd->gram_u, (size_t)ut.n_units * ut.n_units * 4)) ||
+                      (rc = ensure(hd, hd->relu_u, (size_t)RBmax * ut.n_units * 4)) ||
+                      (rc = ensure(hd, hd->pair_list, kBoundPairCap * 8)) || (rc = ensure(hd, hd->pair_count, 8))))
+      return rc;
   }
   const int nbatch = (int)((Rn + RBmax - 1) / RBmax);
   while ((int)hd->join_ev.size() < 2 * nbatch) {
@@ -696,6 +716,15 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       ta.n_cols = n_micro; ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.d = d; ta.matrix = (float*)hd->gram.p;
       const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), 1);
       k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
+      if (use_units) {
+        k_unit_summary<<<(unsigned)ut.n_units, 64, 0, st>>>((const float*)hd->cent.p, (const float*)hd->rad.p, d, ut,
+                                                            (float*)hd->cent_u.p, (float*)hd->rad_u.p, (float*)hd->cnorm_u.p);
+        TileDistArgs tu{};
+        tu.X = hd->cent_u.p; tu.dtypeX = KGC_F32; tu.n_rows = ut.n_units; tu.Y = hd->cent_u.p; tu.dtypeY = KGC_F32;
+        tu.n_cols = ut.n_units; tu.shift = nullptr; tu.dtype_shift = KGC_F32; tu.d = d; tu.matrix = (float*)hd->gram_u.p;
+        const dim3 gu((unsigned)((ut.n_units + 127) / 128), (unsigned)((ut.n_units + 127) / 128), 1);
+        k_tile_dist<2, kEpiMatrix><<<gu, 256, 0, st>>>(tu);
+      }
     } else {
       k_micro_summary<1><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p,
                                                             (float*)hd->rad.p, (float*)hd->cnorm.p);
@@ -742,9 +771,27 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         ba.rad = (const float*)hd->rad.p; ba.cnorm = (const float*)hd->cnorm.p; ba.n_micro = n_micro; ba.RB = RB;
         ba.d = d; ba.delta = delta; ba.bitmap = (uint32_t*)hd->bitmap.p; ba.nH = nH; ba.words_per_row = words_per_row;
         ba.micro_per_bm = BM / kMicro; ba.micro_per_bn = BN / kMicro;
-        const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)((n_micro + kHeadChunk - 1) / kHeadChunk),
-                     (unsigned)((RB + kRelChunk - 1) / kRelChunk));
-        k_bound_l2<<<g, 256, 0, st>>>(ba);
+        if (use_units) {
+          // unit level first (same arithmetic on unit summaries), then the micro-tile pairs of the survivors
+          TileDistArgs tu{};
+          tu.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); tu.dtypeX = dtype; tu.n_rows = RB;
+          tu.Y = hd->cent_u.p; tu.dtypeY = KGC_F32; tu.n_cols = ut.n_units; tu.shift = nullptr; tu.dtype_shift = KGC_F32;
+          tu.d = d; tu.matrix = (float*)hd->relu_u.p;
+          k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((ut.n_units + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(tu);
+          k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)hd->pair_count.p, 2, 0u);
+          BoundL2Args bu = ba;
+          bu.D = (const float*)hd->gram_u.p; bu.u = (const float*)hd->relu_u.p; bu.rad = (const float*)hd->rad_u.p;
+          bu.cnorm = (const float*)hd->cnorm_u.p; bu.n_micro = ut.n_units;
+          BoundPairs bp{(unsigned long long*)hd->pair_list.p, (unsigned long long*)hd->pair_count.p, kBoundPairCap};
+          const dim3 gu((unsigned)((ut.n_units + 255) / 256), (unsigned)((ut.n_units + kHeadChunk - 1) / kHeadChunk),
+                        (unsigned)((RB + kRelChunk - 1) / kRelChunk));
+          k_bound_l2_units<<<gu, 256, 0, st>>>(bu, ba, ut, bp);
+          k_bound_refine<<<dim3(1024, 32, 1), 256, 0, st>>>(ba, ut, bp);
+        } else {
+          const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)((n_micro + kHeadChunk - 1) / kHeadChunk),
+                       (unsigned)((RB + kRelChunk - 1) / kRelChunk));
+          k_bound_l2<<<g, 256, 0, st>>>(ba);
+        }
       } else if (delta >= 0.f) {
         TileDistArgs ta{};
         ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.row_ids = nullptr; ta.n_rows_dev = nullptr; ta.n_rows = n_micro;

@@ -30,14 +30,14 @@ struct GroupState {
   int32_t n_slots;      // rows after layout, multiple of the slot alignment
   int32_t tail_base;    // first slot of the unpadded tail region
   int32_t tail_fill;    // running count of rows placed in the tail region
-  int32_t n_micro_used; // micro-tiles that hold at least one entity
+  int32_t n_big;        // groups of at least kSmallGroup rows: each is one unit of the two-level bound test
 };
 
 __global__ void k_group_init(GroupState* gs, int32_t* unc, int32_t* group_of, int64_t N) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) {
     gs->n_unc = (int32_t)N; gs->n_unc_next = 0; gs->n_piv = 0; gs->n_groups = 0;
-    gs->n_slots = 0; gs->tail_base = 0; gs->tail_fill = 0; gs->n_micro_used = 0;
+    gs->n_slots = 0; gs->tail_base = 0; gs->tail_fill = 0; gs->n_big = 0;
   }
   if (i < N) { unc[i] = (int32_t)i; group_of[i] = -1; }
 }
@@ -85,38 +85,54 @@ __global__ void k_group_hist(const int32_t* group_of, int64_t N, int32_t* gsize)
 // Slot layout: groups of at least kSmallGroup rows start on a micro-tile boundary and are padded to one;
 // all other rows follow, packed.  One block of 1024 threads: each thread owns a contiguous run of groups,
 // an exclusive scan over the threads' padded sizes gives the run offsets.
+// The padded groups are also numbered 0 .. n_big - 1 in slot order and their micro-tile ranges written to
+// unit_first / unit_n: they are the units of the two-level bound test.
 __global__ __launch_bounds__(1024) void k_group_layout(GroupState* gs, const int32_t* gsize, int32_t* goff, int64_t N,
-                                                       int slot_align) {
+                                                       int slot_align, int32_t* unit_first, int32_t* unit_n) {
   __shared__ int part[1024];
   __shared__ int placed_part[1024];
+  __shared__ int big_part[1024];
   const int tid = threadIdx.x;
   const int G = gs->n_groups;
   const int per = (G + 1023) / 1024;
   const int g0 = tid * per, g1 = (g0 + per < G) ? g0 + per : G;
-  int sum = 0, placed = 0;
+  int sum = 0, placed = 0, nbig = 0;
   for (int g = g0; g < g1; ++g) {
     const int sz = gsize[g];
-    if (sz >= kSmallGroup) { sum += (sz + kMicro - 1) / kMicro * kMicro; placed += sz; }
+    if (sz >= kSmallGroup) { sum += (sz + kMicro - 1) / kMicro * kMicro; placed += sz; ++nbig; }
   }
   part[tid] = sum;
   placed_part[tid] = placed;
+  big_part[tid] = nbig;
   __syncthreads();
   for (int off = 1; off < 1024; off <<= 1) {          // inclusive scan, Hillis-Steele
     const int v = tid >= off ? part[tid - off] : 0;
     const int w = tid >= off ? placed_part[tid - off] : 0;
+    const int x = tid >= off ? big_part[tid - off] : 0;
     __syncthreads();
     part[tid] += v;
     placed_part[tid] += w;
+    big_part[tid] += x;
     __syncthreads();
   }
   int cur = part[tid] - sum;                           // exclusive prefix of this thread's run
+  int ui = big_part[tid] - nbig;
   for (int g = g0; g < g1; ++g) {
     const int sz = gsize[g];
-    if (sz >= kSmallGroup) { goff[g] = cur; cur += (sz + kMicro - 1) / kMicro * kMicro; }
-    else goff[g] = -1;
+    if (sz >= kSmallGroup) {
+      const int padded = (sz + kMicro - 1) / kMicro * kMicro;
+      goff[g] = cur;
+      unit_first[ui] = cur / kMicro;
+      unit_n[ui] = padded / kMicro;
+      ++ui;
+      cur += padded;
+    } else {
+      goff[g] = -1;
+    }
   }
   if (tid == 1023) {
     const int total_padded = part[1023];
+    gs->n_big = big_part[1023];
     gs->tail_base = total_padded;
     gs->tail_fill = 0;
     const int64_t total = (int64_t)total_padded + (N - placed_part[1023]);
@@ -435,6 +451,179 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
       keep &= keep - 1u;
       atomicOr(&a.bitmap[((int64_t)(rl0 + q) * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
     }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Two-level bound test (L2).  When groups span several micro-tiles, the flat test over micro-tile pairs does
+// the same work many times: all micro-tiles of a group sit within the group's radius of one another.  A
+// UNIT is a padded group (its run of micro-tiles) or, in the packed tail region, a single micro-tile.  The
+// same bound is first taken on unit pairs -- centre = mean of the micro-tile centres, radius = max over
+// the micro-tiles of (distance of its centre to the unit centre + its radius), so every row of the unit is
+// inside -- and only the micro-tile pairs of surviving unit pairs are tested.  Survivors go through a list;
+// a lane that finds the list full tests its pair's micro-tiles on the spot.
+struct UnitTable {
+  const int32_t* first;   // big units: first micro-tile ...
+  const int32_t* n;       // ... and number of micro-tiles
+  int n_big;              // units 0 .. n_big - 1 are padded groups
+  int tail_first;         // unit n_big + i is micro-tile tail_first + i
+  int n_units;
+};
+__device__ __forceinline__ void unit_range(const UnitTable& ut, int u, int& first, int& n) {
+  if (u < ut.n_big) { first = ut.first[u]; n = ut.n[u]; }
+  else { first = ut.tail_first + (u - ut.n_big); n = 1; }
+}
+
+// one wave per unit
+__global__ __launch_bounds__(64) void k_unit_summary(const float* __restrict__ cent, const float* __restrict__ rad, int d,
+                                                     UnitTable ut, float* __restrict__ centU, float* __restrict__ radU,
+                                                     float* __restrict__ cnormU) {
+  const int u = (int)blockIdx.x;
+  if (u >= ut.n_units) return;
+  const int lane = threadIdx.x;
+  int first, n;
+  unit_range(ut, u, first, n);
+  int cntm = 0;
+  for (int m = first; m < first + n; ++m) cntm += rad[m] >= 0.f;
+  float* c = centU + (int64_t)u * d;
+  if (cntm == 0) {
+    for (int k = lane; k < d; k += 64) c[k] = 0.f;
+    if (lane == 0) { radU[u] = -1.f; cnormU[u] = 0.f; }
+    return;
+  }
+  const float inv = 1.f / (float)cntm;
+  float c2 = 0.f;
+  for (int k = lane; k < d; k += 64) {
+    float s = 0.f;
+    for (int m = first; m < first + n; ++m)
+      if (rad[m] >= 0.f) s += cent[(int64_t)m * d + k];
+    c[k] = s * inv;
+    c2 += (s * inv) * (s * inv);
+  }
+  for (int off = 32; off > 0; off >>= 1) c2 += __shfl_xor(c2, off, 64);
+  __syncthreads();
+  float rmax = 0.f;
+  for (int m = first; m < first + n; ++m) {
+    if (rad[m] < 0.f) continue;
+    float s = 0.f;
+    for (int k = lane; k < d; k += 64) { const float x = cent[(int64_t)m * d + k] - c[k]; s += x * x; }
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    rmax = fmaxf(rmax, sqrtf(s) * (1.f + kBoundSlack) + rad[m]);
+  }
+  if (lane == 0) { radU[u] = rmax * (1.f + kBoundSlack) + 1e-30f; cnormU[u] = sqrtf(c2) * (1.f + kBoundSlack); }
+}
+
+constexpr int kInlineMicroPairs = 8;   // unit pairs with at most this many micro-tile pairs are refined where they are found
+struct BoundPairs {
+  unsigned long long* list;     // (rl << 48) | (unit of heads << 24) | unit of tails
+  unsigned long long* count;    // entries asked for (may exceed cap)
+  unsigned long long cap;
+};
+
+// the micro-tile level of the test for one surviving unit pair and relation; `lane_count` lanes starting at
+// `lane0` share the micro-tile pairs (1 lane = on the spot in the unit-level kernel, a block in k_bound_refine)
+__device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const UnitTable& ut, int rl, int uH, int uT, int lane0,
+                                                 int lane_count) {
+  int fH, nHm, fT, nTm;
+  unit_range(ut, uH, fH, nHm);
+  unit_range(ut, uT, fT, nTm);
+  const float rnq = a.rn[rl], srn = sqrtf(rnq);
+  const float dsl = a.delta * (1.f + kBoundSlack);
+  const float kk = 2.f * (float)(a.d + 12) * 6e-8f;
+  const int64_t total = (int64_t)nHm * nTm;
+  for (int64_t i = lane0; i < total; i += lane_count) {
+    const int64_t mH = fH + i / nTm, mT = fT + i % nTm;
+    const float rH = a.rad[mH], rT = a.rad[mT];
+    if (rH < 0.f || rT < 0.f) continue;
+    const float D = a.D[mH * a.n_micro + mT];
+    const float reach = dsl + rH + rT;
+    const float rhs = reach * reach * (1.f + kBoundSlack) + D * 1.2e-6f - D;
+    const float ek = kk * (a.cnorm[mH] + a.cnorm[mT]);
+    const float lhs = (2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f)) - 2.f * a.u[(int64_t)rl * a.n_micro + mT] -
+                      ek * srn;
+    if (lhs <= rhs) {
+      const int tH = (int)(mH / a.micro_per_bm), tT = (int)(mT / a.micro_per_bn);
+      uint32_t* w = &a.bitmap[((int64_t)rl * a.nH + tH) * a.words_per_row + (tT >> 5)];
+      if (!(*w & (1u << (tT & 31)))) atomicOr(w, 1u << (tT & 31));
+    }
+  }
+}
+
+// Unit level: the flat kernel's arithmetic on unit summaries (a.D, a.u, a.rad, a.cnorm and a.n_micro then
+// describe UNITS); survivors are appended to the list, or refined on the spot when the list is full.
+// `fine` holds the micro-tile level arrays for that case.
+__global__ __launch_bounds__(256) void k_bound_l2_units(const BoundL2Args a, const BoundL2Args fine, const UnitTable ut,
+                                                        const BoundPairs bp) {
+  __shared__ float aH[kHeadChunk][kRelChunk];
+  __shared__ float srnS[kRelChunk];
+  __shared__ float radH[kHeadChunk], cnH[kHeadChunk];
+  const int tid = threadIdx.x;
+  const int64_t mT = (int64_t)blockIdx.x * blockDim.x + tid;
+  const int64_t mH0 = (int64_t)blockIdx.y * kHeadChunk;
+  const int rl0 = (int)blockIdx.z * kRelChunk;
+  {
+    const int hq = tid / kRelChunk, q = tid % kRelChunk;
+    const int rl = rl0 + q;
+    const int64_t mH = mH0 + hq;
+    const float rnq = rl < a.RB ? a.rn[rl] : 0.f;
+    aH[hq][q] = (rl < a.RB && mH < a.n_micro) ? 2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f) : 0.f;
+    if (tid < kRelChunk) srnS[tid] = sqrtf((rl0 + tid < a.RB) ? a.rn[rl0 + tid] : 0.f);
+    if (tid < kHeadChunk) {
+      const int64_t m = mH0 + tid;
+      radH[tid] = m < a.n_micro ? a.rad[m] : -1.f;
+      cnH[tid] = m < a.n_micro ? a.cnorm[m] : 0.f;
+    }
+  }
+  __syncthreads();
+  if (mT >= a.n_micro) return;
+  const float rT = a.rad[mT];
+  if (rT < 0.f) return;
+  const float cT = a.cnorm[mT];
+  float bT[kRelChunk];
+  const int nrel = a.RB - rl0 < kRelChunk ? a.RB - rl0 : kRelChunk;
+#pragma unroll
+  for (int q = 0; q < kRelChunk; ++q) bT[q] = q < nrel ? 2.f * a.u[(int64_t)(rl0 + q) * a.n_micro + mT] : -3e38f;
+  const float dsl = a.delta * (1.f + kBoundSlack);
+  const float kk = 2.f * (float)(a.d + 12) * 6e-8f;
+  for (int hq = 0; hq < kHeadChunk; ++hq) {
+    const float rH = radH[hq];
+    if (rH < 0.f) continue;
+    const int64_t mH = mH0 + hq;
+    const float D = a.D[mH * a.n_micro + mT];
+    const float reach = dsl + rH + rT;
+    const float rhs = reach * reach * (1.f + kBoundSlack) + D * 1.2e-6f - D;
+    const float ek = kk * (cnH[hq] + cT);
+    uint32_t keep = 0u;
+#pragma unroll
+    for (int q = 0; q < kRelChunk; ++q) keep |= (aH[hq][q] - bT[q] - ek * srnS[q] <= rhs) ? (1u << q) : 0u;
+    while (keep) {
+      const int q = __builtin_ctz(keep);
+      keep &= keep - 1u;
+      // a pair of small units (in the packed tail region both are single micro-tiles) is finished here;
+      // only pairs with many micro-tile pairs go through the list
+      int fH, nHm, fT, nTm;
+      unit_range(ut, (int)mH, fH, nHm);
+      unit_range(ut, (int)mT, fT, nTm);
+      unsigned long long pos = bp.cap;
+      if ((int64_t)nHm * nTm > kInlineMicroPairs) pos = atomicAdd(bp.count, 1ull);
+      if (pos < bp.cap)
+        bp.list[pos] = ((unsigned long long)(uint32_t)(rl0 + q) << 48) | ((unsigned long long)(uint32_t)mH << 24) |
+                       (unsigned long long)(uint32_t)mT;
+      else
+        refine_unit_pair(fine, ut, rl0 + q, (int)mH, (int)mT, 0, 1);
+    }
+  }
+}
+
+// Micro-tile level for the listed unit pairs.  The grid strides over the list in x; the gridDim.y blocks of
+// one x share the micro-tile pairs of an entry, so that a pair of large groups (millions of micro-tile pairs
+// in one entry) does not hang on a single block.
+__global__ __launch_bounds__(256) void k_bound_refine(const BoundL2Args fine, const UnitTable ut, const BoundPairs bp) {
+  const unsigned long long n = *bp.count < bp.cap ? *bp.count : bp.cap;
+  for (unsigned long long e = blockIdx.x; e < n; e += gridDim.x) {
+    const unsigned long long v = bp.list[e];
+    refine_unit_pair(fine, ut, (int)(v >> 48), (int)((v >> 24) & 0xffffffull), (int)(v & 0xffffffull),
+                     (int)(blockIdx.y * blockDim.x + threadIdx.x), (int)(gridDim.y * blockDim.x));
   }
 }
 
