@@ -60,6 +60,9 @@ def _load():
         lib.kgco_join_ab.restype = ctypes.c_int64
         lib.kgco_join_ab.argtypes = [dp, dp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                      ctypes.c_double, ctypes.c_int64, ip, ip, ip, dp]
+        lib.kgco_topk.restype = ctypes.c_int64
+        lib.kgco_topk.argtypes = [dp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                  ctypes.c_int64, ip, ip, ip, dp]
         lib.kgco_top1.restype = ctypes.c_int32
         lib.kgco_top1.argtypes = [dp, ctypes.c_int64, ctypes.c_int32, dp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                   ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
@@ -200,6 +203,25 @@ def top1(E, Rv, p: int, exclude_self: bool = False):
     if rc == 0:
         return None
     return {"h": h.value, "r": r.value, "t": t.value, "dist": dist.value}
+
+
+def topk(E, Rv, p: int, k: int, exclude_self: bool = False) -> dict:
+    """The k triples with the smallest ||E[h] + Rv[r] - E[t]||_p (all eligible ones if there are fewer), ascending
+    by (dist, r, h, t): dict of arrays h, r, t, dist and ``count``."""
+    lib = _load()
+    E64, R64 = _f64(E), _f64(Rv)
+    if int(p) not in (1, 2) or k < 0:
+        raise ValueError("p must be 1 or 2 and k >= 0")
+    k = int(k)
+    oh = np.empty(max(k, 1), np.int32); orr = np.empty(max(k, 1), np.int32); ot = np.empty(max(k, 1), np.int32)
+    od = np.empty(max(k, 1), np.float64)
+    n = lib.kgco_topk(_ptr(E64, ctypes.c_double), E64.shape[0], E64.shape[1] if E64.shape[0] else R64.shape[1],
+                      _ptr(R64, ctypes.c_double), R64.shape[0], int(p), 1 if exclude_self else 0, k,
+                      _ptr(oh, ctypes.c_int32), _ptr(orr, ctypes.c_int32), _ptr(ot, ctypes.c_int32), _ptr(od, ctypes.c_double))
+    if n < 0:
+        raise ValueError("bad argument")
+    n = int(n)
+    return {"h": oh[:n].copy(), "r": orr[:n].copy(), "t": ot[:n].copy(), "dist": od[:n].copy(), "count": n}
 
 
 def compute_range(sa, sb, eps: float, impl: str = "two_pointer"):

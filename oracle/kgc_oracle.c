@@ -224,6 +224,55 @@ int32_t kgco_top1(const double *E, int64_t N, int32_t d, const double *Rv, int32
     return 1;
 }
 
+/* ---- top-k: the k smallest distances over all (eligible) triples, the plain definition: every distance
+ * is computed in full and the k smallest by (distance, r, h, t) are kept (a bounded insertion per thread,
+ * merged at the end).  Writes min(k, eligible) records in ascending (distance, r, h, t) order and returns
+ * that number, or -1 on a bad argument. */
+typedef struct { double v; int32_t r, h, t; } topk_rec;
+static int topk_less(const topk_rec *a, const topk_rec *b)
+{
+    if (a->v != b->v) return a->v < b->v;
+    if (a->r != b->r) return a->r < b->r;
+    if (a->h != b->h) return a->h < b->h;
+    return a->t < b->t;
+}
+static void topk_insert(topk_rec *best, int64_t *n, int64_t k, const topk_rec *x)
+{
+    if (*n == k && !topk_less(x, &best[k - 1])) return;
+    int64_t i = (*n < k) ? (*n)++ : k - 1;
+    while (i > 0 && topk_less(x, &best[i - 1])) { best[i] = best[i - 1]; --i; }
+    best[i] = *x;
+}
+int64_t kgco_topk(const double *E, int64_t N, int32_t d, const double *Rv, int32_t R, int32_t p, int32_t exclude_self,
+                  int64_t k, int32_t *oh, int32_t *or_, int32_t *ot, double *od)
+{
+    if ((p != 1 && p != 2) || N < 0 || R < 0 || d < 0 || k < 0) return -1;
+    if (k == 0) return 0;
+    topk_rec *all = (topk_rec *)malloc((size_t)k * sizeof(topk_rec));
+    int64_t nall = 0;
+#pragma omp parallel
+    {
+        topk_rec *best = (topk_rec *)malloc((size_t)k * sizeof(topk_rec));
+        int64_t n = 0;
+#pragma omp for schedule(static) collapse(2) nowait
+        for (int32_t r = 0; r < R; ++r)
+            for (int64_t h = 0; h < N; ++h)
+                for (int64_t t = 0; t < N; ++t) {
+                    if (exclude_self && h == t) continue;
+                    topk_rec x;
+                    x.v = triple_dist(E + h * d, Rv + (int64_t)r * d, E + t * d, d, p);
+                    x.r = r; x.h = (int32_t)h; x.t = (int32_t)t;
+                    topk_insert(best, &n, k, &x);
+                }
+#pragma omp critical
+        for (int64_t i = 0; i < n; ++i) topk_insert(all, &nall, k, &best[i]);
+        free(best);
+    }
+    for (int64_t i = 0; i < nall; ++i) { oh[i] = all[i].h; or_[i] = all[i].r; ot[i] = all[i].t; od[i] = all[i].v; }
+    free(all);
+    return nall;
+}
+
 /* ---- the join ----
  * E[N][d], Rv[R][d] row-major doubles.  pivot: d doubles or NULL for the zero vector (mode 2).
  * range_impl: see kgco_compute_range (mode 2).  Writes min(total, cap) hits to oh/or_/ot/od in an

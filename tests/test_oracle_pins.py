@@ -336,3 +336,29 @@ def test_join_ab_reduces_to_transe_and_cdist():
     straight = oracle.join_ab(A, B, 2, d2)
     swapped = oracle.join_ab(A, B[::-1].copy(), 2, d2)
     assert not (swapped["count"] == straight["count"] and np.array_equal(swapped["h"], straight["h"]))
+
+
+# ---- top-k: the k smallest triple distances ----
+def test_topk_against_sorting_all_distances():
+    from scipy.spatial.distance import cdist
+    g = np.random.default_rng(19)
+    E = g.standard_normal((40, 6)); R = g.standard_normal((3, 6)) * 0.5
+    for p, metric in ((2, "euclidean"), (1, "cityblock")):
+        D = np.stack([cdist(E + R[r], E, metric) for r in range(3)])        # [r][h][t]
+        for excl in (False, True):
+            keys = [(D[r, h, t], r, h, t) for r in range(3) for h in range(40) for t in range(40) if not (excl and h == t)]
+            keys.sort()
+            for k in (1, 7, 100, len(keys) + 5):
+                got = oracle.topk(E, R, p, k, exclude_self=excl)
+                want = keys[:k]
+                assert got["count"] == len(want)
+                assert [(r, h, t) for _, r, h, t in want] == list(zip(got["r"], got["h"], got["t"]))
+                assert np.allclose(got["dist"], [w[0] for w in want], rtol=1e-13, atol=1e-13)
+            one = oracle.top1(E, R, p, exclude_self=excl)
+            first = oracle.topk(E, R, p, 1, exclude_self=excl)
+            assert (one["r"], one["h"], one["t"]) == (first["r"][0], first["h"][0], first["t"][0])
+    assert oracle.topk(E, R, 2, 0)["count"] == 0
+    # consistency with the join: the k-th distance as threshold returns at least k triples, all of the top-k among them
+    got = oracle.topk(E, R, 2, 25)
+    j = oracle.join(E, R, 2, got["dist"][-1], mode="brute")
+    assert j["count"] >= 25 and set(zip(got["r"], got["h"], got["t"])) <= set(zip(j["r"], j["h"], j["t"]))
