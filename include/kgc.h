@@ -159,6 +159,15 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
 int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
              int32_t exclude_self, kgc_triple* out);
 
+/* The k triples with the smallest distances (kgc_top1 for k = 1 .. 65536), optionally without self pairs.
+ *   out_triples  room for k records, 16-byte aligned, in no particular order                 (device)
+ *   found        receives min(k, number of eligible triples)                                 (host)
+ * Joins with a growing threshold, started just above the top-1 bound of kgc_top1, until one returns at least
+ * k records; those are cut to the k smallest by a radix select on the distance (among records whose distances
+ * agree to float precision with the k-th, which ones are returned is unspecified). */
+int kgc_topk(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+             int32_t exclude_self, uint64_t k, kgc_triple* out_triples, uint64_t* found);
+
 /* Copy the statistics of the last kgc_join into *out (host). */
 int kgc_get_stats(const kgc_handle* hd, kgc_stats* out);
 

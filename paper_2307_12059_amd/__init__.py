@@ -23,7 +23,7 @@ KGC_PRUNE_AUTO, KGC_PRUNE_OFF, KGC_PRUNE_ON = 0, 1, 2
 KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
-EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_top1", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
+EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_top1", "kgc_topk", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
            "kgc_version"]
 
 
@@ -83,6 +83,9 @@ def load_library():
     lib.kgc_top1.restype = ctypes.c_int
     lib.kgc_top1.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                              ctypes.POINTER(kgc_triple)]
+    lib.kgc_topk.restype = ctypes.c_int
+    lib.kgc_topk.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                             ctypes.c_uint64, vp, ctypes.POINTER(ctypes.c_uint64)]
     lib.kgc_norms.restype = ctypes.c_int
     lib.kgc_norms.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
     lib.kgc_get_stats.restype = ctypes.c_int
@@ -160,6 +163,14 @@ def kgc_top1(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, exc
     rc = load_library().kgc_top1(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
                                  1 if exclude_self else 0, ctypes.byref(out))
     return rc, out
+
+
+def kgc_topk(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, exclude_self: bool, k: int, out_ptr: int):
+    """Raw call on device addresses.  Returns (code, found)."""
+    found = ctypes.c_uint64(0)
+    rc = load_library().kgc_topk(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
+                                 1 if exclude_self else 0, k, ctypes.c_void_p(out_ptr), ctypes.byref(found))
+    return rc, int(found.value)
 
 
 def kgc_norms(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, nB_ptr: int, nA_ptr: int) -> int:
@@ -272,6 +283,21 @@ class Join:
         if rec.h < 0:
             return None
         return {"h": int(rec.h), "r": int(rec.r), "t": int(rec.t), "dist": float(rec.dist)}
+
+    def topk(self, E, Rv, p: int, k: int, exclude_self: bool = False) -> dict:
+        """The k smallest-distance triples, sorted by (dist, r, h, t) on the host: dict h, r, t, dist, count."""
+        import numpy as np
+        torch = self._torch
+        self._check(E, Rv)
+        out = torch.empty((max(k, 1), 4), dtype=torch.int32, device=E.device)
+        rc, found = kgc_topk(self.handle, E.data_ptr(), E.shape[0], E.shape[1], Rv.data_ptr(), Rv.shape[0], p, exclude_self,
+                             k, out.data_ptr())
+        if rc < 0:
+            raise RuntimeError(f"kgc_topk failed with code {rc}: {kgc_last_error(self.handle)}")
+        host = out[:found].cpu().numpy()
+        h, r, t, dist = host[:, 0].copy(), host[:, 1].copy(), host[:, 2].copy(), host[:, 3].copy().view("float32")
+        order = np.lexsort((t, h, r, dist))
+        return {"h": h[order], "r": r[order], "t": t[order], "dist": dist[order], "count": found}
 
     def norms(self, E, Rv, want_nA: bool = True):
         torch = self._torch

@@ -45,7 +45,7 @@ struct kgc_handle {
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
   DevBuf unit_first, unit_n, cent_u, rad_u, cnorm_u, gram_u, relu_u, pair_list, pair_count;   // two-level bound test
   DevBuf zero_row;                             // kgc_join_ab: the relation vector every relation reads (zeros)
-  DevBuf top1_a, top1_b, top1_pick;            // ... and the operands / entity samples of its sub-sampled dense pass
+  DevBuf top1_a, top1_b, top1_pick, top_samples, topk_state;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
   GroupState* host_gstate = nullptr;           // pinned
   DevCounters* host_counters = nullptr;        // pinned
@@ -333,30 +333,32 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   return s.emitted > cap ? KGC_OVERFLOW : KGC_OK;
 }
 
-int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
-             int32_t exclude_self, kgc_triple* out) {
-  if (!hd) return KGC_E_INVALID;
-  if (!out) return fail(hd, KGC_E_INVALID, "out is NULL");
-  out->h = out->r = out->t = -1;
-  out->dist = INFINITY;
-  int rc = check_common(hd, E, N, d, Rvecs, R);
-  if (rc != KGC_OK) return rc;
-  if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
-  if (N == 0 || R == 0 || (exclude_self && N < 2)) return KGC_OK;          // no eligible triple
+}  // extern "C"
+
+namespace {
+constexpr uint64_t kTopCap = 1u << 20;       // records the inner joins of the top-1 / top-k searches may return
+constexpr int kTopSamples = 1 << 16;
+
+// Upper bounds of the smallest eligible distance for kgc_top1 / kgc_topk.  *sample_bound: the smallest of
+// kTopSamples sampled triples, scored exactly (its triple is known to qualify); *bound: that, or the tighter bound
+// of the sub-sampled dense pass when it applies.  samples (optional, host, kTopSamples doubles) receives every
+// sampled distance.
+int top_bounds(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p, int32_t exclude_self,
+               const RecheckCtx& cx, double* sample_bound_out, double* bound_out, double* samples) {
+  int rc;
   hipStream_t st = hd->stream;
-  constexpr uint64_t kCap = 1u << 20;
-  if ((rc = ensure(hd, hd->top1_buf, kCap * sizeof(kgc_triple))) || (rc = ensure(hd, hd->top1_state, sizeof(Top1State))) ||
-      (rc = ensure(hd, hd->counters, sizeof(DevCounters))))
-    return rc;
   Top1State* ts = (Top1State*)hd->top1_state.p;
   Top1State host{};
-  RecheckCtx cx{};
-  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
-
+  double* dev_samples = nullptr;
+  if (samples) {
+    if ((rc = ensure(hd, hd->top_samples, (size_t)kTopSamples * 8))) return rc;
+    dev_samples = (double*)hd->top_samples.p;
+  }
   // 1. an upper bound of the answer: the smallest of 65,536 sampled eligible triples
-  const int n_sample = 1 << 16;
+  const int n_sample = kTopSamples;
   k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)ts, sizeof(Top1State) / 4, 0xffffffffu);
-  k_top1_sample<<<grid_for((int64_t)n_sample * 16, 256), 256, 0, st>>>(cx, N, R, n_sample, exclude_self ? 1 : 0, ts);
+  k_top1_sample<<<grid_for((int64_t)n_sample * 16, 256), 256, 0, st>>>(cx, N, R, n_sample, exclude_self ? 1 : 0, ts, dev_samples);
+  if (samples) KGC_HIP(hd, hipMemcpyAsync(samples, dev_samples, (size_t)kTopSamples * 8, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipMemcpyAsync(&host, ts, sizeof(Top1State), hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipStreamSynchronize(st));
   double bound;
@@ -404,6 +406,36 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
     KGC_HIP(hd, hipStreamSynchronize(st));
     if (host.sub_bound >= 0.0 && host.sub_bound < bound) bound = host.sub_bound;
   }
+  *sample_bound_out = sample_bound;
+  *bound_out = bound;
+  return KGC_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+             int32_t exclude_self, kgc_triple* out) {
+  if (!hd) return KGC_E_INVALID;
+  if (!out) return fail(hd, KGC_E_INVALID, "out is NULL");
+  out->h = out->r = out->t = -1;
+  out->dist = INFINITY;
+  int rc = check_common(hd, E, N, d, Rvecs, R);
+  if (rc != KGC_OK) return rc;
+  if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
+  if (N == 0 || R == 0 || (exclude_self && N < 2)) return KGC_OK;          // no eligible triple
+  hipStream_t st = hd->stream;
+  constexpr uint64_t kCap = kTopCap;
+  if ((rc = ensure(hd, hd->top1_buf, kCap * sizeof(kgc_triple))) || (rc = ensure(hd, hd->top1_state, sizeof(Top1State))) ||
+      (rc = ensure(hd, hd->counters, sizeof(DevCounters))))
+    return rc;
+  Top1State* ts = (Top1State*)hd->top1_state.p;
+  Top1State host{};
+  RecheckCtx cx{};
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
+
+  double sample_bound = 0.0, bound = 0.0;
+  if ((rc = top_bounds(hd, E, N, d, Rvecs, R, p, exclude_self, cx, &sample_bound, &bound, nullptr)) != KGC_OK) return rc;
 
   // 2. Joins with a shrinking threshold: every triple at or below the bound comes back; if there are more
   //    than the buffer holds, the smallest distance among those that did come back is the next bound.  The
@@ -440,6 +472,77 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   out->h = (int32_t)(uint32_t)(host.key_ht >> 32);
   out->t = (int32_t)(uint32_t)(host.key_ht & 0xffffffffull);
   out->dist = (float)host.dist;
+  return KGC_OK;
+}
+
+int kgc_topk(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+             int32_t exclude_self, uint64_t k, kgc_triple* out_triples, uint64_t* found) {
+  if (!hd) return KGC_E_INVALID;
+  if (!found) return fail(hd, KGC_E_INVALID, "found is NULL");
+  *found = 0;
+  int rc = check_common(hd, E, N, d, Rvecs, R);
+  if (rc != KGC_OK) return rc;
+  if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
+  if (k > (uint64_t)kTopSamples) return fail(hd, KGC_E_INVALID, "k is limited to 65536");
+  if (k > 0 && !out_triples) return fail(hd, KGC_E_INVALID, "out_triples is NULL with k > 0");
+  if ((uintptr_t)out_triples % 16) return fail(hd, KGC_E_INVALID, "out_triples must be 16-byte aligned");
+  if (k == 0 || N == 0 || R == 0 || (exclude_self && N < 2)) return KGC_OK;
+  hipStream_t st = hd->stream;
+  if ((rc = ensure(hd, hd->top1_buf, kTopCap * sizeof(kgc_triple))) || (rc = ensure(hd, hd->top1_state, sizeof(Top1State))) ||
+      (rc = ensure(hd, hd->topk_state, sizeof(TopkState))) || (rc = ensure(hd, hd->counters, sizeof(DevCounters))))
+    return rc;
+  RecheckCtx cx{};
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr;
+  cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
+  const double eligible = (double)N * (double)N * (double)R - (exclude_self ? (double)N * (double)R : 0.0);
+
+  // thresholds to try: from just above the smallest distance upwards.  The k-th smallest of the sampled
+  // distances bounds the k-th smallest of all from above (the sample is drawn with replacement, so on small
+  // problems it can hold a triple twice: the loop below then simply goes on growing the threshold).
+  std::vector<double> samples(kTopSamples);
+  double sample_bound = 0.0, thr = 0.0;
+  if ((rc = top_bounds(hd, E, N, d, Rvecs, R, p, exclude_self, cx, &sample_bound, &thr, samples.data())) != KGC_OK) return rc;
+  std::nth_element(samples.begin(), samples.begin() + (size_t)(k - 1), samples.end());
+  const double kth_sample = samples[(size_t)(k - 1)];
+  const bool take_all = eligible <= (double)kTopCap / 4;       // a small problem: every triple fits the buffer
+  double lo = 0.0;                                             // a threshold known to return fewer than k
+  bool have_lo = false;
+  uint64_t count = 0;
+  hd->no_self = exclude_self ? 1 : 0;
+  for (int rounds = 0;; ++rounds) {
+    float delta = take_all ? INFINITY : (float)thr;
+    if (!take_all && (double)delta < thr) delta = std::nextafterf(delta, INFINITY);
+    rc = kgc_join(hd, E, N, d, Rvecs, R, p, delta, (kgc_triple*)hd->top1_buf.p, kTopCap, &count);
+    if (rc < 0) { hd->no_self = 0; return rc; }
+    if (rounds >= 200) { hd->no_self = 0; return fail(hd, KGC_E_HIP, "top-k search did not settle"); }
+    const uint64_t want = (double)k < eligible ? k : (uint64_t)eligible;
+    if (count < want) {                                        // too few: grow (towards the sampled bound first)
+      lo = thr; have_lo = true;
+      // 8 % steps near the smallest distance (the counts rise steeply there), larger ones if that drags on
+      const double grown = thr > 0.0 ? thr * (rounds < 24 ? 1.08 : 1.5) : (kth_sample > 0.0 ? kth_sample * 0x1p-20 : 1e-30);
+      thr = (thr < kth_sample && grown > kth_sample) ? kth_sample : grown;
+      continue;
+    }
+    if (rc == KGC_OVERFLOW) {                                  // at least k, but more than the buffer holds: shrink
+      thr = have_lo ? 0.5 * (lo + thr) : 0.5 * thr;
+      continue;
+    }
+    break;
+  }
+  hd->no_self = 0;
+
+  // the k smallest of the `count` records, by radix select on the distance bits
+  DevCounters* cnt = (DevCounters*)hd->counters.p;
+  TopkState* tk = (TopkState*)hd->topk_state.p;
+  k_topk_init<<<1, 256, 0, st>>>(tk, k);
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    k_topk_hist<<<256, 256, 0, st>>>((const kgc_triple*)hd->top1_buf.p, &cnt->hits, kTopCap, shift, tk);
+    k_topk_digit<<<1, 64, 0, st>>>(shift, tk);
+  }
+  k_topk_emit<<<256, 256, 0, st>>>((const kgc_triple*)hd->top1_buf.p, &cnt->hits, kTopCap, k, tk, out_triples);
+  KGC_HIP(hd, hipGetLastError());
+  KGC_HIP(hd, hipStreamSynchronize(st));
+  *found = count < k ? count : k;
   return KGC_OK;
 }
 

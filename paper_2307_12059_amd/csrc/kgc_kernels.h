@@ -1327,7 +1327,8 @@ __device__ __forceinline__ uint32_t top1_hash(uint32_t x) {
   return x;
 }
 
-__global__ __launch_bounds__(256) void k_top1_sample(RecheckCtx cx, int64_t N, int R, int n, int no_self, Top1State* st) {
+__global__ __launch_bounds__(256) void k_top1_sample(RecheckCtx cx, int64_t N, int R, int n, int no_self, Top1State* st,
+                                                     double* all = nullptr) {
   const int64_t g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
   const int sub = threadIdx.x & 15;
   if (g >= n) return;                                   // whole 16-lane groups leave together
@@ -1337,7 +1338,10 @@ __global__ __launch_bounds__(256) void k_top1_sample(RecheckCtx cx, int64_t N, i
   const int32_t r = (int32_t)(((uint64_t)c * (uint64_t)R) >> 32);
   if (no_self && t == h) t = (t + 1 == N) ? 0 : t + 1;  // N >= 2 is checked on the host
   const double dist = group16_exact_dist(cx, h, r, t, sub);
-  if (sub == 0) atomicMin(&st->sample_min, (unsigned long long)__double_as_longlong(dist));
+  if (sub == 0) {
+    atomicMin(&st->sample_min, (unsigned long long)__double_as_longlong(dist));
+    if (all) all[g] = dist;                               // top-k: the whole sample goes to the host
+  }
 }
 
 __global__ __launch_bounds__(256) void k_top1_min(const kgc_triple* __restrict__ rec, const unsigned long long* __restrict__ count,
@@ -1392,6 +1396,77 @@ __global__ __launch_bounds__(64) void k_top1_bound(const DevCounters* cnt, int d
   const float m = u * (sqrtf(ma) * 1.01f + (dtype == KGC_BF16 ? 0.f : sqrtf(mb) * 1.01f));
   const float eacc = (float)(kp + 16) * 1.2e-7f * 2.f * (ma + mb);
   st->sub_bound = ((double)sqrtf(D + eacc) + (double)m) * (1.0 + 1e-5);
+}
+
+// ---- top-k: the k smallest of the n records a join returned, by radix select on the float bits of the
+// distance (non-negative floats order like their bits), 8 bits per pass from the top.  State on the device:
+//   prefix / mask  the bits fixed so far;  need  how many records are still wanted among those that match.
+struct TopkState {
+  unsigned int hist[256];
+  unsigned int prefix, mask;
+  unsigned long long need;        // records still to take among the keys that match the prefix
+  unsigned long long taken_less;  // emit: records with a smaller key written so far
+  unsigned long long taken_eq;    // emit: records with the k-th key written so far
+};
+
+__global__ void k_topk_init(TopkState* ts, unsigned long long k) {
+  const int i = threadIdx.x;
+  if (i < 256) ts->hist[i] = 0u;
+  if (i == 0) { ts->prefix = 0u; ts->mask = 0u; ts->need = k; ts->taken_less = 0ull; ts->taken_eq = 0ull; }
+}
+
+__global__ __launch_bounds__(256) void k_topk_hist(const kgc_triple* __restrict__ rec, const unsigned long long* __restrict__ count,
+                                                   unsigned long long cap, int shift, TopkState* ts) {
+  __shared__ unsigned int h[256];
+  h[threadIdx.x] = 0u;
+  __syncthreads();
+  const unsigned long long n = *count < cap ? *count : cap;
+  const unsigned int prefix = ts->prefix, mask = ts->mask;
+  for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (unsigned long long)gridDim.x * blockDim.x) {
+    const unsigned int key = __float_as_uint(rec[i].dist);
+    if ((key & mask) == prefix) atomicAdd(&h[(key >> shift) & 255u], 1u);
+  }
+  __syncthreads();
+  if (h[threadIdx.x]) atomicAdd(&ts->hist[threadIdx.x], h[threadIdx.x]);
+}
+
+// one thread: which digit holds the need-th record among the matching keys; fix it and clear the histogram
+__global__ void k_topk_digit(int shift, TopkState* ts) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  unsigned long long need = ts->need, acc = 0ull;
+  int dsel = 255;
+  for (int b = 0; b < 256; ++b) {
+    const unsigned long long c = ts->hist[b];
+    if (acc + c >= need) { dsel = b; break; }
+    acc += c;
+  }
+  ts->need = need - acc;            // still wanted inside the chosen digit
+  ts->prefix |= (unsigned int)dsel << shift;
+  ts->mask |= 255u << shift;
+  for (int b = 0; b < 256; ++b) ts->hist[b] = 0u;
+}
+
+// after four passes prefix is the k-th smallest key T and need the number of records with key == T to take:
+// every record below T goes out, and the first `need` of those at T that get there
+__global__ __launch_bounds__(256) void k_topk_emit(const kgc_triple* __restrict__ rec, const unsigned long long* __restrict__ count,
+                                                   unsigned long long cap, unsigned long long k, TopkState* ts,
+                                                   kgc_triple* __restrict__ out) {
+  const unsigned long long n = *count < cap ? *count : cap;
+  const unsigned int T = ts->prefix;
+  const unsigned long long need_eq = ts->need;
+  const unsigned long long n_less = (n < k ? n : k) - (need_eq < (n < k ? n : k) ? need_eq : (n < k ? n : k));
+  for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (unsigned long long)gridDim.x * blockDim.x) {
+    const kgc_triple x = rec[i];
+    const unsigned int key = __float_as_uint(x.dist);
+    if (n <= k) { out[i] = x; continue; }                 // fewer records than asked for: all of them
+    if (key < T) out[atomicAdd(&ts->taken_less, 1ull)] = x;
+    else if (key == T) {
+      const unsigned long long j = atomicAdd(&ts->taken_eq, 1ull);
+      if (j < need_eq) out[n_less + j] = x;
+    }
+  }
 }
 
 __global__ __launch_bounds__(64) void k_top1_exact(RecheckCtx cx, Top1State* st) {

@@ -153,5 +153,17 @@ def test_top1_fullsize(name):
             print(f"[{name}] top-1 exclude_self={excl}: {got} in {ms:.1f} ms; oracle min over the join result {best:.7f}", flush=True)
             assert abs(dg - best) <= 1e-6 * best and abs(got["dist"] - best) <= 1e-6 * best
             assert not excl or got["h"] != got["t"]
+        # top-k: the k smallest of the oracle-verified join result (which holds far more than k triples)
+        k = 1000
+        dall = np.sort(oracle.dist_triples(wl.E, wl.Rv, spec.p, full["h"], full["r"], full["t"]))
+        t0 = time.perf_counter()
+        tk = j.topk(E, Rv, spec.p, k)
+        ms = (time.perf_counter() - t0) * 1e3
+        print(f"[{name}] top-{k} in {ms:.1f} ms; largest of them {tk['dist'][-1]:.6f}", flush=True)
+        assert tk["count"] == k
+        dk = np.sort(oracle.dist_triples(wl.E, wl.Rv, spec.p, tk["h"], tk["r"], tk["t"]))
+        assert np.allclose(dk, dall[:k], rtol=1e-6)
+        key = (tk["r"].astype(np.int64) * spec.N + tk["h"]) * spec.N + tk["t"]
+        assert np.unique(key).size == k
     finally:
         j.close()

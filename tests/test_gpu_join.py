@@ -402,3 +402,51 @@ def test_join_ab_is_transe_on_its_connectors(p):
     small = _run_ab(A, wl.E, p, delta, 8)
     assert small["code"] == 1 and small["count"] == got["count"]
     assert _run_ab(A, wl.E, p, -1.0, 8)["count"] == 0
+
+
+# ---- top-k: the k smallest triple distances ----
+def _check_topk(E, Rv, p, k, exclude_self, **kw):
+    import paper_2307_12059_amd as kgc
+    ref = oracle.topk(E, Rv, p, k, exclude_self)
+    j = kgc.Join(**kw)
+    try:
+        got = j.topk(_dev(E, "f32"), _dev(Rv, "f32"), p, k, exclude_self)
+    finally:
+        j.close()
+    assert got["count"] == ref["count"]
+    # the distances are unique (as a sorted list); which of several equal-distance triples come back is not
+    assert np.allclose(got["dist"], ref["dist"], rtol=1e-6, atol=1e-6)
+    key = (got["r"].astype(np.int64) * E.shape[0] + got["h"]) * E.shape[0] + got["t"]
+    assert np.unique(key).size == key.size
+    dg = oracle.dist_triples(E, Rv, p, got["h"], got["r"], got["t"])
+    assert np.allclose(np.sort(dg), ref["dist"], rtol=1e-6, atol=1e-6)
+    if exclude_self:
+        assert np.all(got["h"] != got["t"])
+    return got, ref
+
+
+@pytest.mark.parametrize("exclude_self", [False, True])
+@pytest.mark.parametrize("p", [1, 2])
+def test_topk_hand_case(p, exclude_self):
+    for k in (1, 2, 5, 18, 40):                       # 18 triples in all (12 without the self pairs)
+        got, ref = _check_topk(E3, R2, p, k, exclude_self)
+        assert got["count"] == min(k, 12 if exclude_self else 18)
+
+
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
+@pytest.mark.parametrize("k", [1, 10, 1000, 20000])
+def test_topk_c1(k, prune):
+    wl = workloads.generate("c1_tiny_l2")
+    _check_topk(wl.E, wl.Rv, 2, k, False, prune=prune)
+    if k <= 1000:
+        _check_topk(wl.E, wl.Rv, 1, k, True, prune=prune)
+
+
+def test_topk_mass_ties():
+    g = np.random.default_rng(5)
+    base = g.standard_normal((40, 16)).astype(np.float32)
+    E = np.repeat(base, 60, axis=0)
+    Rv = np.concatenate([np.zeros((1, 16), np.float32), g.standard_normal((2, 16)).astype(np.float32)])
+    for excl in (False, True):
+        got, ref = _check_topk(E, Rv, 2, 5000, excl, prune=PRUNE_ON)      # 144,000 zero-distance triples
+        assert np.all(got["dist"] == 0.0)
