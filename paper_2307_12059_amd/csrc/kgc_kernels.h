@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
                                                         unsigned int* __restrict__ max_slots,
                                                         const uint32_t* __restrict__ active_rows,
                                                         const unsigned int* __restrict__ n_active, int nH, int bm,
-                                                        int64_t rel_stride = 0) {
+                                                        int64_t rel_stride = 0, const int32_t* __restrict__ n_rows_dev = nullptr) {
   extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [kStageRows][KS * 32 + 8]
   __shared__ int32_t ents[kStageRows];
   __shared__ float wmax[4];
@@ -101,6 +101,8 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
       rl = (int)(g / groups_per_rel);
       slot0 = (g - (int64_t)rl * groups_per_rel) * kStageRows;
     }
+    // n_rows_dev: only the first *n_rows_dev slots (rounded up to a 256-row tile) hold rows this time
+    if (n_rows_dev && slot0 >= ((int64_t)*n_rows_dev + 255) / 256 * 256) continue;
     __syncthreads();                                   // previous group fully written out
     if (tid < kStageRows) ents[tid] = slot_ent[slot0 + tid];
     __syncthreads();

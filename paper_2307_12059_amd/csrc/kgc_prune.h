@@ -629,15 +629,15 @@ __global__ __launch_bounds__(256) void k_bound_refine(const BoundL2Args fine, co
 
 // One wave per (relation, head tile) row of the bitmap: count the surviving tail tiles, reserve a range
 // of the column list with one atomic, write the tile numbers in ascending order.
-__global__ __launch_bounds__(64) void k_rows_from_bitmap(const uint32_t* __restrict__ bitmap, int words_per_row,
+__global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __restrict__ bitmap, int words_per_row,
                                                          int64_t n_rows, uint32_t* __restrict__ row_start,
                                                          uint32_t* __restrict__ row_count, uint32_t* __restrict__ cols,
                                                          unsigned long long* __restrict__ total,
                                                          uint32_t* __restrict__ active_rows,
                                                          unsigned int* __restrict__ n_active) {
-  const int64_t row = blockIdx.x;
+  const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);   // four rows per block
   if (row >= n_rows) return;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63;
   const uint32_t* w = bitmap + row * words_per_row;
   uint32_t cnt = 0;
   for (int i = lane; i < words_per_row; i += 64) cnt += __builtin_popcount(w[i]);
