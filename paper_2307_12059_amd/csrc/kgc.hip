@@ -906,7 +906,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
       }
       k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 4, 0u);      // cursor and n_active
-      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 3) / 4), 256, 0, st>>>(
+      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 255) / 256), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p,
           &cnt->n_active);

@@ -627,49 +627,60 @@ __global__ __launch_bounds__(256) void k_bound_refine(const BoundL2Args fine, co
   }
 }
 
-// One wave per (relation, head tile) row of the bitmap: count the surviving tail tiles, reserve a range
-// of the column list with one atomic, write the tile numbers in ascending order.
+// Tile lists from the bitmap.  A wave takes 64 (relation, head tile) rows: every lane counts the surviving
+// tail tiles of its row (almost all rows are empty), the rows that have some reserve a range of the column
+// list with one atomic each and are then written out by the whole wave, one row after the other, tile
+// numbers ascending.
 __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __restrict__ bitmap, int words_per_row,
                                                          int64_t n_rows, uint32_t* __restrict__ row_start,
                                                          uint32_t* __restrict__ row_count, uint32_t* __restrict__ cols,
                                                          unsigned long long* __restrict__ total,
                                                          uint32_t* __restrict__ active_rows,
                                                          unsigned int* __restrict__ n_active) {
-  const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);   // four rows per block
-  if (row >= n_rows) return;
   const int lane = threadIdx.x & 63;
-  const uint32_t* w = bitmap + row * words_per_row;
+  const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64;
+  if (row0 >= n_rows) return;                                  // whole waves leave together
+  const int64_t my_row = row0 + lane;
   uint32_t cnt = 0;
-  for (int i = lane; i < words_per_row; i += 64) cnt += __builtin_popcount(w[i]);
-  for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
-  unsigned long long base = 0;
-  if (lane == 0 && cnt) base = atomicAdd(total, (unsigned long long)cnt);
-  base = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(base >> 32), 0) << 32) |
-         (uint32_t)__shfl((int)(uint32_t)(base & 0xffffffffull), 0);
-  if (lane == 0) {
-    row_start[row] = (uint32_t)base;
-    row_count[row] = cnt;
-    if (cnt) active_rows[atomicAdd(n_active, 1u)] = (uint32_t)row;    // rows that still have work, in any order
+  if (my_row < n_rows) {
+    const uint32_t* w = bitmap + my_row * words_per_row;
+    for (int i = 0; i < words_per_row; ++i) cnt += __builtin_popcount(w[i]);
   }
-  if (cnt == 0) return;
-  // ascending order: words in chunks of 64, prefix of popcounts across lanes
-  uint32_t run = 0;
-  for (int i0 = 0; i0 < words_per_row; i0 += 64) {
-    const int i = i0 + lane;
-    uint32_t word = i < words_per_row ? w[i] : 0u;
-    const uint32_t pc = __builtin_popcount(word);
-    uint32_t pre = pc;
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t o = __shfl_up(pre, off, 64);
-      if (lane >= off) pre += o;
+  unsigned long long my_base = 0;
+  if (my_row < n_rows) {
+    if (cnt) {
+      my_base = atomicAdd(total, (unsigned long long)cnt);
+      active_rows[atomicAdd(n_active, 1u)] = (uint32_t)my_row;   // rows that still have work, in any order
     }
-    uint32_t pos = run + pre - pc;
-    while (word) {
-      const int b = __builtin_ctz(word);
-      word &= word - 1;
-      cols[base + pos++] = (uint32_t)(i * 32 + b);
+    row_start[my_row] = (uint32_t)my_base;
+    row_count[my_row] = cnt;
+  }
+  unsigned long long live = __builtin_amdgcn_ballot_w64(cnt != 0u);
+  while (live) {
+    const int src = (int)__builtin_ctzll(live);
+    live &= live - 1ull;
+    const unsigned long long base = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(my_base >> 32), src) << 32) |
+                                    (uint32_t)__shfl((int)(uint32_t)(my_base & 0xffffffffull), src);
+    const uint32_t* w = bitmap + (row0 + src) * words_per_row;
+    // ascending order: words in chunks of 64, prefix of popcounts across lanes
+    uint32_t run = 0;
+    for (int i0 = 0; i0 < words_per_row; i0 += 64) {
+      const int i = i0 + lane;
+      uint32_t word = i < words_per_row ? w[i] : 0u;
+      const uint32_t pc = __builtin_popcount(word);
+      uint32_t pre = pc;
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(pre, off, 64);
+        if (lane >= off) pre += o;
+      }
+      uint32_t pos = run + pre - pc;
+      while (word) {
+        const int bit = __builtin_ctz(word);
+        word &= word - 1;
+        cols[base + pos++] = (uint32_t)(i * 32 + bit);
+      }
+      run += __shfl(pre, 63, 64);
     }
-    run += __shfl(pre, 63, 64);
   }
 }
 
