@@ -42,6 +42,7 @@ struct kgc_handle {
   // pruning scratch
   DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
   DevBuf active_rows, cnorm, gram, relu, reln, asg_a, asg_b, limr;
+  // every DevBuf member must also be listed in kgc_destroy
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
   DevBuf unit_first, unit_n, cent_u, rad_u, cnorm_u, gram_u, relu_u, pair_list, pair_count;   // two-level bound test
   DevBuf zero_row;                             // kgc_join_ab: the relation vector every relation reads (zeros)
@@ -187,11 +188,12 @@ int kgc_create(const kgc_config* cfg, kgc_handle** out) {
 
 void kgc_destroy(kgc_handle* h) {
   if (!h) return;
-  release(h->slot_ent); release(h->opB); release(h->opA); release(h->normsB); release(h->normsA);
-  release(h->counters); release(h->params);
-  for (DevBuf* b : {&h->gstate, &h->unc_a, &h->unc_b, &h->group_of, &h->piv_ent, &h->best, &h->gsize, &h->goff, &h->gfill,
+  for (DevBuf* b : {&h->slot_ent, &h->opB, &h->opA, &h->normsB, &h->normsA, &h->counters, &h->params,
+                    &h->gstate, &h->unc_a, &h->unc_b, &h->group_of, &h->piv_ent, &h->best, &h->gsize, &h->goff, &h->gfill,
                     &h->cent, &h->rad, &h->bitmap, &h->row_start, &h->row_count, &h->cols, &h->active_rows, &h->cnorm,
-                    &h->gram, &h->relu, &h->reln})
+                    &h->gram, &h->relu, &h->reln, &h->asg_a, &h->asg_b, &h->limr, &h->top1_buf, &h->top1_state,
+                    &h->unit_first, &h->unit_n, &h->cent_u, &h->rad_u, &h->cnorm_u, &h->gram_u, &h->relu_u, &h->pair_list,
+                    &h->pair_count, &h->zero_row, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
     release(*b);
   if (h->host_gstate) (void)hipHostFree(h->host_gstate);
   if (h->host_counters) (void)hipHostFree(h->host_counters);
@@ -336,6 +338,12 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
 }  // extern "C"
 
 namespace {
+// kgc_top1 / kgc_topk switch the handle to "no self pairs" around their inner joins; this puts it back on every way out
+struct NoSelfScope {
+  kgc_handle* h;
+  NoSelfScope(kgc_handle* hd, bool on) : h(hd) { h->no_self = on ? 1 : 0; }
+  ~NoSelfScope() { h->no_self = 0; }
+};
 constexpr uint64_t kTopCap = 1u << 20;       // records the inner joins of the top-1 / top-k searches may return
 constexpr int kTopSamples = 1 << 16;
 
@@ -441,17 +449,16 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   //    than the buffer holds, the smallest distance among those that did come back is the next bound.  The
   //    bound of step 1b rests on an error analysis instead of an exact distance; should a join at it come
   //    back empty, the search falls back to the sampled bound, whose triple is known to qualify.
-  hd->no_self = exclude_self ? 1 : 0;
+  NoSelfScope no_self_scope(hd, exclude_self != 0);
   int rounds = 0;
   for (;; ++rounds) {
     float delta = (float)bound;
     if ((double)delta < bound) delta = std::nextafterf(delta, INFINITY);    // the bounding triple must qualify
     uint64_t count = 0;
     rc = kgc_join(hd, E, N, d, Rvecs, R, p, delta, (kgc_triple*)hd->top1_buf.p, kCap, &count);
-    if (rc < 0) { hd->no_self = 0; return rc; }
+    if (rc < 0) return rc;
     if (count == 0) {
       if (bound < sample_bound) { bound = sample_bound; continue; }
-      hd->no_self = 0;
       return fail(hd, KGC_E_HIP, "top-1 search lost its bounding triple");
     }
     DevCounters* cnt = (DevCounters*)hd->counters.p;
@@ -508,13 +515,13 @@ int kgc_topk(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   double lo = 0.0;                                             // a threshold known to return fewer than k
   bool have_lo = false;
   uint64_t count = 0;
-  hd->no_self = exclude_self ? 1 : 0;
+  NoSelfScope no_self_scope(hd, exclude_self != 0);
   for (int rounds = 0;; ++rounds) {
     float delta = take_all ? INFINITY : (float)thr;
     if (!take_all && (double)delta < thr) delta = std::nextafterf(delta, INFINITY);
     rc = kgc_join(hd, E, N, d, Rvecs, R, p, delta, (kgc_triple*)hd->top1_buf.p, kTopCap, &count);
-    if (rc < 0) { hd->no_self = 0; return rc; }
-    if (rounds >= 200) { hd->no_self = 0; return fail(hd, KGC_E_HIP, "top-k search did not settle"); }
+    if (rc < 0) return rc;
+    if (rounds >= 200) return fail(hd, KGC_E_HIP, "top-k search did not settle");
     const uint64_t want = (double)k < eligible ? k : (uint64_t)eligible;
     if (count < want) {                                        // too few: grow (towards the sampled bound first)
       lo = thr; have_lo = true;
