@@ -145,7 +145,12 @@ int check_common(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void
   return KGC_OK;
 }
 
-int grid_for(int64_t items, int per_block) { return (int)std::min<int64_t>((items + per_block - 1) / per_block, 1 << 20); }
+// Blocks for `items` work items, `per_block` each.  A launch may hold fewer than 2^32 threads per grid dimension, so
+// the count stops at 2^24 - 1 blocks (of at most 256 threads): enough for every per-row or per-slot kernel here
+// (N < 2^31); kernels that can be asked for more (k_fill_u32, the staging kernels) stride over their items.
+int grid_for(int64_t items, int per_block) {
+  return (int)std::min<int64_t>((items + per_block - 1) / per_block, (1 << 24) - 1);
+}
 
 }  // namespace
 

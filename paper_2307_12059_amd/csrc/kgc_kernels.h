@@ -44,8 +44,7 @@ struct DevCounters {
 };
 
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
 __global__ void k_add_u64(unsigned long long* dst, const unsigned long long* src) {
