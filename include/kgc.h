@@ -8,7 +8,7 @@
  *
  * This is the completion problem of Definition 1 (Section 3.1) for the TransE distance, after the
  * transformation of Section 4.3: connector_1(h, r) = h + r, connector_2(t, r) = t,
- * dist(a, b) = ||a - b||_p.  The threshold is inclusive (Section 3.1: "less than or equal"), self
+ * dist(a, b) = ||a - b||_p.  The threshold is inclusive (Section 3.1 includes equality), self
  * pairs h == t are included and nothing is filtered against an existing graph.  The paper calls the
  * distance threshold epsilon; it is named delta here because the paper also uses epsilon for the score.
  *
@@ -135,7 +135,7 @@ int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* R
 int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
                    float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
 
-/* The join in its general form (Section 4.3): for a model that is "transformable to a metric space" the
+/* The join in its general form (Section 4.3): for a model that can be transformed to a metric space the
  * caller supplies the connector outputs and the library joins them under dist(a, b) = ||a - b||_p:
  *   A   R x N x d   a_{r,h} = connector_1(h, r), row-major, contiguous, of the handle's dtype          (device)
  *   B   N x d when b_per_relation == 0 (connector_2 does not depend on r; TransE: b = t), else R x N x d
