@@ -149,7 +149,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
                 int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
 
 /* The top-1 score of Section 3.3: the triple with the smallest dist_3(h, r, t) over E x R x E, or, with
- * exclude_self != 0, over the triples with h != t (the paper's "top-1 score except self-edges").
+ * exclude_self != 0, over the triples with h != t (the second quantity that section looks at).
  *   out   receives the triple and its distance (host).  h = r = t = -1 and dist = +inf when no triple is
  *         eligible (N == 0, R == 0, or exclude_self with N == 1): that is KGC_OK, not an error.
  * Same E / Rvecs / p conventions and error codes as kgc_join.  Found by joins with a shrinking threshold,

@@ -183,8 +183,8 @@ int64_t kgco_join_ab(const double *A, const double *B, int64_t N, int32_t d, int
     return total;
 }
 
-/* ---- top-1: the smallest distance over all triples (the "top-1 score" of Section 3.3), optionally
- * leaving out the self pairs h == t (the paper's "top-1 score except self-edges").  Plain triple loop,
+/* ---- top-1: the smallest distance over all triples (the top-1 score of Section 3.3), optionally
+ * leaving out the self pairs h == t (the second quantity that section looks at).  Plain triple loop,
  * every distance summed in full.  Among equal distances the smallest (r, h, t) wins.  Returns 1 and fills
  * the outputs, or 0 when no triple is eligible (N == 0, R == 0, or exclude_self with N == 1), or -1 on a
  * bad argument. */
