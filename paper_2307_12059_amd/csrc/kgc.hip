@@ -678,12 +678,16 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     const float tau = delta > 0.f ? radius_mult * delta : 0.f;
     const int gN = grid_for(std::max<int64_t>(N, kPivotsPerRound), 256);
     k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
-    // L2 with a head tile that fits in LDS: the rows-against-pivots distances of every round run on the
+    // With a head tile that fits in LDS (d <= 602) the rows-against-pivots distances of every round run on the
     // matrix pipes, as a join of all entities (heads, staged once in identity order) with the round's pivots
-    // (tails) whose epilogue keeps, per entity, the lowest pivot position within tau.  Otherwise (L1, large d)
+    // (tails) whose epilogue keeps, per entity, the lowest pivot position within tau.  Otherwise (large d)
     // the float32 vector kernel does it.  Which member of a cluster ends up with which pivot does not touch
     // the result: centres and radii are taken from the rows after the layout.
-    const bool mfma_assign = (p == 2) && KS <= kDirectHalfMaxKS && delta > 0.f;
+    // An L1 join is grouped in L2 as well: for differences with independent, similarly sized components
+    // ||x||_1 is about sqrt(2 / pi) sqrt(d) ||x||_2, so the L1 radius tau corresponds to that L2 radius; a
+    // different ratio only makes the groups a little larger or smaller.
+    const bool mfma_assign = KS <= kDirectHalfMaxKS && delta > 0.f;
+    const float tau_l2 = (p == 2) ? tau : tau / (0.79788456f * std::sqrt((float)d));
     const int abm = KS <= kDirectMaxKS ? 256 : 128;           // head tile height of the assignment kernel
     void (*assign_kernel)(const JoinStreamArgs) =
         abm == 256 ? k_join_l2_direct<256, 2, 4, kEpiAssignMin> : k_join_l2_direct<128, 1, 8, kEpiAssignMin>;
@@ -715,7 +719,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         sa.KS = KS; sa.k16 = k16; sa.nH = (int)(Npad / abm); sa.nT = kPivotsPerRound / 256; sa.r0 = 0; sa.RB = 1;
         sa.tail_slots = kPivotsPerRound; sa.tail_rows_dev = &gs->n_piv;
         // bf16 rows move a distance by at most 2^-8 (||e|| + ||pivot||); that much either way is of no concern here
-        sa.thr_value = tau * tau;
+        sa.thr_value = tau_l2 * tau_l2;
         sa.best = (unsigned long long*)hd->best.p; sa.group_of = (const int32_t*)hd->group_of.p; sa.n_heads = N;
         // the pivot tiles are dealt to 1, 2 or 4 blocks per head tile, enough to fill the chip
         const int64_t nHa = Npad / abm;
