@@ -997,6 +997,12 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         if (tc.head_resident) {
           dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
           if ((dyn_lds + tc.static_lds) * tc.blocks_per_cu > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
+          if (prune && tc.tail_buffers > 0) {     // room for a row's tile list behind the tail buffers, if the LDS has it
+            const size_t spare = kMaxLds / tc.blocks_per_cu - (dyn_lds + tc.static_lds);
+            sa.cols_lds = (int)std::min<size_t>(spare / 4, (size_t)nT);
+            if (sa.cols_lds < nT) sa.cols_lds = 0;             // a list may hold every tail tile: all or nothing
+            dyn_lds += (size_t)sa.cols_lds * 4;
+          }
           KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
         }
         const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit);

@@ -407,6 +407,7 @@ struct JoinStreamArgs {
   RecheckCtx cx;
   // Group assignment (k_join_l2_direct<.., kEpiAssignMin>): heads are all entities in identity order, tails
   // the pivots of a covering round, staged in an array of their own with tail_slots rows.
+  int cols_lds;                       // head-resident listed kernel: entries of LDS reserved for a row's tile list
   int b_per_rel;                      // 1: the tail operands are staged per relation, [RB][KS][Nslots][32] like A
   int64_t tail_slots;                 // rows per K slice of B when it differs from Nslots (0: the same)
   const int32_t* tail_rows_dev;       // device count of valid tail rows (tail tiles past it are skipped); may be NULL
@@ -677,6 +678,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
   const uint32_t* cols = nullptr;
+  const uint32_t* lcols = nullptr;      // the row's tile list in LDS, when it fits (see below)
   if constexpr (LISTED) {
     if (row_i >= *a.n_active) break;
     const int64_t row = (int64_t)a.active_rows[row_i];
@@ -714,6 +716,17 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
     for (int i = 0; i < LA; ++i) *(uint4*)(&Ares[ks * ASZ + st0 + i * st_step]) = t[i];
   }
 
+  // The tile list of the row goes to LDS behind the tail buffers when there is room (a.cols_lds entries): the
+  // loop then holds no global load besides the prefetches, whose outstanding count the compiler can follow
+  // exactly; a list read from global memory makes every tile change wait for all of them.
+  if (LISTED && ntiles <= a.cols_lds) {
+    uint32_t* l = (uint32_t*)(Bs + 2 * BSZ);
+    for (int t = tid; t < ntiles; t += NT) l[t] = cols[t_begin + t];
+    lcols = l;
+  }
+  // the list must be complete before the first prefetches: with one or two K slices per tile they already move
+  // on to the second tile (the barrier also publishes the head tile; all threads of a block take the same path)
+  if (LISTED) __syncthreads();
   typedef uint32_t regb_t __attribute__((ext_vector_type(4 * LB)));
   regb_t rb0, rb1;
   int pf_k = 0, pf_t = 0, pf_i = 0;
@@ -729,7 +742,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
       if (++pf_k == KS) {                                                                         \
         pf_k = 0;                                                                                 \
         ++pf_t;                                                                                   \
-        tcol = cols ? (int)cols[t_begin + pf_t] : t_begin + pf_t;                                 \
+        tcol = lcols ? (int)lcols[pf_t] : cols ? (int)cols[t_begin + pf_t] : t_begin + pf_t;          \
         pB = Bbase + (int64_t)tcol * BN * (kSliceK * 2);                                          \
       } else {                                                                                    \
         pB += slice_bytes;                                                                        \
@@ -800,7 +813,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
       tile_done = true;                                                                           \
       done_tcol = tcol_cur;                                                                       \
       ck = 0;                                                                                     \
-      if (++ct < ntiles) tcol_cur = cols ? (int)cols[t_begin + ct] : t_begin + ct;                \
+      if (++ct < ntiles) tcol_cur = lcols ? (int)lcols[ct] : cols ? (int)cols[t_begin + ct] : t_begin + ct; \
     } else {                                                                                      \
       ++ck;                                                                                       \
     }                                                                                             \
