@@ -804,12 +804,13 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
                    (rc = ensure(hd, hd->relu, (size_t)RBmax * n_micro * 4)) || (rc = ensure(hd, hd->reln, RBmax * 4))))
       return rc;
     // the two-level test pays when the units are clearly fewer than the micro-tiles (groups of several micro-tiles)
-    use_units = p == 2 && delta >= 0.f && ut.n_units > 0 && ut.n_units < (1 << 24) && (int64_t)ut.n_units * 10 <= n_micro * 6;
+    use_units = delta >= 0.f && ut.n_units > 0 && ut.n_units < (1 << 24) && (int64_t)ut.n_units * 10 <= n_micro * 6;
     if (use_units && ((rc = ensure(hd, hd->cent_u, (size_t)ut.n_units * d * 4)) || (rc = ensure(hd, hd->rad_u, (size_t)ut.n_units * 4)) ||
                       (rc = ensure(hd, hd->cnorm_u, (size_t)ut.n_units * 4)) ||
-                      (rc = ensure(hd, hd->gram_u, (size_t)ut.n_units * ut.n_units * 4)) ||
-                      (rc = ensure(hd, hd->relu_u, (size_t)RBmax * ut.n_units * 4)) ||
                       (rc = ensure(hd, hd->pair_list, kBoundPairCap * 8)) || (rc = ensure(hd, hd->pair_count, 8))))
+      return rc;
+    if (use_units && p == 2 && ((rc = ensure(hd, hd->gram_u, (size_t)ut.n_units * ut.n_units * 4)) ||
+                                (rc = ensure(hd, hd->relu_u, (size_t)RBmax * ut.n_units * 4))))
       return rc;
   }
   const int nbatch = (int)((Rn + RBmax - 1) / RBmax);
@@ -836,7 +837,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), 1);
       k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
       if (use_units) {
-        k_unit_summary<<<(unsigned)ut.n_units, 64, 0, st>>>((const float*)hd->cent.p, (const float*)hd->rad.p, d, ut,
+        k_unit_summary<2><<<(unsigned)ut.n_units, 64, 0, st>>>((const float*)hd->cent.p, (const float*)hd->rad.p, d, ut,
                                                             (float*)hd->cent_u.p, (float*)hd->rad_u.p, (float*)hd->cnorm_u.p);
         TileDistArgs tu{};
         tu.X = hd->cent_u.p; tu.dtypeX = KGC_F32; tu.n_rows = ut.n_units; tu.Y = hd->cent_u.p; tu.dtypeY = KGC_F32;
@@ -847,6 +848,9 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     } else {
       k_micro_summary<1><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p,
                                                             (float*)hd->rad.p, (float*)hd->cnorm.p);
+      if (use_units)
+        k_unit_summary<1><<<(unsigned)ut.n_units, 64, 0, st>>>((const float*)hd->cent.p, (const float*)hd->rad.p, d, ut,
+                                                               (float*)hd->cent_u.p, (float*)hd->rad_u.p, (float*)hd->cnorm_u.p);
     }
   }
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
@@ -918,8 +922,20 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         ta.shift = Rvecs; ta.dtype_shift = dtype; ta.r0 = (int)r0; ta.d = d;
         ta.rad = (const float*)hd->rad.p; ta.delta = delta; ta.bitmap = (uint32_t*)hd->bitmap.p;
         ta.nH = nH; ta.words_per_row = words_per_row; ta.micro_per_bm = BM / kMicro; ta.micro_per_bn = BN / kMicro;
-        const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), (unsigned)RB);
-        k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
+        if (use_units) {
+          // unit level first (unit centres and radii in place of the micro-tile ones), then the micro-tile pairs
+          TileDistArgs tu = ta;
+          tu.X = hd->cent_u.p; tu.Y = hd->cent_u.p; tu.n_rows = ut.n_units; tu.n_cols = ut.n_units; tu.rad = (const float*)hd->rad_u.p;
+          tu.ut = ut; tu.bp = BoundPairs{(unsigned long long*)hd->pair_list.p, (unsigned long long*)hd->pair_count.p, kBoundPairCap};
+          tu.fine_cent = (const float*)hd->cent.p; tu.fine_rad = (const float*)hd->rad.p; tu.n_micro = n_micro;
+          k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)hd->pair_count.p, 2, 0u);
+          const dim3 gu((unsigned)((ut.n_units + 127) / 128), (unsigned)((ut.n_units + 127) / 128), (unsigned)RB);
+          k_tile_dist<1, kEpiBoundUnits><<<gu, 256, 0, st>>>(tu);
+          k_bound_refine_l1<<<dim3(1024, 32, 1), 256, 0, st>>>(tu);
+        } else {
+          const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), (unsigned)RB);
+          k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
+        }
       }
       k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 4, 0u);      // cursor and n_active
       k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 255) / 256), 256, 0, st>>>(

@@ -207,7 +207,29 @@ __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E
 //   MATRIX  the p-th power of every distance is written to a row-major n_rows x n_cols matrix
 //   BOUND   rows and columns are micro-tile centres; a micro-tile pair survives when
 //           dist - rho_row - rho_col <= delta (with slack), and then sets the bit of its join tile
-enum { kEpiAssign = 0, kEpiBound = 1, kEpiMatrix = 2 };
+enum { kEpiAssign = 0, kEpiBound = 1, kEpiMatrix = 2, kEpiBoundUnits = 3 };
+
+// Units of the two-level bound test (see k_bound_l2_units further down): a padded group's run of micro-tiles, or a
+// single micro-tile of the packed tail region.
+struct UnitTable {
+  const int32_t* first;   // big units: first micro-tile ...
+  const int32_t* n;       // ... and number of micro-tiles
+  int n_big;              // units 0 .. n_big - 1 are padded groups
+  int tail_first;         // unit n_big + i is micro-tile tail_first + i
+  int n_units;
+};
+__device__ __forceinline__ void unit_range(const UnitTable& ut, int u, int& first, int& n) {
+  if (u < ut.n_big) { first = ut.first[u]; n = ut.n[u]; }
+  else { first = ut.tail_first + (u - ut.n_big); n = 1; }
+}
+
+constexpr int kInlineMicroPairs = 8;   // unit pairs with at most this many micro-tile pairs are refined where they are found
+struct BoundPairs {
+  unsigned long long* list;     // (rl << 48) | (unit of heads << 24) | unit of tails
+  unsigned long long* count;    // entries asked for (may exceed cap)
+  unsigned long long cap;
+};
+
 
 struct TileDistArgs {
   const void* X; int dtypeX; const int32_t* row_ids; const int32_t* n_rows_dev; int64_t n_rows;
@@ -218,7 +240,35 @@ struct TileDistArgs {
   float* matrix;                                   // MATRIX
   const float* rad; float delta; uint32_t* bitmap; // BOUND
   int nH, words_per_row, micro_per_bm, micro_per_bn;
+  // BOUND on units (L1): rows / columns are unit centres, rad their radii; survivors are refined on the
+  // micro-tile summaries below (small pairs on the spot, the others through the list)
+  UnitTable ut; BoundPairs bp;
+  const float* fine_cent; const float* fine_rad; int64_t n_micro;
 };
+
+// L1 bound of one unit pair on its micro-tile pairs: dist_1(c_H + r, c_T) - rho_H - rho_T <= delta, centre
+// distances summed over d by the calling lane; `lane_count` lanes starting at `lane0` share the pairs.
+__device__ __forceinline__ void refine_unit_pair_l1(const TileDistArgs& a, int rl, int uH, int uT, int lane0, int lane_count) {
+  int fH, nHm, fT, nTm;
+  unit_range(a.ut, uH, fH, nHm);
+  unit_range(a.ut, uT, fT, nTm);
+  const int64_t so = (int64_t)(a.r0 + rl) * a.d;
+  const int64_t total = (int64_t)nHm * nTm;
+  for (int64_t i = lane0; i < total; i += lane_count) {
+    const int64_t mH = fH + i / nTm, mT = fT + i % nTm;
+    const float rH = a.fine_rad[mH], rT = a.fine_rad[mT];
+    if (rH < 0.f || rT < 0.f) continue;
+    const float* cH = a.fine_cent + mH * a.d;
+    const float* cT = a.fine_cent + mT * a.d;
+    float s = 0.f;
+    for (int k = 0; k < a.d; ++k) s += fabsf(cH[k] + ld_elem(a.shift, so + k, a.dtype_shift) - cT[k]);
+    if (s * (1.f - kBoundSlack) - rH - rT <= a.delta * (1.f + kBoundSlack)) {
+      const int tH = (int)(mH / a.micro_per_bm), tT = (int)(mT / a.micro_per_bn);
+      uint32_t* w = &a.bitmap[((int64_t)rl * a.nH + tH) * a.words_per_row + (tT >> 5)];
+      if (!(*w & (1u << (tT & 31)))) atomicOr(w, 1u << (tT & 31));
+    }
+  }
+}
 
 template <int P, int EPI>
 __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
@@ -330,6 +380,35 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           if (cid[lc + j] >= 0) o[j] = acc[i][jg * 4 + j];
+      }
+    }
+  } else if (EPI == kEpiBoundUnits) {
+    const int rl = (int)blockIdx.z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int lr = (i >> 2) * 64 + ty * 4 + (i & 3);
+      if (rid[lr] < 0) continue;
+      const float rr = a.rad[row0 + lr];
+      if (rr < 0.f) continue;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int lc = (j >> 2) * 64 + tx * 4 + (j & 3);
+        if (cid[lc] < 0) continue;
+        const float rc = a.rad[col0 + lc];
+        if (rc < 0.f) continue;
+        const float dist = (P == 2) ? sqrtf(acc[i][j]) : acc[i][j];
+        if (dist * (1.f - kBoundSlack) - rr - rc > a.delta * (1.f + kBoundSlack)) continue;
+        const int uH = (int)(row0 + lr), uT = (int)(col0 + lc);
+        int fH, nHm, fT, nTm;
+        unit_range(a.ut, uH, fH, nHm);
+        unit_range(a.ut, uT, fT, nTm);
+        unsigned long long pos = a.bp.cap;
+        if ((int64_t)nHm * nTm > kInlineMicroPairs) pos = atomicAdd(a.bp.count, 1ull);
+        if (pos < a.bp.cap)
+          a.bp.list[pos] = ((unsigned long long)(uint32_t)rl << 48) | ((unsigned long long)(uint32_t)uH << 24) |
+                           (unsigned long long)(uint32_t)uT;
+        else
+          refine_unit_pair_l1(a, rl, uH, uT, 0, 1);
       }
     }
   } else {
@@ -462,19 +541,8 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
 // the micro-tiles of (distance of its centre to the unit centre + its radius), so every row of the unit is
 // inside -- and only the micro-tile pairs of surviving unit pairs are tested.  Survivors go through a list;
 // a lane that finds the list full tests its pair's micro-tiles on the spot.
-struct UnitTable {
-  const int32_t* first;   // big units: first micro-tile ...
-  const int32_t* n;       // ... and number of micro-tiles
-  int n_big;              // units 0 .. n_big - 1 are padded groups
-  int tail_first;         // unit n_big + i is micro-tile tail_first + i
-  int n_units;
-};
-__device__ __forceinline__ void unit_range(const UnitTable& ut, int u, int& first, int& n) {
-  if (u < ut.n_big) { first = ut.first[u]; n = ut.n[u]; }
-  else { first = ut.tail_first + (u - ut.n_big); n = 1; }
-}
-
-// one wave per unit
+// one wave per unit; P: the join's metric (radii in that metric)
+template <int P>
 __global__ __launch_bounds__(64) void k_unit_summary(const float* __restrict__ cent, const float* __restrict__ rad, int d,
                                                      UnitTable ut, float* __restrict__ centU, float* __restrict__ radU,
                                                      float* __restrict__ cnormU) {
@@ -506,19 +574,12 @@ __global__ __launch_bounds__(64) void k_unit_summary(const float* __restrict__ c
   for (int m = first; m < first + n; ++m) {
     if (rad[m] < 0.f) continue;
     float s = 0.f;
-    for (int k = lane; k < d; k += 64) { const float x = cent[(int64_t)m * d + k] - c[k]; s += x * x; }
+    for (int k = lane; k < d; k += 64) { const float x = cent[(int64_t)m * d + k] - c[k]; s += (P == 2) ? x * x : fabsf(x); }
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    rmax = fmaxf(rmax, sqrtf(s) * (1.f + kBoundSlack) + rad[m]);
+    rmax = fmaxf(rmax, ((P == 2) ? sqrtf(s) : s) * (1.f + kBoundSlack) + rad[m]);
   }
   if (lane == 0) { radU[u] = rmax * (1.f + kBoundSlack) + 1e-30f; cnormU[u] = sqrtf(c2) * (1.f + kBoundSlack); }
 }
-
-constexpr int kInlineMicroPairs = 8;   // unit pairs with at most this many micro-tile pairs are refined where they are found
-struct BoundPairs {
-  unsigned long long* list;     // (rl << 48) | (unit of heads << 24) | unit of tails
-  unsigned long long* count;    // entries asked for (may exceed cap)
-  unsigned long long cap;
-};
 
 // the micro-tile level of the test for one surviving unit pair and relation; `lane_count` lanes starting at
 // `lane0` share the micro-tile pairs (1 lane = on the spot in the unit-level kernel, a block in k_bound_refine)
@@ -612,6 +673,16 @@ __global__ __launch_bounds__(256) void k_bound_l2_units(const BoundL2Args a, con
       else
         refine_unit_pair(fine, ut, rl0 + q, (int)mH, (int)mT, 0, 1);
     }
+  }
+}
+
+// L1 form of k_bound_refine (below): the listed unit pairs on their micro-tile summaries.
+__global__ __launch_bounds__(256) void k_bound_refine_l1(const TileDistArgs a) {
+  const unsigned long long n = *a.bp.count < a.bp.cap ? *a.bp.count : a.bp.cap;
+  for (unsigned long long e = blockIdx.x; e < n; e += gridDim.x) {
+    const unsigned long long v = a.bp.list[e];
+    refine_unit_pair_l1(a, (int)(v >> 48), (int)((v >> 24) & 0xffffffull), (int)(v & 0xffffffull),
+                        (int)(blockIdx.y * blockDim.x + threadIdx.x), (int)(gridDim.y * blockDim.x));
   }
 }
 
