@@ -168,6 +168,12 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
 int kgc_topk(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
              int32_t exclude_self, uint64_t k, kgc_triple* out_triples, uint64_t* found);
 
+/* kgc_topk over the relations r_begin <= r < r_end only (kgc_topk is the range [0, R)); with a range of one
+ * relation, the k best (h, t) pairs of that relation. */
+int kgc_topk_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                   int32_t exclude_self, int32_t r_begin, int32_t r_end, uint64_t k, kgc_triple* out_triples,
+                   uint64_t* found);
+
 /* Copy the statistics of the last kgc_join into *out (host). */
 int kgc_get_stats(const kgc_handle* hd, kgc_stats* out);
 

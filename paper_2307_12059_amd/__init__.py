@@ -23,7 +23,7 @@ KGC_PRUNE_AUTO, KGC_PRUNE_OFF, KGC_PRUNE_ON = 0, 1, 2
 KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
-EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_top1", "kgc_topk", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
+EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_top1", "kgc_topk", "kgc_topk_range", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
            "kgc_version"]
 
 
@@ -86,6 +86,9 @@ def load_library():
     lib.kgc_topk.restype = ctypes.c_int
     lib.kgc_topk.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                              ctypes.c_uint64, vp, ctypes.POINTER(ctypes.c_uint64)]
+    lib.kgc_topk_range.restype = ctypes.c_int
+    lib.kgc_topk_range.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64, vp, ctypes.POINTER(ctypes.c_uint64)]
     lib.kgc_norms.restype = ctypes.c_int
     lib.kgc_norms.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
     lib.kgc_get_stats.restype = ctypes.c_int
@@ -170,6 +173,16 @@ def kgc_topk(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, exc
     found = ctypes.c_uint64(0)
     rc = load_library().kgc_topk(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
                                  1 if exclude_self else 0, k, ctypes.c_void_p(out_ptr), ctypes.byref(found))
+    return rc, int(found.value)
+
+
+def kgc_topk_range(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, exclude_self: bool, r_begin: int,
+                   r_end: int, k: int, out_ptr: int):
+    """Raw call on device addresses.  Returns (code, found)."""
+    found = ctypes.c_uint64(0)
+    rc = load_library().kgc_topk_range(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
+                                       1 if exclude_self else 0, r_begin, r_end, k, ctypes.c_void_p(out_ptr),
+                                       ctypes.byref(found))
     return rc, int(found.value)
 
 
@@ -284,14 +297,16 @@ class Join:
             return None
         return {"h": int(rec.h), "r": int(rec.r), "t": int(rec.t), "dist": float(rec.dist)}
 
-    def topk(self, E, Rv, p: int, k: int, exclude_self: bool = False) -> dict:
-        """The k smallest-distance triples, sorted by (dist, r, h, t) on the host: dict h, r, t, dist, count."""
+    def topk(self, E, Rv, p: int, k: int, exclude_self: bool = False, r_range=None) -> dict:
+        """The k smallest-distance triples, sorted by (dist, r, h, t) on the host: dict h, r, t, dist, count.
+        ``r_range = (r_begin, r_end)`` restricts the search to those relations (one relation: its k best pairs)."""
         import numpy as np
         torch = self._torch
         self._check(E, Rv)
         out = torch.empty((max(k, 1), 4), dtype=torch.int32, device=E.device)
-        rc, found = kgc_topk(self.handle, E.data_ptr(), E.shape[0], E.shape[1], Rv.data_ptr(), Rv.shape[0], p, exclude_self,
-                             k, out.data_ptr())
+        lo, hi = (0, Rv.shape[0]) if r_range is None else (int(r_range[0]), int(r_range[1]))
+        rc, found = kgc_topk_range(self.handle, E.data_ptr(), E.shape[0], E.shape[1], Rv.data_ptr(), Rv.shape[0], p,
+                                   exclude_self, lo, hi, k, out.data_ptr())
         if rc < 0:
             raise RuntimeError(f"kgc_topk failed with code {rc}: {kgc_last_error(self.handle)}")
         host = out[:found].cpu().numpy()

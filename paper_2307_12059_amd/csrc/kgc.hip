@@ -356,8 +356,9 @@ constexpr int kTopSamples = 1 << 16;
 // kTopSamples sampled triples, scored exactly (its triple is known to qualify); *bound: that, or the tighter bound
 // of the sub-sampled dense pass when it applies.  samples (optional, host, kTopSamples doubles) receives every
 // sampled distance.
-int top_bounds(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p, int32_t exclude_self,
-               const RecheckCtx& cx, double* sample_bound_out, double* bound_out, double* samples) {
+int top_bounds(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t r_begin, int32_t R, int32_t p,
+               int32_t exclude_self, const RecheckCtx& cx, double* sample_bound_out, double* bound_out, double* samples) {
+  // R counts the relations of the search, r_begin .. r_begin + R - 1
   int rc;
   hipStream_t st = hd->stream;
   Top1State* ts = (Top1State*)hd->top1_state.p;
@@ -370,7 +371,7 @@ int top_bounds(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* 
   // 1. an upper bound of the answer: the smallest of 65,536 sampled eligible triples
   const int n_sample = kTopSamples;
   k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)ts, sizeof(Top1State) / 4, 0xffffffffu);
-  k_top1_sample<<<grid_for((int64_t)n_sample * 16, 256), 256, 0, st>>>(cx, N, R, n_sample, exclude_self ? 1 : 0, ts, dev_samples);
+  k_top1_sample<<<grid_for((int64_t)n_sample * 16, 256), 256, 0, st>>>(cx, N, r_begin, R, n_sample, exclude_self ? 1 : 0, ts, dev_samples);
   if (samples) KGC_HIP(hd, hipMemcpyAsync(samples, dev_samples, (size_t)kTopSamples * 8, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipMemcpyAsync(&host, ts, sizeof(Top1State), hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipStreamSynchronize(st));
@@ -403,7 +404,7 @@ int top_bounds(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* 
                                                                (uint16_t*)hd->top1_b.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
                                                                kStageRows);
     k_stage_operands<true><<<grid_for((int64_t)Rs * (m / kStageRows), 1), 256, stage_lds, st>>>(
-        E, Rvecs, hd->cfg.dtype, d, 0, Rs, heads, m, KS, (uint16_t*)hd->top1_a.p, nullptr, cnt->max_a, nullptr, nullptr, 0,
+        E, Rvecs, hd->cfg.dtype, d, r_begin, Rs, heads, m, KS, (uint16_t*)hd->top1_a.p, nullptr, cnt->max_a, nullptr, nullptr, 0,
         kStageRows);
     JoinStreamArgs sa{};
     sa.A = (const uint16_t*)hd->top1_a.p; sa.B = (const uint16_t*)hd->top1_b.p; sa.prm = nullptr; sa.Nslots = m;
@@ -448,7 +449,7 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
 
   double sample_bound = 0.0, bound = 0.0;
-  if ((rc = top_bounds(hd, E, N, d, Rvecs, R, p, exclude_self, cx, &sample_bound, &bound, nullptr)) != KGC_OK) return rc;
+  if ((rc = top_bounds(hd, E, N, d, Rvecs, 0, R, p, exclude_self, cx, &sample_bound, &bound, nullptr)) != KGC_OK) return rc;
 
   // 2. Joins with a shrinking threshold: every triple at or below the bound comes back; if there are more
   //    than the buffer holds, the smallest distance among those that did come back is the next bound.  The
@@ -489,16 +490,23 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
 
 int kgc_topk(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
              int32_t exclude_self, uint64_t k, kgc_triple* out_triples, uint64_t* found) {
+  return kgc_topk_range(hd, E, N, d, Rvecs, R, p, exclude_self, 0, R, k, out_triples, found);
+}
+
+int kgc_topk_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                   int32_t exclude_self, int32_t r_begin, int32_t r_end, uint64_t k, kgc_triple* out_triples, uint64_t* found) {
   if (!hd) return KGC_E_INVALID;
   if (!found) return fail(hd, KGC_E_INVALID, "found is NULL");
   *found = 0;
   int rc = check_common(hd, E, N, d, Rvecs, R);
   if (rc != KGC_OK) return rc;
+  if (r_begin < 0 || r_end < r_begin || r_end > R) return fail(hd, KGC_E_INVALID, "relation range outside [0, R]");
+  const int32_t Rn = r_end - r_begin;
   if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
   if (k > (uint64_t)kTopSamples) return fail(hd, KGC_E_INVALID, "k is limited to 65536");
   if (k > 0 && !out_triples) return fail(hd, KGC_E_INVALID, "out_triples is NULL with k > 0");
   if ((uintptr_t)out_triples % 16) return fail(hd, KGC_E_INVALID, "out_triples must be 16-byte aligned");
-  if (k == 0 || N == 0 || R == 0 || (exclude_self && N < 2)) return KGC_OK;
+  if (k == 0 || N == 0 || Rn == 0 || (exclude_self && N < 2)) return KGC_OK;
   hipStream_t st = hd->stream;
   if ((rc = ensure(hd, hd->top1_buf, kTopCap * sizeof(kgc_triple))) || (rc = ensure(hd, hd->top1_state, sizeof(Top1State))) ||
       (rc = ensure(hd, hd->topk_state, sizeof(TopkState))) || (rc = ensure(hd, hd->counters, sizeof(DevCounters))))
@@ -506,14 +514,14 @@ int kgc_topk(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   RecheckCtx cx{};
   cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr;
   cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
-  const double eligible = (double)N * (double)N * (double)R - (exclude_self ? (double)N * (double)R : 0.0);
+  const double eligible = (double)N * (double)N * (double)Rn - (exclude_self ? (double)N * (double)Rn : 0.0);
 
   // thresholds to try: from just above the smallest distance upwards.  The k-th smallest of the sampled
   // distances bounds the k-th smallest of all from above (the sample is drawn with replacement, so on small
   // problems it can hold a triple twice: the loop below then simply goes on growing the threshold).
   std::vector<double> samples(kTopSamples);
   double sample_bound = 0.0, thr = 0.0;
-  if ((rc = top_bounds(hd, E, N, d, Rvecs, R, p, exclude_self, cx, &sample_bound, &thr, samples.data())) != KGC_OK) return rc;
+  if ((rc = top_bounds(hd, E, N, d, Rvecs, r_begin, Rn, p, exclude_self, cx, &sample_bound, &thr, samples.data())) != KGC_OK) return rc;
   std::nth_element(samples.begin(), samples.begin() + (size_t)(k - 1), samples.end());
   const double kth_sample = samples[(size_t)(k - 1)];
   const bool take_all = eligible <= (double)kTopCap / 4;       // a small problem: every triple fits the buffer
@@ -524,7 +532,7 @@ int kgc_topk(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   for (int rounds = 0;; ++rounds) {
     float delta = take_all ? INFINITY : (float)thr;
     if (!take_all && (double)delta < thr) delta = std::nextafterf(delta, INFINITY);
-    rc = kgc_join(hd, E, N, d, Rvecs, R, p, delta, (kgc_triple*)hd->top1_buf.p, kTopCap, &count);
+    rc = kgc_join_range(hd, E, N, d, Rvecs, R, p, delta, r_begin, r_end, (kgc_triple*)hd->top1_buf.p, kTopCap, &count);
     if (rc < 0) return rc;
     if (rounds >= 200) return fail(hd, KGC_E_HIP, "top-k search did not settle");
     const uint64_t want = (double)k < eligible ? k : (uint64_t)eligible;

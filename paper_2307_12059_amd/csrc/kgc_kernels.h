@@ -1341,15 +1341,15 @@ __device__ __forceinline__ uint32_t top1_hash(uint32_t x) {
   return x;
 }
 
-__global__ __launch_bounds__(256) void k_top1_sample(RecheckCtx cx, int64_t N, int R, int n, int no_self, Top1State* st,
-                                                     double* all = nullptr) {
+__global__ __launch_bounds__(256) void k_top1_sample(RecheckCtx cx, int64_t N, int r_begin, int R, int n, int no_self,
+                                                     Top1State* st, double* all = nullptr) {
   const int64_t g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
   const int sub = threadIdx.x & 15;
   if (g >= n) return;                                   // whole 16-lane groups leave together
   const uint32_t a = top1_hash((uint32_t)g * 3u + 1u), b = top1_hash((uint32_t)g * 3u + 2u), c = top1_hash((uint32_t)g * 3u + 3u);
   const int32_t h = (int32_t)(((uint64_t)a * (uint64_t)N) >> 32);
   int32_t t = (int32_t)(((uint64_t)b * (uint64_t)N) >> 32);
-  const int32_t r = (int32_t)(((uint64_t)c * (uint64_t)R) >> 32);
+  const int32_t r = r_begin + (int32_t)(((uint64_t)c * (uint64_t)R) >> 32);      // R relations from r_begin on
   if (no_self && t == h) t = (t + 1 == N) ? 0 : t + 1;  // N >= 2 is checked on the host
   const double dist = group16_exact_dist(cx, h, r, t, sub);
   if (sub == 0) {

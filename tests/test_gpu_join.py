@@ -450,3 +450,27 @@ def test_topk_mass_ties():
     for excl in (False, True):
         got, ref = _check_topk(E, Rv, 2, 5000, excl, prune=PRUNE_ON)      # 144,000 zero-distance triples
         assert np.all(got["dist"] == 0.0)
+
+
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
+def test_topk_per_relation(prune):
+    """kgc_topk_range with a range of one relation: the k best (h, t) pairs of that relation."""
+    import paper_2307_12059_amd as kgc
+    wl = workloads.generate("c1_tiny_l2")
+    j = kgc.Join(prune=prune)
+    try:
+        Ed, Rd = _dev(wl.E, "f32"), _dev(wl.Rv, "f32")
+        for r in (0, 3, wl.Rv.shape[0] - 1):
+            for k, excl in ((1, False), (50, True)):
+                got = j.topk(Ed, Rd, 2, k, excl, r_range=(r, r + 1))
+                ref = oracle.topk(wl.E, wl.Rv[r:r + 1], 2, k, excl)
+                assert got["count"] == ref["count"] == k
+                assert np.all(got["r"] == r)
+                assert np.allclose(got["dist"], ref["dist"], rtol=1e-6, atol=1e-6)
+                dg = oracle.dist_triples(wl.E, wl.Rv, 2, got["h"], got["r"], got["t"])
+                assert np.allclose(np.sort(dg), ref["dist"], rtol=1e-6, atol=1e-6)
+        assert j.topk(Ed, Rd, 2, 5, r_range=(2, 2))["count"] == 0
+        with pytest.raises(RuntimeError):
+            j.topk(Ed, Rd, 2, 5, r_range=(0, wl.Rv.shape[0] + 1))
+    finally:
+        j.close()
