@@ -474,3 +474,27 @@ def test_topk_per_relation(prune):
             j.topk(Ed, Rd, 2, 5, r_range=(0, wl.Rv.shape[0] + 1))
     finally:
         j.close()
+
+
+@pytest.mark.parametrize("p", [1, 2])
+def test_block_pairs_through_the_general_form(p):
+    """The partition-based join of Section 4.7: entities cut into blocks, every (head block, tail block) pair joined
+    on its own through kgc_join_ab (A = head block + r, B = tail block), indices shifted by the block offsets.
+    The union is the join of the whole (the float32 rounding of A stays far inside the boundary band)."""
+    wl = workloads.generate("c1_tiny_l2")
+    E, Rv = wl.E[:900], wl.Rv
+    delta = wl.delta if p == 2 else 2.6
+    ref = oracle.join(E, Rv, p, delta, mode="abandon")
+    assert ref["count"] > 0
+    nb = 300
+    parts = {k: [] for k in ("h", "r", "t", "dist")}
+    for h0 in range(0, 900, nb):
+        A = (E[None, h0:h0 + nb, :] + Rv[:, None, :]).astype(np.float32)
+        for t0 in range(0, 900, nb):
+            got = _run_ab(A, E[t0:t0 + nb], p, delta, 1 << 16)
+            assert got["code"] == 0
+            parts["h"].append(got["h"] + h0); parts["t"].append(got["t"] + t0)
+            parts["r"].append(got["r"]); parts["dist"].append(got["dist"])
+    merged = {k: np.concatenate(v) for k, v in parts.items()}
+    rep = parity.compare(merged, ref, E, Rv, p, delta, 900)
+    assert rep["gpu_count"] + rep["only_oracle_in_band"] >= ref["count"] - rep["boundary_band"]
