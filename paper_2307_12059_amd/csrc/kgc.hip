@@ -343,6 +343,124 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
 }  // extern "C"
 
 namespace {
+// Row order for pruning: entities grouped around local pivots (see kgc_prune.h), groups laid out as runs of slots.
+// Fills hd->slot_ent, reads back the number of slots, the number of groups and the unit table of the two-level
+// bound test.  `rows` is the N x d array that is grouped (the entity array of kgc_join).
+int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, float delta, int KS, int k16, int64_t* Nslots_out,
+               uint64_t* n_groups_out, UnitTable* ut_out) {
+  int rc;
+  hipStream_t st = hd->stream;
+  const int dtype = hd->cfg.dtype;
+  int64_t Nslots = 0;
+  uint64_t n_groups = 0;
+  UnitTable ut{};
+  // worst case: every group of kSmallGroup rows is padded to a micro-tile
+  const int64_t max_padded_groups = std::min<int64_t>(kMaxGroups, N / kSmallGroup + 1);
+  const int64_t slots_cap = ((N + (kMicro - 1) * max_padded_groups) + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
+  if ((rc = ensure(hd, hd->slot_ent, slots_cap * 4)) || (rc = ensure(hd, hd->gstate, sizeof(GroupState))) ||
+      (rc = ensure(hd, hd->unc_a, N * 4)) || (rc = ensure(hd, hd->unc_b, N * 4)) ||
+      (rc = ensure(hd, hd->group_of, N * 4)) || (rc = ensure(hd, hd->piv_ent, kPivotsPerRound * 4)) ||
+      (rc = ensure(hd, hd->best, N * 8)) || (rc = ensure(hd, hd->gsize, kMaxGroups * 4)) ||
+      (rc = ensure(hd, hd->goff, kMaxGroups * 4)) || (rc = ensure(hd, hd->gfill, kMaxGroups * 4)) ||
+      (rc = ensure(hd, hd->unit_first, kMaxGroups * 4)) || (rc = ensure(hd, hd->unit_n, kMaxGroups * 4)))
+    return rc;
+  GroupState* gs = (GroupState*)hd->gstate.p;
+  int32_t* unc = (int32_t*)hd->unc_a.p;
+  int32_t* unc_next = (int32_t*)hd->unc_b.p;
+  const float radius_mult = hd->cfg.group_radius > 0.f ? hd->cfg.group_radius : 2.0f;
+  const float tau = delta > 0.f ? radius_mult * delta : 0.f;
+  const int gN = grid_for(std::max<int64_t>(N, kPivotsPerRound), 256);
+  k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
+  // With a head tile that fits in LDS (d <= 602) the rows-against-pivots distances of every round run on the
+  // matrix pipes, as a join of all entities (heads, staged once in identity order) with the round's pivots
+  // (tails) whose epilogue keeps, per entity, the lowest pivot position within tau.  Otherwise (large d)
+  // the float32 vector kernel does it.  Which member of a cluster ends up with which pivot does not touch
+  // the result: centres and radii are taken from the rows after the layout.
+  // An L1 join is grouped in L2 as well: for differences with independent, similarly sized components
+  // ||x||_1 is about sqrt(2 / pi) sqrt(d) ||x||_2, so the L1 radius tau corresponds to that L2 radius; a
+  // different ratio only makes the groups a little larger or smaller.
+  const bool mfma_assign = KS <= kDirectHalfMaxKS && delta > 0.f;
+  const float tau_l2 = (p == 2) ? tau : tau / (0.79788456f * std::sqrt((float)d));
+  const int abm = KS <= kDirectMaxKS ? 256 : 128;           // head tile height of the assignment kernel
+  void (*assign_kernel)(const JoinStreamArgs) =
+      abm == 256 ? k_join_l2_direct<256, 2, 4, kEpiAssignMin> : k_join_l2_direct<128, 1, 8, kEpiAssignMin>;
+  const int64_t Npad = (N + 255) / 256 * 256;
+  const size_t asg_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
+  if (mfma_assign) {
+    if ((rc = ensure(hd, hd->asg_a, (size_t)KS * Npad * kSliceK * 2)) ||
+        (rc = ensure(hd, hd->asg_b, (size_t)KS * kPivotsPerRound * kSliceK * 2)))
+      return rc;
+    // slot_ent is free until the layout fills it: identity order for the staging of the heads
+    k_identity_slots<<<grid_for(Npad, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Npad);
+    k_stage_operands<true><<<grid_for(Npad / kStageRows, 1), 256, asg_lds, st>>>(
+        E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Npad, KS, (uint16_t*)hd->asg_a.p, nullptr, nullptr,
+        nullptr, nullptr, 0, kStageRows);
+    KGC_HIP(hd, hipFuncSetAttribute((const void*)assign_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)((size_t)KS * abm * kSliceK * 2)));
+  }
+  for (int round = 0; round < kGroupRounds; ++round) {
+    // sampling density of the pivots among the still uncovered entities: 1/16, 1/16, 1/8, 1/8, 1/4, 1/2
+    static const int kShift[kGroupRounds] = {4, 4, 3, 3, 2, 1};
+    k_round_begin<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->piv_ent.p, (unsigned long long*)hd->best.p,
+                                     kShift[round], mfma_assign ? 1 : 0);
+    if (mfma_assign) {
+      k_stage_operands<false><<<kPivotsPerRound / kStageRows, 256, asg_lds, st>>>(
+          E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->piv_ent.p, kPivotsPerRound, KS, (uint16_t*)hd->asg_b.p, nullptr,
+          nullptr, nullptr, nullptr, 0, kStageRows, 0, &gs->n_piv);
+      JoinStreamArgs sa{};
+      sa.A = (const uint16_t*)hd->asg_a.p; sa.B = (const uint16_t*)hd->asg_b.p; sa.prm = nullptr; sa.Nslots = Npad;
+      sa.KS = KS; sa.k16 = k16; sa.nH = (int)(Npad / abm); sa.nT = kPivotsPerRound / 256; sa.r0 = 0; sa.RB = 1;
+      sa.tail_slots = kPivotsPerRound; sa.tail_rows_dev = &gs->n_piv;
+      // bf16 rows move a distance by at most 2^-8 (||e|| + ||pivot||); that much either way is of no concern here
+      sa.thr_value = tau_l2 * tau_l2;
+      sa.best = (unsigned long long*)hd->best.p; sa.group_of = (const int32_t*)hd->group_of.p; sa.n_heads = N;
+      // the pivot tiles are dealt to 1, 2 or 4 blocks per head tile, enough to fill the chip
+      const int64_t nHa = Npad / abm;
+      const unsigned zsplit = nHa >= 1024 ? 1u : nHa >= 512 ? 2u : 4u;
+      hipLaunchKernelGGL(assign_kernel, dim3((unsigned)nHa, 1, zsplit), dim3(512), (size_t)KS * abm * kSliceK * 2, st, sa);
+    } else {
+      TileDistArgs ta{};
+      ta.X = E; ta.dtypeX = dtype; ta.row_ids = unc; ta.n_rows_dev = &gs->n_unc; ta.n_rows = N;
+      ta.Y = E; ta.dtypeY = dtype; ta.col_ids = (const int32_t*)hd->piv_ent.p; ta.n_cols_dev = &gs->n_piv;
+      ta.n_cols = kPivotsPerRound;
+      ta.shift = nullptr; ta.dtype_shift = dtype; ta.r0 = 0; ta.d = d; ta.best = (unsigned long long*)hd->best.p;
+      ta.delta = tau;
+      const dim3 g((unsigned)((std::min<int64_t>(kPivotsPerRound, N) + 127) / 128), (unsigned)((N + 127) / 128), 1);
+      if (p == 2) k_tile_dist<2, kEpiAssign><<<g, 256, 0, st>>>(ta);
+      else k_tile_dist<1, kEpiAssign><<<g, 256, 0, st>>>(ta);
+    }
+    k_round_commit<<<gN, 256, 0, st>>>(gs, unc, (const unsigned long long*)hd->best.p, (int32_t*)hd->group_of.p,
+                                      unc_next, mfma_assign ? 1 : 0);
+    k_round_end<<<1, 64, 0, st>>>(gs);
+    std::swap(unc, unc_next);
+  }
+  k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gsize.p, kMaxGroups, 0u);
+  k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gfill.p, kMaxGroups, 0u);
+  k_fill_u32<<<grid_for(slots_cap, 256), 256, 0, st>>>((uint32_t*)hd->slot_ent.p, slots_cap, 0xffffffffu);
+  k_group_hist<<<gN, 256, 0, st>>>((const int32_t*)hd->group_of.p, N, (int32_t*)hd->gsize.p);
+  k_group_layout<<<1, 1024, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign,
+                                     (int32_t*)hd->unit_first.p, (int32_t*)hd->unit_n.p);
+  k_scatter_slots<<<gN, 256, 0, st>>>(gs, (const int32_t*)hd->group_of.p, (const int32_t*)hd->goff.p,
+                                     (int32_t*)hd->gfill.p, N, (int32_t*)hd->slot_ent.p);
+  KGC_HIP(hd, hipGetLastError());
+  // the layout decides the number of rows, which sizes every later launch: one small read-back
+  KGC_HIP(hd, hipMemcpyAsync(hd->host_gstate, gs, sizeof(GroupState), hipMemcpyDeviceToHost, st));
+  KGC_HIP(hd, hipStreamSynchronize(st));
+  Nslots = hd->host_gstate->n_slots;
+  n_groups = (uint64_t)hd->host_gstate->n_groups;
+  if (Nslots < N || Nslots > slots_cap || Nslots % kSlotAlign) return fail(hd, KGC_E_HIP, "group layout out of range");
+  ut.first = (const int32_t*)hd->unit_first.p; ut.n = (const int32_t*)hd->unit_n.p;
+  ut.n_big = hd->host_gstate->n_big;
+  ut.tail_first = hd->host_gstate->tail_base / kMicro;
+  ut.n_units = ut.n_big + (int)(Nslots / kMicro) - ut.tail_first;
+  if (ut.n_big < 0 || ut.n_big > kMaxGroups || ut.tail_first < 0 || ut.tail_first > Nslots / kMicro)
+    return fail(hd, KGC_E_HIP, "unit table out of range");
+  *Nslots_out = Nslots;
+  *n_groups_out = n_groups;
+  *ut_out = ut;
+  return KGC_OK;
+}
+
 // kgc_top1 / kgc_topk switch the handle to "no self pairs" around their inner joins; this puts it back on every way out
 struct NoSelfScope {
   kgc_handle* h;
@@ -669,107 +787,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   UnitTable ut{};                 // two-level bound test: filled after the layout
   bool use_units = false;
   if (prune) {
-    // worst case: every group of kSmallGroup rows is padded to a micro-tile
-    const int64_t max_padded_groups = std::min<int64_t>(kMaxGroups, N / kSmallGroup + 1);
-    const int64_t slots_cap = ((N + (kMicro - 1) * max_padded_groups) + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
-    if ((rc = ensure(hd, hd->slot_ent, slots_cap * 4)) || (rc = ensure(hd, hd->gstate, sizeof(GroupState))) ||
-        (rc = ensure(hd, hd->unc_a, N * 4)) || (rc = ensure(hd, hd->unc_b, N * 4)) ||
-        (rc = ensure(hd, hd->group_of, N * 4)) || (rc = ensure(hd, hd->piv_ent, kPivotsPerRound * 4)) ||
-        (rc = ensure(hd, hd->best, N * 8)) || (rc = ensure(hd, hd->gsize, kMaxGroups * 4)) ||
-        (rc = ensure(hd, hd->goff, kMaxGroups * 4)) || (rc = ensure(hd, hd->gfill, kMaxGroups * 4)) ||
-        (rc = ensure(hd, hd->unit_first, kMaxGroups * 4)) || (rc = ensure(hd, hd->unit_n, kMaxGroups * 4)))
-      return rc;
-    GroupState* gs = (GroupState*)hd->gstate.p;
-    int32_t* unc = (int32_t*)hd->unc_a.p;
-    int32_t* unc_next = (int32_t*)hd->unc_b.p;
-    const float radius_mult = hd->cfg.group_radius > 0.f ? hd->cfg.group_radius : 2.0f;
-    const float tau = delta > 0.f ? radius_mult * delta : 0.f;
-    const int gN = grid_for(std::max<int64_t>(N, kPivotsPerRound), 256);
-    k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
-    // With a head tile that fits in LDS (d <= 602) the rows-against-pivots distances of every round run on the
-    // matrix pipes, as a join of all entities (heads, staged once in identity order) with the round's pivots
-    // (tails) whose epilogue keeps, per entity, the lowest pivot position within tau.  Otherwise (large d)
-    // the float32 vector kernel does it.  Which member of a cluster ends up with which pivot does not touch
-    // the result: centres and radii are taken from the rows after the layout.
-    // An L1 join is grouped in L2 as well: for differences with independent, similarly sized components
-    // ||x||_1 is about sqrt(2 / pi) sqrt(d) ||x||_2, so the L1 radius tau corresponds to that L2 radius; a
-    // different ratio only makes the groups a little larger or smaller.
-    const bool mfma_assign = KS <= kDirectHalfMaxKS && delta > 0.f;
-    const float tau_l2 = (p == 2) ? tau : tau / (0.79788456f * std::sqrt((float)d));
-    const int abm = KS <= kDirectMaxKS ? 256 : 128;           // head tile height of the assignment kernel
-    void (*assign_kernel)(const JoinStreamArgs) =
-        abm == 256 ? k_join_l2_direct<256, 2, 4, kEpiAssignMin> : k_join_l2_direct<128, 1, 8, kEpiAssignMin>;
-    const int64_t Npad = (N + 255) / 256 * 256;
-    const size_t asg_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
-    if (mfma_assign) {
-      if ((rc = ensure(hd, hd->asg_a, (size_t)KS * Npad * kSliceK * 2)) ||
-          (rc = ensure(hd, hd->asg_b, (size_t)KS * kPivotsPerRound * kSliceK * 2)))
-        return rc;
-      // slot_ent is free until the layout fills it: identity order for the staging of the heads
-      k_identity_slots<<<grid_for(Npad, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Npad);
-      k_stage_operands<true><<<grid_for(Npad / kStageRows, 1), 256, asg_lds, st>>>(
-          E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Npad, KS, (uint16_t*)hd->asg_a.p, nullptr, nullptr,
-          nullptr, nullptr, 0, kStageRows);
-      KGC_HIP(hd, hipFuncSetAttribute((const void*)assign_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)((size_t)KS * abm * kSliceK * 2)));
-    }
-    for (int round = 0; round < kGroupRounds; ++round) {
-      // sampling density of the pivots among the still uncovered entities: 1/16, 1/16, 1/8, 1/8, 1/4, 1/2
-      static const int kShift[kGroupRounds] = {4, 4, 3, 3, 2, 1};
-      k_round_begin<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->piv_ent.p, (unsigned long long*)hd->best.p,
-                                       kShift[round], mfma_assign ? 1 : 0);
-      if (mfma_assign) {
-        k_stage_operands<false><<<kPivotsPerRound / kStageRows, 256, asg_lds, st>>>(
-            E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->piv_ent.p, kPivotsPerRound, KS, (uint16_t*)hd->asg_b.p, nullptr,
-            nullptr, nullptr, nullptr, 0, kStageRows, 0, &gs->n_piv);
-        JoinStreamArgs sa{};
-        sa.A = (const uint16_t*)hd->asg_a.p; sa.B = (const uint16_t*)hd->asg_b.p; sa.prm = nullptr; sa.Nslots = Npad;
-        sa.KS = KS; sa.k16 = k16; sa.nH = (int)(Npad / abm); sa.nT = kPivotsPerRound / 256; sa.r0 = 0; sa.RB = 1;
-        sa.tail_slots = kPivotsPerRound; sa.tail_rows_dev = &gs->n_piv;
-        // bf16 rows move a distance by at most 2^-8 (||e|| + ||pivot||); that much either way is of no concern here
-        sa.thr_value = tau_l2 * tau_l2;
-        sa.best = (unsigned long long*)hd->best.p; sa.group_of = (const int32_t*)hd->group_of.p; sa.n_heads = N;
-        // the pivot tiles are dealt to 1, 2 or 4 blocks per head tile, enough to fill the chip
-        const int64_t nHa = Npad / abm;
-        const unsigned zsplit = nHa >= 1024 ? 1u : nHa >= 512 ? 2u : 4u;
-        hipLaunchKernelGGL(assign_kernel, dim3((unsigned)nHa, 1, zsplit), dim3(512), (size_t)KS * abm * kSliceK * 2, st, sa);
-      } else {
-        TileDistArgs ta{};
-        ta.X = E; ta.dtypeX = dtype; ta.row_ids = unc; ta.n_rows_dev = &gs->n_unc; ta.n_rows = N;
-        ta.Y = E; ta.dtypeY = dtype; ta.col_ids = (const int32_t*)hd->piv_ent.p; ta.n_cols_dev = &gs->n_piv;
-        ta.n_cols = kPivotsPerRound;
-        ta.shift = nullptr; ta.dtype_shift = dtype; ta.r0 = 0; ta.d = d; ta.best = (unsigned long long*)hd->best.p;
-        ta.delta = tau;
-        const dim3 g((unsigned)((std::min<int64_t>(kPivotsPerRound, N) + 127) / 128), (unsigned)((N + 127) / 128), 1);
-        if (p == 2) k_tile_dist<2, kEpiAssign><<<g, 256, 0, st>>>(ta);
-        else k_tile_dist<1, kEpiAssign><<<g, 256, 0, st>>>(ta);
-      }
-      k_round_commit<<<gN, 256, 0, st>>>(gs, unc, (const unsigned long long*)hd->best.p, (int32_t*)hd->group_of.p,
-                                        unc_next, mfma_assign ? 1 : 0);
-      k_round_end<<<1, 64, 0, st>>>(gs);
-      std::swap(unc, unc_next);
-    }
-    k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gsize.p, kMaxGroups, 0u);
-    k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gfill.p, kMaxGroups, 0u);
-    k_fill_u32<<<grid_for(slots_cap, 256), 256, 0, st>>>((uint32_t*)hd->slot_ent.p, slots_cap, 0xffffffffu);
-    k_group_hist<<<gN, 256, 0, st>>>((const int32_t*)hd->group_of.p, N, (int32_t*)hd->gsize.p);
-    k_group_layout<<<1, 1024, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign,
-                                       (int32_t*)hd->unit_first.p, (int32_t*)hd->unit_n.p);
-    k_scatter_slots<<<gN, 256, 0, st>>>(gs, (const int32_t*)hd->group_of.p, (const int32_t*)hd->goff.p,
-                                       (int32_t*)hd->gfill.p, N, (int32_t*)hd->slot_ent.p);
-    KGC_HIP(hd, hipGetLastError());
-    // the layout decides the number of rows, which sizes every later launch: one small read-back
-    KGC_HIP(hd, hipMemcpyAsync(hd->host_gstate, gs, sizeof(GroupState), hipMemcpyDeviceToHost, st));
-    KGC_HIP(hd, hipStreamSynchronize(st));
-    Nslots = hd->host_gstate->n_slots;
-    n_groups = (uint64_t)hd->host_gstate->n_groups;
-    if (Nslots < N || Nslots > slots_cap || Nslots % kSlotAlign) return fail(hd, KGC_E_HIP, "group layout out of range");
-    ut.first = (const int32_t*)hd->unit_first.p; ut.n = (const int32_t*)hd->unit_n.p;
-    ut.n_big = hd->host_gstate->n_big;
-    ut.tail_first = hd->host_gstate->tail_base / kMicro;
-    ut.n_units = ut.n_big + (int)(Nslots / kMicro) - ut.tail_first;
-    if (ut.n_big < 0 || ut.n_big > kMaxGroups || ut.tail_first < 0 || ut.tail_first > Nslots / kMicro)
-      return fail(hd, KGC_E_HIP, "unit table out of range");
+    if ((rc = group_rows(hd, E, N, d, p, delta, KS, k16, &Nslots, &n_groups, &ut)) != KGC_OK) return rc;
   } else {
     if ((rc = ensure(hd, hd->slot_ent, Nslots * 4))) return rc;
     k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
