@@ -143,8 +143,9 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
  * finds every (h, r, t) with ||A[r][h] - B[r or 0][t]||_p <= delta.  TransE is A[r][h] = E[h] + Rv[r], B = E; the
  * structured-embedding model of the same section is A[r] = E W1_r^T, B[r] = E W2_r^T with p = 1.  Output, count,
  * overflow and error conventions are those of kgc_join; the exact stage scores (double)a - (double)b.  The
- * relations run through the dense join kernels in batches, as in kgc_join with pruning off; the handle's pruning
- * setting is not used, since the grouping of kgc_join relies on connector_1 being a translation. */
+ * relations run through the join kernels of kgc_join in batches.  With pruning on (the handle's setting) the
+ * rows of B (of its first relation) are grouped, every A[r] and B[r] is summarised in that order, and tile pairs
+ * whose pivot bound (Lemma 1, Section 4.4) exceeds delta are skipped; the result does not depend on it. */
 int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t d, int32_t R, int32_t b_per_relation,
                 int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
 

@@ -45,7 +45,7 @@ struct kgc_handle {
   // every DevBuf member must also be listed in kgc_destroy
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
   DevBuf unit_first, unit_n, cent_u, rad_u, cnorm_u, gram_u, relu_u, pair_list, pair_count;   // two-level bound test
-  DevBuf zero_row;                             // kgc_join_ab: the relation vector every relation reads (zeros)
+  DevBuf zero_row, cent_a, rad_a;              // kgc_join_ab: the zero relation row; micro-tile summaries of A[r]
   DevBuf top1_a, top1_b, top1_pick, top_samples, topk_state;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
   GroupState* host_gstate = nullptr;           // pinned
@@ -145,6 +145,9 @@ int check_common(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void
   return KGC_OK;
 }
 
+int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, float delta, int KS, int k16, int64_t* Nslots_out,
+               uint64_t* n_groups_out, UnitTable* ut_out);        // further down
+
 // Blocks for `items` work items, `per_block` each.  A launch may hold fewer than 2^32 threads per grid dimension, so
 // the count stops at 2^24 - 1 blocks (of at most 256 threads): enough for every per-row or per-slot kernel here
 // (N < 2^31); kernels that can be asked for more (k_fill_u32, the staging kernels) stride over their items.
@@ -198,7 +201,7 @@ void kgc_destroy(kgc_handle* h) {
                     &h->cent, &h->rad, &h->bitmap, &h->row_start, &h->row_count, &h->cols, &h->active_rows, &h->cnorm,
                     &h->gram, &h->relu, &h->reln, &h->asg_a, &h->asg_b, &h->limr, &h->top1_buf, &h->top1_state,
                     &h->unit_first, &h->unit_n, &h->cent_u, &h->rad_u, &h->cnorm_u, &h->gram_u, &h->relu_u, &h->pair_list,
-                    &h->pair_count, &h->zero_row, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
+                    &h->pair_count, &h->zero_row, &h->cent_a, &h->rad_a, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
     release(*b);
   if (h->host_gstate) (void)hipHostFree(h->host_gstate);
   if (h->host_counters) (void)hipHostFree(h->host_counters);
@@ -230,22 +233,20 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   hipStream_t st = hd->stream;
   const int dtype = hd->cfg.dtype;
   const size_t esz = dtype == KGC_BF16 ? 2 : 4;
+  const bool prune = hd->cfg.prune != KGC_PRUNE_OFF && delta >= 0.f;
   const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
   const int k16 = (d + kNormCols + 15) / 16;
-  // the dense kernels of kgc_join, one relation per launch (the tail side may change with the relation)
-  const int tile_id = KS <= kDirectMaxKS ? kDirectL2Tile : KS <= kDirectHalfMaxKS ? kDirectHalfL2Tile : kDefaultL2Tile;
+  // the kernels of kgc_join: dense, or (pruned) walking the tile lists
+  int tile_id;
+  if (prune) tile_id = ((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile;
+  else tile_id = KS <= kDirectMaxKS ? kDirectL2Tile : KS <= kDirectHalfMaxKS ? kDirectHalfL2Tile : kDefaultL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
-  const int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
-  const int nH = (int)(Nslots / BM), nT = (int)(Nslots / BN);
-  if (nH > 65535 && p == 1) return fail(hd, KGC_E_INVALID, "N too large for one launch grid");
-  const size_t op_bytes = (size_t)KS * Nslots * kSliceK * 2;
   if ((rc = ensure(hd, hd->counters, sizeof(DevCounters))) || (rc = ensure(hd, hd->params, sizeof(JoinParams))) ||
-      (rc = ensure(hd, hd->slot_ent, Nslots * 4)) || (rc = ensure(hd, hd->zero_row, (size_t)d * 4)))
+      (rc = ensure(hd, hd->zero_row, (size_t)d * 4)))
     return rc;
   DevCounters* cnt = (DevCounters*)hd->counters.p;
   JoinParams* prm = (JoinParams*)hd->params.p;
-  const int32_t* slot_ent = (const int32_t*)hd->slot_ent.p;
   while (hd->join_ev.size() < 2) {
     hipEvent_t e;
     KGC_HIP(hd, hipEventCreate(&e));
@@ -254,7 +255,27 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   KGC_HIP(hd, hipEventRecord(hd->ev[0], st));
   k_fill_u32<<<grid_for(sizeof(DevCounters) / 4, 256), 256, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
   k_fill_u32<<<grid_for(d, 256), 256, 0, st>>>((uint32_t*)hd->zero_row.p, d, 0u);
-  k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
+
+  // Row order.  Pruned: the rows of B (of its first relation) are grouped as the entities of kgc_join are, and every
+  // relation's A[r] and B[r] are summarised in that order: connectors are maps of one entity set, so rows that are
+  // close in B[0] tend to be close in the others; where they are not, the radii grow and less is pruned, never more.
+  int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
+  uint64_t n_groups = 0;
+  if (prune) {
+    UnitTable unused{};
+    if ((rc = group_rows(hd, B, N, d, p, delta, KS, k16, &Nslots, &n_groups, &unused)) != KGC_OK) return rc;
+  } else {
+    if ((rc = ensure(hd, hd->slot_ent, Nslots * 4))) return rc;
+    k_identity_slots<<<grid_for(Nslots, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Nslots);
+  }
+  const int32_t* slot_ent = (const int32_t*)hd->slot_ent.p;
+  const int nH = (int)(Nslots / BM), nT = (int)(Nslots / BN);
+  const int64_t n_micro = Nslots / kMicro;
+  const int words_per_row = (nT + 31) / 32;
+  const int64_t tiles_per_rel = (int64_t)nH * nT;
+  if (nH > 65535 && p == 1 && !prune) return fail(hd, KGC_E_INVALID, "N too large for one launch grid");
+  if (prune && tiles_per_rel > kMaxTileList) return fail(hd, KGC_E_INVALID, "N too large for the pruned tile list");
+  const size_t op_bytes = (size_t)KS * Nslots * kSliceK * 2;
   KGC_HIP(hd, hipEventRecord(hd->join_ev[0], st));
 
   RecheckCtx cx{};
@@ -263,47 +284,116 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p; cx.delta = (double)delta;
   cx.out = out_triples; cx.cap = cap; cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates; cx.no_self = 0;
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
-  // relation batches: the staged operands of a batch must fit the workspace
+  // relation batches: the staged operands, the summaries and the tile lists of a batch must fit the workspace
   const int64_t ws = hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
   int64_t RBmax = std::min<int64_t>(R, 65535);
   if (p == 2) RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, ws / (int64_t)(op_bytes * (b_per_relation ? 2 : 1))));
+  if (prune) {
+    RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, kMaxTileList / tiles_per_rel));
+    RBmax = std::max<int64_t>(1, std::min<int64_t>(RBmax, ws / (int64_t)((size_t)n_micro * d * 4 * 2)));
+  }
   if (p == 2 && ((rc = ensure(hd, hd->opA, op_bytes * (size_t)RBmax)) ||
                  (rc = ensure(hd, hd->opB, op_bytes * (size_t)(b_per_relation ? RBmax : 1)))))
     return rc;
-  size_t dyn_lds = 0;
-  int64_t nsplit = 1;
+  const int64_t nb_sum = b_per_relation ? RBmax : 1;        // tail summaries held at a time
+  if (prune && ((rc = ensure(hd, hd->cent, (size_t)nb_sum * n_micro * d * 4)) || (rc = ensure(hd, hd->rad, (size_t)nb_sum * n_micro * 4)) ||
+                (rc = ensure(hd, hd->cnorm, (size_t)RBmax * n_micro * 4)) ||
+                (rc = ensure(hd, hd->cent_a, (size_t)RBmax * n_micro * d * 4)) || (rc = ensure(hd, hd->rad_a, (size_t)RBmax * n_micro * 4)) ||
+                (rc = ensure(hd, hd->bitmap, (size_t)RBmax * nH * words_per_row * 4)) ||
+                (rc = ensure(hd, hd->row_start, (size_t)RBmax * nH * 4)) || (rc = ensure(hd, hd->row_count, (size_t)RBmax * nH * 4)) ||
+                (rc = ensure(hd, hd->cols, (size_t)RBmax * tiles_per_rel * 4)) ||
+                (rc = ensure(hd, hd->active_rows, (size_t)RBmax * nH * 4))))
+    return rc;
+  const unsigned row_grid_max = 4096;
   int nbatch = 0;
   for (int64_t r0 = 0; r0 < R; r0 += RBmax, ++nbatch) {
     const int RB = (int)std::min<int64_t>(RBmax, R - r0);
+    const uint32_t* active_rows = nullptr;
+    const unsigned int* n_active = nullptr;
+    if (prune) {
+      // summaries of the batch's A[r] (and B[r]) rows in slot order, bound on micro-tile pairs, tile lists
+      if (b_per_relation || r0 == 0) {
+        if (p == 2)
+          k_micro_summary<2><<<dim3((unsigned)n_micro, (unsigned)(b_per_relation ? RB : 1), 1), 64, 0, st>>>(
+              B, dtype, d, slot_ent, n_micro, (float*)hd->cent.p, (float*)hd->rad.p, (float*)hd->cnorm.p,
+              b_per_relation ? (int)r0 : 0, b_per_relation ? (int64_t)N * d : 0);
+        else
+          k_micro_summary<1><<<dim3((unsigned)n_micro, (unsigned)(b_per_relation ? RB : 1), 1), 64, 0, st>>>(
+              B, dtype, d, slot_ent, n_micro, (float*)hd->cent.p, (float*)hd->rad.p, (float*)hd->cnorm.p,
+              b_per_relation ? (int)r0 : 0, b_per_relation ? (int64_t)N * d : 0);
+      }
+      if (p == 2)
+        k_micro_summary<2><<<dim3((unsigned)n_micro, (unsigned)RB, 1), 64, 0, st>>>(
+            A, dtype, d, slot_ent, n_micro, (float*)hd->cent_a.p, (float*)hd->rad_a.p, (float*)hd->cnorm.p, (int)r0, (int64_t)N * d);
+      else
+        k_micro_summary<1><<<dim3((unsigned)n_micro, (unsigned)RB, 1), 64, 0, st>>>(
+            A, dtype, d, slot_ent, n_micro, (float*)hd->cent_a.p, (float*)hd->rad_a.p, (float*)hd->cnorm.p, (int)r0, (int64_t)N * d);
+      const int64_t bm_words = (int64_t)RB * nH * words_per_row;
+      k_fill_u32<<<grid_for(bm_words, 256), 256, 0, st>>>((uint32_t*)hd->bitmap.p, bm_words, 0u);
+      TileDistArgs ta{};
+      ta.X = hd->cent_a.p; ta.dtypeX = KGC_F32; ta.n_rows = n_micro; ta.Y = hd->cent.p; ta.dtypeY = KGC_F32; ta.n_cols = n_micro;
+      ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.r0 = 0; ta.d = d;
+      ta.rad = (const float*)hd->rad.p; ta.rad_rows = (const float*)hd->rad_a.p; ta.x_rel_rows = n_micro;
+      ta.y_rel_rows = b_per_relation ? n_micro : 0;
+      ta.delta = delta; ta.bitmap = (uint32_t*)hd->bitmap.p; ta.nH = nH; ta.words_per_row = words_per_row;
+      ta.micro_per_bm = BM / kMicro; ta.micro_per_bn = BN / kMicro;
+      const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), (unsigned)RB);
+      if (p == 2) k_tile_dist<2, kEpiBound><<<g, 256, 0, st>>>(ta);
+      else k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
+      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 4, 0u);      // cursor and n_active
+      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 255) / 256), 256, 0, st>>>(
+          (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
+          (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p, &cnt->n_active);
+      k_add_u64<<<1, 64, 0, st>>>(&cnt->tiles, &cnt->tile_cursor);
+      active_rows = (const uint32_t*)hd->active_rows.p;
+      n_active = &cnt->n_active;
+    }
+    const unsigned row_grid = (unsigned)std::min<int64_t>((int64_t)RB * nH, row_grid_max);
     if (p == 2) {
-      const int stage_grid = grid_for((int64_t)RB * (Nslots / kStageRows), 1);
+      const int stage_all = grid_for((int64_t)RB * (Nslots / kStageRows), 1);
       if (b_per_relation)
-        k_stage_operands<false><<<stage_grid, 256, stage_lds, st>>>(B, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
-                                                                  (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
-                                                                  kStageRows, (int64_t)N * d);
+        k_stage_operands<false><<<stage_all, 256, stage_lds, st>>>(B, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
+                                                                 (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
+                                                                 kStageRows, (int64_t)N * d);
       else if (r0 == 0)
         k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
             B, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
             kStageRows, 0);
-      k_stage_operands<true><<<stage_grid, 256, stage_lds, st>>>(A, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
-                                                               (uint16_t*)hd->opA.p, nullptr, cnt->max_a, nullptr, nullptr, 0,
-                                                               kStageRows, (int64_t)N * d);
+      // head rows: all of them (dense), or those of the head tiles that still have tail tiles (pruned)
+      const int stage_a = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 16384) : stage_all;
+      k_stage_operands<true><<<stage_a, 256, stage_lds, st>>>(A, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
+                                                             (uint16_t*)hd->opA.p, nullptr, cnt->max_a, active_rows, n_active, nH, BM,
+                                                             (int64_t)N * d);
       // the maxima only grow from batch to batch: the filter threshold stays on the safe side
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
-      if (tc.head_resident) {
-        dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
-        KGC_HIP(hd, hipFuncSetAttribute((const void*)tc.stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
-      }
-      const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
-      const int64_t range_bytes = tc.head_resident ? kL2RangeBytesResident : kL2RangeBytes;
-      nsplit = (nT * tile_bytes + range_bytes - 1) / range_bytes;
-      nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
-      nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
       JoinStreamArgs sa{};
       sa.A = (const uint16_t*)hd->opA.p; sa.B = (const uint16_t*)hd->opB.p; sa.prm = prm; sa.Nslots = Nslots;
       sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = (int)r0; sa.RB = RB; sa.b_per_rel = b_per_relation ? 1 : 0;
       sa.cx = cx;
-      hipLaunchKernelGGL(tc.stream_kernel, dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit), dim3(tc.threads), dyn_lds, st, sa);
+      void (*kern)(const JoinStreamArgs) = prune ? tc.listed_kernel : tc.stream_kernel;
+      size_t dyn_lds = 0;
+      if (tc.head_resident) {
+        dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
+        if (prune && tc.tail_buffers > 0) {
+          const size_t spare = kMaxLds / tc.blocks_per_cu - (dyn_lds + tc.static_lds);
+          sa.cols_lds = (int)std::min<size_t>(spare / 4, (size_t)nT);
+          if (sa.cols_lds < nT) sa.cols_lds = 0;
+          dyn_lds += (size_t)sa.cols_lds * 4;
+        }
+        KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
+      }
+      if (prune) {
+        sa.row_start = (const uint32_t*)hd->row_start.p; sa.row_count = (const uint32_t*)hd->row_count.p;
+        sa.cols = (const uint32_t*)hd->cols.p; sa.active_rows = active_rows; sa.n_active = n_active;
+        hipLaunchKernelGGL(kern, dim3(row_grid, 1, 1), dim3(tc.threads), dyn_lds, st, sa);
+      } else {
+        const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
+        const int64_t range_bytes = tc.head_resident ? kL2RangeBytesResident : kL2RangeBytes;
+        int64_t nsplit = (nT * tile_bytes + range_bytes - 1) / range_bytes;
+        nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
+        nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
+        hipLaunchKernelGGL(kern, dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit), dim3(tc.threads), dyn_lds, st, sa);
+      }
     } else {
       k_row_l1_max<<<grid_for((int64_t)RB * N * 32, 256), 256, 0, st>>>((const char*)A + (size_t)r0 * N * d * esz, (int64_t)RB * N, d,
                                                                     dtype, cnt->max_a);
@@ -314,7 +404,13 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, 0);
       JoinL1Args la{};
       la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = (int)r0; la.RB = RB; la.cx = cx;
-      hipLaunchKernelGGL(k_join_l1, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(256), 0, st, la);
+      if (prune) {
+        la.row_start = (const uint32_t*)hd->row_start.p; la.row_count = (const uint32_t*)hd->row_count.p;
+        la.cols = (const uint32_t*)hd->cols.p; la.active_rows = active_rows; la.n_active = n_active;
+        hipLaunchKernelGGL(k_join_l1, dim3(row_grid, 1, 1), dim3(256), 0, st, la);
+      } else {
+        hipLaunchKernelGGL(k_join_l1, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(256), 0, st, la);
+      }
     }
     hd->stats.join_launches++;
   }
@@ -327,14 +423,17 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   kgc_stats& s = hd->stats;
   s.emitted = hd->host_counters->hits;
   s.candidates = hd->host_counters->candidates;
-  s.tiles_total = s.tiles_evaluated = (uint64_t)nH * (uint64_t)nT * (uint64_t)R;
-  s.pairs_evaluated = s.triples_total;
+  s.tiles_total = (uint64_t)tiles_per_rel * (uint64_t)R;
+  s.tiles_evaluated = prune ? hd->host_counters->tiles : s.tiles_total;
+  s.tiles_pruned = s.tiles_total - s.tiles_evaluated;
+  s.pairs_evaluated = prune ? s.tiles_evaluated * (uint64_t)BM * (uint64_t)BN : s.triples_total;
+  s.groups = n_groups;
   s.tile_m = BM; s.tile_n = BN;
   s.k_padded = (p == 2) ? k16 * 16 : d;
   s.relation_batches = nbatch;
   s.join_variant = (p == 2) ? tile_id + 1 : 0;
   (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);
-  (void)hipEventElapsedTime(&s.ms_join, hd->join_ev[0], hd->join_ev[1]);   // staging of each batch included
+  (void)hipEventElapsedTime(&s.ms_join, hd->join_ev[0], hd->join_ev[1]);   // staging, summaries and bound of each batch included
   s.ms_precompute = s.ms_total - s.ms_join;
   *count = s.emitted;
   return s.emitted > cap ? KGC_OVERFLOW : KGC_OK;

@@ -157,10 +157,14 @@ template <int P>
 __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E, int dtype, int d,
                                                       const int32_t* __restrict__ slot_ent, int64_t n_micro,
                                                       float* __restrict__ cent, float* __restrict__ rad,
-                                                      float* __restrict__ cnorm) {
+                                                      float* __restrict__ cnorm, int r0 = 0, int64_t rel_stride = 0) {
+  // blockIdx.y: relation of a batch, for per-relation rows E[(r0 + y) * rel_stride + ...] (summaries then lie
+  // relation after relation); one relation and rel_stride 0 for the TransE join
   const int64_t m = blockIdx.x;
   if (m >= n_micro) return;
   const int lane = threadIdx.x;
+  E = (const char*)E + (int64_t)(r0 + (int)blockIdx.y) * rel_stride * (dtype == KGC_BF16 ? 2 : 4);
+  cent += (int64_t)blockIdx.y * n_micro * d; rad += (int64_t)blockIdx.y * n_micro; cnorm += (int64_t)blockIdx.y * n_micro;
   __shared__ int32_t ents[kMicro];
   if (lane < kMicro) ents[lane] = slot_ent[m * kMicro + lane];
   __syncthreads();
@@ -240,6 +244,9 @@ struct TileDistArgs {
   float* matrix;                                   // MATRIX
   const float* rad; float delta; uint32_t* bitmap; // BOUND
   int nH, words_per_row, micro_per_bm, micro_per_bn;
+  // BOUND with per-relation summaries (the general form): relation blockIdx.z reads rows z * x_rel_rows + i of X and
+  // z * y_rel_rows + j of Y (0: one set for all relations); rad_rows: radii of the rows when they differ from the columns'
+  int64_t x_rel_rows, y_rel_rows; const float* rad_rows;
   // BOUND on units (L1): rows / columns are unit centres, rad their radii; survivors are refined on the
   // micro-tile summaries below (small pairs on the spot, the others through the list)
   UnitTable ut; BoundPairs bp;
@@ -298,7 +305,8 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
     for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
   const int srow = tid >> 1, sk0 = (tid & 1) * 8;
   const int re = rid[srow], ce = cid[srow];
-  const int64_t xo = (int64_t)(re < 0 ? 0 : re) * d, yo = (int64_t)(ce < 0 ? 0 : ce) * d;
+  const int64_t xo = ((int64_t)blockIdx.z * a.x_rel_rows + (re < 0 ? 0 : re)) * d,
+                yo = ((int64_t)blockIdx.z * a.y_rel_rows + (ce < 0 ? 0 : ce)) * d;
   const int64_t so = (int64_t)(a.r0 + (int)blockIdx.z) * d;
   for (int k0 = 0; k0 < d; k0 += BK) {
     float va[8], vb[8];
@@ -413,17 +421,19 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
     }
   } else {
     const int rl = (int)blockIdx.z;
+    const float* rad_r = (a.rad_rows ? a.rad_rows : a.rad) + (int64_t)rl * a.x_rel_rows;
+    const float* rad_c = a.rad + (int64_t)rl * a.y_rel_rows;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int lr = (i >> 2) * 64 + ty * 4 + (i & 3);
       if (rid[lr] < 0) continue;
-      const float rr = a.rad[row0 + lr];
+      const float rr = rad_r[row0 + lr];
       if (rr < 0.f) continue;                                  // empty micro-tile
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int lc = (j >> 2) * 64 + tx * 4 + (j & 3);
         if (cid[lc] < 0) continue;
-        const float rc = a.rad[col0 + lc];
+        const float rc = rad_c[col0 + lc];
         if (rc < 0.f) continue;
         const float dist = (P == 2) ? sqrtf(acc[i][j]) : acc[i][j];
         const float lb = dist * (1.f - kBoundSlack) - rr - rc;  // radii already carry their slack

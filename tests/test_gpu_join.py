@@ -325,13 +325,13 @@ def test_join_range_partition(mode):
 
 
 # ---- general form of Section 4.3: connector outputs supplied by the caller (kgc_join_ab) ----
-def _run_ab(A, B, p, delta, cap, dtype="f32"):
+def _run_ab(A, B, p, delta, cap, dtype="f32", prune=PRUNE_OFF):
     import paper_2307_12059_amd as kgc
     torch = _torch()
     def dev(x):
         t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
         return t.to(torch.bfloat16).contiguous() if dtype == "bf16" else t
-    j = kgc.Join(dtype=dtype)
+    j = kgc.Join(dtype=dtype, prune=prune)
     try:
         return j.join_ab(dev(A), dev(B), p, delta, cap)
     finally:
@@ -360,10 +360,11 @@ def _compare_ab(got, ref, A, B, p, delta, N):
     return int(only_g.sum()), int(only_r.sum())
 
 
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("p", [1, 2])
-@pytest.mark.parametrize("N,R,d", [(300, 3, 37), (520, 2, 200), (260, 2, 300), (200, 2, 700)])
-def test_join_ab_structured_embedding(p, dtype, N, R, d):
+@pytest.mark.parametrize("N,R,d", [(300, 3, 37), (520, 2, 200), (260, 2, 300), (200, 2, 700), (1500, 5, 64)])
+def test_join_ab_structured_embedding(p, dtype, N, R, d, prune):
     """Relation-dependent connectors on both sides (the structured-embedding model of Section 4.3)."""
     g = np.random.default_rng(N + d + p)
     cent = g.standard_normal((4, d))
@@ -380,28 +381,37 @@ def test_join_ab_structured_embedding(p, dtype, N, R, d):
     delta = float(np.float32(np.quantile(probe, 0.05)))
     ref = oracle.join_ab(A, B, p, delta)
     assert ref["count"] > 0
-    got = _run_ab(A, B, p, delta, max(1024, 2 * ref["count"]), dtype=dtype)
+    got = _run_ab(A, B, p, delta, max(1024, 2 * ref["count"]), dtype=dtype, prune=prune)
     assert got["code"] == 0
     _compare_ab(got, ref, A, B, p, delta, N)
-    assert got["stats"]["join_variant"] == (0 if p == 1 else 15 if d <= 282 else 17 if d <= 602 else 9)
+    if prune == PRUNE_OFF:
+        assert got["stats"]["join_variant"] == (0 if p == 1 else 15 if d <= 282 else 17 if d <= 602 else 9)
+    else:
+        assert got["stats"]["join_variant"] == (0 if p == 1 else 12 if d <= 218 else 9)
+        assert got["stats"]["groups"] > 0
+        if N >= 1500:
+            assert got["stats"]["tiles_pruned"] > 0
 
 
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
 @pytest.mark.parametrize("p", [1, 2])
-def test_join_ab_is_transe_on_its_connectors(p):
+def test_join_ab_is_transe_on_its_connectors(p, prune):
     """A[r][h] = E[h] + Rv[r] (formed in float32), B = E shared: the same triples as kgc_join up to the rounding of A."""
     wl = workloads.generate("c1_tiny_l2")
     delta = wl.delta if p == 2 else 2.6
     A = (wl.E[None, :, :] + wl.Rv[:, None, :]).astype(np.float32)
     ref = oracle.join_ab(A, wl.E, p, delta)
-    got = _run_ab(A, wl.E, p, delta, max(1024, 2 * ref["count"]))
+    got = _run_ab(A, wl.E, p, delta, max(1024, 2 * ref["count"]), prune=prune)
     assert got["code"] == 0 and ref["count"] > 0
     _compare_ab(got, ref, A, wl.E, p, delta, wl.E.shape[0])
+    if prune == PRUNE_ON:
+        assert got["stats"]["tiles_pruned"] > 0
     base = oracle.join(wl.E, wl.Rv, p, delta, mode="abandon")
     assert abs(got["count"] - base["count"]) <= 5
     # overflow and empty inputs follow kgc_join's conventions
-    small = _run_ab(A, wl.E, p, delta, 8)
+    small = _run_ab(A, wl.E, p, delta, 8, prune=prune)
     assert small["code"] == 1 and small["count"] == got["count"]
-    assert _run_ab(A, wl.E, p, -1.0, 8)["count"] == 0
+    assert _run_ab(A, wl.E, p, -1.0, 8, prune=prune)["count"] == 0
 
 
 # ---- top-k: the k smallest triple distances ----
