@@ -610,7 +610,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
             }
           }
         }
-        block_recheck<WGM * WGN, NW, 2>(cm, a.r0 + rl, a.cx, &queue, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
+        block_recheck<WGM * WGN, NW, 1>(cm, a.r0 + rl, a.cx, &queue, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
           const int tile = e >> 4, v = e & 15;
           const int i = tile / TN, j = tile % TN;
           hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);
