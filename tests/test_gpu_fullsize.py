@@ -167,3 +167,38 @@ def test_top1_fullsize(name):
         assert np.unique(key).size == k
     finally:
         j.close()
+
+
+def test_general_form_fullsize_c3():
+    """kgc_join_ab on the TransE connectors of the L1 workload at full size (pruned): the same set as kgc_join, except for
+    triples the float32 rounding of A = E + Rv moves across the threshold, which must lie in the boundary band."""
+    import torch
+
+    import paper_2307_12059_amd as kgc
+    wl = workloads.generate("c3_l1")
+    spec = wl.spec
+    E = torch.from_numpy(wl.E).cuda(); Rv = torch.from_numpy(wl.Rv).cuda()
+    A = (E.unsqueeze(0) + Rv.unsqueeze(1)).contiguous()
+    cap = int(6 * spec.selectivity * spec.n_triples) + 4096
+    j = kgc.Join(prune=kgc.KGC_PRUNE_ON)
+    try:
+        base = j.join(E, Rv, spec.p, wl.delta, cap)
+        got = j.join_ab(A, E, spec.p, wl.delta, cap)
+    finally:
+        j.close()
+    assert got["code"] == 0 and got["stats"]["tiles_pruned"] > 0.99 * got["stats"]["tiles_total"]
+    N = spec.N
+    kb = (base["r"].astype(np.int64) * N + base["h"]) * N + base["t"]
+    kg = (got["r"].astype(np.int64) * N + got["h"]) * N + got["t"]
+    assert np.unique(kg).size == kg.size
+    diff = np.concatenate([np.setdiff1d(kb, kg), np.setdiff1d(kg, kb)])
+    print(f"[c3_l1] general form: {got['count']} triples, {diff.size} differ from kgc_join", flush=True)
+    if diff.size:
+        r, rem = np.divmod(diff, N * N)
+        h, t = np.divmod(rem, N)
+        dref = oracle.dist_triples(wl.E, wl.Rv, spec.p, h.astype(np.int32), r.astype(np.int32), t.astype(np.int32))
+        assert np.all(np.abs(dref - wl.delta) <= parity.BAND * wl.delta)
+    # distances of the common triples against the oracle on the connectors the join saw
+    Ah = (wl.E[got["h"][:2000]] + wl.Rv[got["r"][:2000]]).astype(np.float32).astype(np.float64)
+    dab = np.abs(Ah - wl.E[got["t"][:2000]].astype(np.float64)).sum(-1)
+    np.testing.assert_allclose(got["dist"][:2000], dab, rtol=parity.DIST_RTOL)
