@@ -467,9 +467,8 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
   int32_t* unc = (int32_t*)hd->unc_a.p;
   int32_t* unc_next = (int32_t*)hd->unc_b.p;
   const float radius_mult = hd->cfg.group_radius > 0.f ? hd->cfg.group_radius : 2.0f;
-  const float tau = delta > 0.f ? radius_mult * delta : 0.f;
+  float tau = delta > 0.f ? radius_mult * delta : 0.f;
   const int gN = grid_for(std::max<int64_t>(N, kPivotsPerRound), 256);
-  k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
   // With a head tile that fits in LDS (d <= 602) the rows-against-pivots distances of every round run on the
   // matrix pipes, as a join of all entities (heads, staged once in identity order) with the round's pivots
   // (tails) whose epilogue keeps, per entity, the lowest pivot position within tau.  Otherwise (large d)
@@ -479,7 +478,6 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
   // ||x||_1 is about sqrt(2 / pi) sqrt(d) ||x||_2, so the L1 radius tau corresponds to that L2 radius; a
   // different ratio only makes the groups a little larger or smaller.
   const bool mfma_assign = KS <= kDirectHalfMaxKS && delta > 0.f;
-  const float tau_l2 = (p == 2) ? tau : tau / (0.79788456f * std::sqrt((float)d));
   const int abm = KS <= kDirectMaxKS ? 256 : 128;           // head tile height of the assignment kernel
   void (*assign_kernel)(const JoinStreamArgs) =
       abm == 256 ? k_join_l2_direct<256, 2, 4, kEpiAssignMin> : k_join_l2_direct<128, 1, 8, kEpiAssignMin>;
@@ -497,6 +495,15 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
     KGC_HIP(hd, hipFuncSetAttribute((const void*)assign_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)((size_t)KS * abm * kSliceK * 2)));
   }
+  // A radius far below the spacing of the rows groups nothing: every row then lands in the packed tail region in
+  // arbitrary order, micro-tiles mix rows from everywhere and no tile can be pruned.  When more than half of the
+  // rows end up there, the grouping is repeated with four times the radius (at most three times): groups of the
+  // size of the natural clusters prune well even when delta is much smaller than a cluster.
+  for (int attempt = 0;; ++attempt) {
+  const float tau_l2 = (p == 2) ? tau : tau / (0.79788456f * std::sqrt((float)d));
+  unc = (int32_t*)hd->unc_a.p;
+  unc_next = (int32_t*)hd->unc_b.p;
+  k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
   for (int round = 0; round < kGroupRounds; ++round) {
     // sampling density of the pivots among the still uncovered entities: 1/16, 1/16, 1/8, 1/8, 1/4, 1/2
     static const int kShift[kGroupRounds] = {4, 4, 3, 3, 2, 1};
@@ -545,6 +552,9 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
   // the layout decides the number of rows, which sizes every later launch: one small read-back
   KGC_HIP(hd, hipMemcpyAsync(hd->host_gstate, gs, sizeof(GroupState), hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipStreamSynchronize(st));
+  if (attempt >= 3 || !(tau > 0.f) || (int64_t)hd->host_gstate->tail_fill * 2 <= N) break;
+  tau *= 4.f;
+  }   // attempts
   Nslots = hd->host_gstate->n_slots;
   n_groups = (uint64_t)hd->host_gstate->n_groups;
   if (Nslots < N || Nslots > slots_cap || Nslots % kSlotAlign) return fail(hd, KGC_E_HIP, "group layout out of range");

@@ -508,3 +508,18 @@ def test_block_pairs_through_the_general_form(p):
     merged = {k: np.concatenate(v) for k, v in parts.items()}
     rep = parity.compare(merged, ref, E, Rv, p, delta, 900)
     assert rep["gpu_count"] + rep["only_oracle_in_band"] >= ref["count"] - rep["boundary_band"]
+
+
+@pytest.mark.parametrize("p", [1, 2])
+def test_pruning_with_a_threshold_far_below_the_cluster_size(p):
+    """A small delta must not switch the pruning off: the group radius is widened until groups form."""
+    g = np.random.default_rng(3)
+    cent = 4.0 * g.standard_normal((12, 48))
+    E = (cent[g.integers(0, 12, 3000)] + 0.3 * g.standard_normal((3000, 48))).astype(np.float32)
+    Rv = (cent[g.integers(0, 12, 5)] - cent[g.integers(0, 12, 5)]).astype(np.float32)
+    # members of a cluster are about 0.3 * sqrt(2 * 48) = 2.9 apart (L2); the threshold is a small fraction of that
+    delta = 0.4 if p == 2 else 2.0
+    got, ref, rep = _check(E, Rv, p, delta, prune=PRUNE_ON)
+    st = got["stats"]
+    assert st["tiles_pruned"] >= 0.8 * st["tiles_total"], st
+    assert rep["only_gpu_in_band"] == 0 and rep["only_oracle_in_band"] == 0
