@@ -613,7 +613,7 @@ int top_bounds(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* 
   //     with an epilogue that keeps only the smallest squared distance -- costs about a millisecond and
   //     usually lands within a few tens of percent of the answer.
   const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
-  if (p == 2 && KS <= kDirectMaxKS && N >= 1024) {
+  if (KS <= kDirectMaxKS && N >= 1024) {     // (the pass measures in L2; for an L1 search its bound is scaled below)
     const int m = (int)std::min<int64_t>(8192, (N / 2) / 256 * 256);
     const int Rs = (int)std::min<int32_t>(R, 32);
     const int k16 = (d + kNormCols + 15) / 16;
@@ -645,7 +645,9 @@ int top_bounds(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* 
     k_top1_bound<<<1, 64, 0, st>>>(cnt, hd->cfg.dtype, KS * kSliceK, ts);
     KGC_HIP(hd, hipMemcpyAsync(&host, ts, sizeof(Top1State), hipMemcpyDeviceToHost, st));
     KGC_HIP(hd, hipStreamSynchronize(st));
-    if (host.sub_bound >= 0.0 && host.sub_bound < bound) bound = host.sub_bound;
+    // ||x||_1 <= sqrt(d) ||x||_2: the pair that attains the L2 bound is at most that far apart in L1
+    const double sub = p == 2 ? host.sub_bound : host.sub_bound * std::sqrt((double)d) * (1.0 + 1e-6);
+    if (host.sub_bound >= 0.0 && sub < bound) bound = sub;
   }
   *sample_bound_out = sample_bound;
   *bound_out = bound;
