@@ -30,7 +30,7 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def cpu_baseline(wl, target_seconds=12.0):
+def cpu_baseline(wl, target_seconds=20.0):
     """The oracle as it stands (brute-force mode, all host threads) on a bounded sample of the workload."""
     import numpy as np
 
