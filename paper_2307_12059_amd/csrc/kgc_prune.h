@@ -723,9 +723,19 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
   if (row0 >= n_rows) return;                                  // whole waves leave together
   const int64_t my_row = row0 + lane;
   uint32_t cnt = 0;
-  if (my_row < n_rows) {
-    const uint32_t* w = bitmap + my_row * words_per_row;
-    for (int i = 0; i < words_per_row; ++i) cnt += __builtin_popcount(w[i]);
+  if (words_per_row <= 8) {                  // short rows: every lane counts its own
+    if (my_row < n_rows) {
+      const uint32_t* w = bitmap + my_row * words_per_row;
+      for (int i = 0; i < words_per_row; ++i) cnt += __builtin_popcount(w[i]);
+    }
+  } else {                                   // long rows: the wave counts them one after the other, words over lanes
+    for (int rr = 0; rr < 64 && row0 + rr < n_rows; ++rr) {
+      const uint32_t* w = bitmap + (row0 + rr) * words_per_row;
+      uint32_t c = 0;
+      for (int i = lane; i < words_per_row; i += 64) c += __builtin_popcount(w[i]);
+      for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
+      if (lane == rr) cnt = c;
+    }
   }
   unsigned long long my_base = 0;
   if (my_row < n_rows) {
