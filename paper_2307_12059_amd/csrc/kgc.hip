@@ -897,6 +897,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   uint64_t n_groups = 0;
   UnitTable ut{};                 // two-level bound test: filled after the layout
   bool use_units = false;
+  bool fine_direct = false;       // ... whose micro-tile level then sums centre distances directly (no M x M matrix)
   if (prune) {
     if ((rc = group_rows(hd, E, N, d, p, delta, KS, k16, &Nslots, &n_groups, &ut)) != KGC_OK) return rc;
   } else {
@@ -946,6 +947,9 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
                       (rc = ensure(hd, hd->cnorm_u, (size_t)ut.n_units * 4)) ||
                       (rc = ensure(hd, hd->pair_list, kBoundPairCap * 8)) || (rc = ensure(hd, hd->pair_count, 8))))
       return rc;
+    // with few micro-tiles the M x M matrix of centre distances and the R x M products cost more than the handful of
+    // micro-tile pairs that are looked up in them
+    fine_direct = use_units && p == 2 && n_micro <= 8192;
     if (use_units && p == 2 && ((rc = ensure(hd, hd->gram_u, (size_t)ut.n_units * ut.n_units * 4)) ||
                                 (rc = ensure(hd, hd->relu_u, (size_t)RBmax * ut.n_units * 4))))
       return rc;
@@ -967,12 +971,14 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     if (p == 2) {
       k_micro_summary<2><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p,
                                                             (float*)hd->rad.p, (float*)hd->cnorm.p);
-      // squared distances between all micro-tile centres, once: the part of the bound that no relation changes
-      TileDistArgs ta{};
-      ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.n_rows = n_micro; ta.Y = hd->cent.p; ta.dtypeY = KGC_F32;
-      ta.n_cols = n_micro; ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.d = d; ta.matrix = (float*)hd->gram.p;
-      const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), 1);
-      k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
+      if (!fine_direct) {
+        // squared distances between all micro-tile centres, once: the part of the bound that no relation changes
+        TileDistArgs ta{};
+        ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.n_rows = n_micro; ta.Y = hd->cent.p; ta.dtypeY = KGC_F32;
+        ta.n_cols = n_micro; ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.d = d; ta.matrix = (float*)hd->gram.p;
+        const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), 1);
+        k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
+      }
       if (use_units) {
         k_unit_summary<2><<<(unsigned)ut.n_units, 64, 0, st>>>((const float*)hd->cent.p, (const float*)hd->rad.p, d, ut,
                                                             (float*)hd->cent_u.p, (float*)hd->rad_u.p, (float*)hd->cnorm_u.p);
@@ -1021,13 +1027,16 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         // u[rl][m] = r . c_m as a tiled product, ||r||^2 by one wave per relation
         k_rel_centre_dot<<<grid_for((int64_t)RB * 64, 256), 256, 0, st>>>(
             Rvecs, dtype, d, (int)r0, RB, (const float*)hd->cent.p, 0, (float*)hd->relu.p, (float*)hd->reln.p);
-        TileDistArgs td{};
-        td.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); td.dtypeX = dtype; td.n_rows = RB;
-        td.Y = hd->cent.p; td.dtypeY = KGC_F32; td.n_cols = n_micro; td.shift = nullptr; td.dtype_shift = KGC_F32;
-        td.d = d; td.matrix = (float*)hd->relu.p;
-        k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((n_micro + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(td);
+        if (!fine_direct) {
+          TileDistArgs td{};
+          td.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); td.dtypeX = dtype; td.n_rows = RB;
+          td.Y = hd->cent.p; td.dtypeY = KGC_F32; td.n_cols = n_micro; td.shift = nullptr; td.dtype_shift = KGC_F32;
+          td.d = d; td.matrix = (float*)hd->relu.p;
+          k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((n_micro + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(td);
+        }
         BoundL2Args ba{};
-        ba.D = (const float*)hd->gram.p; ba.u = (const float*)hd->relu.p; ba.rn = (const float*)hd->reln.p;
+        ba.D = fine_direct ? nullptr : (const float*)hd->gram.p; ba.u = (const float*)hd->relu.p; ba.rn = (const float*)hd->reln.p;
+        ba.cent = (const float*)hd->cent.p; ba.Rv = Rvecs; ba.dtype = dtype; ba.r0 = (int)r0;
         ba.rad = (const float*)hd->rad.p; ba.cnorm = (const float*)hd->cnorm.p; ba.n_micro = n_micro; ba.RB = RB;
         ba.d = d; ba.delta = delta; ba.bitmap = (uint32_t*)hd->bitmap.p; ba.nH = nH; ba.words_per_row = words_per_row;
         ba.micro_per_bm = BM / kMicro; ba.micro_per_bn = BN / kMicro;

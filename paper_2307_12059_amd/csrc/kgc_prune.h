@@ -480,6 +480,9 @@ struct BoundL2Args {
   const float* D; const float* u; const float* rn; const float* rad; const float* cnorm;
   int64_t n_micro; int RB; int d; float delta;
   uint32_t* bitmap; int nH, words_per_row, micro_per_bm, micro_per_bn;
+  // micro-tile level of the two-level test without the D and u matrices (D == NULL): centre distances are then
+  // summed directly from the centres and the relation vector
+  const float* cent; const void* Rv; int dtype; int r0;
 };
 constexpr int kHeadChunk = 16;
 __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
@@ -606,6 +609,22 @@ __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const Uni
     const int64_t mH = fH + i / nTm, mT = fT + i % nTm;
     const float rH = a.rad[mH], rT = a.rad[mT];
     if (rH < 0.f || rT < 0.f) continue;
+    if (!a.D) {           // small problems: no matrices, the distance of c_H + r and c_T summed over d
+      const float* cH = a.cent + mH * a.d;
+      const float* cT = a.cent + mT * a.d;
+      const int64_t so = (int64_t)(a.r0 + rl) * a.d;
+      float sq = 0.f;
+      for (int k = 0; k < a.d; ++k) {
+        const float x = cH[k] + ld_elem(a.Rv, so + k, a.dtype) - cT[k];
+        sq += x * x;
+      }
+      if (sqrtf(sq) * (1.f - kBoundSlack) - rH - rT <= dsl) {
+        const int tH = (int)(mH / a.micro_per_bm), tT = (int)(mT / a.micro_per_bn);
+        uint32_t* w = &a.bitmap[((int64_t)rl * a.nH + tH) * a.words_per_row + (tT >> 5)];
+        if (!(*w & (1u << (tT & 31)))) atomicOr(w, 1u << (tT & 31));
+      }
+      continue;
+    }
     const float D = a.D[mH * a.n_micro + mT];
     const float reach = dsl + rH + rT;
     const float rhs = reach * reach * (1.f + kBoundSlack) + D * 1.2e-6f - D;
@@ -676,7 +695,8 @@ __global__ __launch_bounds__(256) void k_bound_l2_units(const BoundL2Args a, con
       unit_range(ut, (int)mH, fH, nHm);
       unit_range(ut, (int)mT, fT, nTm);
       unsigned long long pos = bp.cap;
-      if ((int64_t)nHm * nTm > kInlineMicroPairs) pos = atomicAdd(bp.count, 1ull);
+      // (without the matrices a micro-tile pair costs a loop over d: then every pair but a single one is listed)
+      if ((int64_t)nHm * nTm > (fine.D ? kInlineMicroPairs : 1)) pos = atomicAdd(bp.count, 1ull);
       if (pos < bp.cap)
         bp.list[pos] = ((unsigned long long)(uint32_t)(rl0 + q) << 48) | ((unsigned long long)(uint32_t)mH << 24) |
                        (unsigned long long)(uint32_t)mT;
