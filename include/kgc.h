@@ -58,8 +58,9 @@ typedef struct {
                                  1-5   one block per tile pair, 128/256-row tiles (dense mode only)
                                  6-10  streaming: a block walks tail tiles, head and tail slices through LDS (any d)
                                  11-14 head tile resident in LDS, tail slices through LDS (d <= 218; pruned default 12)
-                                 15-17 head tile resident, tail fragments straight to registers, no barrier in the
-                                       loop (dense mode only; 15-16: d <= 282, dense default 15; 17: d <= 602)
+                                 15-18 head tile resident, tail fragments straight to registers, no barrier in the
+                                       loop (dense mode only; 15-16: d <= 282; 17: d <= 602; 18: d <= 282, one
+                                       straight-line instantiation per number of K steps, the dense default)
                                  A variant that cannot run the request (pruned mode, d) fails with KGC_E_INVALID. */
     int64_t workspace_bytes;  /* cap on scratch held for staged operands; 0 = 16 GiB.  Larger joins run in relation batches */
     void*   stream;           /* hipStream_t to enqueue on; NULL = the default stream */
@@ -183,6 +184,17 @@ const char* kgc_last_error(const kgc_handle* hd);
 
 /* Release the handle and its scratch memory.  NULL is allowed. */
 void kgc_destroy(kgc_handle* hd);
+
+/* Calibration of the roofline of the L2 join (measurement support, Section 5's question of what the hardware
+ * sustains): a loop of nothing but bf16 32x32x16 MFMAs on a wave tile of the join's kind, on pseudo-random operands,
+ * run for about ms_target milliseconds so that the clock the chip settles on under that load is the one measured.
+ *   wave_tile  0: 4 x 2 accumulator blocks (128 x 64, two waves per SIMD, the join kernels' shape); 1: 4 x 4 (one wave per SIMD)
+ *   feed       0: operands stay in registers; 1: head fragments read from LDS every K step, as in the join;
+ *              2: ... and tail fragments read from global memory through the vector cache in the join's pattern
+ *   stream     hipStream_t to run on (NULL = default stream)
+ *   tflops     receives the sustained rate in TFLOP/s (host);  ms receives the duration of the timed launch (host)
+ * Allocates and frees its own scratch.  KGC_E_INVALID on a bad argument. */
+int kgc_calibrate_mfma(int32_t wave_tile, int32_t feed, int32_t ms_target, void* stream, double* tflops, float* ms);
 
 /* Library version, "major.minor.patch". */
 const char* kgc_version(void);

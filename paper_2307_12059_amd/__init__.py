@@ -24,7 +24,7 @@ KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
 EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_top1", "kgc_topk", "kgc_topk_range", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
-           "kgc_version"]
+           "kgc_version", "kgc_calibrate_mfma"]
 
 
 class kgc_triple(ctypes.Structure):
@@ -99,6 +99,9 @@ def load_library():
     lib.kgc_destroy.argtypes = [vp]
     lib.kgc_version.restype = ctypes.c_char_p
     lib.kgc_version.argtypes = []
+    lib.kgc_calibrate_mfma.restype = ctypes.c_int
+    lib.kgc_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double),
+                                       ctypes.POINTER(ctypes.c_float)]
     _lib = lib
     return lib
 
@@ -184,6 +187,13 @@ def kgc_topk_range(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: in
                                        1 if exclude_self else 0, r_begin, r_end, k, ctypes.c_void_p(out_ptr),
                                        ctypes.byref(found))
     return rc, int(found.value)
+
+
+def kgc_calibrate_mfma(wave_tile: int, feed: int, ms_target: int, stream: int = 0):
+    """Returns (code, TFLOP/s, ms of the timed launch)."""
+    tf, ms = ctypes.c_double(0.0), ctypes.c_float(0.0)
+    rc = load_library().kgc_calibrate_mfma(wave_tile, feed, ms_target, ctypes.c_void_p(stream), ctypes.byref(tf), ctypes.byref(ms))
+    return rc, float(tf.value), float(ms.value)
 
 
 def kgc_norms(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, nB_ptr: int, nA_ptr: int) -> int:

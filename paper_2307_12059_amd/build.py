@@ -8,8 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkgc.so")
 SOURCES = [os.path.join(CSRC, "kgc.hip")]
-HEADERS = [os.path.join(CSRC, "kgc_device.h"), os.path.join(CSRC, "kgc_kernels.h"),
-           os.path.join(os.path.dirname(HERE), "include", "kgc.h")]
+HEADERS = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")) + [
+    os.path.join(os.path.dirname(HERE), "include", "kgc.h")]
 
 # -packed-fp32-ops is switched off on purpose: the compiler then emits no v_pk_*_f32 instructions.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

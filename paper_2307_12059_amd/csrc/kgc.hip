@@ -10,6 +10,8 @@
 #include <vector>
 
 #include "kgc_kernels.h"
+#include "kgc_dense.h"
+#include "kgc_calibrate.h"
 #include "kgc_prune.h"
 
 using namespace kgc;
@@ -21,7 +23,7 @@ constexpr int64_t kSlotAlign = 256;            // rows are padded to a multiple 
 constexpr int64_t kDefaultWorkspace = 16ll << 30;
 constexpr size_t kBoundPairCap = 8u << 20;      // surviving (relation, unit, unit) entries of one batch kept in the list
 constexpr int64_t kL2RangeBytes = 1ll << 20;
-constexpr int64_t kL2RangeBytesResident = 3ll << 20;   // head-resident blocks leave the whole L2 to the tail rows
+constexpr int64_t kL2RangeBytesResident = 4ll << 20;   // head-resident blocks leave the whole L2 to the tail rows
 constexpr size_t kMaxLds = 160 * 1024;         // LDS per workgroup on gfx950
 constexpr int64_t kMaxTileList = 1ll << 30;    // entries of the surviving-tile list per relation batch (4 bytes each)
 
@@ -123,10 +125,12 @@ const TileCfg kL2Tiles[] = {
     {256, 256, 512, nullptr, k_join_l2_direct<256, 2, 4, kEpiJoin>, nullptr, true, 0, 1, 0},
     {256, 256, 512, nullptr, k_join_l2_direct<256, 1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
     {128, 256, 512, nullptr, k_join_l2_direct<128, 1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
+    {256, 256, 512, nullptr, k_join_l2_dense<1>, nullptr, true, 0, 1, 0},      // placeholder: see dense_kernel_for
 };
 constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles: streaming, 256 x 256, 8 waves
 constexpr int kResidentL2Tile = 11;               // head-resident, 256 x 256, 8 waves (2 x 4)
 constexpr int kDirectL2Tile = 14;                 // head-resident and barrier-free (dense mode only), 8 waves (2 x 4)
+constexpr int kDenseL2Tile = 17;                  // the same with a straight-line tile body per number of K steps (dense default)
 constexpr int kDirectMaxKS = 9;                   // its head tile then takes 144 of the 160 KiB of LDS
 constexpr int kDirectHalfL2Tile = 16;             // the same with a 128-row head tile (wave tile 128 x 32), for larger d
 constexpr int kDirectHalfMaxKS = 19;              // 152 KiB
@@ -239,7 +243,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   // the kernels of kgc_join: dense, or (pruned) walking the tile lists
   int tile_id;
   if (prune) tile_id = ((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile;
-  else tile_id = KS <= kDirectMaxKS ? kDirectL2Tile : KS <= kDirectHalfMaxKS ? kDirectHalfL2Tile : kDefaultL2Tile;
+  else tile_id = KS <= kDirectMaxKS ? kDenseL2Tile : KS <= kDirectHalfMaxKS ? kDirectHalfL2Tile : kDefaultL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
   if ((rc = ensure(hd, hd->counters, sizeof(DevCounters))) || (rc = ensure(hd, hd->params, sizeof(JoinParams))) ||
@@ -371,6 +375,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = (int)r0; sa.RB = RB; sa.b_per_rel = b_per_relation ? 1 : 0;
       sa.cx = cx;
       void (*kern)(const JoinStreamArgs) = prune ? tc.listed_kernel : tc.stream_kernel;
+      if (tile_id == kDenseL2Tile) kern = dense_kernel_for(k16);
       size_t dyn_lds = 0;
       if (tc.head_resident) {
         dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
@@ -795,6 +800,58 @@ int kgc_topk_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   return KGC_OK;
 }
 
+int kgc_calibrate_mfma(int32_t wave_tile, int32_t feed, int32_t ms_target, void* stream, double* tflops, float* ms) {
+  if (wave_tile < 0 || wave_tile > 1 || feed < 0 || feed > 2 || ms_target < 1 || ms_target > 5000 || !tflops || !ms)
+    return KGC_E_INVALID;
+  hipStream_t st = (hipStream_t)stream;
+  // tail rows: seven 32-wide slices (d = 200) of a range of about 3 MiB, as one block of the dense join walks
+  CalibArgs ca{};
+  ca.slices = 7;
+  ca.rows = 27 * 256;
+  uint16_t* G = nullptr;
+  float* sink = nullptr;
+  const int64_t n = (int64_t)ca.slices * ca.rows * 32;
+  if (hipMalloc((void**)&G, n * 2) != hipSuccess) return KGC_E_NOMEM;
+  if (hipMalloc((void**)&sink, 4096 * 512 * 4) != hipSuccess) { (void)hipFree(G); return KGC_E_NOMEM; }
+  ca.G = G;
+  ca.sink = sink;
+  k_calib_fill<<<1024, 256, 0, st>>>(G, n);
+  void (*kern)(const CalibArgs) = nullptr;
+  int waves = 8, blocks_of = 8;
+  if (wave_tile == 0) kern = feed == 0 ? k_calib_mfma<4, 2, 2, 4, 0> : feed == 1 ? k_calib_mfma<4, 2, 2, 4, 1> : k_calib_mfma<4, 2, 2, 4, 2>;
+  else { kern = feed == 0 ? k_calib_mfma<4, 4, 2, 2, 0> : feed == 1 ? k_calib_mfma<4, 4, 2, 2, 1> : k_calib_mfma<4, 4, 2, 2, 2>; waves = 4; blocks_of = 16; }
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = KGC_OK;
+  float t = 0.f;
+  const unsigned grid = 256 * 8;                           // eight blocks per CU, one after the other
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) rc = KGC_E_HIP;
+  // a short launch gives the rate, the timed launch is then sized for ms_target
+  int iters = 6 * 200;
+  for (int pass = 0; pass < 2 && rc == KGC_OK; ++pass) {
+    ca.iters = iters;
+    if (hipEventRecord(e0, st) != hipSuccess) { rc = KGC_E_HIP; break; }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), 0, st, ca);
+    if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&t, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess) { rc = KGC_E_HIP; break; }
+    if (pass == 0) {
+      const double per_iter = (double)t / iters;
+      int64_t want = (int64_t)((double)ms_target / (per_iter > 1e-9 ? per_iter : 1e-9));
+      want = want / 6 * 6;
+      iters = (int)(want < 6 ? 6 : want > (1 << 28) ? (1 << 28) : want);
+    }
+  }
+  if (rc == KGC_OK) {
+    const double flop = (double)grid * waves * (double)iters * blocks_of * 32768.0;
+    *tflops = flop / ((double)t * 1e-3) / 1e12;
+    *ms = t;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(G);
+  (void)hipFree(sink);
+  return rc;
+}
+
 int kgc_get_stats(const kgc_handle* h, kgc_stats* out) {
   if (!h || !out) return KGC_E_INVALID;
   *out = h->stats;
@@ -876,7 +933,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   int tile_id = kDefaultL2Tile;
   if (fact) tile_id = kDirectL2Tile;
   else if (hd->cfg.tile_cfg > 0) tile_id = hd->cfg.tile_cfg - 1;
-  else if (!prune && KS <= kDirectMaxKS) tile_id = kDirectL2Tile;
+  else if (!prune && KS <= kDirectMaxKS) tile_id = kDenseL2Tile;
   else if (!prune && KS <= kDirectHalfMaxKS) tile_id = kDirectHalfL2Tile;
   else if (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds) tile_id = kResidentL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
@@ -1155,6 +1212,10 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
         }
         void (*kern)(const JoinStreamArgs) = prune ? tc.listed_kernel : tc.stream_kernel;
+        if (tile_id == kDenseL2Tile) {
+          if (KS > kDirectMaxKS) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
+          kern = dense_kernel_for(k16);
+        }
         size_t dyn_lds = 0;
         if (tc.head_resident) {
           dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;

@@ -56,7 +56,7 @@ PRUNE_OFF, PRUNE_ON = 1, 2
 
 
 @pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
-@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17])
+@pytest.mark.parametrize("tile_cfg", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18])
 def test_c1_l2_full_parity(tile_cfg, prune):
     if prune == PRUNE_ON and (1 <= tile_cfg <= 5 or tile_cfg >= 15):
         pytest.skip("one-block-per-tile and barrier-free variants have no pruned mode")
@@ -385,7 +385,7 @@ def test_join_ab_structured_embedding(p, dtype, N, R, d, prune):
     assert got["code"] == 0
     _compare_ab(got, ref, A, B, p, delta, N)
     if prune == PRUNE_OFF:
-        assert got["stats"]["join_variant"] == (0 if p == 1 else 15 if d <= 282 else 17 if d <= 602 else 9)
+        assert got["stats"]["join_variant"] == (0 if p == 1 else 18 if d <= 282 else 17 if d <= 602 else 9)
     else:
         assert got["stats"]["join_variant"] == (0 if p == 1 else 12 if d <= 218 else 9)
         assert got["stats"]["groups"] > 0
