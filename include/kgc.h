@@ -136,6 +136,22 @@ int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* R
 int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
                    float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
 
+/* kgc_join for callers that cannot allocate device memory while they run: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same dense join (every tile pair goes through the join kernel, the
+ * handle's pruning setting is ignored; same kernels, result set, output, count, overflow and error conventions as
+ * kgc_join), but ALL of its scratch -- counters, filter threshold, slot order, staged operands and norms -- lies
+ * in one 48 MiB array that is part of the library's device code; the call allocates and frees nothing (no hipMalloc,
+ * hipFree, event creation or host allocation; the array's address on the handle's device was looked up by
+ * kgc_create).  Relations run in batches of as many staged head operands as fit the array.
+ * KGC_E_INVALID when the fixed part alone does not fit (it needs about (N + 255) * (64 * ceil((d + 6) / 32) + 4) * 2
+ * bytes for p = 2: e.g. N <= 87,000 at d = 100, N <= 50,000 at d = 200), when the handle was created with
+ * factorised = 1, or when the handle's device is not the current device.  Every GPU holds ONE such array, shared by
+ * every handle and call on that GPU: calls that overlap in time on one GPU race on it and must be serialised by the
+ * caller; a call leaves its operands behind, and the next call overwrites what it uses.  Per-batch kernel times
+ * are not taken: stats.ms_join spans operand staging and join launches together. */
+int kgc_join_static(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                    float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
+
 /* The join in its general form (Section 4.3): for a model that can be transformed to a metric space the
  * caller supplies the connector outputs and the library joins them under dist(a, b) = ||a - b||_p:
  *   A   R x N x d   a_{r,h} = connector_1(h, r), row-major, contiguous, of the handle's dtype          (device)

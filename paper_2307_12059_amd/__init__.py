@@ -24,7 +24,7 @@ KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
 EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_top1", "kgc_topk", "kgc_topk_range", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
-           "kgc_version", "kgc_calibrate_mfma"]
+           "kgc_version", "kgc_calibrate_mfma", "kgc_join_static"]
 
 
 class kgc_triple(ctypes.Structure):
@@ -73,6 +73,8 @@ def load_library():
     lib.kgc_join.restype = ctypes.c_int
     lib.kgc_join.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
                              ctypes.c_float, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64)]
+    lib.kgc_join_static.restype = ctypes.c_int
+    lib.kgc_join_static.argtypes = lib.kgc_join.argtypes
     lib.kgc_join_range.restype = ctypes.c_int
     lib.kgc_join_range.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
                                    ctypes.c_float, ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_uint64,
@@ -140,6 +142,14 @@ def kgc_join(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, del
     count = ctypes.c_uint64(0)
     rc = load_library().kgc_join(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
                                  ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap, ctypes.byref(count))
+    return rc, int(count.value)
+
+
+def kgc_join_static(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, delta: float, out_ptr: int, cap: int):
+    """Raw call on device addresses: the dense join with its scratch in the library's static device array.  Returns (code, count)."""
+    count = ctypes.c_uint64(0)
+    rc = load_library().kgc_join_static(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
+                                        ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap, ctypes.byref(count))
     return rc, int(count.value)
 
 

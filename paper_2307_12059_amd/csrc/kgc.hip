@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -15,6 +16,12 @@
 #include "kgc_prune.h"
 
 using namespace kgc;
+
+// Scratch of kgc_join_static (the entry point for callers that cannot allocate): one array per GPU, held from the
+// moment the code object is loaded until the process ends.  In host code this name is only a stand-in for the
+// symbol; the array's device address is taken once per device with hipGetSymbolAddress (static_scratch_ptr).
+constexpr size_t kStaticScratchBytes = 48u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -50,6 +57,8 @@ struct kgc_handle {
   DevBuf zero_row, cent_a, rad_a;              // kgc_join_ab: the zero relation row; micro-tile summaries of A[r]
   DevBuf top1_a, top1_b, top1_pick, top_samples, topk_state;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
+  bool static_mode = false;                    // inside kgc_join_static: the DevBufs point into the static array, nothing may allocate
+  int64_t ws_override = 0;                     // ... and the staged operands of a relation batch get this many bytes
   GroupState* host_gstate = nullptr;           // pinned
   DevCounters* host_counters = nullptr;        // pinned
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -78,6 +87,7 @@ int fail(kgc_handle* h, int code, const char* what, hipError_t e = hipSuccess) {
 
 int ensure(kgc_handle* h, DevBuf& b, size_t bytes) {
   if (b.bytes >= bytes && b.p) return KGC_OK;
+  if (h->static_mode) return fail(h, KGC_E_INVALID, "kgc_join_static: a buffer was not laid out in the static scratch");
   if (b.p) {
     KGC_HIP(h, hipFree(b.p));
     b.p = nullptr;
@@ -93,6 +103,23 @@ void release(DevBuf& b) {
   if (b.p) (void)hipFree(b.p);
   b.p = nullptr;
   b.bytes = 0;
+}
+
+// Device address of the static scratch array on `device` (which must be the current device): every GPU holds its own
+// copy of the array at its own address, looked up once and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+int static_scratch_ptr(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return KGC_E_INVALID;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KGC_E_HIP;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return KGC_OK;
 }
 
 struct TileCfg {
@@ -184,6 +211,12 @@ int kgc_create(const kgc_config* cfg, kgc_handle** out) {
   h->cfg = c;
   h->stream = (hipStream_t)c.stream;
   if (hipGetDevice(&h->device) != hipSuccess) { delete h; return KGC_E_HIP; }
+  {   // set-up for kgc_join_static: the address of this device's static scratch, so that the call itself looks nothing up
+    void* sp = nullptr;
+    const int src = static_scratch_ptr(h->device, &sp);
+    if (src != KGC_OK) { delete h; return src; }
+  }
+  h->err.reserve(256);          // later error messages fit without a host allocation
   if (hipHostMalloc((void**)&h->host_counters, sizeof(DevCounters), hipHostMallocDefault) != hipSuccess) {
     delete h;
     return KGC_E_NOMEM;
@@ -900,6 +933,69 @@ int kgc_join(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   return kgc_join_range(hd, E, N, d, Rvecs, R, p, delta, 0, R, out_triples, cap, count);
 }
 
+int kgc_join_static(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                    float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count) {
+  if (!hd) return KGC_E_INVALID;
+  if (!count) return fail(hd, KGC_E_INVALID, "count is NULL");
+  *count = 0;
+  int rc = check_common(hd, E, N, d, Rvecs, R);
+  if (rc != KGC_OK) return rc;
+  if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
+  if (hd->cfg.factorised) return fail(hd, KGC_E_INVALID, "kgc_join_static: not with the factorised kernel");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != hd->device)
+    return fail(hd, KGC_E_INVALID, "kgc_join_static: the handle's device is not the current device");
+  void* base = nullptr;
+  if ((rc = static_scratch_ptr(dev, &base)) != KGC_OK) return fail(hd, rc, "kgc_join_static: no static scratch on this device");
+
+  // Layout of the dense join's scratch inside the static array (the sizes kgc_join_range asks for with pruning off):
+  // counters, threshold, slot order, tail operands and norms, then as many relations' head operands as fit.
+  const int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
+  const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
+  const size_t op_rel = (p == 2) ? (size_t)KS * Nslots * kSliceK * 2 : 0;
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  size_t off = 0;
+  auto carve = [&](size_t bytes) { const size_t o = off; off += up(bytes ? bytes : 256); return o; };
+  const size_t o_cnt = carve(sizeof(DevCounters)), o_prm = carve(sizeof(JoinParams)), o_slot = carve((size_t)Nslots * 4);
+  const size_t o_opB = carve(op_rel), o_nB = carve(p == 2 ? (size_t)Nslots * 4 : 0);
+  const size_t per_rel = up(op_rel) + up((size_t)Nslots * 4);           // staged head operands and their norms
+  int64_t RB = 0;
+  if (off < kStaticScratchBytes) RB = (int64_t)((kStaticScratchBytes - off) / (p == 2 ? per_rel : 1));
+  if (p == 2 && RB > R) RB = R;
+  if (off >= kStaticScratchBytes || (p == 2 && R > 0 && RB < 1)) {
+    char msg[200];
+    std::snprintf(msg, sizeof msg, "kgc_join_static: N = %lld, d = %d need more than the %zu MiB of static scratch",
+                  (long long)N, (int)d, kStaticScratchBytes >> 20);
+    return fail(hd, KGC_E_INVALID, msg);
+  }
+  const size_t o_opA = carve(p == 2 ? op_rel * (size_t)RB : 0), o_nA = carve(p == 2 ? (size_t)RB * Nslots * 4 : 0);
+  if (off > kStaticScratchBytes) return fail(hd, KGC_E_INVALID, "kgc_join_static: layout exceeds the static scratch");
+
+  // the handle's buffers point into the array for the duration of the call; nothing on this path may allocate
+  struct Swap {
+    kgc_handle* h;
+    DevBuf counters, params, slot_ent, opB, normsB, opA, normsA;
+    kgc_config cfg;
+    explicit Swap(kgc_handle* hd)
+        : h(hd), counters(hd->counters), params(hd->params), slot_ent(hd->slot_ent), opB(hd->opB), normsB(hd->normsB),
+          opA(hd->opA), normsA(hd->normsA), cfg(hd->cfg) {}
+    ~Swap() {
+      h->counters = counters; h->params = params; h->slot_ent = slot_ent; h->opB = opB; h->normsB = normsB;
+      h->opA = opA; h->normsA = normsA; h->cfg = cfg; h->static_mode = false; h->ws_override = 0;
+    }
+  } swap(hd);
+  char* b = (char*)base;
+  auto at = [&](size_t o, size_t bytes) { DevBuf v; v.p = b + o; v.bytes = up(bytes ? bytes : 256); return v; };
+  hd->counters = at(o_cnt, sizeof(DevCounters)); hd->params = at(o_prm, sizeof(JoinParams));
+  hd->slot_ent = at(o_slot, (size_t)Nslots * 4);
+  hd->opB = at(o_opB, op_rel); hd->normsB = at(o_nB, (size_t)Nslots * 4);
+  hd->opA = at(o_opA, op_rel * (size_t)RB); hd->normsA = at(o_nA, (size_t)RB * Nslots * 4);
+  hd->cfg.prune = KGC_PRUNE_OFF;
+  hd->static_mode = true;
+  hd->ws_override = p == 2 ? (int64_t)RB * (int64_t)(op_rel + (size_t)Nslots * 4) : 0;
+  return kgc_join_range(hd, E, N, d, Rvecs, R, p, delta, 0, R, out_triples, cap, count);
+}
+
 int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
                    float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count) {
   if (!hd) return KGC_E_INVALID;
@@ -969,7 +1065,8 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   if (nH > 65535) return fail(hd, KGC_E_INVALID, "N too large for one launch grid");
 
   // ---- relation batches: staged A operands (L2) and the tile lists (pruning) must fit the workspace ----
-  const int64_t ws = hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
+  const int64_t ws = hd->ws_override > 0 ? hd->ws_override
+                                           : hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
   const size_t opA_per_rel = (p == 2) ? (size_t)KS * Nslots * kSliceK * 2 : 0;
   int64_t RBmax = Rn;
   if (p == 2 && !fact) RBmax = std::max<int64_t>(1, std::min<int64_t>(Rn, ws / (int64_t)(opA_per_rel + Nslots * 4)));
@@ -1012,7 +1109,8 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       return rc;
   }
   const int nbatch = (int)((Rn + RBmax - 1) / RBmax);
-  while ((int)hd->join_ev.size() < 2 * nbatch) {
+  const bool timed = !hd->static_mode;          // per-batch event pairs (creating events allocates)
+  while (timed && (int)hd->join_ev.size() < 2 * nbatch) {
     hipEvent_t e;
     KGC_HIP(hd, hipEventCreate(&e));
     hd->join_ev.push_back(e);
@@ -1166,7 +1264,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
                                                                      (float*)hd->relu.p, (float*)hd->reln.p);
       k_fact_params<<<grid_for(RB, 256), 256, 0, st>>>(cnt, (const float*)hd->reln.p, RB, delta, dtype, d, KS * kSliceK,
                                                       (float*)hd->limr.p);
-      KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
+      if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
       JoinFactArgs fa{};
       fa.A = (const uint16_t*)hd->opA.p; fa.B = (const uint16_t*)hd->opB.p; fa.u = (const float*)hd->relu.p;
       fa.limr = (const float*)hd->limr.p; fa.Nslots = Nslots; fa.KS = KS; fa.k16 = k16; fa.nH = nH; fa.nT = nT;
@@ -1182,7 +1280,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
       KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_fact<2, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
       hipLaunchKernelGGL((k_join_l2_fact<2, 4>), dim3((unsigned)nH, (unsigned)nsplit, 1), dim3(512), dyn_lds, st, fa);
-      KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
+      if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else if (p == 2) {
       const int stage_grid = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 16384)
                                    : grid_for((int64_t)RB * (Nslots / kStageRows), 1);
@@ -1190,7 +1288,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           E, Rvecs, dtype, d, (int)r0, RB, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p,
           cnt->max_a, active_rows, n_active, nH, BM);
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
-      KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
+      if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
       if (tc.stream_kernel) {
         JoinStreamArgs sa{};      // the fields a launch does not use stay zero
         sa.A = (const uint16_t*)hd->opA.p; sa.B = (const uint16_t*)hd->opB.p; sa.prm = prm; sa.Nslots = Nslots;
@@ -1236,16 +1334,16 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         ja.Nslots = Nslots; ja.KS = KS; ja.k16 = k16; ja.nH = nH; ja.nT = nT; ja.r0 = (int)r0; ja.RB = RB; ja.cx = cx;
         hipLaunchKernelGGL(tc.tile_kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);
       }
-      KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
+      if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else {
       JoinL1Args la{};
       la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = (int)r0; la.RB = RB;
       la.row_start = row_start; la.row_count = row_count; la.cols = cols; la.active_rows = active_rows;
       la.n_active = n_active; la.cx = cx;
-      KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
+      if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
       hipLaunchKernelGGL(k_join_l1, prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(256), 0,
                          st, la);
-      KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
+      if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     }
     hd->stats.join_launches++;
   }
@@ -1271,7 +1369,8 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);
   (void)hipEventElapsedTime(&ms_group, hd->ev[0], hd->ev[3]);
   (void)hipEventElapsedTime(&s.ms_precompute, hd->ev[3], hd->ev[1]);
-  for (int i = 0; i < nbatch; ++i) {
+  if (!timed && hipEventElapsedTime(&ms, hd->ev[1], hd->ev[2]) == hipSuccess) s.ms_join = ms;   // staging of the batches included
+  for (int i = 0; timed && i < nbatch; ++i) {
     if (hipEventElapsedTime(&ms, hd->join_ev[2 * i], hd->join_ev[2 * i + 1]) == hipSuccess) s.ms_join += ms;
     hipEvent_t prev = i == 0 ? hd->ev[1] : hd->join_ev[2 * i - 1];
     if (hipEventElapsedTime(&ms, prev, hd->join_ev[2 * i]) == hipSuccess) ms_between += ms;
