@@ -21,13 +21,37 @@ PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA
 PEAK_VALU_TLANEOPS = 39.3          # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz, plain (unpacked) float32 lane-ops
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per launch of the dense join kernel, from separate rocprofv3 --pmc runs of this script
-# (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 KiB, factors from a plain 1 GiB copy; see profiles/traffic_*.txt).
-# Counters cannot be read from inside the timed run, so the figure is attached to the matching configuration.
-MEASURED_TRAFFIC_BYTES = {
-    ("c2_mid_l2", "k_join_l2_direct", "dense"): 1.07e10,
-    ("c4_large_l2", "k_join_l2_direct", "dense"): 1.60e11,
-}
+
+
+def measured_traffic(workload, kernel, tile_cfg, mode):
+    """HBM-side bytes per launch of a join kernel from profiles/traffic.json: separate rocprofv3 --pmc runs of this
+    script (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a plain copy of known size).
+    Counters cannot be read inside the timed run, so the figure is attached to the configuration it was taken on;
+    None when the file has no entry for this workload, kernel, tile variant and mode."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            entries = json.load(f)["entries"]
+    except (OSError, ValueError, KeyError):
+        return None
+    for e in entries:
+        if (e.get("workload"), e.get("kernel"), e.get("tile_cfg"), e.get("mode")) == (workload, kernel, tile_cfg, mode):
+            return e.get("bytes_per_launch")
+    return None
+
+
+def calibrate(ms_target):
+    """The in-library calibration loops (kgc_calibrate_mfma): what bf16 32x32x16 MFMAs sustain on this machine, alone and
+    when fed as the join kernel is."""
+    import paper_2307_12059_amd as kgc
+    out = {"unit": "TFLOP/s", "ms_target": ms_target, "wave_tile": "4x2 blocks (128 x 64), two waves per SIMD"}
+    for feed, key in ((0, "mfma_only"), (1, "head_fragments_from_lds"), (2, "lds_and_tail_fragments_from_cache")):
+        rc, tf, ms = kgc.kgc_calibrate_mfma(0, feed, ms_target)
+        if rc != 0:
+            raise RuntimeError(f"kgc_calibrate_mfma failed with code {rc}")
+        out[key] = tf
+    rc, tf, ms = kgc.kgc_calibrate_mfma(1, 0, ms_target)
+    out["mfma_only_4x4_tile"] = tf
+    return out
 
 
 def cpu_baseline(wl, target_seconds=20.0):
@@ -70,6 +94,13 @@ def main():
                          "A[r][h] = E[h] + Rv[r], B = E of the workload; needs R * N * d elements of extra memory")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB (reference for the FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--calibrate-mfma", type=int, default=0, metavar="MS",
+                    help="only run the MFMA calibration loops, about this many milliseconds each, and print them as one JSON line")
+    ap.add_argument("--calibration-ms", type=int, default=250,
+                    help="length of each in-run calibration loop behind roofline.frac_calibrated (0: skip)")
+    ap.add_argument("--dense-c4", type=int, default=3, metavar="STEPS",
+                    help="extra dense (prune off) steps on c4_large_l2 (N=100000, d=200), the configuration the MFMA target "
+                         "is stated on, reported as dense_c4 with a roofline of its own (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -94,19 +125,29 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_MiB": args.calibrate_copy, "bytes_read": n * 4, "bytes_written": n * 4, "copies": 3}))
         return
+    if args.calibrate_mfma > 0:
+        print(json.dumps({"calibrate_mfma": calibrate(args.calibrate_mfma), "peak_datasheet": PEAK_BF16_TFLOPS}))
+        return
+
+    def resident(wl):
+        spec = wl.spec
+        if spec.storage == "bf16":
+            E = torch.from_numpy(wl.E_bits.view(np.int16)).cuda().view(torch.bfloat16)
+            Rv = torch.from_numpy(wl.Rv_bits.view(np.int16)).cuda().view(torch.bfloat16)
+        else:
+            E = torch.from_numpy(wl.E).cuda()
+            Rv = torch.from_numpy(wl.Rv).cuda()
+        cap = int(4 * spec.selectivity * spec.n_triples) + 4096
+        return E, Rv, cap, torch.empty((cap, 4), dtype=torch.int32, device="cuda")
+
     wl = workloads.generate(args.workload)
     spec = wl.spec
     N, R, d, p = spec.N, spec.R, spec.d, spec.p
-    if spec.storage == "bf16":
-        E = torch.from_numpy(wl.E_bits.view(np.int16)).cuda().view(torch.bfloat16)
-        Rv = torch.from_numpy(wl.Rv_bits.view(np.int16)).cuda().view(torch.bfloat16)
-    else:
-        E = torch.from_numpy(wl.E).cuda()
-        Rv = torch.from_numpy(wl.Rv).cuda()
-    cap = int(4 * spec.selectivity * spec.n_triples) + 4096
-    out = torch.empty((cap, 4), dtype=torch.int32, device="cuda")
+    E, Rv, cap, out = resident(wl)
 
-    def run(prune, steps, warmup, factorised=False):
+    def run(prune, steps, warmup, factorised=False, wl=wl, E=E, Rv=Rv, cap=cap, out=out):
+        spec = wl.spec
+        N, R, d, p = spec.N, spec.R, spec.d, spec.p
         j = kgc.Join(dtype=spec.storage, prune=kgc.KGC_PRUNE_ON if prune else kgc.KGC_PRUNE_OFF, tile_cfg=args.tile,
                      factorised=factorised)
         res = None
@@ -141,7 +182,8 @@ def main():
         roof["frac"] = roof["achieved"] / roof["peak"]
         roof["traffic"] = None      # filled below for configurations with a committed counter measurement
         v = st["join_variant"]
-        roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_fact" if v == 100 else "k_join_l2_direct" if v >= 15 else "k_join_l2_ares" if v >= 11
+        roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_fact" if v == 100 else "k_join_l2_dense" if v == 18
+                          else "k_join_l2_direct" if v >= 15 else "k_join_l2_ares" if v >= 11
                           else "k_join_l2_stream" if v >= 6 else "k_join_l2")
         roof["tile_cfg"] = v
         roof["launches_per_step"] = launches
@@ -159,13 +201,25 @@ def main():
     est_fact_s = 1.5 * N * N * R / 3.0e13
     want_dense = args.also_dense > 0 and est_dense_s * (args.also_dense + 1) <= 20.0
     dense = main_run if args.prune == "off" else (run(False, args.also_dense, 1) if want_dense else None)
-    roof = dict((dense or main_run)["roofline"])
+    calib = calibrate(args.calibration_ms) if (p == 2 and args.calibration_ms > 0) else None
+
+    def finish_roofline(r, wl_name, n_rows, n_rel, stats, mode):
+        """traffic, algorithmic bytes and the calibrated fraction of a join kernel's roofline block"""
+        r = dict(r)
+        r["traffic"] = measured_traffic(wl_name, r["kernel"], r["tile_cfg"], mode)
+        r["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE / WRITE_SIZE of separate runs, profiles/traffic.json)"
+        if r["bound"] == "mfma":
+            # every staged operand row once: R * N head rows and N tail rows, each in whole 32-wide K slices of bf16
+            k_read = (stats["k_padded"] + 31) // 32 * 32
+            r["algorithmic_bytes"] = 2.0 * k_read * n_rows * (n_rel + 1) if mode == "dense" else None
+            if calib is not None:
+                r["peak_calibrated"] = calib["mfma_only"]
+                r["frac_calibrated"] = r["achieved"] / calib["mfma_only"]
+        return r
+
+    roof = finish_roofline((dense or main_run)["roofline"], spec.name, N, R, (dense or main_run)["stats"],
+                           "dense" if dense is not None else "pruned")
     roof["measured_in"] = "dense (prune off) steps of this invocation" if dense is not None else "the timed (pruned) steps"
-    if dense is not None:
-        roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((spec.name, roof["kernel"], "dense"))
-        roof["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, separate runs)"
-        # every staged operand row read once: R * N head rows and N tail rows of k_padded bf16 values
-        roof["algorithmic_bytes"] = 2.0 * main_run["stats"]["k_padded"] * N * (R + 1) if p == 2 else None
     line = {
         "metric": "triple-scores/sec (effective N\u00b2R) + MFMA util %",
         "value": N * N * R / (main_run["ms_per_step"] * 1e-3),
@@ -189,6 +243,11 @@ def main():
         # view, MFMA-busy cycles and the sustained clock, is in profiles/counters_*.txt)
         "mfma_util_pct": 100.0 * roof["frac"] if p == 2 else None,
     }
+    if calib is not None:
+        line["calibration"] = calib
+    if args.prune == "on":
+        # the timed (pruned) steps' own join kernel: same accounting, on the pairs of the surviving tiles
+        line["roofline_pruned"] = finish_roofline(main_run["roofline"], spec.name, N, R, main_run["stats"], "pruned")
     if dense is not None and dense is not main_run:
         line["dense"] = {"ms_per_step": dense["ms_per_step"], "value": N * N * R / (dense["ms_per_step"] * 1e-3),
                          "hits": dense["count"], "phase_ms": dense["phase_ms"],
@@ -199,6 +258,18 @@ def main():
         assert fr["count"] == main_run["count"], "factorised and main runs disagree on the number of hits"
         line["dense_factorised"] = {"ms_per_step": fr["ms_per_step"], "value": N * N * R / (fr["ms_per_step"] * 1e-3),
                                     "hits": fr["count"], "phase_ms": fr["phase_ms"], "roofline": fr["roofline"]}
+    if args.dense_c4 > 0 and spec.name != "c4_large_l2" and p == 2:
+        # the MFMA target (>= 50 % of the bf16 peak on dense tiles) is stated at N = 100,000, d = 200: a few dense steps there
+        wl4 = workloads.generate("c4_large_l2")
+        E4, Rv4, cap4, out4 = resident(wl4)
+        r4 = run(False, args.dense_c4, 1, wl=wl4, E=E4, Rv=Rv4, cap=cap4, out=out4)
+        s4 = wl4.spec
+        roof4 = finish_roofline(r4["roofline"], s4.name, s4.N, s4.R, r4["stats"], "dense")
+        line["dense_c4"] = {"workload": f"{s4.name}: N={s4.N} R={s4.R} d={s4.d} L2 {s4.storage} storage, delta={wl4.delta:.6g}, prune off",
+                            "steps": args.dense_c4, "ms_per_step": r4["ms_per_step"],
+                            "value": s4.N * s4.N * s4.R / (r4["ms_per_step"] * 1e-3), "hits": r4["count"],
+                            "phase_ms": r4["phase_ms"], "roofline": roof4, "mfma_util_pct": 100.0 * roof4["frac"]}
+        del E4, Rv4, out4
     if args.general_form > 0:
         # the general form of Section 4.3 on the TransE connectors: same kernels, connector outputs supplied here
         A = (E.unsqueeze(0) + Rv.unsqueeze(1)).contiguous()

@@ -77,7 +77,8 @@ typedef struct {
     uint64_t tiles_total;       /* tile triples (r, head tile, tail tile) of the dense problem */
     uint64_t tiles_evaluated;   /* tile triples that went through the join kernel */
     uint64_t tiles_pruned;      /* tiles_total - tiles_evaluated */
-    uint64_t pairs_evaluated;   /* (h, r, t) scored by the join kernel, padding rows excluded */
+    uint64_t pairs_evaluated;   /* (h, r, t) scored by the join kernel: N * N * R with pruning off; with pruning on,
+                                   tiles_evaluated * tile_m * tile_n (padding rows of the grouped layout included) */
     uint64_t candidates;        /* triples that passed the low-precision stage and were re-scored in double */
     uint64_t emitted;           /* hits found (= *count) */
     uint64_t join_launches;     /* launches of the join kernel */

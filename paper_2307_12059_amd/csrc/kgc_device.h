@@ -28,6 +28,13 @@ __device__ __forceinline__ float ld_elem(const void* base, int64_t idx, int dtyp
 }
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63u); }
+// The same value, but opaque to the optimiser where it is taken: address arithmetic that the rare exact path derives
+// from it then stays inside that path instead of being hoisted into (and spilled from) the kernel's prologue.
+__device__ __forceinline__ int lane_id_here() {
+  int l = (int)(threadIdx.x & 63u);
+  asm volatile("" : "+v"(l));
+  return l;
+}
 
 // ---- wave-level compaction (the "generate the results" step of Section 4.5) ----
 // Every lane of the wave calls this with its own predicate.  One ballot gives the hit mask, its
@@ -231,7 +238,7 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
 template <typename MapFn>
 __device__ __forceinline__ void recheck_and_emit(unsigned long long cm, int32_t r, const RecheckCtx& cx,
                                                  MapFn map) {
-  const int lane = lane_id();
+  const int lane = lane_id_here();
   const int grp = lane >> 4, sub = lane & 15;
   unsigned long long ncand = 0ull;
   for (;;) {
