@@ -391,16 +391,16 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       if (b_per_relation)
         k_stage_operands<false><<<stage_all, 256, stage_lds, st>>>(B, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
                                                                  (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
-                                                                 kStageRows, (int64_t)N * d);
+                                                                 kStageRows, (int64_t)N * d, nullptr, delta);
       else if (r0 == 0)
         k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
             B, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
-            kStageRows, 0);
+            kStageRows, 0, nullptr, delta);
       // head rows: all of them (dense), or those of the head tiles that still have tail tiles (pruned)
       const int stage_a = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 16384) : stage_all;
       k_stage_operands<true><<<stage_a, 256, stage_lds, st>>>(A, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
                                                              (uint16_t*)hd->opA.p, nullptr, cnt->max_a, active_rows, n_active, nH, BM,
-                                                             (int64_t)N * d);
+                                                             (int64_t)N * d, nullptr, delta);
       // the maxima only grow from batch to batch: the filter threshold stays on the safe side
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
       JoinStreamArgs sa{};
@@ -1154,7 +1154,8 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
   if (p == 2) {
     k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
-        E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b, nullptr, nullptr, 0, kStageRows);
+        E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b, nullptr, nullptr, 0, kStageRows,
+        0, nullptr, fact ? -1.f : delta);      // (the factorised filter has an error analysis of its own: plain norms)
     if (fact)     // the head side of the factorised form carries no relation: the plain rows, once
       k_stage_operands<true><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
           E, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p, cnt->max_a, nullptr,
@@ -1286,7 +1287,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
                                    : grid_for((int64_t)RB * (Nslots / kStageRows), 1);
       k_stage_operands<true><<<stage_grid, 256, stage_lds, st>>>(
           E, Rvecs, dtype, d, (int)r0, RB, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p,
-          cnt->max_a, active_rows, n_active, nH, BM);
+          cnt->max_a, active_rows, n_active, nH, BM, 0, nullptr, delta);
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
       if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
       if (tc.stream_kernel) {

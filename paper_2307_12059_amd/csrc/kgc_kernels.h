@@ -68,6 +68,14 @@ __global__ void k_identity_slots(int32_t* slot_ent, int64_t N, int64_t Nslots) {
 // nA + nB - 2 a~.b~ = ||a~ - b~||^2.  The three pieces are the float32 norm cut into 8-bit mantissa
 // chunks, exact in bf16.  Padding rows get a norm of 1e30 so they never pass the filter.  The squared
 // norms are also written out plainly; with the zero pivot they are distA^2 and distB^2 of Section 4.5.
+//
+// Filter slack (slack_delta >= 0, the joins).  Rounding to bf16 moves a row x by e = ||x - x~||, which this
+// kernel MEASURES per row (it holds x and x~) instead of bounding it by 2^-8 ||x||.  By the triangle
+// inequality (the argument of Lemma 1, Section 4.4) a true hit ||a - b|| <= delta has
+//     ||a~ - b~||^2 <= (delta + e_a + e_b)^2 <= delta^2 + (2 delta e_a + 2 e_a^2) + (2 delta e_b + 2 e_b^2),
+// so each row's own term 2 delta e + 2 e^2 is taken off its norm column and the join compares against
+// delta^2 (plus the float32 accumulation bound): rows that round well pay nothing for those that do not.
+// e is widened by 0.1 % and by 2^-23 ||x|| (the float32 addition h + r and its own summation).
 constexpr int kStageRows = 32;
 template <bool IS_A>
 __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__ E, const void* __restrict__ Rv,
@@ -77,7 +85,8 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
                                                         unsigned int* __restrict__ max_slots,
                                                         const uint32_t* __restrict__ active_rows,
                                                         const unsigned int* __restrict__ n_active, int nH, int bm,
-                                                        int64_t rel_stride = 0, const int32_t* __restrict__ n_rows_dev = nullptr) {
+                                                        int64_t rel_stride = 0, const int32_t* __restrict__ n_rows_dev = nullptr,
+                                                        float slack_delta = -1.f) {
   extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [kStageRows][KS * 32 + 8]
   __shared__ int32_t ents[kStageRows];
   __shared__ float wmax[4];
@@ -121,15 +130,29 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
     __syncthreads();
     {   // eight threads per row: norm of the rounded row, then the norm columns and the zero padding
       const int row = tid >> 3, sub = tid & 7;
-      float sq = 0.f;
+      float sq = 0.f, er = 0.f;
+      const int ent_r = ents[row];
       for (int c = sub; c < d; c += 8) {
         const float v = bf16_to_f32(tile[row * W + c]);
         sq += v * v;
+        if (slack_delta >= 0.f && slack_delta <= 3e38f && ent_r >= 0) {   // the row again (from cache), against its rounded copy
+          float x = ld_elem(E, eo + (int64_t)ent_r * d + c, dtype);
+          if (IS_A && Rv) x += ld_elem(Rv, ro + c, dtype);
+          er += (x - v) * (x - v);
+        }
       }
       sq += __shfl_xor(sq, 4, 8);
       sq += __shfl_xor(sq, 2, 8);
       sq += __shfl_xor(sq, 1, 8);
-      const float nrm = ents[row] >= 0 ? sq : 1e30f;
+      er += __shfl_xor(er, 4, 8);
+      er += __shfl_xor(er, 2, 8);
+      er += __shfl_xor(er, 1, 8);
+      float nrm = ent_r >= 0 ? sq : 1e30f;
+      const float plain = nrm;                               // the maxima behind the accumulation bound stay plain
+      if (slack_delta >= 0.f && slack_delta <= 3e38f && ent_r >= 0) {    // (an infinite threshold passes everything anyway)
+        const float e = sqrtf(er) * 1.001f + 1.2e-7f * sqrtf(sq);
+        nrm = sq - (2.f * slack_delta * e + 2.f * e * e) * 1.0001f;
+      }
       uint16_t piece[3];
       float rem = nrm;
 #pragma unroll
@@ -146,8 +169,8 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
         tile[row * W + c] = o;
       }
       if (sub == 0) {
-        if (norms) norms[(int64_t)rl * Nslots + slot0 + row] = nrm;
-        if (ents[row] >= 0) vmax = fmaxf(vmax, nrm);
+        if (norms) norms[(int64_t)rl * Nslots + slot0 + row] = plain;
+        if (ents[row] >= 0) vmax = fmaxf(vmax, plain);
       }
     }
     __syncthreads();
@@ -211,11 +234,9 @@ __global__ __launch_bounds__(256) void k_row_l1_max(const void* __restrict__ X, 
 
 // Filter thresholds, computed on the device so that no host round trip sits between kernel 1 and the join.
 //
-// L2.  a~, b~ are a, b rounded to bf16 (unit roundoff 2^-8), so ||a~ - a|| <= 2^-8 ||a|| and likewise b.
-// By the triangle inequality (the argument of Lemma 1, Section 4.4) a true hit ||a - b|| <= delta has
-// ||a~ - b~|| <= delta + m with m = u (max||a|| + max||b||), u slightly above 2^-8.  The contraction
-// returns ||a~ - b~||^2 with an accumulated float32 error of at most e_acc, so the filter keeps
-// D <= (delta + m)^2 + e_acc and loses no hit.  With bf16 storage b~ = b and drops out of m.
+// L2.  The staged norm columns already carry every row's own rounding slack (see k_stage_operands), so that a
+// true hit has D' = ||a~ - b~||^2 - slack_a - slack_b <= delta^2.  The contraction returns D' with an accumulated
+// float32 error of at most e_acc, so the filter keeps D' <= delta^2 + e_acc and loses no hit.
 // L1.  The float32 sum of |fl(fl(h + r) - t)| differs from the exact sum by at most
 // 2^-23 (max||h||_1 + max||r||_1) + (d + 2) 2^-23 (delta + that); the filter keeps sums below delta + margin.
 __global__ __launch_bounds__(64) void k_join_params(DevCounters* cnt, JoinParams* prm, float delta, int p, int dtype,
@@ -234,12 +255,8 @@ __global__ __launch_bounds__(64) void k_join_params(DevCounters* cnt, JoinParams
   if (delta < 0.f) {
     thr = -1.f;                                   // squared distances and sums are >= 0: nothing passes
   } else if (p == 2) {
-    const float u = 1.01f / 256.f;
-    const float na = sqrtf(ma) * 1.01f, nb = sqrtf(mb) * 1.01f;
-    const float m = u * (na + (dtype == KGC_BF16 ? 0.f : nb));
     const float eacc = (float)(kp + 16) * 1.2e-7f * 2.f * (ma + mb);
-    const float dm = delta + m;
-    thr = (dm * dm + eacc) * (1.f + 1e-6f);
+    thr = (delta * delta + eacc) * (1.f + 1e-6f);
   } else {
     const float base = 1.2e-7f * (ma + mb);
     thr = (delta + base + (float)(d + 2) * 1.2e-7f * (delta + base)) * (1.f + 1e-6f);
