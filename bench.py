@@ -237,6 +237,7 @@ def main():
                   "pruned_frac": main_run["stats"]["tiles_pruned"] / max(1, main_run["stats"]["tiles_total"])},
         "groups": main_run["stats"]["groups"],
         "candidates": main_run["stats"]["candidates"],
+        "exact_blocks": main_run["stats"]["exact_blocks"],
         "phase_ms": main_run["phase_ms"],
         "roofline": roof,
         # MFMA utilisation of the dense join tiles: algorithmic flop rate over the bf16 MFMA peak (the counter

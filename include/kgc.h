@@ -92,7 +92,8 @@ typedef struct {
     int32_t  relation_batches;
     int32_t  join_variant;      /* which join kernel ran: 0 = L1 (VALU); for L2 the tile_cfg number that was used,
                                    100 = the relation-factorised kernel */
-    int32_t  reserved;
+    int32_t  exact_blocks;      /* 32 x 32 blocks of pairs that the pruned L2 joins re-scored as whole blocks in double
+                                   precision (their candidates come in patches); 0 for the other paths */
 } kgc_stats;
 
 /* Create a handle.  cfg may be NULL (defaults).  Returns KGC_OK and stores the handle in *out (host),

@@ -46,7 +46,7 @@ class kgc_stats(ctypes.Structure):
                 ("ms_total", ctypes.c_float), ("ms_precompute", ctypes.c_float), ("ms_prune", ctypes.c_float),
                 ("ms_join", ctypes.c_float), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
                 ("k_padded", ctypes.c_int32), ("relation_batches", ctypes.c_int32), ("join_variant", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("exact_blocks", ctypes.c_int32)]
 
     def as_dict(self) -> dict:
         return {name: getattr(self, name) for name, _ in self._fields_}

@@ -33,6 +33,7 @@ constexpr int64_t kL2RangeBytes = 1ll << 20;
 constexpr int64_t kL2RangeBytesResident = 4ll << 20;   // head-resident blocks leave the whole L2 to the tail rows
 constexpr size_t kMaxLds = 160 * 1024;         // LDS per workgroup on gfx950
 constexpr int64_t kMaxTileList = 1ll << 30;    // entries of the surviving-tile list per relation batch (4 bytes each)
+constexpr unsigned int kExactListCap = 1u << 20;   // accumulator blocks one batch may list for the exact stage (16 bytes each)
 
 struct DevBuf {
   void* p = nullptr;
@@ -54,6 +55,7 @@ struct kgc_handle {
   // every DevBuf member must also be listed in kgc_destroy
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
   DevBuf unit_first, unit_n, cent_u, rad_u, cnorm_u, gram_u, relu_u, pair_list, pair_count;   // two-level bound test
+  DevBuf xlist;                                // accumulator blocks listed for the exact stage (pruned L2 joins)
   DevBuf zero_row, cent_a, rad_a;              // kgc_join_ab: the zero relation row; micro-tile summaries of A[r]
   DevBuf top1_a, top1_b, top1_pick, top_samples, topk_state;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
@@ -128,7 +130,7 @@ struct TileCfg {
   void (*stream_kernel)(const JoinStreamArgs);    // one block per (relation, head tile), streaming over tail tiles
   void (*listed_kernel)(const JoinStreamArgs);    // the same kernel walking the tile lists of pruned mode
   bool head_resident;                             // stream_kernel keeps the head tile's K slices in LDS (dynamic LDS)
-  size_t static_lds;                              // head-resident kernels: bytes of their candidate queue
+  size_t static_lds;                              // head-resident kernels: bytes of static LDS beside the tiles (none today)
   int blocks_per_cu;                              // head-resident kernels: workgroups meant to share one CU's LDS
   int tail_buffers;                               // head-resident kernels: tail slices held in LDS (0: tail rows bypass LDS)
 };
@@ -145,10 +147,10 @@ const TileCfg kL2Tiles[] = {
     {128, 128, 256, nullptr, k_join_l2_stream<128, 128, 2, 2, 2, false>, k_join_l2_stream<128, 128, 2, 2, 2, true>, false, 0, 1, 2},
     {256, 256, 512, nullptr, k_join_l2_stream<256, 256, 4, 2, 1, false>, k_join_l2_stream<256, 256, 4, 2, 1, true>, false, 0, 1, 2},
     {128, 256, 256, nullptr, k_join_l2_stream<128, 256, 2, 2, 2, false>, k_join_l2_stream<128, 256, 2, 2, 2, true>, false, 0, 1, 2},
-    {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 4, 2, 1, 512, false>, k_join_l2_ares<256, 256, 4, 2, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
-    {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 2, 4, 1, 512, false>, k_join_l2_ares<256, 256, 2, 4, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
-    {256, 128, 512, nullptr, k_join_l2_ares<256, 128, 4, 2, 1, 512, false>, k_join_l2_ares<256, 128, 4, 2, 1, 512, true>, true, sizeof(BlockQueueT<512>), 1, 2},
-    {128, 128, 256, nullptr, k_join_l2_ares<128, 128, 2, 2, 2, 256, false>, k_join_l2_ares<128, 128, 2, 2, 2, 256, true>, true, sizeof(BlockQueueT<256>), 2, 2},
+    {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 4, 2, 1, 512, false>, k_join_l2_ares<256, 256, 4, 2, 1, 512, true>, true, 0, 1, 2},
+    {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 2, 4, 1, 512, false>, k_join_l2_ares<256, 256, 2, 4, 1, 512, true>, true, 0, 1, 2},
+    {256, 128, 512, nullptr, k_join_l2_ares<256, 128, 4, 2, 1, 512, false>, k_join_l2_ares<256, 128, 4, 2, 1, 512, true>, true, 0, 1, 2},
+    {128, 128, 256, nullptr, k_join_l2_ares<128, 128, 2, 2, 2, 256, false>, k_join_l2_ares<128, 128, 2, 2, 2, 256, true>, true, 0, 2, 2},
     {256, 256, 512, nullptr, k_join_l2_direct<256, 2, 4, kEpiJoin>, nullptr, true, 0, 1, 0},
     {256, 256, 512, nullptr, k_join_l2_direct<256, 1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
     {128, 256, 512, nullptr, k_join_l2_direct<128, 1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
@@ -176,8 +178,26 @@ int check_common(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void
   return KGC_OK;
 }
 
+// Which vector reads the exact stage may use on the caller's arrays: decided here, from the addresses, d and the
+// strides (multiples of d), and handed to the kernels in the context.
+void set_alignment(RecheckCtx& cx) {
+  auto al = [](const void* p, uintptr_t a) { return ((uintptr_t)p % a) == 0; };
+  cx.base16 = al(cx.E, 16) && al(cx.Et, 16) && al(cx.Rv, 16) ? 1 : 0;
+  const uintptr_t four = cx.dtype == KGC_BF16 ? 8 : 16;
+  cx.vec_ok = (cx.d % 4 == 0 && al(cx.E, four) && al(cx.Et, four) && al(cx.Rv, four)) ? 1 : 0;
+}
+
 int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, float delta, int KS, int k16, int64_t* Nslots_out,
                uint64_t* n_groups_out, UnitTable* ut_out);        // further down
+
+// the exact stage of the blocks a pruned L2 join kernel has listed (instantiated per storage type and row alignment)
+void launch_exact_blocks(hipStream_t st, const ExactEntry* list, const unsigned int* count, unsigned long long* total,
+                         const RecheckCtx& cx) {
+  const bool bf = cx.dtype == KGC_BF16, vec = cx.vec_ok != 0;
+  auto kern = bf ? (vec ? k_exact_blocks<true, true> : k_exact_blocks<true, false>)
+                 : (vec ? k_exact_blocks<false, true> : k_exact_blocks<false, false>);
+  hipLaunchKernelGGL(kern, dim3(1024), dim3(256), 0, st, list, count, kExactListCap, total, cx);
+}
 
 // Blocks for `items` work items, `per_block` each.  A launch may hold fewer than 2^32 threads per grid dimension, so
 // the count stops at 2^24 - 1 blocks (of at most 256 threads): enough for every per-row or per-slot kernel here
@@ -238,7 +258,7 @@ void kgc_destroy(kgc_handle* h) {
                     &h->cent, &h->rad, &h->bitmap, &h->row_start, &h->row_count, &h->cols, &h->active_rows, &h->cnorm,
                     &h->gram, &h->relu, &h->reln, &h->asg_a, &h->asg_b, &h->limr, &h->top1_buf, &h->top1_state,
                     &h->unit_first, &h->unit_n, &h->cent_u, &h->rad_u, &h->cnorm_u, &h->gram_u, &h->relu_u, &h->pair_list,
-                    &h->pair_count, &h->zero_row, &h->cent_a, &h->rad_a, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
+                    &h->pair_count, &h->xlist, &h->zero_row, &h->cent_a, &h->rad_a, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
     release(*b);
   if (h->host_gstate) (void)hipHostFree(h->host_gstate);
   if (h->host_counters) (void)hipHostFree(h->host_counters);
@@ -275,7 +295,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   const int k16 = (d + kNormCols + 15) / 16;
   // the kernels of kgc_join: dense, or (pruned) walking the tile lists
   int tile_id;
-  if (prune) tile_id = ((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile;
+  if (prune) tile_id = ((size_t)KS * 256 + 2 * 256) * kSliceK * 2 <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile;
   else tile_id = KS <= kDirectMaxKS ? kDenseL2Tile : KS <= kDirectHalfMaxKS ? kDirectHalfL2Tile : kDefaultL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
@@ -320,6 +340,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   cx.Rv = hd->zero_row.p; cx.rstride = 0;             // the head rows already are connector_1(h, r)
   cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p; cx.delta = (double)delta;
   cx.out = out_triples; cx.cap = cap; cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates; cx.no_self = 0;
+  set_alignment(cx);
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
   // relation batches: the staged operands, the summaries and the tile lists of a batch must fit the workspace
   const int64_t ws = hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
@@ -420,6 +441,11 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
         }
         KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
       }
+      const bool lists_blocks = tile_id != kDenseL2Tile && tile_id != kDirectL2Tile && tile_id != kDirectHalfL2Tile;
+      if (lists_blocks) {
+        if ((rc = ensure(hd, hd->xlist, (size_t)kExactListCap * sizeof(ExactEntry)))) return rc;
+        sa.xlist = (ExactEntry*)hd->xlist.p; sa.xcount = &cnt->n_exact; sa.xcap = kExactListCap;
+      }
       if (prune) {
         sa.row_start = (const uint32_t*)hd->row_start.p; sa.row_count = (const uint32_t*)hd->row_count.p;
         sa.cols = (const uint32_t*)hd->cols.p; sa.active_rows = active_rows; sa.n_active = n_active;
@@ -431,6 +457,10 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
         nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
         nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
         hipLaunchKernelGGL(kern, dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit), dim3(tc.threads), dyn_lds, st, sa);
+      }
+      if (lists_blocks) {      // the exact stage of what the launch listed, then an empty list for the next batch
+        launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, &cnt->exact_total, cx);
+        k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 1, 0u);
       }
     } else {
       k_row_l1_max<<<grid_for((int64_t)RB * N * 32, 256), 256, 0, st>>>((const char*)A + (size_t)r0 * N * d * esz, (int64_t)RB * N, d,
@@ -470,6 +500,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   s.k_padded = (p == 2) ? k16 * 16 : d;
   s.relation_batches = nbatch;
   s.join_variant = (p == 2) ? tile_id + 1 : 0;
+  s.exact_blocks = (int32_t)std::min<unsigned long long>(hd->host_counters->exact_total, 2147483647ull);
   (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);
   (void)hipEventElapsedTime(&s.ms_join, hd->join_ev[0], hd->join_ev[1]);   // staging, summaries and bound of each batch included
   s.ms_precompute = s.ms_total - s.ms_join;
@@ -714,6 +745,7 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   Top1State host{};
   RecheckCtx cx{};
   cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
+  set_alignment(cx);
 
   double sample_bound = 0.0, bound = 0.0;
   if ((rc = top_bounds(hd, E, N, d, Rvecs, 0, R, p, exclude_self, cx, &sample_bound, &bound, nullptr)) != KGC_OK) return rc;
@@ -781,6 +813,7 @@ int kgc_topk_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   RecheckCtx cx{};
   cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr;
   cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
+  set_alignment(cx);
   const double eligible = (double)N * (double)N * (double)Rn - (exclude_self ? (double)N * (double)Rn : 0.0);
 
   // thresholds to try: from just above the smallest distance upwards.  The k-th smallest of the sampled
@@ -1023,7 +1056,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   const int k16 = (d + kNormCols + 15) / 16;
   // automatic choice.  Dense: the barrier-free head-resident kernel while the head tile fits in LDS with
   // some room to spare (256 rows for KS <= 9, d <= 282; 128 rows for KS <= 19, d <= 602).  Pruned: the head-resident kernel with its candidate queue
-  // (KS <= 7, d <= 218).  Otherwise the streaming kernel.
+  // (KS <= 8, d <= 250).  Otherwise the streaming kernel.
   // the relation-factorised form (optional, dense L2 only, head tile in LDS) has one tile shape of its own
   const bool fact = hd->cfg.factorised != 0 && p == 2 && !prune && KS <= kDirectMaxKS;
   int tile_id = kDefaultL2Tile;
@@ -1031,7 +1064,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   else if (hd->cfg.tile_cfg > 0) tile_id = hd->cfg.tile_cfg - 1;
   else if (!prune && KS <= kDirectMaxKS) tile_id = kDenseL2Tile;
   else if (!prune && KS <= kDirectHalfMaxKS) tile_id = kDirectHalfL2Tile;
-  else if (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 + sizeof(BlockQueue) <= kMaxLds) tile_id = kResidentL2Tile;
+  else if (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 <= kMaxLds) tile_id = kResidentL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
   if (p == 2 && prune && !tc.listed_kernel)
     return fail(hd, KGC_E_INVALID, "this tile variant has no pruned mode; choose a streaming variant");
@@ -1120,6 +1153,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
   cx.delta = (double)delta; cx.out = out_triples; cx.cap = cap; cx.no_self = hd->no_self;
   cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates;
+  set_alignment(cx);
 
   KGC_HIP(hd, hipEventRecord(hd->ev[3], st));     // end of grouping
   if (prune) {
@@ -1132,7 +1166,11 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.n_rows = n_micro; ta.Y = hd->cent.p; ta.dtypeY = KGC_F32;
         ta.n_cols = n_micro; ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.d = d; ta.matrix = (float*)hd->gram.p;
         const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), 1);
-        k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
+        if (n_micro <= 4096)      // few centres: small tiles, so that the launch fills the chip
+          k_small_matrix<2><<<dim3((unsigned)((n_micro + 31) / 32), (unsigned)((n_micro + 31) / 32), 1), 256, 0, st>>>(
+              hd->cent.p, KGC_F32, n_micro, (const float*)hd->cent.p, n_micro, d, (float*)hd->gram.p);
+        else
+          k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
       }
       if (use_units) {
         k_unit_summary<2><<<(unsigned)ut.n_units, 64, 0, st>>>((const float*)hd->cent.p, (const float*)hd->rad.p, d, ut,
@@ -1188,7 +1226,11 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           td.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); td.dtypeX = dtype; td.n_rows = RB;
           td.Y = hd->cent.p; td.dtypeY = KGC_F32; td.n_cols = n_micro; td.shift = nullptr; td.dtype_shift = KGC_F32;
           td.d = d; td.matrix = (float*)hd->relu.p;
-          k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((n_micro + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(td);
+          if (n_micro <= 4096 && RB <= 4096)
+            k_small_matrix<0><<<dim3((unsigned)((n_micro + 31) / 32), (unsigned)((RB + 31) / 32), 1), 256, 0, st>>>(
+                td.X, dtype, RB, (const float*)hd->cent.p, n_micro, d, (float*)hd->relu.p);
+          else
+            k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((n_micro + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(td);
         }
         BoundL2Args ba{};
         ba.D = fine_direct ? nullptr : (const float*)hd->gram.p; ba.u = (const float*)hd->relu.p; ba.rn = (const float*)hd->reln.p;
@@ -1328,7 +1370,19 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
         }
         const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit);
+        // the head-resident and streaming kernels list the accumulator blocks that hold candidates; a kernel of its own
+        // then scores the list (the barrier-free dense kernels re-score in place: their candidates are few per tile)
+        const bool lists_blocks = tile_id != kDenseL2Tile && tile_id != kDirectL2Tile && tile_id != kDirectL2Tile + 1 &&
+                                  tile_id != kDirectHalfL2Tile;
+        if (lists_blocks) {
+          if ((rc = ensure(hd, hd->xlist, (size_t)kExactListCap * sizeof(ExactEntry)))) return rc;
+          sa.xlist = (ExactEntry*)hd->xlist.p; sa.xcount = &cnt->n_exact; sa.xcap = kExactListCap;
+        }
         hipLaunchKernelGGL(kern, grid, dim3(tc.threads), dyn_lds, st, sa);
+        if (lists_blocks) {
+          launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, &cnt->exact_total, cx);
+          k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 1, 0u);
+        }
       } else {
         JoinArgs ja{};
         ja.A = (const uint16_t*)hd->opA.p; ja.B = (const uint16_t*)hd->opB.p; ja.prm = prm;
@@ -1365,6 +1419,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   s.k_padded = (p == 2) ? k16 * 16 : d;
   s.relation_batches = nbatch;
   s.join_variant = (p == 2) ? (fact ? 100 : tile_id + 1) : 0;
+  s.exact_blocks = (int32_t)std::min<unsigned long long>(hd->host_counters->exact_total, 2147483647ull);
   // phase times from the events: [ev0 grouping ev3 | summaries + B staging ev1 | per batch: bound test + A staging | join]
   float ms = 0.f, ms_group = 0.f, ms_between = 0.f;
   (void)hipEventElapsedTime(&s.ms_total, hd->ev[0], hd->ev[2]);

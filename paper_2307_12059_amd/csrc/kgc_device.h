@@ -85,6 +85,10 @@ struct RecheckCtx {
   unsigned long long* hit_counter;
   unsigned long long* cand_counter;
   int no_self;               // 1: candidates with h == t are dropped (the top-1 search without self pairs)
+  // alignment of the caller's arrays, decided on the host (bases, d and strides), never found out on the device:
+  int base16;                // 1: E, Et and Rv start on 16-byte boundaries (the 16-byte row reads of the per-candidate form
+                             //    also need d % 4 == 0 for float32, d % 8 == 0 for bfloat16)
+  int vec_ok;                // 1: every row starts on a boundary of four elements (16 bytes float32, 8 bytes bfloat16)
 };
 
 // Exact score of one triple by a 16-lane group (the TransE distance of Section 4.3 in double):
@@ -98,7 +102,7 @@ __device__ __forceinline__ double group16_exact_dist(const RecheckCtx& cx, int32
                 ro = (int64_t)r * cx.rstride;
   double s0 = 0.0, s1 = 0.0;
   const bool p2 = cx.p == 2;
-  if (cx.dtype == KGC_F32 && (d & 3) == 0) {
+  if (cx.dtype == KGC_F32 && (d & 3) == 0 && cx.base16) {
     const float4* eh = (const float4*)((const float*)cx.E + ho);
     const float4* et = (const float4*)((const float*)cx.Et + to);
     const float4* rv = (const float4*)((const float*)cx.Rv + ro);
@@ -111,7 +115,7 @@ __device__ __forceinline__ double group16_exact_dist(const RecheckCtx& cx, int32
       s0 += p2 ? (x0 * x0 + x1 * x1) : (fabs(x0) + fabs(x1));
       s1 += p2 ? (x2 * x2 + x3 * x3) : (fabs(x2) + fabs(x3));
     }
-  } else if (cx.dtype == KGC_BF16 && (d & 7) == 0) {
+  } else if (cx.dtype == KGC_BF16 && (d & 7) == 0 && cx.base16) {
     const uint4* eh = (const uint4*)((const uint16_t*)cx.E + ho);
     const uint4* et = (const uint4*)((const uint16_t*)cx.Et + to);
     const uint4* rv = (const uint4*)((const uint16_t*)cx.Rv + ro);
@@ -165,7 +169,7 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
     to[n] = (int64_t)r * cx.tstride + (int64_t)(ok ? t[n] : 0) * d;
     s0[n] = 0.0; s1[n] = 0.0;
   }
-  if (cx.dtype == KGC_F32 && (d & 3) == 0) {
+  if (cx.dtype == KGC_F32 && (d & 3) == 0 && cx.base16) {
     const float4* rv = (const float4*)((const float*)cx.Rv + ro);
     const int nch = d >> 2;
 #pragma unroll 1
@@ -185,7 +189,7 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
         s1[n] += p2 ? (q2 * q2 + q3 * q3) : (fabs(q2) + fabs(q3));
       }
     }
-  } else if (cx.dtype == KGC_BF16 && (d & 7) == 0) {
+  } else if (cx.dtype == KGC_BF16 && (d & 7) == 0 && cx.base16) {
     const uint4* rv = (const uint4*)((const uint16_t*)cx.Rv + ro);
     const int nch = d >> 3;
 #pragma unroll 1
@@ -225,6 +229,188 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
     s += __shfl_xor(s, 2, 16);
     s += __shfl_xor(s, 1, 16);
     out[n] = p2 ? sqrt(s) : s;
+  }
+}
+
+// ---- second stage, block form (L2): one 32 x 32 accumulator block re-scored by its wave on the fp64 matrix pipes ----
+// Filter candidates come in patches: a pair of entity groups that a relation aligns fills much of a 32 x 32
+// accumulator block, and re-scoring its pairs one by one reads every row dozens of times.  Here the wave that owns
+// the block scores ALL its 1,024 pairs at once in double precision: a = (double)E[h] + (double)Rv[r] (exact) and
+// t = (double)Et[t] are the operands of v_mfma_f64_16x16x4_f64, four dimensions per step, four 16 x 16 sub-blocks;
+// the squared norms are summed beside it, and ||a - t||^2 = ||a||^2 + ||t||^2 - 2 a.t (the expansion of Section
+// 4.3's dist for p = 2, now in double: with ||a||^2 + ||t||^2 of the order of d and an unit roundoff of 2^-53 its
+// error is of the order of d^2 2^-53, some 1e-12 of the norms).  A pair is a hit when that value is below delta^2
+// by more than this error, not a hit when it is above by more than it, and in the (practically empty) band between,
+// or when a hit's value is tiny against the norms, the lane falls back to the definition: x_k = (E[h][k] + Rv[r][k]) - Et[t][k] in double, summed over k ascending,
+// sqrt, <= delta.  Every true hit of the block passed the low-precision filter, so testing all pairs of the block
+// gives exactly the hits among its candidates.  Hits leave with ONE atomic per block (a wave prefix sum over the
+// lanes' hit counts).
+//   hs0  slot of the block's first head row;  ts0  slot of its first tail column.   All 64 lanes call this together.
+// Operand layout of the instruction: A[i][k] in lane 16 k + i, B[k][j] in lane 16 k + j, D[i][j] in element i / 4 of
+// lane 16 (i % 4) + j (for double precision the four elements of a lane are four rows apart, not adjacent).
+// It runs in a kernel of its own (k_exact_blocks) over the blocks the pruned join kernels LIST: inside the tile loop
+// it either made the loop spill (inlined) or made every wave launch set up a stack (as a call), and a wave scoring
+// a block held up the seven others of its tile; listed, the blocks of a whole launch are scored side by side.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+struct ExactEntry { int32_t r, hs0, ts0, pad; };             // relation, first head slot, first tail slot of a block
+// four consecutive elements k .. k + 3 of a row, widened to float.  VEC: the row starts on a boundary of four
+// elements and d is a multiple of four (one 16- or 8-byte load); otherwise element by element, zeros past d.
+template <bool BF16, bool VEC>
+__device__ __forceinline__ f32x4_t exact_ld4(const void* base, int64_t off, int k, int d) {
+  f32x4_t o = {0.f, 0.f, 0.f, 0.f};
+  if (VEC) {
+    const int kc = k < d ? k : 0;                      // (past the end: a valid address, the values are not used)
+    if (BF16) {
+      const uint2 v = *(const uint2*)((const uint16_t*)base + off + kc);
+      o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+      o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+    } else {
+      const float4 v = *(const float4*)((const float*)base + off + kc);
+      o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int ke = k + e < d ? k + e : 0;
+      o[e] = BF16 ? bf16_to_f32(((const uint16_t*)base)[off + ke]) : ((const float*)base)[off + ke];
+    }
+  }
+  return o;
+}
+// BF16: the storage type of the rows; VEC: rows may be read four elements at a time (template parameters, so that
+// the loads below are straight-line code)
+template <bool BF16, bool VEC>
+__device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, int64_t hs0, int64_t ts0) {
+  const int lane = lane_id_here();
+  const int rr = lane & 15, kk = lane >> 4;         // operand row (or column), and which of a step's four operand slots
+  const int d = cx.d, dtype = cx.dtype;
+  int32_t hent[2], tent[2];
+  int64_t ho[2], to[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    hent[q] = cx.slot_ent[hs0 + 16 * q + rr];
+    tent[q] = cx.slot_ent[ts0 + 16 * q + rr];
+    ho[q] = (int64_t)r * cx.hstride + (int64_t)(hent[q] < 0 ? 0 : hent[q]) * d;
+    to[q] = (int64_t)r * cx.tstride + (int64_t)(tent[q] < 0 ? 0 : tent[q]) * d;
+  }
+  const int64_t ro = (int64_t)r * cx.rstride;
+  f64x4_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+  double na[2] = {0.0, 0.0}, nt[2] = {0.0, 0.0};
+  // A dot product does not care in which order its dimensions are taken as long as both operands agree, so the four
+  // operand slots of a step need not hold four CONSECUTIVE dimensions: the dimensions are taken in groups of 16, and
+  // lane (row, slot) reads the four consecutive elements 16 g + 4 slot .. + 3 of its row in one load and feeds them
+  // to four successive steps (step e of the group multiplies dimensions 16 g + 4 slot + e, slot = 0 .. 3).
+  // The rows are walked in chunks of kGroups groups: ALL loads of a chunk are issued before any is used, so a chunk
+  // costs one memory round trip.  Elements past d count as zero.
+  constexpr int kGroups = 8;
+  for (int k0 = 0; k0 < d; k0 += 16 * kGroups) {
+    f32x4_t hv[2][kGroups], tv[2][kGroups], rv[kGroups];
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+      const int k = k0 + 16 * g + 4 * kk;
+      rv[g] = exact_ld4<BF16, VEC>(cx.Rv, ro, k, d);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        hv[q][g] = exact_ld4<BF16, VEC>(cx.E, ho[q], k, d);
+        tv[q][g] = exact_ld4<BF16, VEC>(cx.Et, to[q], k, d);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);                 // (the loads stay together, ahead of the arithmetic)
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+      if (k0 + 16 * g >= d) break;                     // the same for the whole wave
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool in = k0 + 16 * g + 4 * kk + e < d;
+        double av[2], bv[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          av[q] = in ? (double)hv[q][g][e] + (double)rv[g][e] : 0.0;
+          bv[q] = in ? (double)tv[q][g][e] : 0.0;
+          na[q] += av[q] * av[q];
+          nt[q] += bv[q] * bv[q];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i], bv[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+  // a row's norm: the sum over the four lanes that hold its operand slots 0 .. 3
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    na[q] += __shfl_xor(na[q], 16, 64); na[q] += __shfl_xor(na[q], 32, 64);
+    nt[q] += __shfl_xor(nt[q], 16, 64); nt[q] += __shfl_xor(nt[q], 32, 64);
+  }
+  const double d2 = cx.delta * cx.delta;
+  uint32_t hit = 0u;
+  float dist[16];
+  int32_t hsel[16];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int hrow = 4 * v + kk;                   // the pair's head row inside sub-block row i: held by lane hrow
+      const double nah = __shfl(na[i], hrow, 64);
+      const int32_t h = __shfl(hent[i], hrow, 64);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int e = (i * 2 + j) * 4 + v;
+        const int32_t t = tent[j];
+        const double scale = nah + nt[j];
+        const double D = scale - 2.0 * acc[i][j][v];
+        double dd = 0.0;
+        bool ok = D <= d2;
+        const bool valid = h >= 0 && t >= 0 && !(cx.no_self && h == t);
+        // too close to call from the expansion, or so small against the norms that its square root would carry the
+        // expansion's error into the reported distance (near-duplicate rows, self pairs under r = 0): the definition
+        if (valid && (fabs(D - d2) <= 1e-11 * scale || (D <= d2 && D < 1e-6 * scale))) {
+          double ssum = 0.0;
+          const int64_t hoff = (int64_t)r * cx.hstride + (int64_t)h * d, toff = (int64_t)r * cx.tstride + (int64_t)t * d;
+          for (int k = 0; k < d; ++k) {
+            const double x = ((double)ld_elem(cx.E, hoff + k, dtype) + (double)ld_elem(cx.Rv, ro + k, dtype)) -
+                             (double)ld_elem(cx.Et, toff + k, dtype);
+            ssum += x * x;
+          }
+          dd = sqrt(ssum);
+          ok = dd <= cx.delta;
+        } else if (valid && ok) {
+          dd = sqrt(D > 0.0 ? D : 0.0);                 // (a square root in double is long: only where it is reported)
+        }
+        hsel[e] = h;
+        dist[e] = (float)dd;
+        if (valid && ok) hit |= 1u << e;
+      }
+    }
+  const int nh = __builtin_popcount(hit);
+  int incl = nh;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += o;
+  }
+  const int total = __shfl(incl, 63, 64);
+  if (total > 0) {
+    unsigned long long base = 0ull;
+    if (lane == 63) base = atomicAdd(cx.hit_counter, (unsigned long long)total);
+    const uint32_t blo = (uint32_t)__shfl((int)(uint32_t)(base & 0xffffffffull), 63, 64);
+    const uint32_t bhi = (uint32_t)__shfl((int)(uint32_t)(base >> 32), 63, 64);
+    unsigned long long pos = (((unsigned long long)bhi << 32) | blo) + (unsigned long long)(incl - nh);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      if (!((hit >> e) & 1u)) continue;
+      if (pos < cx.cap) {
+        kgc_triple rec;
+        rec.h = hsel[e]; rec.r = r; rec.t = tent[(e >> 2) & 1]; rec.dist = dist[e];
+        cx.out[pos] = rec;
+      }
+      ++pos;
+    }
   }
 }
 

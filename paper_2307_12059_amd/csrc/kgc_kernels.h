@@ -39,8 +39,11 @@ struct DevCounters {
   unsigned int n_active;          // rows (relation, head tile) of the batch that still have tail tiles
   unsigned int pad0;
   unsigned long long tiles;       // surviving tiles over all batches
+  unsigned long long exact_total; // accumulator blocks scored by the block form of the exact stage, over all batches
   unsigned int max_a[1024];       // running maxima of ||bf16(h + r)||^2 (L2) or ||e||_1 (L1), float bits, spread over slots
   unsigned int max_b[1024];       // running maxima of ||bf16(t)||^2 (L2) or ||r||_1 (L1)
+  unsigned int n_exact;           // accumulator blocks listed for the exact stage by the pruned L2 join kernels (per batch)
+  unsigned int pad1;
 };
 
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
@@ -424,6 +427,9 @@ struct JoinStreamArgs {
   RecheckCtx cx;
   // Group assignment (k_join_l2_direct<.., kEpiAssignMin>): heads are all entities in identity order, tails
   // the pivots of a covering round, staged in an array of their own with tail_slots rows.
+  ExactEntry* xlist;                  // pruned mode: where the kernel lists the accumulator blocks that hold candidates,
+  unsigned int* xcount;               // how many it has listed, and how many the list holds; a block that finds the
+  unsigned int xcap;                  // list full is re-scored on the spot, candidate by candidate
   int cols_lds;                       // head-resident listed kernel: entries of LDS reserved for a row's tile list
   int b_per_rel;                      // 1: the tail operands are staged per relation, [RB][KS][Nslots][32] like A
   int64_t tail_slots;                 // rows per K slice of B when it differs from Nslots (0: the same)
@@ -435,6 +441,36 @@ struct JoinStreamArgs {
   int64_t n_heads;                    // entities (head slots past it are padding)
 };
 enum { kEpiJoin = 0, kEpiAssignMin = 1, kEpiMinDist = 2 };
+
+// A 32 x 32 accumulator block with candidates (mask: this lane's 16 elements), at the end of a tile of a pruned join:
+// listed for k_exact_blocks, or, when the list is full, re-scored here candidate by candidate.
+__device__ __forceinline__ void list_block(const JoinStreamArgs& a, uint32_t mask, int32_t r, int64_t hs0, int64_t ts0) {
+  const int lane = lane_id();
+  unsigned int idx = 0u;
+  if (lane == 0) idx = atomicAdd(a.xcount, 1u);
+  idx = (unsigned int)__shfl((int)idx, 0, 64);
+  if (idx < a.xcap) {
+    if (lane == 0) a.xlist[idx] = ExactEntry{r, (int32_t)hs0, (int32_t)ts0, 0};
+  } else {
+    recheck_and_emit((unsigned long long)mask, r, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
+      hslot = hs0 + 8 * (e >> 2) + 4 * (src >> 5) + (e & 3);
+      tslot = ts0 + (src & 31);
+    });
+  }
+}
+
+// The exact stage of the pruned L2 joins: one wave per listed block (exact_block_l2), the grid strides over the list.
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(256, 2) void k_exact_blocks(const ExactEntry* __restrict__ list, const unsigned int* __restrict__ count,
+                                                      unsigned int cap, unsigned long long* __restrict__ total, const RecheckCtx cx) {
+  const unsigned int n = *count < cap ? *count : cap;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *total += n;
+  const unsigned int w0 = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+  for (unsigned int e = w0; e < n; e += nw) {
+    const ExactEntry x = list[e];
+    exact_block_l2<BF16, VEC>(x.r, cx, (int64_t)x.hs0, (int64_t)x.ts0);
+  }
+}
 
 // LISTED: the block walks tile lists (pruned mode); otherwise the grid enumerates the dense problem and the
 // kernel holds no load of the list in its inner loop (such a load would make every tile end wait for all
@@ -448,13 +484,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
   constexpr int ASZ = BM * kSliceK, BSZ = BN * kSliceK;      // elements per LDS buffer (64-byte rows, swizzled)
   static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
 
-  __shared__ BlockQueueT<(LISTED ? 512 : 1)> queue;          // pruned mode: candidates are re-scored by the whole block
   __shared__ __attribute__((aligned(16))) uint16_t As[2 * ASZ];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[2 * BSZ];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  if (LISTED && tid == 0) { queue.count = 0u; queue.pending = 0u; queue.flag = 0u; queue.nhits = 0u; }   // published by the first barrier
+  int ncand_lane = 0;                                        // pruned mode: candidates this lane sent to the exact stage
 
   // pruned mode: the grid strides over the rows (relation, head tile) that still have tail tiles
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
@@ -605,34 +640,31 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
     const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;
     constexpr int NW = (TM * TN + 3) / 4;
     if constexpr (LISTED) {
-      // Surviving tiles hold their hits in clusters: the block re-scores them together (one output atomic per
-      // round instead of one per wave step).  The decision to enter is made block-uniform through queue.flag.
-      if (has && lane == 0) queue.flag = 1u;
-      __syncthreads();
-      if (queue.flag) {
-        unsigned long long cm[NW];
+      // Surviving tiles hold their candidates in patches: each accumulator block that has some is re-scored as a
+      // whole in double precision by a kernel of its own: here it is only listed (list_block).
+      if (has) {
+        uint32_t masks[TM * TN];
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-          cm[w] = 0ull;
-          if (has) {
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int tile = w * 4 + q;
-              if (tile < TM * TN) {
-                const int i = tile / TN, j = tile % TN;
+          for (int j = 0; j < TN; ++j) {
+            uint32_t mask = 0u;
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                  if (acc[i][j][v] <= thr) cm[w] |= 1ull << (q * 16 + v);
-              }
-            }
+            for (int v = 0; v < 16; ++v)
+              if (acc[i][j][v] <= thr) mask |= 1u << v;
+            masks[i * TN + j] = mask;
+          }
+        // one copy of the exact path: the blocks are walked by a real loop, their masks picked by selects
+#pragma unroll 1
+        for (int b = 0; b < TM * TN; ++b) {
+          uint32_t mask = 0u;
+#pragma unroll
+          for (int k = 0; k < TM * TN; ++k) mask = (b == k) ? masks[k] : mask;
+          if (__builtin_amdgcn_ballot_w64(mask != 0u) != 0ull) {
+            ncand_lane += __builtin_popcount(mask);
+            list_block(a, mask, a.r0 + rl, hbase + (b / TN) * 32, tbase + (b % TN) * 32);
           }
         }
-        block_recheck<WGM * WGN, NW, 1>(cm, a.r0 + rl, a.cx, &queue, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
-          const int tile = e >> 4, v = e & 15;
-          const int i = tile / TN, j = tile % TN;
-          hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);
-          tslot = tbase + j * 32 + (src & 31);
-        });
       }
     } else if (has) {
 #pragma unroll
@@ -663,6 +695,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 #undef KGC_MFMA_STEP
   if (!LISTED) break;
   }   // rows
+  if (LISTED) {
+    for (int off = 32; off > 0; off >>= 1) ncand_lane += __shfl_xor(ncand_lane, off, 64);
+    if (lane == 0 && ncand_lane) atomicAdd(a.cx.cand_counter, (unsigned long long)ncand_lane);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -670,8 +706,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 // head tile (the staged a = h + r rows, BM x KS x 64 bytes) into LDS and keeps them there, so only the
 // tail rows are streamed: half the global -> LDS traffic per tile, and the L2 only has to hold the tail
 // range.  Tail slices are prefetched two slices ahead through two register sets.  Needs
-// (KS * BM + 2 * BN) * 64 bytes of LDS plus the candidate queue (QCAP entries of 24 bytes): KS <= 7
-// (d <= 218) with one 256 x 256 block per CU, or with two 128 x 128 blocks per CU whose barriers and
+// (KS * BM + 2 * BN) * 64 bytes of LDS: KS <= 8 (d <= 250) with one 256 x 256 block per CU, or with two 128 x 128 blocks per CU whose barriers and
 // tile ends then fall at different times, so that one block's MFMAs fill the other's bubbles.
 template <int BM, int BN, int WGM, int WGN, int MINB, int QCAP, bool LISTED>
 __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const JoinStreamArgs a) {
@@ -683,14 +718,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
   static_assert(LA * NT == BM * 4 && LB * NT == BN * 4, "tile rows must divide over the threads");
 
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [KS][BM][32] head slices, then [2][BN][32] tail slices
-  __shared__ BlockQueueT<QCAP> queue;
   const int KS = a.KS;
   uint16_t* Ares = lds;
   uint16_t* Bs = lds + KS * ASZ;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  if (tid == 0) { queue.count = 0u; queue.pending = 0u; queue.flag = 0u; queue.nhits = 0u; }   // published by the prologue barrier
+  int ncand_lane = 0;                                        // candidates this lane sent to the exact stage
 
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
@@ -783,8 +817,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
   const int last_two = (a.k16 - (KS - 1) * 2) >= 2;
   const int total = ntiles * KS;
   int ck = 0, ct = 0;
-  int tcol_cur = tcol, done_tcol = tcol;
-  bool tile_done = false, done_has = false;
+  int tcol_cur = tcol;
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -820,60 +853,43 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
       KGC_MFMA_STEP(fa, fb);                                                                      \
     }                                                                                             \
     if (last_slice) {                                                                             \
-      /* end of a tile: does any element pass the filter?  The exact path runs after the block barrier. */ \
+      /* End of a tile: does any element pass the filter?  Candidates come in patches, so every accumulator    */ \
+      /* block that holds some is listed for the exact kernel (list_block): no queue, no extra barrier.         */ \
+      /* MFMA 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32. */ \
       float mn = acc[0][0][0];                                                                    \
       _Pragma("unroll") for (int i = 0; i < TM; ++i)                                              \
         _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
           _Pragma("unroll") for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);            \
-      done_has = __builtin_amdgcn_ballot_w64(mn <= thr) != 0ull;                                  \
-      if (done_has && lane == 0) queue.flag = 1u;                                                 \
-      tile_done = true;                                                                           \
-      done_tcol = tcol_cur;                                                                       \
-      ck = 0;                                                                                     \
-      if (++ct < ntiles) tcol_cur = lcols ? (int)lcols[ct] : cols ? (int)cols[t_begin + ct] : t_begin + ct; \
-    } else {                                                                                      \
-      ++ck;                                                                                       \
-    }                                                                                             \
-  } while (0)
-
-  // After the barrier that ends a tile's last slice: if any wave flagged candidates, the whole block
-  // re-scores them together.  MFMA 32x32 accumulator layout: register v of lane l holds row
-  // 8*(v/4) + 4*(l/32) + (v%4), column l%32; element index = (mfma tile * 16 + v).
-#define KGC_TILE_END()                                                                            \
-  do {                                                                                            \
-    if (tile_done) {                                                                              \
-      tile_done = false;                                                                          \
-      if (queue.flag) {                                                                           \
-        constexpr int NW = (TM * TN + 3) / 4;                                                     \
-        unsigned long long cm[NW];                                                                \
-        _Pragma("unroll") for (int w = 0; w < NW; ++w) {                                          \
-          cm[w] = 0ull;                                                                           \
-          if (done_has) {                                                                         \
-            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
-              const int tile = w * 4 + q;                                                         \
-              if (tile < TM * TN) {                                                               \
-                const int i = tile / TN, j = tile % TN;                                           \
-                _Pragma("unroll") for (int v = 0; v < 16; ++v)                                    \
-                  if (acc[i][j][v] <= thr) cm[w] |= 1ull << (q * 16 + v);                         \
-              }                                                                                   \
-            }                                                                                     \
+      if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {                                       \
+        const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
+        const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;                                  \
+        uint32_t masks[TM * TN];                                                                  \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
+          _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                        \
+            uint32_t mask = 0u;                                                                   \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v)                                        \
+              if (acc[i][j][v] <= thr) mask |= 1u << v;                                           \
+            masks[i * TN + j] = mask;                                                             \
+          }                                                                                       \
+        /* one copy of the exact path: the blocks are walked by a real loop, their masks picked by selects */ \
+        _Pragma("unroll 1") for (int b = 0; b < TM * TN; ++b) {                                   \
+          uint32_t mask = 0u;                                                                     \
+          _Pragma("unroll") for (int k = 0; k < TM * TN; ++k) mask = (b == k) ? masks[k] : mask;  \
+          if (__builtin_amdgcn_ballot_w64(mask != 0u) != 0ull) {                                  \
+            ncand_lane += __builtin_popcount(mask);                                               \
+            list_block(a, mask, a.r0 + rl, hbase + (b / TN) * 32, tbase + (b % TN) * 32);          \
           }                                                                                       \
         }                                                                                         \
-        const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
-        const int64_t tbase = (int64_t)done_tcol * BN + wn * WTN;                                 \
-        block_recheck<WGM * WGN, NW, 4>(cm, a.r0 + rl, a.cx, &queue,                                 \
-                                     [=](int e, int src, int64_t& hslot, int64_t& tslot) {        \
-          const int tile = e >> 4, v = e & 15;                                                    \
-          const int i = tile / TN, j = tile % TN;                                                 \
-          hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);                       \
-          tslot = tbase + j * 32 + (src & 31);                                                    \
-        });                                                                                       \
-        /* The accumulators are dead by now (the next tile starts from a zero C operand); writing them */ \
-        /* here says so to the compiler, which then has their 128 registers for the exact path above.  */ \
+        /* The accumulators were dead through the exact path (the next tile starts from a zero C operand); */ \
+        /* writing them here says so to the compiler, which then had their registers for it.              */ \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
           _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;                    \
       }                                                                                           \
+      ck = 0;                                                                                     \
+      if (++ct < ntiles) tcol_cur = lcols ? (int)lcols[ct] : cols ? (int)cols[t_begin + ct] : t_begin + ct; \
+    } else {                                                                                      \
+      ++ck;                                                                                       \
     }                                                                                             \
   } while (0)
 
@@ -892,21 +908,20 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
     KGC_COMPUTE(0);
     KGC_SSTORE(1, rb1);
     __syncthreads();
-    KGC_TILE_END();
     // odd step: slice i + 1 is in buffer 1; set 1 is free for slice i + 3; set 0 holds slice i + 2
     KGC_GLOAD(rb1);
     if (i + 1 < total) KGC_COMPUTE(1);
     KGC_SSTORE(0, rb0);
     __syncthreads();
-    KGC_TILE_END();
   }
-#undef KGC_TILE_END
 #undef KGC_GLOAD
 #undef KGC_SSTORE
 #undef KGC_MFMA_STEP
 #undef KGC_COMPUTE
   if (!LISTED) break;
   }   // rows
+  for (int off = 32; off > 0; off >>= 1) ncand_lane += __shfl_xor(ncand_lane, off, 64);
+  if (lane == 0 && ncand_lane) atomicAdd(a.cx.cand_counter, (unsigned long long)ncand_lane);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -188,16 +188,25 @@ __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E
   for (int off = 32; off > 0; off >>= 1) c2 += __shfl_xor(c2, off, 64);
   if (lane == 0) cnorm[m] = sqrtf(c2) * (1.f + kBoundSlack);
   __syncthreads();   // centre visible to the whole wave (same block)
+  // radius: lane (q, half) sums row q's distance to the centre over one half of the dimensions (its loads are
+  // independent of each other, so they pipeline), the two halves are added, the maximum is taken over the rows
   float rmax = 0.f;
-  for (int q = 0; q < kMicro; ++q) {
-    if (ents[q] < 0) continue;
+  {
+    const int q = lane & 31, half = lane >> 5;
+    const int kmid = (d + 1) / 2;
+    const int kb = half ? kmid : 0, ke = half ? d : kmid;
     float s = 0.f;
-    for (int k = lane; k < d; k += 64) {
-      const float x = ld_elem(E, (int64_t)ents[q] * d + k, dtype) - c[k];
-      s += (P == 2) ? x * x : fabsf(x);
+    if (ents[q] >= 0) {
+      const int64_t eo = (int64_t)ents[q] * d;
+#pragma unroll 4
+      for (int k = kb; k < ke; ++k) {
+        const float x = ld_elem(E, eo + k, dtype) - c[k];
+        s += (P == 2) ? x * x : fabsf(x);
+      }
     }
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    rmax = fmaxf(rmax, (P == 2) ? sqrtf(s) : s);
+    s += __shfl_xor(s, 32, 64);
+    rmax = (P == 2) ? sqrtf(s) : s;
+    for (int off = 16; off > 0; off >>= 1) rmax = fmaxf(rmax, __shfl_xor(rmax, off, 64));
   }
   if (lane == 0) rad[m] = rmax * (1.f + kBoundSlack) + 1e-30f;
 }
@@ -443,6 +452,46 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
         }
       }
     }
+  }
+}
+
+// The same MATRIX results for small operands (a few hundred to a few thousand rows and columns: micro-tile centres,
+// relation vectors), where the 128 x 128 tiles above leave most of the chip idle: 32 x 32 results per block of 256
+// threads, K through LDS 32 dimensions at a time, four rows x one column per thread.  out[i][j] = ||x_i - y_j||^2
+// (P = 2) or x_i . y_j (P = 0), row-major n_rows x n_cols; X rows of the given type, Y rows float32.
+template <int P>
+__global__ __launch_bounds__(256) void k_small_matrix(const void* __restrict__ X, int dtypeX, int64_t n_rows,
+                                                      const float* __restrict__ Y, int64_t n_cols, int d,
+                                                      float* __restrict__ out) {
+  __shared__ float xs[32][33], ys[32][33];
+  const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
+  const int64_t row0 = (int64_t)blockIdx.y * 32, col0 = (int64_t)blockIdx.x * 32;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < d; k0 += 32) {
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int rw = ty + 8 * q, k = k0 + tx;
+      const bool in = k < d;
+      xs[rw][tx] = (in && row0 + rw < n_rows) ? ld_elem(X, (row0 + rw) * d + k, dtypeX) : 0.f;
+      ys[rw][tx] = (in && col0 + rw < n_cols) ? Y[(col0 + rw) * d + k] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      const float b = ys[tx][k];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = xs[ty + 8 * q][k];
+        if (P == 0) acc[q] += a * b;
+        else { const float x = a - b; acc[q] += x * x; }
+      }
+    }
+  }
+  if (col0 + tx < n_cols) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (row0 + ty + 8 * q < n_rows) out[(row0 + ty + 8 * q) * n_cols + col0 + tx] = acc[q];
   }
 }
 
