@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -55,7 +56,8 @@ struct kgc_handle {
   // every DevBuf member must also be listed in kgc_destroy
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
   DevBuf unit_first, unit_n, cent_u, rad_u, cnorm_u, gram_u, relu_u, pair_list, pair_count;   // two-level bound test
-  DevBuf xlist;                                // accumulator blocks listed for the exact stage (pruned L2 joins)
+  DevBuf xlist;                                // accumulator blocks listed for the exact stage (L2 joins)
+  unsigned int xcap = kExactListCap;           // its length in entries: grows when a batch wanted to list more
   DevBuf zero_row, cent_a, rad_a;              // kgc_join_ab: the zero relation row; micro-tile summaries of A[r]
   DevBuf top1_a, top1_b, top1_pick, top_samples, topk_state;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
@@ -157,7 +159,16 @@ const TileCfg kL2Tiles[] = {
     {256, 256, 512, nullptr, k_join_l2_dense<1>, nullptr, true, 0, 1, 0},      // placeholder: see dense_kernel_for
 };
 constexpr int kDefaultL2Tile = 8;                 // index into kL2Tiles: streaming, 256 x 256, 8 waves
-constexpr int kResidentL2Tile = 11;               // head-resident, 256 x 256, 8 waves (2 x 4)
+constexpr int kResidentL2Tile = 13;               // head-resident, 128 x 128, 4 waves, two blocks per CU (pruned default)
+constexpr int kResidentLargeL2Tile = 11;          // head-resident, 256 x 256, 8 waves (2 x 4): pruned joins over many entities
+constexpr int64_t kResidentLargeN = 1 << 18;      // ... from this many on: rows then hold many surviving tiles each, and the
+                                                  // larger wave tile (half the LDS reads per MFMA) pays; below, the finer
+                                                  // tiles follow the surviving patches more closely and balance better
+// the pruned default for N entities and KS slices (both head-resident shapes need KS <= 8 to fit their LDS)
+inline int pruned_l2_tile(int64_t N, int KS, int fallback) {
+  if (((size_t)KS * 128 + 2 * 128) * kSliceK * 2 * 2 > kMaxLds) return fallback;
+  return N >= kResidentLargeN ? kResidentLargeL2Tile : kResidentL2Tile;
+}
 constexpr int kDirectL2Tile = 14;                 // head-resident and barrier-free (dense mode only), 8 waves (2 x 4)
 constexpr int kDenseL2Tile = 17;                  // the same with a straight-line tile body per number of K steps (dense default)
 constexpr int kDirectMaxKS = 9;                   // its head tile then takes 144 of the 160 KiB of LDS
@@ -191,12 +202,12 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
                uint64_t* n_groups_out, UnitTable* ut_out);        // further down
 
 // the exact stage of the blocks a pruned L2 join kernel has listed (instantiated per storage type and row alignment)
-void launch_exact_blocks(hipStream_t st, const ExactEntry* list, const unsigned int* count, unsigned long long* total,
-                         const RecheckCtx& cx) {
+void launch_exact_blocks(hipStream_t st, const ExactEntry* list, const unsigned int* count, unsigned int cap,
+                         unsigned long long* total, unsigned int* need, const RecheckCtx& cx) {
   const bool bf = cx.dtype == KGC_BF16, vec = cx.vec_ok != 0;
   auto kern = bf ? (vec ? k_exact_blocks<true, true> : k_exact_blocks<true, false>)
                  : (vec ? k_exact_blocks<false, true> : k_exact_blocks<false, false>);
-  hipLaunchKernelGGL(kern, dim3(1024), dim3(256), 0, st, list, count, kExactListCap, total, cx);
+  hipLaunchKernelGGL(kern, dim3(1024), dim3(256), 0, st, list, count, cap, total, need, cx);
 }
 
 // Blocks for `items` work items, `per_block` each.  A launch may hold fewer than 2^32 threads per grid dimension, so
@@ -237,6 +248,8 @@ int kgc_create(const kgc_config* cfg, kgc_handle** out) {
     if (src != KGC_OK) { delete h; return src; }
   }
   h->err.reserve(256);          // later error messages fit without a host allocation
+  // the first length of the exact stage's block list (it grows by itself; tests set it small to see it grow)
+  if (const char* e = std::getenv("KGC_EXACT_LIST_CAP")) h->xcap = (unsigned int)std::max(1L, std::atol(e));
   if (hipHostMalloc((void**)&h->host_counters, sizeof(DevCounters), hipHostMallocDefault) != hipSuccess) {
     delete h;
     return KGC_E_NOMEM;
@@ -295,7 +308,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   const int k16 = (d + kNormCols + 15) / 16;
   // the kernels of kgc_join: dense, or (pruned) walking the tile lists
   int tile_id;
-  if (prune) tile_id = ((size_t)KS * 256 + 2 * 256) * kSliceK * 2 <= kMaxLds ? kResidentL2Tile : kDefaultL2Tile;
+  if (prune) tile_id = pruned_l2_tile(N, KS, kDefaultL2Tile);
   else tile_id = KS <= kDirectMaxKS ? kDenseL2Tile : KS <= kDirectHalfMaxKS ? kDirectHalfL2Tile : kDefaultL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
@@ -398,7 +411,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), (unsigned)RB);
       if (p == 2) k_tile_dist<2, kEpiBound><<<g, 256, 0, st>>>(ta);
       else k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
-      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 4, 0u);      // cursor and n_active
+      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
       k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 255) / 256), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p, &cnt->n_active);
@@ -418,7 +431,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
             B, nullptr, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, nullptr, cnt->max_b, nullptr, nullptr, 0,
             kStageRows, 0, nullptr, delta);
       // head rows: all of them (dense), or those of the head tiles that still have tail tiles (pruned)
-      const int stage_a = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 16384) : stage_all;
+      const int stage_a = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 4096) : stage_all;
       k_stage_operands<true><<<stage_a, 256, stage_lds, st>>>(A, nullptr, dtype, d, (int)r0, RB, slot_ent, Nslots, KS,
                                                              (uint16_t*)hd->opA.p, nullptr, cnt->max_a, active_rows, n_active, nH, BM,
                                                              (int64_t)N * d, nullptr, delta);
@@ -443,8 +456,8 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       }
       const bool lists_blocks = tile_id != kDenseL2Tile && tile_id != kDirectL2Tile && tile_id != kDirectHalfL2Tile;
       if (lists_blocks) {
-        if ((rc = ensure(hd, hd->xlist, (size_t)kExactListCap * sizeof(ExactEntry)))) return rc;
-        sa.xlist = (ExactEntry*)hd->xlist.p; sa.xcount = &cnt->n_exact; sa.xcap = kExactListCap;
+        if ((rc = ensure(hd, hd->xlist, (size_t)hd->xcap * sizeof(ExactEntry)))) return rc;
+        sa.xlist = (ExactEntry*)hd->xlist.p; sa.xcount = &cnt->n_exact; sa.xcap = hd->xcap;
       }
       if (prune) {
         sa.row_start = (const uint32_t*)hd->row_start.p; sa.row_count = (const uint32_t*)hd->row_count.p;
@@ -459,7 +472,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
         hipLaunchKernelGGL(kern, dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit), dim3(tc.threads), dyn_lds, st, sa);
       }
       if (lists_blocks) {      // the exact stage of what the launch listed, then an empty list for the next batch
-        launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, &cnt->exact_total, cx);
+        launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, hd->xcap, &cnt->exact_total, &cnt->exact_need, cx);
         k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 1, 0u);
       }
     } else {
@@ -487,6 +500,14 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 48, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
   KGC_HIP(hd, hipStreamSynchronize(st));
+
+  // A batch that wanted to list more accumulator blocks than the list holds has dropped the rest (and counted
+  // them): the list grows to what was asked for and the join runs again from the start.
+  if (hd->host_counters->exact_need > hd->xcap) {
+    const unsigned long long need = hd->host_counters->exact_need;
+    hd->xcap = (unsigned int)std::min<unsigned long long>(need + need / 4 + 1024, 0xffffffffull);
+    return kgc_join_ab(hd, A, B, N, d, R, b_per_relation, p, delta, out_triples, cap, count);
+  }
 
   kgc_stats& s = hd->stats;
   s.emitted = hd->host_counters->hits;
@@ -1064,7 +1085,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   else if (hd->cfg.tile_cfg > 0) tile_id = hd->cfg.tile_cfg - 1;
   else if (!prune && KS <= kDirectMaxKS) tile_id = kDenseL2Tile;
   else if (!prune && KS <= kDirectHalfMaxKS) tile_id = kDirectHalfL2Tile;
-  else if (((size_t)KS * 256 + 2 * 256) * kSliceK * 2 <= kMaxLds) tile_id = kResidentL2Tile;
+  else if (prune) tile_id = pruned_l2_tile(N, KS, kDefaultL2Tile);
   const TileCfg tc = kL2Tiles[tile_id];
   if (p == 2 && prune && !tc.listed_kernel)
     return fail(hd, KGC_E_INVALID, "this tile variant has no pruned mode; choose a streaming variant");
@@ -1281,7 +1302,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
         }
       }
-      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 4, 0u);      // cursor and n_active
+      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
       k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 255) / 256), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p,
@@ -1325,7 +1346,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       hipLaunchKernelGGL((k_join_l2_fact<2, 4>), dim3((unsigned)nH, (unsigned)nsplit, 1), dim3(512), dyn_lds, st, fa);
       if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else if (p == 2) {
-      const int stage_grid = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 16384)
+      const int stage_grid = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 4096)
                                    : grid_for((int64_t)RB * (Nslots / kStageRows), 1);
       k_stage_operands<true><<<stage_grid, 256, stage_lds, st>>>(
           E, Rvecs, dtype, d, (int)r0, RB, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p,
@@ -1375,12 +1396,12 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         const bool lists_blocks = tile_id != kDenseL2Tile && tile_id != kDirectL2Tile && tile_id != kDirectL2Tile + 1 &&
                                   tile_id != kDirectHalfL2Tile;
         if (lists_blocks) {
-          if ((rc = ensure(hd, hd->xlist, (size_t)kExactListCap * sizeof(ExactEntry)))) return rc;
-          sa.xlist = (ExactEntry*)hd->xlist.p; sa.xcount = &cnt->n_exact; sa.xcap = kExactListCap;
+          if ((rc = ensure(hd, hd->xlist, (size_t)hd->xcap * sizeof(ExactEntry)))) return rc;
+          sa.xlist = (ExactEntry*)hd->xlist.p; sa.xcount = &cnt->n_exact; sa.xcap = hd->xcap;
         }
         hipLaunchKernelGGL(kern, grid, dim3(tc.threads), dyn_lds, st, sa);
         if (lists_blocks) {
-          launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, &cnt->exact_total, cx);
+          launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, hd->xcap, &cnt->exact_total, &cnt->exact_need, cx);
           k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 1, 0u);
         }
       } else {
@@ -1406,6 +1427,14 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 48, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
   KGC_HIP(hd, hipStreamSynchronize(st));
+
+  // A batch that wanted to list more accumulator blocks than the list holds has dropped the rest (and counted
+  // them): the list grows to what was asked for and the join runs again from the start.
+  if (hd->host_counters->exact_need > hd->xcap) {
+    const unsigned long long need = hd->host_counters->exact_need;
+    hd->xcap = (unsigned int)std::min<unsigned long long>(need + need / 4 + 1024, 0xffffffffull);
+    return kgc_join_range(hd, E, N, d, Rvecs, R, p, delta, r_begin, r_end, out_triples, cap, count);
+  }
 
   kgc_stats& s = hd->stats;
   s.emitted = hd->host_counters->hits;

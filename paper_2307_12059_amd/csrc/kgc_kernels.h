@@ -37,7 +37,7 @@ struct DevCounters {
   unsigned long long candidates;  // triples re-scored in double
   unsigned long long tile_cursor; // next free entry of the surviving-tile list (per relation batch)
   unsigned int n_active;          // rows (relation, head tile) of the batch that still have tail tiles
-  unsigned int pad0;
+  unsigned int exact_need;        // most accumulator blocks any one batch wanted to list (see list_block)
   unsigned long long tiles;       // surviving tiles over all batches
   unsigned long long exact_total; // accumulator blocks scored by the block form of the exact stage, over all batches
   unsigned int max_a[1024];       // running maxima of ||bf16(h + r)||^2 (L2) or ||e||_1 (L1), float bits, spread over slots
@@ -62,9 +62,8 @@ __global__ void k_identity_slots(int32_t* slot_ent, int64_t N, int64_t Nslots) {
 
 // ---------------------------------------------------------------------------------------------
 // Kernel 1.  One block stages kStageRows consecutive slots of one relation (IS_A: the row is
-// a = h + r; otherwise the row is b = t and there is a single "relation").  The rows are read with
-// consecutive threads on consecutive dimensions, rounded to bf16 into an LDS tile, their squared
-// norms ||.||^2 are summed in float32 from the rounded values, and the staged rows
+// a = h + r; otherwise the row is b = t and there is a single "relation").  The rows are rounded to bf16
+// into an LDS tile, their squared norms ||.||^2 are summed in float32 from the rounded values, and the staged rows
 //     A:  [ a~ (d) | nA_hi nA_mid nA_lo | 1 1 1 | 0 ... ]
 //     B:  [ -2 b~ (d) | 1 1 1 | nB_hi nB_mid nB_lo | 0 ... ]
 // are written slice by slice, 16 bytes per thread, so that the dot product of an A row and a B row is
@@ -79,7 +78,60 @@ __global__ void k_identity_slots(int32_t* slot_ent, int64_t N, int64_t Nslots) {
 // so each row's own term 2 delta e + 2 e^2 is taken off its norm column and the join compares against
 // delta^2 (plus the float32 accumulation bound): rows that round well pay nothing for those that do not.
 // e is widened by 0.1 % and by 2^-23 ||x|| (the float32 addition h + r and its own summation).
-constexpr int kStageRows = 32;
+//
+// Work split: a block of four waves stages kStageRows = 64 consecutive slots, 16 per wave, and nothing is shared
+// between the waves (no block barrier).  A wave reads two rows per load instruction, 32 lanes x 4 consecutive
+// dimensions each (one 16-byte or 8-byte load per lane where base and row length allow), keeps the per-row sums of
+// squares in registers (8 row pairs), writes the rounded values to its own LDS tile, reduces the sums across lanes
+// with a halving exchange (9 shuffles for 16 rows), adds the norm columns, and copies the tile out slice by slice,
+// 1 KiB per store instruction.
+constexpr int kStageRows = 64;
+constexpr int kStageWaveRows = 16;
+
+// four consecutive elements of a row from column c on (n = d - c of them exist); vec: 16-byte (f32) / 8-byte (bf16) loads allowed
+__device__ __forceinline__ void stage_ld4(const void* base, int64_t off, int n, int dtype, bool vec, float v[4]) {
+  v[0] = v[1] = v[2] = v[3] = 0.f;
+  if (n <= 0) return;
+  if (vec && n >= 4) {
+    if (dtype == KGC_BF16) {
+      const uint2 t = *(const uint2*)((const uint16_t*)base + off);
+      v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+      v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+    } else {
+      const float4 t = *(const float4*)((const float*)base + off);
+      v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+    return;
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (k < n) v[k] = ld_elem(base, off + k, dtype);
+}
+
+// sums of 8 per-lane values over the 32 lanes of each half wave: afterwards lane l holds the total of value
+// ((l >> 4) & 1) * 4 + ((l >> 3) & 1) * 2 + ((l >> 2) & 1)
+__device__ __forceinline__ float stage_reduce8(const float v[8], int lane) {
+  float a[4], b[2], c;
+  const bool b4 = lane & 16, b3 = lane & 8, b2 = lane & 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float send = b4 ? v[i] : v[i + 4], keep = b4 ? v[i + 4] : v[i];
+    a[i] = keep + __shfl_xor(send, 16, 64);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float send = b3 ? a[i] : a[i + 2], keep = b3 ? a[i + 2] : a[i];
+    b[i] = keep + __shfl_xor(send, 8, 64);
+  }
+  {
+    const float send = b2 ? b[0] : b[1], keep = b2 ? b[1] : b[0];
+    c = keep + __shfl_xor(send, 4, 64);
+  }
+  c += __shfl_xor(c, 2, 64);
+  c += __shfl_xor(c, 1, 64);
+  return c;
+}
+
 template <bool IS_A>
 __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__ E, const void* __restrict__ Rv,
                                                         int dtype, int d, int r0, int RB,
@@ -90,11 +142,15 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
                                                         const unsigned int* __restrict__ n_active, int nH, int bm,
                                                         int64_t rel_stride = 0, const int32_t* __restrict__ n_rows_dev = nullptr,
                                                         float slack_delta = -1.f) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t tile[];   // [kStageRows][KS * 32 + 8]
-  __shared__ int32_t ents[kStageRows];
-  __shared__ float wmax[4];
-  const int tid = threadIdx.x;
+  extern __shared__ __attribute__((aligned(16))) uint16_t tile_all[];   // [4 waves][16 rows][KS * 32 + 8]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
   const int W = KS * kSliceK + 8;
+  uint16_t* tile = tile_all + wave * kStageWaveRows * W;
+  const int esz = dtype == KGC_BF16 ? 2 : 4;
+  // vector loads: every row of E (and of Rv) starts on a 4-element boundary of an aligned array
+  const bool vec = (d % 4 == 0) && ((uintptr_t)E % (4 * esz) == 0) && (!(IS_A && Rv) || (uintptr_t)Rv % (4 * esz) == 0);
+  const bool slack = slack_delta >= 0.f && slack_delta <= 3e38f;       // (an infinite threshold passes everything anyway)
   // dense joins stage every row group of every relation of the batch; pruned joins only the head tiles
   // (rows of the active list) that still have tail tiles to meet
   const int64_t groups_per_rel = Nslots / kStageRows;
@@ -114,94 +170,84 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
     }
     // n_rows_dev: only the first *n_rows_dev slots (rounded up to a 256-row tile) hold rows this time
     if (n_rows_dev && slot0 >= ((int64_t)*n_rows_dev + 255) / 256 * 256) continue;
-    __syncthreads();                                   // previous group fully written out
-    if (tid < kStageRows) ents[tid] = slot_ent[slot0 + tid];
-    __syncthreads();
+    slot0 += wave * kStageWaveRows;
+    const int ent_l = lane < kStageWaveRows ? slot_ent[slot0 + lane] : -1;
     const int64_t ro = (int64_t)(r0 + rl) * d;
     const int64_t eo = (int64_t)(r0 + rl) * rel_stride;       // per-relation source rows (0: one array for all)
-    for (int e = tid; e < kStageRows * d; e += 256) {
-      const int row = e / d, c = e - row * d;
-      const int ent = ents[row];
-      uint16_t o = 0;
-      if (ent >= 0) {
-        float v = ld_elem(E, eo + (int64_t)ent * d + c, dtype);
-        if (IS_A && Rv) v += ld_elem(Rv, ro + c, dtype);     // Rv == nullptr: the plain row (a = h)
-        o = f32_to_bf16_rne(v);
-      }
-      tile[row * W + c] = o;
-    }
-    __syncthreads();
-    {   // eight threads per row: norm of the rounded row, then the norm columns and the zero padding
-      const int row = tid >> 3, sub = tid & 7;
-      float sq = 0.f, er = 0.f;
-      const int ent_r = ents[row];
-      for (int c = sub; c < d; c += 8) {
-        const float v = bf16_to_f32(tile[row * W + c]);
-        sq += v * v;
-        if (slack_delta >= 0.f && slack_delta <= 3e38f && ent_r >= 0) {   // the row again (from cache), against its rounded copy
-          float x = ld_elem(E, eo + (int64_t)ent_r * d + c, dtype);
-          if (IS_A && Rv) x += ld_elem(Rv, ro + c, dtype);
-          er += (x - v) * (x - v);
-        }
-      }
-      sq += __shfl_xor(sq, 4, 8);
-      sq += __shfl_xor(sq, 2, 8);
-      sq += __shfl_xor(sq, 1, 8);
-      er += __shfl_xor(er, 4, 8);
-      er += __shfl_xor(er, 2, 8);
-      er += __shfl_xor(er, 1, 8);
-      float nrm = ent_r >= 0 ? sq : 1e30f;
-      const float plain = nrm;                               // the maxima behind the accumulation bound stay plain
-      if (slack_delta >= 0.f && slack_delta <= 3e38f && ent_r >= 0) {    // (an infinite threshold passes everything anyway)
-        const float e = sqrtf(er) * 1.001f + 1.2e-7f * sqrtf(sq);
-        nrm = sq - (2.f * slack_delta * e + 2.f * e * e) * 1.0001f;
-      }
-      uint16_t piece[3];
-      float rem = nrm;
+    float sq[8], er[8];
 #pragma unroll
-      for (int q = 0; q < 3; ++q) {
-        piece[q] = f32_to_bf16_trunc(rem);
-        rem -= bf16_to_f32(piece[q]);
+    for (int i = 0; i < 8; ++i) sq[i] = er[i] = 0.f;
+    for (int c0 = 0; c0 < KS * kSliceK; c0 += 128) {
+      const int c = c0 + 4 * l32;
+      float rv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (IS_A && Rv) stage_ld4(Rv, ro + c, d - c, dtype, vec, rv);     // Rv == nullptr: the plain row (a = h)
+      float x[8][4];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int ent = __shfl(ent_l, 2 * i + half, 64);
+        stage_ld4(E, eo + (int64_t)(ent < 0 ? 0 : ent) * d + c, ent < 0 ? 0 : d - c, dtype, vec, x[i]);
       }
-      const uint16_t one = 0x3F80u;
-      for (int c = d + sub; c < KS * kSliceK; c += 8) {
-        const int q = c - d;
-        uint16_t o = 0;
-        if (q < 3) o = IS_A ? (q == 0 ? piece[0] : q == 1 ? piece[1] : piece[2]) : one;
-        else if (q < kNormCols) o = IS_A ? one : (q == 3 ? piece[0] : q == 4 ? piece[1] : piece[2]);
-        tile[row * W + c] = o;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        uint16_t o[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float v = x[i][k] + rv[k];                     // (columns past d and padding rows: 0 + 0)
+          o[k] = f32_to_bf16_rne(v);
+          const float f = bf16_to_f32(o[k]);
+          sq[i] += f * f;
+          er[i] += (v - f) * (v - f);
+          if (!IS_A) o[k] = f32_to_bf16_rne(-2.f * f);        // B rows carry -2 b~ (exact: a sign flip and an exponent step)
+        }
+        if (c < KS * kSliceK)
+          *(uint2*)(&tile[(2 * i + half) * W + c]) = make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
       }
-      if (sub == 0) {
+    }
+    // per-row totals: lane l now speaks for row 2 * i + half with i from bits 4, 3, 2 of l (four lanes hold the same)
+    const float sqr = stage_reduce8(sq, lane), err = stage_reduce8(er, lane);
+    {
+      const int i = (((lane >> 4) & 1) << 2) | (((lane >> 3) & 1) << 1) | ((lane >> 2) & 1);
+      const int row = 2 * i + half;
+      const int ent_r = __shfl(ent_l, row, 64);
+      float nrm = ent_r >= 0 ? sqr : 1e30f;
+      const float plain = nrm;                                 // the maxima behind the accumulation bound stay plain
+      if (slack && ent_r >= 0) {
+        const float e = sqrtf(err) * 1.001f + 1.2e-7f * sqrtf(sqr);
+        nrm = sqr - (2.f * slack_delta * e + 2.f * e * e) * 1.0001f;
+      }
+      if ((lane & 3) == 0) {
+        uint16_t piece[3];
+        float rem = nrm;
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+          piece[q] = f32_to_bf16_trunc(rem);
+          rem -= bf16_to_f32(piece[q]);
+        }
+        const uint16_t one = 0x3F80u;
+#pragma unroll
+        for (int q = 0; q < kNormCols; ++q)
+          tile[row * W + d + q] = (q < 3) == IS_A ? piece[q % 3] : one;
         if (norms) norms[(int64_t)rl * Nslots + slot0 + row] = plain;
-        if (ents[row] >= 0) vmax = fmaxf(vmax, plain);
+        if (ent_r >= 0) vmax = fmaxf(vmax, plain);
       }
     }
-    __syncthreads();
-    if (!IS_A) {   // B rows carry -2 b~ (exact: a sign flip and an exponent step)
-      for (int e = tid; e < kStageRows * d; e += 256) {
-        const int row = e / d, c = e - row * d;
-        tile[row * W + c] = f32_to_bf16_rne(-2.f * bf16_to_f32(tile[row * W + c]));
-      }
-      __syncthreads();
-    }
-    // write out: slice ks of these rows is kStageRows * 64 contiguous bytes
-    if (tid < kStageRows * 4) {
-      const int row = tid >> 2, part = tid & 3;
-      uint16_t* obase = out + ((int64_t)rl * KS * Nslots + slot0) * kSliceK + tid * 8;
+    // the tile is this wave's own: its LDS operations complete in order, the fence keeps the compiler from moving them
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    {   // write out: slice ks of these 16 rows is 16 * 64 contiguous bytes
+      const int row = lane >> 2, part = lane & 3;
+      uint16_t* obase = out + ((int64_t)rl * KS * Nslots + slot0) * kSliceK + lane * 8;
       for (int ks = 0; ks < KS; ++ks) {
         const uint4 v = *(const uint4*)(&tile[row * W + ks * kSliceK + part * 8]);
         *(uint4*)(obase + (int64_t)ks * Nslots * kSliceK) = v;
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
   }
-  if (max_slots) {   // one atomic per block, spread over kMaxSlots addresses
+  if (max_slots) {   // one atomic per wave, spread over kMaxSlots addresses
     for (int off = 32; off > 0; off >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, off, 64));
-    if ((tid & 63) == 0) wmax[tid >> 6] = vmax;
-    __syncthreads();
-    if (tid == 0) {
-      const float m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
-      atomicMax(&max_slots[blockIdx.x % kMaxSlots], __float_as_uint(m));   // non-negative floats order like their bits
-    }
+    if (lane == 0) atomicMax(&max_slots[(blockIdx.x * 4 + wave) % kMaxSlots], __float_as_uint(vmax));   // non-negative floats order like their bits
   }
 }
 
@@ -442,29 +488,25 @@ struct JoinStreamArgs {
 };
 enum { kEpiJoin = 0, kEpiAssignMin = 1, kEpiMinDist = 2 };
 
-// A 32 x 32 accumulator block with candidates (mask: this lane's 16 elements), at the end of a tile of a pruned join:
-// listed for k_exact_blocks, or, when the list is full, re-scored here candidate by candidate.
-__device__ __forceinline__ void list_block(const JoinStreamArgs& a, uint32_t mask, int32_t r, int64_t hs0, int64_t ts0) {
-  const int lane = lane_id();
-  unsigned int idx = 0u;
-  if (lane == 0) idx = atomicAdd(a.xcount, 1u);
-  idx = (unsigned int)__shfl((int)idx, 0, 64);
-  if (idx < a.xcap) {
-    if (lane == 0) a.xlist[idx] = ExactEntry{r, (int32_t)hs0, (int32_t)ts0, 0};
-  } else {
-    recheck_and_emit((unsigned long long)mask, r, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
-      hslot = hs0 + 8 * (e >> 2) + 4 * (src >> 5) + (e & 3);
-      tslot = ts0 + (src & 31);
-    });
+// A 32 x 32 accumulator block with candidates, at the end of a tile: listed for k_exact_blocks.  A full list drops
+// the entry but still counts it: the host then sees how long the list has to be and runs the join again.
+__device__ __forceinline__ void list_block(const JoinStreamArgs& a, int32_t r, int64_t hs0, int64_t ts0) {
+  if (lane_id() == 0) {
+    const unsigned int idx = atomicAdd(a.xcount, 1u);
+    if (idx < a.xcap) a.xlist[idx] = ExactEntry{r, (int32_t)hs0, (int32_t)ts0, 0};
   }
 }
 
 // The exact stage of the pruned L2 joins: one wave per listed block (exact_block_l2), the grid strides over the list.
 template <bool BF16, bool VEC>
 __global__ __launch_bounds__(256, 2) void k_exact_blocks(const ExactEntry* __restrict__ list, const unsigned int* __restrict__ count,
-                                                      unsigned int cap, unsigned long long* __restrict__ total, const RecheckCtx cx) {
+                                                      unsigned int cap, unsigned long long* __restrict__ total,
+                                                      unsigned int* __restrict__ need, const RecheckCtx cx) {
   const unsigned int n = *count < cap ? *count : cap;
-  if (blockIdx.x == 0 && threadIdx.x == 0) *total += n;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    *total += n;
+    if (*count > *need) *need = *count;
+  }
   const unsigned int w0 = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
   for (unsigned int e = w0; e < n; e += nw) {
     const ExactEntry x = list[e];
@@ -489,7 +531,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  int ncand_lane = 0;                                        // pruned mode: candidates this lane sent to the exact stage
+  int ncand_lane = 0;                                        // candidates this lane sent to the exact stage
 
   // pruned mode: the grid strides over the rows (relation, head tile) that still have tail tiles
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
@@ -638,56 +680,21 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
     // MFMA 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + (v%4), column l%32.
     const int64_t hbase = (int64_t)tH * BM + wm * WTM;
     const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;
-    constexpr int NW = (TM * TN + 3) / 4;
-    if constexpr (LISTED) {
-      // Surviving tiles hold their candidates in patches: each accumulator block that has some is re-scored as a
-      // whole in double precision by a kernel of its own: here it is only listed (list_block).
-      if (has) {
-        uint32_t masks[TM * TN];
+    // Surviving tiles hold their candidates in patches: each accumulator block that has some is re-scored as a
+    // whole in double precision by a kernel of its own: here it is only listed (list_block).
+    if (has) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            uint32_t mask = 0u;
+        for (int j = 0; j < TN; ++j) {
+          int n = 0;
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-              if (acc[i][j][v] <= thr) mask |= 1u << v;
-            masks[i * TN + j] = mask;
-          }
-        // one copy of the exact path: the blocks are walked by a real loop, their masks picked by selects
-#pragma unroll 1
-        for (int b = 0; b < TM * TN; ++b) {
-          uint32_t mask = 0u;
-#pragma unroll
-          for (int k = 0; k < TM * TN; ++k) mask = (b == k) ? masks[k] : mask;
-          if (__builtin_amdgcn_ballot_w64(mask != 0u) != 0ull) {
-            ncand_lane += __builtin_popcount(mask);
-            list_block(a, mask, a.r0 + rl, hbase + (b / TN) * 32, tbase + (b % TN) * 32);
+          for (int v = 0; v < 16; ++v) n += (acc[i][j][v] <= thr) ? 1 : 0;
+          if (__builtin_amdgcn_ballot_w64(n != 0) != 0ull) {
+            ncand_lane += n;
+            list_block(a, a.r0 + rl, hbase + i * 32, tbase + j * 32);
           }
         }
-      }
-    } else if (has) {
-#pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        unsigned long long cm = 0ull;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int tile = w * 4 + q;
-          if (tile < TM * TN) {
-            const int i = tile / TN, j = tile % TN;
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-              if (acc[i][j][v] <= thr) cm |= 1ull << (q * 16 + v);
-          }
-        }
-        if (__builtin_amdgcn_ballot_w64(cm != 0ull) == 0ull) continue;
-        recheck_and_emit(cm, a.r0 + rl, a.cx, [=](int e, int src, int64_t& hslot, int64_t& tslot) {
-          const int tile = w * 4 + (e >> 4), v = e & 15;
-          const int i = tile / TN, j = tile % TN;
-          hslot = hbase + i * 32 + 8 * (v >> 2) + 4 * (src >> 5) + (v & 3);
-          tslot = tbase + j * 32 + (src & 31);
-        });
-      }
     }
   }
 #undef KGC_GLOAD
@@ -695,10 +702,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_stream(const Jo
 #undef KGC_MFMA_STEP
   if (!LISTED) break;
   }   // rows
-  if (LISTED) {
-    for (int off = 32; off > 0; off >>= 1) ncand_lane += __shfl_xor(ncand_lane, off, 64);
-    if (lane == 0 && ncand_lane) atomicAdd(a.cx.cand_counter, (unsigned long long)ncand_lane);
-  }
+  for (int off = 32; off > 0; off >>= 1) ncand_lane += __shfl_xor(ncand_lane, off, 64);
+  if (lane == 0 && ncand_lane) atomicAdd(a.cx.cand_counter, (unsigned long long)ncand_lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -863,28 +868,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
       if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {                                       \
         const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
         const int64_t tbase = (int64_t)tcol_cur * BN + wn * WTN;                                  \
-        uint32_t masks[TM * TN];                                                                  \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
           _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                        \
-            uint32_t mask = 0u;                                                                   \
-            _Pragma("unroll") for (int v = 0; v < 16; ++v)                                        \
-              if (acc[i][j][v] <= thr) mask |= 1u << v;                                           \
-            masks[i * TN + j] = mask;                                                             \
+            int n = 0;                                                                            \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) n += (acc[i][j][v] <= thr) ? 1 : 0;    \
+            if (__builtin_amdgcn_ballot_w64(n != 0) != 0ull) {                                    \
+              ncand_lane += n;                                                                    \
+              list_block(a, a.r0 + rl, hbase + i * 32, tbase + j * 32);                           \
+            }                                                                                     \
           }                                                                                       \
-        /* one copy of the exact path: the blocks are walked by a real loop, their masks picked by selects */ \
-        _Pragma("unroll 1") for (int b = 0; b < TM * TN; ++b) {                                   \
-          uint32_t mask = 0u;                                                                     \
-          _Pragma("unroll") for (int k = 0; k < TM * TN; ++k) mask = (b == k) ? masks[k] : mask;  \
-          if (__builtin_amdgcn_ballot_w64(mask != 0u) != 0ull) {                                  \
-            ncand_lane += __builtin_popcount(mask);                                               \
-            list_block(a, mask, a.r0 + rl, hbase + (b / TN) * 32, tbase + (b % TN) * 32);          \
-          }                                                                                       \
-        }                                                                                         \
-        /* The accumulators were dead through the exact path (the next tile starts from a zero C operand); */ \
-        /* writing them here says so to the compiler, which then had their registers for it.              */ \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
-          _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
-            _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;                    \
       }                                                                                           \
       ck = 0;                                                                                     \
       if (++ct < ntiles) tcol_cur = lcols ? (int)lcols[ct] : cols ? (int)cols[t_begin + ct] : t_begin + ct; \

@@ -523,7 +523,9 @@ __global__ __launch_bounds__(256) void k_rel_centre_dot(const void* __restrict__
 // not need a d-dimensional loop per (r, H, T):
 //     ||c_H + r - c_T||^2 = ||c_H - c_T||^2 + 2 (r.c_H - r.c_T) + ||r||^2 = D[H][T] + 2 (u[r][H] - u[r][T]) + rn[r]
 // (the same observation that makes distB independent of r in Section 5.2, applied to the bound).  The float32 cancellation error of the sum is bounded by
-// err = 2 (d + 8) 2^-24 ||r|| (||c_H|| + ||c_T||) + 2^-20 D and added on the keeping side.
+// err = 2 (d + 8) 2^-24 ||r|| (||c_H|| + ||c_T||) + (d + 8) 2^-24 D and added on the keeping side: D itself is a float32
+// sum of d squared differences (relative error at most (d + 4) 2^-24 in the worst case), and for TransE data it is far
+// larger than reach^2 (r cancels c_H - c_T), so its error is charged in full, not absorbed in the slack of reach^2.
 constexpr int kRelChunk = 16;
 struct BoundL2Args {
   const float* D; const float* u; const float* rn; const float* rad; const float* cnorm;
@@ -580,7 +582,7 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
     const int64_t mH = mH0 + hq;
     const float D = a.D[mH * a.n_micro + mT];
     const float reach = dsl + rH + rT;
-    const float rhs = reach * reach * (1.f + kBoundSlack) + D * 1.2e-6f - D;
+    const float rhs = reach * reach * (1.f + kBoundSlack) + D * ((float)(a.d + 8) * 6e-8f) - D;
     const float ek = kk * (cnH[hq] + cT);
     const int tH = (int)(mH / a.micro_per_bm);
     uint32_t keep = 0u;
@@ -676,7 +678,7 @@ __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const Uni
     }
     const float D = a.D[mH * a.n_micro + mT];
     const float reach = dsl + rH + rT;
-    const float rhs = reach * reach * (1.f + kBoundSlack) + D * 1.2e-6f - D;
+    const float rhs = reach * reach * (1.f + kBoundSlack) + D * ((float)(a.d + 8) * 6e-8f) - D;
     const float ek = kk * (a.cnorm[mH] + a.cnorm[mT]);
     const float lhs = (2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f)) - 2.f * a.u[(int64_t)rl * a.n_micro + mT] -
                       ek * srn;
@@ -730,7 +732,7 @@ __global__ __launch_bounds__(256) void k_bound_l2_units(const BoundL2Args a, con
     const int64_t mH = mH0 + hq;
     const float D = a.D[mH * a.n_micro + mT];
     const float reach = dsl + rH + rT;
-    const float rhs = reach * reach * (1.f + kBoundSlack) + D * 1.2e-6f - D;
+    const float rhs = reach * reach * (1.f + kBoundSlack) + D * ((float)(a.d + 8) * 6e-8f) - D;
     const float ek = kk * (cnH[hq] + cT);
     uint32_t keep = 0u;
 #pragma unroll

@@ -387,7 +387,7 @@ def test_join_ab_structured_embedding(p, dtype, N, R, d, prune):
     if prune == PRUNE_OFF:
         assert got["stats"]["join_variant"] == (0 if p == 1 else 18 if d <= 282 else 17 if d <= 602 else 9)
     else:
-        assert got["stats"]["join_variant"] == (0 if p == 1 else 12 if d <= 218 else 9)
+        assert got["stats"]["join_variant"] == (0 if p == 1 else 14 if d <= 250 else 9)
         assert got["stats"]["groups"] > 0
         if N >= 1500:
             assert got["stats"]["tiles_pruned"] > 0
