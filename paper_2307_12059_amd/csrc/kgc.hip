@@ -51,7 +51,7 @@ struct kgc_handle {
   kgc_stats stats{};
   DevBuf slot_ent, opB, opA, normsB, normsA, counters, params;
   // pruning scratch
-  DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols;
+  DevBuf gstate, unc_a, unc_b, group_of, piv_ent, best, gsize, goff, gfill, cent, rad, bitmap, row_start, row_count, cols, tile_rows;
   DevBuf active_rows, cnorm, gram, relu, reln, asg_a, asg_b, limr;
   // every DevBuf member must also be listed in kgc_destroy
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
@@ -271,7 +271,7 @@ void kgc_destroy(kgc_handle* h) {
                     &h->cent, &h->rad, &h->bitmap, &h->row_start, &h->row_count, &h->cols, &h->active_rows, &h->cnorm,
                     &h->gram, &h->relu, &h->reln, &h->asg_a, &h->asg_b, &h->limr, &h->top1_buf, &h->top1_state,
                     &h->unit_first, &h->unit_n, &h->cent_u, &h->rad_u, &h->cnorm_u, &h->gram_u, &h->relu_u, &h->pair_list,
-                    &h->pair_count, &h->xlist, &h->zero_row, &h->cent_a, &h->rad_a, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
+                    &h->pair_count, &h->xlist, &h->tile_rows, &h->zero_row, &h->cent_a, &h->rad_a, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
     release(*b);
   if (h->host_gstate) (void)hipHostFree(h->host_gstate);
   if (h->host_counters) (void)hipHostFree(h->host_counters);
@@ -311,6 +311,8 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   if (prune) tile_id = pruned_l2_tile(N, KS, kDefaultL2Tile);
   else tile_id = KS <= kDirectMaxKS ? kDenseL2Tile : KS <= kDirectHalfMaxKS ? kDirectHalfL2Tile : kDefaultL2Tile;
   const TileCfg tc = kL2Tiles[tile_id];
+  // pruned L2 joins on the 128 x 128 head-resident tiles may go tile by tile instead (decided per batch on the device)
+  const bool pairs_ok = prune && p == 2 && tile_id == kResidentL2Tile;
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
   if ((rc = ensure(hd, hd->counters, sizeof(DevCounters))) || (rc = ensure(hd, hd->params, sizeof(JoinParams))) ||
       (rc = ensure(hd, hd->zero_row, (size_t)d * 4)))
@@ -373,6 +375,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
                 (rc = ensure(hd, hd->bitmap, (size_t)RBmax * nH * words_per_row * 4)) ||
                 (rc = ensure(hd, hd->row_start, (size_t)RBmax * nH * 4)) || (rc = ensure(hd, hd->row_count, (size_t)RBmax * nH * 4)) ||
                 (rc = ensure(hd, hd->cols, (size_t)RBmax * tiles_per_rel * 4)) ||
+                (pairs_ok && (rc = ensure(hd, hd->tile_rows, (size_t)RBmax * tiles_per_rel * 4))) ||
                 (rc = ensure(hd, hd->active_rows, (size_t)RBmax * nH * 4))))
     return rc;
   const unsigned row_grid_max = 4096;
@@ -412,10 +415,11 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       if (p == 2) k_tile_dist<2, kEpiBound><<<g, 256, 0, st>>>(ta);
       else k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
       k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
-      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 255) / 256), 256, 0, st>>>(
+      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 256 * kBitmapRowsPerLane - 1) / (256 * kBitmapRowsPerLane)), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
-          (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p, &cnt->n_active);
-      k_add_u64<<<1, 64, 0, st>>>(&cnt->tiles, &cnt->tile_cursor);
+          (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p, &cnt->n_active,
+          pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr);
+      k_batch_tiles<<<1, 64, 0, st>>>(cnt, pairs_ok ? 1 : 0);
       active_rows = (const uint32_t*)hd->active_rows.p;
       n_active = &cnt->n_active;
     }
@@ -462,7 +466,13 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       if (prune) {
         sa.row_start = (const uint32_t*)hd->row_start.p; sa.row_count = (const uint32_t*)hd->row_count.p;
         sa.cols = (const uint32_t*)hd->cols.p; sa.active_rows = active_rows; sa.n_active = n_active;
+        if (pairs_ok) { sa.tile_rows = (const uint32_t*)hd->tile_rows.p; sa.tile_total = &cnt->tile_cursor; sa.pair_mode = &cnt->pair_mode; }
         hipLaunchKernelGGL(kern, dim3(row_grid, 1, 1), dim3(tc.threads), dyn_lds, st, sa);
+        if (pairs_ok) {
+          const size_t pair_lds = (size_t)2 * KS * 128 * kSliceK * 2;
+          KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_pairs, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pair_lds));
+          hipLaunchKernelGGL(k_join_l2_pairs, dim3(2048), dim3(256), pair_lds, st, sa);
+        }
       } else {
         const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
         const int64_t range_bytes = tc.head_resident ? kL2RangeBytesResident : kL2RangeBytes;
@@ -1087,6 +1097,8 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   else if (!prune && KS <= kDirectHalfMaxKS) tile_id = kDirectHalfL2Tile;
   else if (prune) tile_id = pruned_l2_tile(N, KS, kDefaultL2Tile);
   const TileCfg tc = kL2Tiles[tile_id];
+  // pruned L2 joins on the 128 x 128 head-resident tiles may go tile by tile instead (decided per batch on the device)
+  const bool pairs_ok = prune && p == 2 && tile_id == kResidentL2Tile;
   if (p == 2 && prune && !tc.listed_kernel)
     return fail(hd, KGC_E_INVALID, "this tile variant has no pruned mode; choose a streaming variant");
   const int BM = (p == 2) ? tc.bm : kL1Tile, BN = (p == 2) ? tc.bn : kL1Tile;
@@ -1144,6 +1156,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         (rc = ensure(hd, hd->row_start, (size_t)RBmax * nH * 4)) ||
         (rc = ensure(hd, hd->row_count, (size_t)RBmax * nH * 4)) ||
         (rc = ensure(hd, hd->cols, (size_t)RBmax * tiles_per_rel * 4)) ||
+        (pairs_ok && (rc = ensure(hd, hd->tile_rows, (size_t)RBmax * tiles_per_rel * 4))) ||
         (rc = ensure(hd, hd->active_rows, (size_t)RBmax * nH * 4)) || (rc = ensure(hd, hd->cnorm, n_micro * 4)))
       return rc;
     if (p == 2 && ((rc = ensure(hd, hd->gram, (size_t)n_micro * n_micro * 4)) ||
@@ -1303,11 +1316,11 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         }
       }
       k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
-      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 255) / 256), 256, 0, st>>>(
+      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 256 * kBitmapRowsPerLane - 1) / (256 * kBitmapRowsPerLane)), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p,
-          &cnt->n_active);
-      k_add_u64<<<1, 64, 0, st>>>(&cnt->tiles, &cnt->tile_cursor);
+          &cnt->n_active, pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr);
+      k_batch_tiles<<<1, 64, 0, st>>>(cnt, pairs_ok ? 1 : 0);
       row_start = (const uint32_t*)hd->row_start.p;
       row_count = (const uint32_t*)hd->row_count.p;
       cols = (const uint32_t*)hd->cols.p;
@@ -1399,7 +1412,13 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           if ((rc = ensure(hd, hd->xlist, (size_t)hd->xcap * sizeof(ExactEntry)))) return rc;
           sa.xlist = (ExactEntry*)hd->xlist.p; sa.xcount = &cnt->n_exact; sa.xcap = hd->xcap;
         }
+        if (pairs_ok) { sa.tile_rows = (const uint32_t*)hd->tile_rows.p; sa.tile_total = &cnt->tile_cursor; sa.pair_mode = &cnt->pair_mode; }
         hipLaunchKernelGGL(kern, grid, dim3(tc.threads), dyn_lds, st, sa);
+        if (pairs_ok) {          // the same batch tile by tile, when the device chose that (the other kernel then returned at once)
+          const size_t pair_lds = (size_t)2 * KS * 128 * kSliceK * 2;
+          KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_pairs, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pair_lds));
+          hipLaunchKernelGGL(k_join_l2_pairs, dim3(2048), dim3(256), pair_lds, st, sa);
+        }
         if (lists_blocks) {
           launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, hd->xcap, &cnt->exact_total, &cnt->exact_need, cx);
           k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 1, 0u);

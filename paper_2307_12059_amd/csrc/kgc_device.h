@@ -253,13 +253,13 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
 // a block held up the seven others of its tile; listed, the blocks of a whole launch are scored side by side.
 typedef double f64x4_t __attribute__((ext_vector_type(4)));
 struct ExactEntry { int32_t r, hs0, ts0, pad; };             // relation, first head slot, first tail slot of a block
-// four consecutive elements k .. k + 3 of a row, widened to float.  VEC: the row starts on a boundary of four
-// elements and d is a multiple of four (one 16- or 8-byte load); otherwise element by element, zeros past d.
+// four consecutive elements k .. k + 3 of a row, widened to float, zeros past d.  VEC: the row starts on a boundary of
+// four elements and d is a multiple of four (one 16- or 8-byte load); otherwise element by element.
 template <bool BF16, bool VEC>
 __device__ __forceinline__ f32x4_t exact_ld4(const void* base, int64_t off, int k, int d) {
   f32x4_t o = {0.f, 0.f, 0.f, 0.f};
   if (VEC) {
-    const int kc = k < d ? k : 0;                      // (past the end: a valid address, the values are not used)
+    const int kc = k < d ? k : 0;                      // (past the end: a valid address, the values are dropped)
     if (BF16) {
       const uint2 v = *(const uint2*)((const uint16_t*)base + off + kc);
       o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
@@ -268,11 +268,13 @@ __device__ __forceinline__ f32x4_t exact_ld4(const void* base, int64_t off, int 
       const float4 v = *(const float4*)((const float*)base + off + kc);
       o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
     }
+    if (k >= d) o = f32x4_t{0.f, 0.f, 0.f, 0.f};
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int ke = k + e < d ? k + e : 0;
-      o[e] = BF16 ? bf16_to_f32(((const uint16_t*)base)[off + ke]) : ((const float*)base)[off + ke];
+      const float x = BF16 ? bf16_to_f32(((const uint16_t*)base)[off + ke]) : ((const float*)base)[off + ke];
+      o[e] = k + e < d ? x : 0.f;
     }
   }
   return o;
@@ -325,12 +327,11 @@ __device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, 
       if (k0 + 16 * g >= d) break;                     // the same for the whole wave
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const bool in = k0 + 16 * g + 4 * kk + e < d;
         double av[2], bv[2];
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-          av[q] = in ? (double)hv[q][g][e] + (double)rv[g][e] : 0.0;
-          bv[q] = in ? (double)tv[q][g][e] : 0.0;
+          av[q] = (double)hv[q][g][e] + (double)rv[g][e];     // (elements past d were read as zeros)
+          bv[q] = (double)tv[q][g][e];
           na[q] += av[q] * av[q];
           nt[q] += bv[q] * bv[q];
         }
@@ -364,7 +365,7 @@ __device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, 
         const int32_t t = tent[j];
         const double scale = nah + nt[j];
         const double D = scale - 2.0 * acc[i][j][v];
-        double dd = 0.0;
+        float dd = 0.f;                                // (reported in float32: no square root in double needed)
         bool ok = D <= d2;
         const bool valid = h >= 0 && t >= 0 && !(cx.no_self && h == t);
         // too close to call from the expansion, or so small against the norms that its square root would carry the
@@ -377,13 +378,14 @@ __device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, 
                              (double)ld_elem(cx.Et, toff + k, dtype);
             ssum += x * x;
           }
-          dd = sqrt(ssum);
-          ok = dd <= cx.delta;
+          const double ds = sqrt(ssum);
+          ok = ds <= cx.delta;
+          dd = (float)ds;
         } else if (valid && ok) {
-          dd = sqrt(D > 0.0 ? D : 0.0);                 // (a square root in double is long: only where it is reported)
+          dd = sqrtf((float)(D > 0.0 ? D : 0.0));
         }
         hsel[e] = h;
-        dist[e] = (float)dd;
+        dist[e] = dd;
         if (valid && ok) hit |= 1u << e;
       }
     }

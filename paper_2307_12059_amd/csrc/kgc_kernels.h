@@ -43,7 +43,7 @@ struct DevCounters {
   unsigned int max_a[1024];       // running maxima of ||bf16(h + r)||^2 (L2) or ||e||_1 (L1), float bits, spread over slots
   unsigned int max_b[1024];       // running maxima of ||bf16(t)||^2 (L2) or ||r||_1 (L1)
   unsigned int n_exact;           // accumulator blocks listed for the exact stage by the pruned L2 join kernels (per batch)
-  unsigned int pad1;
+  unsigned int pair_mode;         // pruned L2 batch: 1 = its rows keep so few tiles that they are taken tile by tile
 };
 
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
@@ -52,6 +52,16 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
 
 __global__ void k_add_u64(unsigned long long* dst, const unsigned long long* src) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *dst += *src;
+}
+
+// after the tile lists of a pruned batch: the running total of surviving tiles, and which L2 join kernel takes the
+// batch: tile by tile when its rows keep at most kPairModeTilesPerRow tiles on average (and the host allows it)
+constexpr unsigned long long kPairModeTilesPerRow = 3;
+__global__ void k_batch_tiles(DevCounters* c, int allow_pairs) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    c->tiles += c->tile_cursor;
+    c->pair_mode = (allow_pairs && c->tile_cursor <= kPairModeTilesPerRow * c->n_active && c->tile_cursor < 0xffffffffull) ? 1u : 0u;
+  }
 }
 
 // slot -> entity for the dense order: identity, -1 on the padding rows
@@ -476,6 +486,9 @@ struct JoinStreamArgs {
   ExactEntry* xlist;                  // pruned mode: where the kernel lists the accumulator blocks that hold candidates,
   unsigned int* xcount;               // how many it has listed, and how many the list holds; a block that finds the
   unsigned int xcap;                  // list full is re-scored on the spot, candidate by candidate
+  const uint32_t* tile_rows;          // pruned mode, tile-at-a-time kernel: the row of every entry of cols ...
+  const unsigned long long* tile_total;   // ... how many entries there are ...
+  const unsigned int* pair_mode;      // ... and whether that kernel (1) or the row-walking one (0) takes this batch
   int cols_lds;                       // head-resident listed kernel: entries of LDS reserved for a row's tile list
   int b_per_rel;                      // 1: the tail operands are staged per relation, [RB][KS][Nslots][32] like A
   int64_t tail_slots;                 // rows per K slice of B when it differs from Nslots (0: the same)
@@ -497,7 +510,8 @@ __device__ __forceinline__ void list_block(const JoinStreamArgs& a, int32_t r, i
   }
 }
 
-// The exact stage of the pruned L2 joins: one wave per listed block (exact_block_l2), the grid strides over the list.
+// The exact stage of the L2 joins that list blocks: one wave per listed block (exact_block_l2), the grid strides over
+// the list.
 template <bool BF16, bool VEC>
 __global__ __launch_bounds__(256, 2) void k_exact_blocks(const ExactEntry* __restrict__ list, const unsigned int* __restrict__ count,
                                                       unsigned int cap, unsigned long long* __restrict__ total,
@@ -730,6 +744,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   int ncand_lane = 0;                                        // candidates this lane sent to the exact stage
+  if (LISTED && a.pair_mode && *a.pair_mode) return;         // this batch goes tile by tile (k_join_l2_pairs)
 
   for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
   int tH, rl, t_begin, t_end;
@@ -763,13 +778,22 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
   const int rd_b = (wn * WTN + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
   const int rd_step = (((lane >> 5) ^ rsw) & 2) ? -16 : 16;
 
-  // ---- head tile: all K slices into LDS, once ----
-  for (int ks = 0; ks < KS; ++ks) {
-    uint4 t[LA];
+  // ---- head tile: all K slices into LDS, once; four slices' loads in flight together (a row with one or two
+  // ---- tiles is mostly memory round trips); past the last slice the loads repeat it and nothing is stored
+  for (int ks0 = 0; ks0 < KS; ks0 += 4) {
+    uint4 t[4][LA];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) t[i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+    for (int j = 0; j < 4; ++j) {
+      const int ks = ks0 + j < KS ? ks0 + j : KS - 1;
 #pragma unroll
-    for (int i = 0; i < LA; ++i) *(uint4*)(&Ares[ks * ASZ + st0 + i * st_step]) = t[i];
+      for (int i = 0; i < LA; ++i) t[j][i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (ks0 + j < KS) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) *(uint4*)(&Ares[(ks0 + j) * ASZ + st0 + i * st_step]) = t[j][i];
+      }
   }
 
   // The tile list of the row goes to LDS behind the tail buffers when there is room (a.cols_lds entries): the
@@ -912,6 +936,117 @@ __global__ __launch_bounds__(WGM* WGN * 64, MINB) void k_join_l2_ares(const Join
 #undef KGC_COMPUTE
   if (!LISTED) break;
   }   // rows
+  for (int off = 32; off > 0; off >>= 1) ncand_lane += __shfl_xor(ncand_lane, off, 64);
+  if (lane == 0 && ncand_lane) atomicAdd(a.cx.cand_counter, (unsigned long long)ncand_lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 2, one surviving tile at a time (pruned joins whose rows keep only a tile or two each).  Walking such a
+// row costs the row-walking kernels a chain of some ten memory round trips (row record, tile list, head tile,
+// the tail slices one behind the other) for a microsecond of arithmetic.  Here a block takes one (row, tail tile)
+// entry of the list, reads ALL K slices of both 128-row tiles with every load in flight at once, and multiplies out
+// of LDS: three round trips per tile.  The host launches both kernels; a device flag set from the batch's tile and
+// row counts (k_batch_tiles) says which of them works.  LDS: 2 * KS * 8 KiB.
+__global__ __launch_bounds__(256, 2) void k_join_l2_pairs(const JoinStreamArgs a) {
+  constexpr int BM = 128, BN = 128, NT = 256, WGN = 2, WTM = 64, WTN = 64, TM = 2, TN = 2;
+  constexpr int LA = (BM * 4) / NT;
+  constexpr int ASZ = BM * kSliceK;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [KS][128][32] head slices, then the same for the tail tile
+  if (!*a.pair_mode) return;
+  const int KS = a.KS;
+  uint16_t* As = lds;
+  uint16_t* Bs = lds + KS * ASZ;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const unsigned int total = (unsigned int)*a.tile_total;
+  const int64_t slice_bytes = a.Nslots * kSliceK * 2;
+  const uint32_t voff = (uint32_t)tid * 16u;
+  const int st0 = (tid >> 2) * kSliceK + (((tid & 3) ^ lds_swizzle(tid >> 2)) * 8);
+  constexpr int st_step = (NT / 4) * kSliceK;
+  const int rsw = lds_swizzle(lane & 31);
+  const int rd_a = (wm * WTM + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
+  const int rd_b = (wn * WTN + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
+  const int rd_step = (((lane >> 5) ^ rsw) & 2) ? -16 : 16;
+  const float thr = a.prm->thr;
+  const bool last_two = (a.k16 - (KS - 1) * 2) >= 2;
+  int ncand_lane = 0;
+  for (unsigned int e = blockIdx.x; e < total; e += gridDim.x) {
+    const uint32_t row = a.tile_rows[e], tcol = a.cols[e];
+    const int rl = (int)(row / (uint32_t)a.nH), tH = (int)(row - (uint32_t)rl * (uint32_t)a.nH);
+    const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * (kSliceK * 2);
+    const char* Bbase = (const char*)a.B + (a.b_per_rel ? (int64_t)rl * KS * a.Nslots * (kSliceK * 2) : 0) +
+                        (int64_t)tcol * BN * (kSliceK * 2);
+    __syncthreads();                                         // the previous tile is done with the LDS
+    for (int ks0 = 0; ks0 < KS; ks0 += 4) {                  // (past the last slice the loads repeat it and nothing is stored)
+      uint4 ta[4][LA], tb[4][LA];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int ks = ks0 + j < KS ? ks0 + j : KS - 1;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+          ta[j][i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+          tb[j][i] = *(const uint4*)(Bbase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (ks0 + j < KS) {
+#pragma unroll
+          for (int i = 0; i < LA; ++i) {
+            *(uint4*)(&As[(ks0 + j) * ASZ + st0 + i * st_step]) = ta[j][i];
+            *(uint4*)(&Bs[(ks0 + j) * ASZ + st0 + i * st_step]) = tb[j][i];
+          }
+        }
+    }
+    __syncthreads();
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint16_t* Ac = As + ks * ASZ + rd_a;
+      const uint16_t* Bc = Bs + ks * ASZ + rd_b;
+      const int nstep = (ks < KS - 1 || last_two) ? 2 : 1;
+      for (int step = 0; step < nstep; ++step) {
+        bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8_t*)(Ac + i * 32 * kSliceK + step * rd_step);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8_t*)(Bc + j * 32 * kSliceK + step * rd_step);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+    }
+    // the filter on the squared distance; blocks that hold candidates are listed for the exact kernel
+    float mn = acc[0][0][0];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);
+    if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {
+      const int64_t hbase = (int64_t)tH * BM + wm * WTM;
+      const int64_t tbase = (int64_t)tcol * BN + wn * WTN;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          int n = 0;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) n += (acc[i][j][v] <= thr) ? 1 : 0;
+          if (__builtin_amdgcn_ballot_w64(n != 0) != 0ull) {
+            ncand_lane += n;
+            list_block(a, a.r0 + rl, hbase + i * 32, tbase + j * 32);
+          }
+        }
+    }
+  }
   for (int off = 32; off > 0; off >>= 1) ncand_lane += __shfl_xor(ncand_lane, off, 64);
   if (lane == 0 && ncand_lane) atomicAdd(a.cx.cand_counter, (unsigned long long)ncand_lane);
 }

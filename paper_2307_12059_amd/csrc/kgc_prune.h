@@ -153,6 +153,10 @@ __global__ void k_scatter_slots(GroupState* gs, const int32_t* group_of, const i
 
 // One wave per micro-tile: centre = mean of its rows, radius = max distance of a row to the centre (in
 // the join's metric), widened for float32 rounding.  An empty micro-tile gets radius -1.
+// The rows are read once, 64 dimensions at a time with the lanes on consecutive dimensions: the 32 loads of a chunk
+// are independent of each other (one memory round trip), the chunk's centre values come from their sum, and each
+// row's distance to the centre grows by its part of the chunk; the 32 row sums are then added across the lanes by a
+// halving exchange (32 shuffles).
 template <int P>
 __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E, int dtype, int d,
                                                       const int32_t* __restrict__ slot_ent, int64_t n_micro,
@@ -160,16 +164,14 @@ __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E
                                                       float* __restrict__ cnorm, int r0 = 0, int64_t rel_stride = 0) {
   // blockIdx.y: relation of a batch, for per-relation rows E[(r0 + y) * rel_stride + ...] (summaries then lie
   // relation after relation); one relation and rel_stride 0 for the TransE join
+  static_assert(kMicro == 32, "the row sums below are laid out for 32 rows");
   const int64_t m = blockIdx.x;
   if (m >= n_micro) return;
   const int lane = threadIdx.x;
   E = (const char*)E + (int64_t)(r0 + (int)blockIdx.y) * rel_stride * (dtype == KGC_BF16 ? 2 : 4);
   cent += (int64_t)blockIdx.y * n_micro * d; rad += (int64_t)blockIdx.y * n_micro; cnorm += (int64_t)blockIdx.y * n_micro;
-  __shared__ int32_t ents[kMicro];
-  if (lane < kMicro) ents[lane] = slot_ent[m * kMicro + lane];
-  __syncthreads();
-  int cnt = 0;
-  for (int q = 0; q < kMicro; ++q) cnt += ents[q] >= 0;
+  const int32_t ent_l = lane < kMicro ? slot_ent[m * kMicro + lane] : -1;
+  const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(ent_l >= 0));
   float* c = cent + m * d;
   if (cnt == 0) {
     for (int k = lane; k < d; k += 64) c[k] = 0.f;
@@ -178,36 +180,52 @@ __global__ __launch_bounds__(64) void k_micro_summary(const void* __restrict__ E
   }
   const float inv = 1.f / (float)cnt;
   float c2 = 0.f;
-  for (int k = lane; k < d; k += 64) {
-    float s = 0.f;
-    for (int q = 0; q < kMicro; ++q)
-      if (ents[q] >= 0) s += ld_elem(E, (int64_t)ents[q] * d + k, dtype);
-    c[k] = s * inv;
-    c2 += (s * inv) * (s * inv);
+  float rs[kMicro];                                   // this lane's part of every row's distance to the centre
+#pragma unroll
+  for (int q = 0; q < kMicro; ++q) rs[q] = 0.f;
+  for (int k0 = 0; k0 < d; k0 += 64) {
+    const int k = k0 + lane;
+    float v[kMicro];
+#pragma unroll
+    for (int q = 0; q < kMicro; ++q) v[q] = 0.f;
+    if (k < d) {
+#pragma unroll
+      for (int q = 0; q < kMicro; ++q) {
+        const int32_t ent = __builtin_amdgcn_readlane(ent_l, q);
+        if (ent >= 0) v[q] = ld_elem(E, (int64_t)ent * d + k, dtype);
+      }
+      float sum = 0.f;
+#pragma unroll
+      for (int q = 0; q < kMicro; ++q) sum += v[q];
+      const float ck = sum * inv;
+      c[k] = ck;
+      c2 += ck * ck;
+#pragma unroll
+      for (int q = 0; q < kMicro; ++q) {
+        const float x = v[q] - ck;
+        if (__builtin_amdgcn_readlane(ent_l, q) >= 0) rs[q] += (P == 2) ? x * x : fabsf(x);
+      }
+    }
   }
   for (int off = 32; off > 0; off >>= 1) c2 += __shfl_xor(c2, off, 64);
   if (lane == 0) cnorm[m] = sqrtf(c2) * (1.f + kBoundSlack);
-  __syncthreads();   // centre visible to the whole wave (same block)
-  // radius: lane (q, half) sums row q's distance to the centre over one half of the dimensions (its loads are
-  // independent of each other, so they pipeline), the two halves are added, the maximum is taken over the rows
-  float rmax = 0.f;
+  // row totals: after the five halving steps lane l holds the sum of row 16 b5 + 8 b4 + 4 b3 + 2 b2 + b1 (bits of l)
+  float a16[16], a8[8], a4[4], a2[2], a1;
   {
-    const int q = lane & 31, half = lane >> 5;
-    const int kmid = (d + 1) / 2;
-    const int kb = half ? kmid : 0, ke = half ? d : kmid;
-    float s = 0.f;
-    if (ents[q] >= 0) {
-      const int64_t eo = (int64_t)ents[q] * d;
-#pragma unroll 4
-      for (int k = kb; k < ke; ++k) {
-        const float x = ld_elem(E, eo + k, dtype) - c[k];
-        s += (P == 2) ? x * x : fabsf(x);
-      }
-    }
-    s += __shfl_xor(s, 32, 64);
-    rmax = (P == 2) ? sqrtf(s) : s;
-    for (int off = 16; off > 0; off >>= 1) rmax = fmaxf(rmax, __shfl_xor(rmax, off, 64));
+    const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8, b2 = lane & 4, b1 = lane & 2;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a16[i] = (b5 ? rs[i + 16] : rs[i]) + __shfl_xor(b5 ? rs[i] : rs[i + 16], 32, 64);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a8[i] = (b4 ? a16[i + 8] : a16[i]) + __shfl_xor(b4 ? a16[i] : a16[i + 8], 16, 64);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a4[i] = (b3 ? a8[i + 4] : a8[i]) + __shfl_xor(b3 ? a8[i] : a8[i + 4], 8, 64);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a2[i] = (b2 ? a4[i + 2] : a4[i]) + __shfl_xor(b2 ? a4[i] : a4[i + 2], 4, 64);
+    a1 = (b1 ? a2[1] : a2[0]) + __shfl_xor(b1 ? a2[0] : a2[1], 2, 64);
+    a1 += __shfl_xor(a1, 1, 64);
   }
+  float rmax = (P == 2) ? sqrtf(a1) : a1;             // (a missing row has sum 0)
+  for (int off = 32; off > 0; off >>= 1) rmax = fmaxf(rmax, __shfl_xor(rmax, off, 64));
   if (lane == 0) rad[m] = rmax * (1.f + kBoundSlack) + 1e-30f;
 }
 
@@ -537,27 +555,29 @@ struct BoundL2Args {
 };
 constexpr int kHeadChunk = 16;
 __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
-  // block = 256 tail micro-tiles x kHeadChunk head micro-tiles x kRelChunk relations; the per-head and
-  // per-relation scalars sit in LDS, the thread's own r.c_T values in registers, so one test costs one
-  // (shared) D load per kRelChunk relations and a handful of VALU operations
-  __shared__ float aH[kHeadChunk][kRelChunk];       // 2 r.c_H + ||r||^2 per (head micro-tile, relation)
+  // block = 256 tail micro-tiles x kHeadChunk head micro-tiles x kRelChunk relations; the per-(head, relation)
+  // terms sit in LDS, the thread's own per-relation terms in registers, so one test costs one (shared) D load per
+  // kRelChunk relations, one addition and one comparison
+  __shared__ __attribute__((aligned(16))) float aH[kHeadChunk][kRelChunk];   // 2 r.c_H + ||r||^2 - kk ||c_H|| ||r|| per (head micro-tile, relation)
   __shared__ float srnS[kRelChunk];
-  __shared__ float radH[kHeadChunk], cnH[kHeadChunk];
+  __shared__ float radH[kHeadChunk];
   const int tid = threadIdx.x;
   const int64_t mT = (int64_t)blockIdx.x * blockDim.x + tid;
   const int64_t mH0 = (int64_t)blockIdx.y * kHeadChunk;
   const int rl0 = (int)blockIdx.z * kRelChunk;
+  const float kk = 2.f * (float)(a.d + 12) * 6e-8f;
   {
     const int hq = tid / kRelChunk, q = tid % kRelChunk;        // 256 threads = kHeadChunk x kRelChunk
     const int rl = rl0 + q;
     const int64_t mH = mH0 + hq;
     const float rnq = rl < a.RB ? a.rn[rl] : 0.f;
-    aH[hq][q] = (rl < a.RB && mH < a.n_micro) ? 2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f) : 0.f;
+    const bool in = rl < a.RB && mH < a.n_micro;
+    const float ah = in ? 2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f) : 0.f;
+    aH[hq][q] = in ? ah - (kk * a.cnorm[mH]) * sqrtf(rnq) : 0.f;
     if (tid < kRelChunk) srnS[tid] = sqrtf((rl0 + tid < a.RB) ? a.rn[rl0 + tid] : 0.f);
     if (tid < kHeadChunk) {
       const int64_t m = mH0 + tid;
       radH[tid] = m < a.n_micro ? a.rad[m] : -1.f;
-      cnH[tid] = m < a.n_micro ? a.cnorm[m] : 0.f;
     }
   }
   __syncthreads();
@@ -565,30 +585,44 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
   const float rT = a.rad[mT];
   if (rT < 0.f) return;                                          // empty micro-tile
   const float cT = a.cnorm[mT];
-  // dist^2 <= lim + ek sqrt(rn)   <=>   (2 u_H + rn) - 2 u_T - ek sqrt(rn) <= lim - D: the left side needs one
-  // subtraction and one fused multiply-add per relation, the right side is formed once per micro-tile pair.
-  // The four extra roundings of this order (each at most 2^-24 of |2 u_H + rn|, |2 u_T| or D) are paid for
-  // on the keeping side: 4 more units in the (d + 8) factor of ek, 2.4e-7 of rn and of D.
+  // dist^2 <= lim + ek sqrt(rn), ek = kk (||c_H|| + ||c_T||)
+  //   <=>   (2 u_H + rn) - kk ||c_H|| sqrt(rn)  <=  (lim - D) + (2 u_T + kk ||c_T|| sqrt(rn)):
+  // the left side is formed once per (head micro-tile, relation) and block, the last term once per (thread, relation),
+  // lim - D once per micro-tile pair, which leaves one addition and one comparison per test.  The extra roundings of
+  // this order (two each at most 2^-24 of |2 u_H + rn| and of |2 u_T|, three of D) are paid for on the keeping side:
+  // 4 more units in the (d + 8) factor of ek, 2.4e-7 of rn and of D.
   float bT[kRelChunk];
   const int nrel = a.RB - rl0 < kRelChunk ? a.RB - rl0 : kRelChunk;
 #pragma unroll
-  for (int q = 0; q < kRelChunk; ++q) bT[q] = q < nrel ? 2.f * a.u[(int64_t)(rl0 + q) * a.n_micro + mT] : -3e38f;
+  for (int q = 0; q < kRelChunk; ++q)
+    bT[q] = q < nrel ? 2.f * a.u[(int64_t)(rl0 + q) * a.n_micro + mT] + (kk * cT) * srnS[q] : -3e38f;   // past the batch: never passes
   const int tT = (int)(mT / a.micro_per_bn);
   const float dsl = a.delta * (1.f + kBoundSlack);
-  const float kk = 2.f * (float)(a.d + 12) * 6e-8f;
+  const float dk = (float)(a.d + 8) * 6e-8f;
+  // the centre distances of the chunk, all loads in flight together (a head past the end reads row 0; it is skipped below)
+  float Dv[kHeadChunk];
+  {
+    const float* Dp = a.D + mH0 * a.n_micro + mT;
+    const int nvalid = a.n_micro - mH0 < kHeadChunk ? (int)(a.n_micro - mH0) : kHeadChunk;     // the same for the block
+#pragma unroll
+    for (int hq = 0; hq < kHeadChunk; ++hq) Dv[hq] = Dp[hq < nvalid ? (int64_t)hq * a.n_micro : 0];
+  }
+#pragma unroll
   for (int hq = 0; hq < kHeadChunk; ++hq) {
     const float rH = radH[hq];
     if (rH < 0.f) continue;                                      // empty or past the end
     const int64_t mH = mH0 + hq;
-    const float D = a.D[mH * a.n_micro + mT];
+    const float D = Dv[hq];
     const float reach = dsl + rH + rT;
-    const float rhs = reach * reach * (1.f + kBoundSlack) + D * ((float)(a.d + 8) * 6e-8f) - D;
-    const float ek = kk * (cnH[hq] + cT);
-    const int tH = (int)(mH / a.micro_per_bm);
+    const float rhs = reach * reach * (1.f + kBoundSlack) + D * dk - D;
+    bool any = false;
+#pragma unroll
+    for (int q = 0; q < kRelChunk; ++q) any |= aH[hq][q] <= rhs + bT[q];
+    if (__builtin_amdgcn_ballot_w64(any) == 0ull) continue;      // almost always: nothing survives
     uint32_t keep = 0u;
 #pragma unroll
-    for (int q = 0; q < kRelChunk; ++q)
-      keep |= (aH[hq][q] - bT[q] - ek * srnS[q] <= rhs) ? (1u << q) : 0u;     // past the batch: bT = -3e38 never passes
+    for (int q = 0; q < kRelChunk; ++q) keep |= (aH[hq][q] <= rhs + bT[q]) ? (1u << q) : 0u;
+    const int tH = (int)(mH / a.micro_per_bm);
     while (keep) {
       const int q = __builtin_ctz(keep);
       keep &= keep - 1u;
@@ -779,69 +813,109 @@ __global__ __launch_bounds__(256) void k_bound_refine(const BoundL2Args fine, co
   }
 }
 
-// Tile lists from the bitmap.  A wave takes 64 (relation, head tile) rows: every lane counts the surviving
-// tail tiles of its row (almost all rows are empty), the rows that have some reserve a range of the column
-// list with one atomic each and are then written out by the whole wave, one row after the other, tile
+// Tile lists from the bitmap.  A wave takes kBitmapRowsPerLane x 64 (relation, head tile) rows: every lane counts
+// the surviving tail tiles of its rows (almost all rows are empty); the wave reserves its part of the column list and
+// of the active-row list with ONE atomic each (thousands of atomics on the same two counters cost more than the
+// whole scan), and the rows that have tiles are then written out by the whole wave, one row after the other, tile
 // numbers ascending.
+constexpr int kBitmapRowsPerLane = 8;
 __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __restrict__ bitmap, int words_per_row,
                                                          int64_t n_rows, uint32_t* __restrict__ row_start,
                                                          uint32_t* __restrict__ row_count, uint32_t* __restrict__ cols,
                                                          unsigned long long* __restrict__ total,
                                                          uint32_t* __restrict__ active_rows,
-                                                         unsigned int* __restrict__ n_active) {
+                                                         unsigned int* __restrict__ n_active,
+                                                         uint32_t* __restrict__ tile_rows) {      // may be NULL: the row of every entry of cols
   const int lane = threadIdx.x & 63;
-  const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64;
+  const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * (64 * kBitmapRowsPerLane);
   if (row0 >= n_rows) return;                                  // whole waves leave together
-  const int64_t my_row = row0 + lane;
-  uint32_t cnt = 0;
-  if (words_per_row <= 8) {                  // short rows: every lane counts its own
+  uint32_t cnt[kBitmapRowsPerLane];
+#pragma unroll
+  for (int k = 0; k < kBitmapRowsPerLane; ++k) {
+    const int64_t base_row = row0 + k * 64;
+    cnt[k] = 0;
+    if (words_per_row <= 8) {                // short rows: every lane counts its own
+      if (base_row + lane < n_rows) {
+        const uint32_t* w = bitmap + (base_row + lane) * words_per_row;
+        for (int i = 0; i < words_per_row; ++i) cnt[k] += __builtin_popcount(w[i]);
+      }
+    } else {                                 // long rows: the wave counts them one after the other, words over lanes
+      for (int rr = 0; rr < 64 && base_row + rr < n_rows; ++rr) {
+        const uint32_t* w = bitmap + (base_row + rr) * words_per_row;
+        uint32_t c = 0;
+        for (int i = lane; i < words_per_row; i += 64) c += __builtin_popcount(w[i]);
+        for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
+        if (lane == rr) cnt[k] = c;
+      }
+    }
+  }
+  // this lane's tiles and rows, their exclusive prefix over the wave, one reservation per wave
+  uint32_t ltiles = 0, lrows = 0;
+#pragma unroll
+  for (int k = 0; k < kBitmapRowsPerLane; ++k) { ltiles += cnt[k]; lrows += cnt[k] ? 1u : 0u; }
+  uint32_t ptiles = ltiles, prows = lrows;
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t ot = __shfl_up(ptiles, off, 64), orw = __shfl_up(prows, off, 64);
+    if (lane >= off) { ptiles += ot; prows += orw; }
+  }
+  const uint32_t wtiles = __shfl(ptiles, 63, 64), wrows = __shfl(prows, 63, 64);
+  unsigned long long wbase = 0;
+  unsigned int abase = 0;
+  if (lane == 0 && wrows) {
+    wbase = atomicAdd(total, (unsigned long long)wtiles);
+    abase = atomicAdd(n_active, wrows);
+  }
+  wbase = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(wbase >> 32), 0, 64) << 32) |
+          (uint32_t)__shfl((int)(uint32_t)(wbase & 0xffffffffull), 0, 64);
+  abase = (unsigned int)__shfl((int)abase, 0, 64);
+  unsigned long long my_base = wbase + (ptiles - ltiles);
+  unsigned int my_act = abase + (prows - lrows);
+  unsigned long long bases[kBitmapRowsPerLane];
+#pragma unroll
+  for (int k = 0; k < kBitmapRowsPerLane; ++k) {
+    const int64_t my_row = row0 + k * 64 + lane;
+    bases[k] = cnt[k] ? my_base : 0ull;
     if (my_row < n_rows) {
-      const uint32_t* w = bitmap + my_row * words_per_row;
-      for (int i = 0; i < words_per_row; ++i) cnt += __builtin_popcount(w[i]);
+      row_start[my_row] = (uint32_t)bases[k];
+      row_count[my_row] = cnt[k];
+      if (cnt[k]) active_rows[my_act++] = (uint32_t)my_row;   // rows that still have work, in any order
     }
-  } else {                                   // long rows: the wave counts them one after the other, words over lanes
-    for (int rr = 0; rr < 64 && row0 + rr < n_rows; ++rr) {
-      const uint32_t* w = bitmap + (row0 + rr) * words_per_row;
-      uint32_t c = 0;
-      for (int i = lane; i < words_per_row; i += 64) c += __builtin_popcount(w[i]);
-      for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
-      if (lane == rr) cnt = c;
-    }
+    my_base += cnt[k];
   }
-  unsigned long long my_base = 0;
-  if (my_row < n_rows) {
-    if (cnt) {
-      my_base = atomicAdd(total, (unsigned long long)cnt);
-      active_rows[atomicAdd(n_active, 1u)] = (uint32_t)my_row;   // rows that still have work, in any order
-    }
-    row_start[my_row] = (uint32_t)my_base;
-    row_count[my_row] = cnt;
-  }
-  unsigned long long live = __builtin_amdgcn_ballot_w64(cnt != 0u);
-  while (live) {
-    const int src = (int)__builtin_ctzll(live);
-    live &= live - 1ull;
-    const unsigned long long base = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(my_base >> 32), src) << 32) |
-                                    (uint32_t)__shfl((int)(uint32_t)(my_base & 0xffffffffull), src);
-    const uint32_t* w = bitmap + (row0 + src) * words_per_row;
-    // ascending order: words in chunks of 64, prefix of popcounts across lanes
-    uint32_t run = 0;
-    for (int i0 = 0; i0 < words_per_row; i0 += 64) {
-      const int i = i0 + lane;
-      uint32_t word = i < words_per_row ? w[i] : 0u;
-      const uint32_t pc = __builtin_popcount(word);
-      uint32_t pre = pc;
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(pre, off, 64);
-        if (lane >= off) pre += o;
+  if (!wrows) return;
+#pragma unroll 1
+  for (int k = 0; k < kBitmapRowsPerLane; ++k) {
+    uint32_t c = 0;
+    unsigned long long bk = 0;
+#pragma unroll
+    for (int q = 0; q < kBitmapRowsPerLane; ++q) { c = (q == k) ? cnt[q] : c; bk = (q == k) ? bases[q] : bk; }
+    unsigned long long live = __builtin_amdgcn_ballot_w64(c != 0u);
+    while (live) {
+      const int src = (int)__builtin_ctzll(live);
+      live &= live - 1ull;
+      const unsigned long long base = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(bk >> 32), src, 64) << 32) |
+                                      (uint32_t)__shfl((int)(uint32_t)(bk & 0xffffffffull), src, 64);
+      const uint32_t* w = bitmap + (row0 + k * 64 + src) * words_per_row;
+      // ascending order: words in chunks of 64, prefix of popcounts across lanes
+      uint32_t run = 0;
+      for (int i0 = 0; i0 < words_per_row; i0 += 64) {
+        const int i = i0 + lane;
+        uint32_t word = i < words_per_row ? w[i] : 0u;
+        const uint32_t pc = __builtin_popcount(word);
+        uint32_t pre = pc;
+        for (int off = 1; off < 64; off <<= 1) {
+          const uint32_t o = __shfl_up(pre, off, 64);
+          if (lane >= off) pre += o;
+        }
+        uint32_t pos = run + pre - pc;
+        while (word) {
+          const int bit = __builtin_ctz(word);
+          word &= word - 1;
+          if (tile_rows) tile_rows[base + pos] = (uint32_t)(row0 + k * 64 + src);
+          cols[base + pos++] = (uint32_t)(i * 32 + bit);
+        }
+        run += __shfl(pre, 63, 64);
       }
-      uint32_t pos = run + pre - pc;
-      while (word) {
-        const int bit = __builtin_ctz(word);
-        word &= word - 1;
-        cols[base + pos++] = (uint32_t)(i * 32 + bit);
-      }
-      run += __shfl(pre, 63, 64);
     }
   }
 }
