@@ -168,6 +168,22 @@ int kgc_join_static(kgc_handle* hd, const void* E, int64_t N, int32_t d, const v
 int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t d, int32_t R, int32_t b_per_relation,
                 int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
 
+/* The structured-embedding instance of the general form (Section 4.3): connector_1(h, r) = W_lhs[r] h and
+ * connector_2(t, r) = W_rhs[r] t, joined under ||a - b||_p (the model's own norm is p = 1; p = 2 is accepted).
+ *   E       N x d row-major, contiguous, of the handle's dtype                                       (device)
+ *   W_lhs   R x d x d, W_lhs[r][i][j] row-major (a_i = sum_j W_lhs[r][i][j] h_j), same dtype        (device)
+ *   W_rhs   R x d x d, the same for the tail side                                                    (device)
+ * The library forms the connector rows itself, relation batch by relation batch, in float32 (products of the
+ * stored values, float32 accumulation) in buffers of the handle: 2 * batch * N * d * 4 bytes, a batch being as many
+ * relations as fit a quarter of config.workspace_bytes (at most 4 GiB a side); the caller never holds R x N x d.
+ * Each batch then runs through the kernels of kgc_join_ab on those rows, and the exact stage scores the stored
+ * float32 connector rows in double.  A connector element therefore carries a rounding error of about
+ * sqrt(d) * 2^-24 of |W row| |e|, a distance one of about sqrt(2 d) (p = 2) or 2 d (p = 1) times that: triples whose
+ * exact distance lies that close to delta may fall on either side.  Output, count, overflow and error conventions are
+ * those of kgc_join; kgc_get_stats reports the sums over the batches. */
+int kgc_join_se(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* W_lhs, const void* W_rhs, int32_t R,
+                int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
+
 /* The top-1 score of Section 3.3: the triple with the smallest dist_3(h, r, t) over E x R x E, or, with
  * exclude_self != 0, over the triples with h != t (the second quantity that section looks at).
  *   out   receives the triple and its distance (host).  h = r = t = -1 and dist = +inf when no triple is

@@ -23,7 +23,7 @@ KGC_PRUNE_AUTO, KGC_PRUNE_OFF, KGC_PRUNE_ON = 0, 1, 2
 KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
-EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_top1", "kgc_topk", "kgc_topk_range", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
+EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_join_se", "kgc_top1", "kgc_topk", "kgc_topk_range", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
            "kgc_version", "kgc_calibrate_mfma", "kgc_join_static"]
 
 
@@ -79,6 +79,9 @@ def load_library():
     lib.kgc_join_range.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
                                    ctypes.c_float, ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_uint64,
                                    ctypes.POINTER(ctypes.c_uint64)]
+    lib.kgc_join_se.restype = ctypes.c_int
+    lib.kgc_join_se.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64)]
     lib.kgc_join_ab.restype = ctypes.c_int
     lib.kgc_join_ab.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                 ctypes.c_float, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64)]
@@ -169,6 +172,16 @@ def kgc_join_ab(handle, A_ptr: int, B_ptr: int, N: int, d: int, R: int, b_per_re
     count = ctypes.c_uint64(0)
     rc = load_library().kgc_join_ab(ctypes.c_void_p(handle), ctypes.c_void_p(A_ptr), ctypes.c_void_p(B_ptr), N, d, R,
                                     1 if b_per_relation else 0, p, ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap,
+                                    ctypes.byref(count))
+    return rc, int(count.value)
+
+
+def kgc_join_se(handle, E_ptr: int, N: int, d: int, Wl_ptr: int, Wr_ptr: int, R: int, p: int, delta: float, out_ptr: int,
+                cap: int):
+    """Raw call on device addresses: the structured-embedding join (connectors formed on the device).  Returns (code, count)."""
+    count = ctypes.c_uint64(0)
+    rc = load_library().kgc_join_se(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(Wl_ptr),
+                                    ctypes.c_void_p(Wr_ptr), R, p, ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap,
                                     ctypes.byref(count))
     return rc, int(count.value)
 
@@ -302,6 +315,27 @@ class Join:
         rc, count = kgc_join_ab(self.handle, A.data_ptr(), B.data_ptr(), N, d, R, per_rel, p, float(delta), out.data_ptr(), cap)
         if rc < 0:
             raise RuntimeError(f"kgc_join_ab failed with code {rc}: {kgc_last_error(self.handle)}")
+        n = min(count, cap)
+        host = out[:n].cpu().numpy()
+        return {"code": rc, "count": count, "stats": kgc_get_stats(self.handle), "h": host[:, 0].copy(),
+                "r": host[:, 1].copy(), "t": host[:, 2].copy(), "dist": host[:, 3].copy().view("float32")}
+
+    def join_se(self, E, W_lhs, W_rhs, p: int, delta: float, cap: int) -> dict:
+        """The structured-embedding join: ``E`` is N x d, ``W_lhs`` and ``W_rhs`` are R x d x d."""
+        torch = self._torch
+        want = torch.float32 if self.dtype == "f32" else torch.bfloat16
+        for x in (E, W_lhs, W_rhs):
+            if not (x.is_cuda and x.is_contiguous() and x.dtype == want):
+                raise ValueError("E, W_lhs and W_rhs must be contiguous CUDA tensors of the handle's dtype")
+        N, d = E.shape
+        R = W_lhs.shape[0]
+        if tuple(W_lhs.shape) != (R, d, d) or tuple(W_rhs.shape) != (R, d, d):
+            raise ValueError("W_lhs and W_rhs must be R x d x d")
+        out = torch.empty((max(cap, 1), 4), dtype=torch.int32, device=E.device)
+        rc, count = kgc_join_se(self.handle, E.data_ptr(), N, d, W_lhs.data_ptr(), W_rhs.data_ptr(), R, p, float(delta),
+                                out.data_ptr(), cap)
+        if rc < 0:
+            raise RuntimeError(f"kgc_join_se failed with code {rc}: {kgc_last_error(self.handle)}")
         n = min(count, cap)
         host = out[:n].cpu().numpy()
         return {"code": rc, "count": count, "stats": kgc_get_stats(self.handle), "h": host[:, 0].copy(),

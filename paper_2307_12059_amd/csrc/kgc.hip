@@ -56,6 +56,7 @@ struct kgc_handle {
   // every DevBuf member must also be listed in kgc_destroy
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
   DevBuf unit_first, unit_n, cent_u, rad_u, cnorm_u, gram_u, relu_u, pair_list, pair_count;   // two-level bound test
+  DevBuf se_a, se_b;                           // connector rows of a relation batch (kgc_join_se)
   DevBuf xlist;                                // accumulator blocks listed for the exact stage (L2 joins)
   unsigned int xcap = kExactListCap;           // its length in entries: grows when a batch wanted to list more
   DevBuf zero_row, cent_a, rad_a;              // kgc_join_ab: the zero relation row; micro-tile summaries of A[r]
@@ -271,7 +272,7 @@ void kgc_destroy(kgc_handle* h) {
                     &h->cent, &h->rad, &h->bitmap, &h->row_start, &h->row_count, &h->cols, &h->active_rows, &h->cnorm,
                     &h->gram, &h->relu, &h->reln, &h->asg_a, &h->asg_b, &h->limr, &h->top1_buf, &h->top1_state,
                     &h->unit_first, &h->unit_n, &h->cent_u, &h->rad_u, &h->cnorm_u, &h->gram_u, &h->relu_u, &h->pair_list,
-                    &h->pair_count, &h->xlist, &h->tile_rows, &h->zero_row, &h->cent_a, &h->rad_a, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
+                    &h->pair_count, &h->xlist, &h->tile_rows, &h->se_a, &h->se_b, &h->zero_row, &h->cent_a, &h->rad_a, &h->top1_a, &h->top1_b, &h->top1_pick, &h->top_samples, &h->topk_state})
     release(*b);
   if (h->host_gstate) (void)hipHostFree(h->host_gstate);
   if (h->host_counters) (void)hipHostFree(h->host_counters);
@@ -537,6 +538,71 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   s.ms_precompute = s.ms_total - s.ms_join;
   *count = s.emitted;
   return s.emitted > cap ? KGC_OVERFLOW : KGC_OK;
+}
+
+
+// The structured-embedding instance of the general form (Section 4.3): a = W_lhs[r] h, b = W_rhs[r] t.  The
+// connector rows of a relation batch are formed here, in float32 (a tiled float32 product: the chip's float32 vector
+// and matrix rates are the same, and the exact stage needs every bit of them), into the handle's own buffers, and the
+// batch then runs through kgc_join_ab on those rows; its records get the batch's first relation added.
+int kgc_join_se(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* W_lhs, const void* W_rhs, int32_t R,
+                int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count) {
+  if (!hd) return KGC_E_INVALID;
+  if (!count) return fail(hd, KGC_E_INVALID, "count is NULL");
+  *count = 0;
+  if (N < 0 || R < 0 || d < 1) return fail(hd, KGC_E_INVALID, "negative size or d < 1");
+  if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
+  if (cap > 0 && !out_triples) return fail(hd, KGC_E_INVALID, "out_triples is NULL but cap > 0");
+  if (N == 0 || R == 0) { hd->stats = kgc_stats{}; return KGC_OK; }
+  if (!E || !W_lhs || !W_rhs) return fail(hd, KGC_E_INVALID, "E, W_lhs or W_rhs is NULL");
+  if (hd->static_mode) return fail(hd, KGC_E_INVALID, "kgc_join_se allocates: not available inside kgc_join_static");
+  hipStream_t st = hd->stream;
+  const int dtype = hd->cfg.dtype;
+  // connector rows of as many relations as fit half the workspace (both sides, float32), at most 4 GiB a side
+  const int64_t ws = hd->cfg.workspace_bytes > 0 ? hd->cfg.workspace_bytes : kDefaultWorkspace;
+  const int64_t per_rel = (int64_t)N * d * 4;
+  const int64_t RB_max = std::max<int64_t>(1, std::min<int64_t>({(int64_t)R, (ws / 4) / per_rel, (4ll << 30) / per_rel}));
+  int rc;
+  if ((rc = ensure(hd, hd->se_a, (size_t)RB_max * per_rel)) || (rc = ensure(hd, hd->se_b, (size_t)RB_max * per_rel))) return rc;
+  kgc_stats total{};
+  uint64_t found = 0, written = 0;
+  const size_t esz = dtype == KGC_BF16 ? 2 : 4;
+  int batches = 0;
+  for (int64_t r0 = 0; r0 < R; r0 += RB_max, ++batches) {
+    const int RB = (int)std::min<int64_t>(RB_max, R - r0);
+    for (int side = 0; side < 2; ++side) {
+      TileDistArgs td{};
+      td.X = E; td.dtypeX = dtype; td.n_rows = N;
+      td.Y = (const char*)(side ? W_rhs : W_lhs) + (size_t)r0 * d * d * esz; td.dtypeY = dtype; td.n_cols = d;
+      td.y_rel_rows = d; td.shift = nullptr; td.dtype_shift = dtype; td.d = d;
+      td.matrix = (float*)(side ? hd->se_b.p : hd->se_a.p); td.matrix_rel_stride = (int64_t)N * d;
+      k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((d + 127) / 128), (unsigned)((N + 127) / 128), (unsigned)RB), 256, 0, st>>>(td);
+    }
+    KGC_HIP(hd, hipGetLastError());
+    // the batch through the general form, on float32 rows whatever the handle's storage type
+    const int32_t keep_dtype = hd->cfg.dtype;
+    hd->cfg.dtype = KGC_F32;
+    uint64_t c = 0;
+    rc = kgc_join_ab(hd, hd->se_a.p, hd->se_b.p, N, d, RB, 1, p, delta, out_triples ? out_triples + written : nullptr,
+                     cap - written, &c);
+    hd->cfg.dtype = keep_dtype;
+    if (rc != KGC_OK && rc != KGC_OVERFLOW) return rc;
+    const uint64_t kept = std::min<uint64_t>(c, cap - written);
+    if (kept > 0 && r0 > 0) k_shift_relation<<<grid_for((int64_t)kept, 256), 256, 0, st>>>(out_triples + written, kept, (int32_t)r0);
+    found += c; written += kept;
+    const kgc_stats& b = hd->stats;
+    total.tiles_total += b.tiles_total; total.tiles_evaluated += b.tiles_evaluated; total.tiles_pruned += b.tiles_pruned;
+    total.pairs_evaluated += b.pairs_evaluated; total.candidates += b.candidates; total.join_launches += b.join_launches;
+    total.ms_total += b.ms_total; total.ms_precompute += b.ms_precompute; total.ms_prune += b.ms_prune; total.ms_join += b.ms_join;
+    total.relation_batches += b.relation_batches; total.exact_blocks += b.exact_blocks;
+    total.groups = b.groups; total.tile_m = b.tile_m; total.tile_n = b.tile_n; total.k_padded = b.k_padded; total.join_variant = b.join_variant;
+  }
+  KGC_HIP(hd, hipStreamSynchronize(st));
+  total.triples_total = (uint64_t)N * (uint64_t)N * (uint64_t)R;
+  total.emitted = found;
+  hd->stats = total;
+  *count = found;
+  return found > cap ? KGC_OVERFLOW : KGC_OK;
 }
 
 }  // extern "C"

@@ -54,6 +54,11 @@ __global__ void k_add_u64(unsigned long long* dst, const unsigned long long* src
   if (threadIdx.x == 0 && blockIdx.x == 0) *dst += *src;
 }
 
+// relation numbers of a batch's records become numbers of the whole join (kgc_join_se)
+__global__ void k_shift_relation(kgc_triple* rec, uint64_t n, int32_t r0) {
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) rec[i].r += r0;
+}
+
 // after the tile lists of a pruned batch: the running total of surviving tiles, and which L2 join kernel takes the
 // batch: tile by tile when its rows keep at most kPairModeTilesPerRow tiles on average (and the host allows it)
 constexpr unsigned long long kPairModeTilesPerRow = 3;

@@ -269,6 +269,7 @@ struct TileDistArgs {
   int d;
   unsigned long long* best;                        // ASSIGN
   float* matrix;                                   // MATRIX
+  int64_t matrix_rel_stride;                       // MATRIX: relation blockIdx.z writes its n_rows x n_cols block this many floats further on
   const float* rad; float delta; uint32_t* bitmap; // BOUND
   int nH, words_per_row, micro_per_bm, micro_per_bn;
   // BOUND with per-relation summaries (the general form): relation blockIdx.z reads rows z * x_rel_rows + i of X and
@@ -411,7 +412,7 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
 #pragma unroll
       for (int jg = 0; jg < 2; ++jg) {
         const int lc = jg * 64 + tx * 4;
-        float* o = a.matrix + (row0 + lr) * n_cols + col0 + lc;
+        float* o = a.matrix + (int64_t)blockIdx.z * a.matrix_rel_stride + (row0 + lr) * n_cols + col0 + lc;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           if (cid[lc + j] >= 0) o[j] = acc[i][jg * 4 + j];

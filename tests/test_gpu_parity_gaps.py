@@ -297,3 +297,72 @@ def test_seeded_sweep_general_form(seed):
             dg = np.sqrt((x * x).sum(-1)) if p == 2 else np.abs(x).sum(-1)
             assert np.all(np.abs(dg - delta) <= tol), "a GPU triple the definition rejects, outside the band"
         assert np.all(np.abs(ref["dist"][orr] - delta) <= tol), "a qualifying triple is missing, outside the band"
+
+
+# ---- the structured-embedding instance (Section 4.3): connectors formed on the device, oracle on float64 connectors
+def _se_case(g, N, R, d, sig, dtype):
+    E, _ = _clustered(g, N, R, d, 6, sig)
+    W1 = (np.eye(d) + 0.03 * g.standard_normal((R, d, d)) / np.sqrt(d)).astype(np.float32)
+    W2 = (np.eye(d) + 0.03 * g.standard_normal((R, d, d)) / np.sqrt(d)).astype(np.float32)
+    E, W1, W2 = _seen(E, dtype), _seen(W1, dtype), _seen(W2, dtype)
+    # the connector rows in double, from the values the device sees: a_{r,h} = W1[r] h, b_{r,t} = W2[r] t
+    A = np.einsum("rij,nj->rni", W1.astype(np.float64), E.astype(np.float64))
+    B = np.einsum("rij,nj->rni", W2.astype(np.float64), E.astype(np.float64))
+    return E, W1, W2, A, B
+
+
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
+@pytest.mark.parametrize("p", [1, 2])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,R,d,ws", [(700, 5, 64, 0), (300, 3, 37, 0), (520, 7, 200, 4 * 3 * 520 * 200 * 4)])
+def test_structured_embedding_join(p, dtype, N, R, d, ws, prune):
+    import paper_2307_12059_amd as kgc
+    g = np.random.default_rng(5000 + p + d)
+    sig = 0.1
+    E, W1, W2, A, B = _se_case(g, N, R, d, sig, dtype)
+    delta = float(np.float32(sig * np.sqrt(2.0 * d) if p == 2 else sig * np.sqrt(2.0) * d * 0.8))
+    ref = oracle.join_ab(A, B, p, delta)
+    assert ref["count"] > 100
+    j = kgc.Join(dtype=dtype, prune=prune, workspace_bytes=ws)
+    try:
+        got = j.join_se(_dev(E, dtype), _dev(W1, dtype), _dev(W2, dtype), p, delta, max(1024, 2 * ref["count"]))
+    finally:
+        j.close()
+    assert got["code"] == 0
+    if ws:
+        assert got["stats"]["relation_batches"] >= 3     # the connector buffers held three relations at a time
+    gk = (got["r"].astype(np.int64) * N + got["h"]) * N + got["t"]
+    rk = (ref["r"].astype(np.int64) * N + ref["h"]) * N + ref["t"]
+    assert np.unique(gk).size == gk.size == got["count"]
+    og, orr = ~np.isin(gk, rk), ~np.isin(rk, gk)
+    tol = parity.BAND * abs(delta)       # float32 connector rounding (about 1e-5 of a distance here) stays inside it
+    if og.any():
+        x = A[got["r"][og], got["h"][og]] - B[got["r"][og], got["t"][og]]
+        dg = np.sqrt((x * x).sum(-1)) if p == 2 else np.abs(x).sum(-1)
+        assert np.all(np.abs(dg - delta) <= tol), "a GPU triple the definition rejects, outside the band"
+    assert np.all(np.abs(ref["dist"][orr] - delta) <= tol), "a qualifying triple is missing, outside the band"
+    # reported distances against the float64 connectors
+    x = A[got["r"], got["h"]] - B[got["r"], got["t"]]
+    dref = np.sqrt((x * x).sum(-1)) if p == 2 else np.abs(x).sum(-1)
+    np.testing.assert_allclose(got["dist"], dref, rtol=parity.DIST_RTOL, atol=parity.DIST_ATOL)
+
+
+def test_structured_embedding_join_overflow_and_empty():
+    import paper_2307_12059_amd as kgc
+    import torch
+    g = np.random.default_rng(5100)
+    N, R, d = 300, 4, 32
+    E, W1, W2, A, B = _se_case(g, N, R, d, 0.1, "f32")
+    delta = float(np.float32(0.1 * np.sqrt(2.0) * d * 0.8))
+    ref = oracle.join_ab(A, B, 1, delta)
+    j = kgc.Join(dtype="f32", workspace_bytes=4 * 2 * N * d * 4)       # two relations per connector batch
+    try:
+        got = j.join_se(_dev(E, "f32"), _dev(W1, "f32"), _dev(W2, "f32"), 1, delta, 50)
+        assert got["code"] == kgc.KGC_OVERFLOW and got["count"] == ref["count"] and got["h"].size == 50
+        rk = set(((ref["r"].astype(np.int64) * N + ref["h"]) * N + ref["t"]).tolist())
+        gk = ((got["r"].astype(np.int64) * N + got["h"]) * N + got["t"]).tolist()
+        assert len(set(gk)) == 50 and all(k in rk for k in gk)       # (no band triples at this seed)
+        none = j.join_se(_dev(E, "f32"), torch.empty((0, d, d), device="cuda"), torch.empty((0, d, d), device="cuda"), 1, delta, 10)
+        assert none["code"] == 0 and none["count"] == 0
+    finally:
+        j.close()
