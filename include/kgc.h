@@ -168,6 +168,37 @@ int kgc_join_static(kgc_handle* hd, const void* E, int64_t N, int32_t d, const v
 int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t d, int32_t R, int32_t b_per_relation,
                 int32_t p, float delta, kgc_triple* out_triples, uint64_t cap, uint64_t* count);
 
+/* Where a join over blocks stands.  Zero it before the first call of a join; the library updates it. */
+typedef struct {
+    uint64_t unit;        /* units (relation range, head block, tail block) done so far: the next call starts with this one */
+    uint64_t units;       /* units of the whole join (known after the first call) */
+    uint64_t need;        /* after KGC_OVERFLOW: the number of triples of the unit that did not fit */
+    uint64_t reserved;
+} kgc_cursor;
+
+/* The partition-based join (Section 4.7): kgc_join cut into units that are joined one after the other, with a
+ * cursor, so that a result larger than the output buffer can be drained piece by piece.
+ *   block_rows   rows per block of the join's row order (rounded up to a multiple of 256).  With pruning on that order
+ *                is the grouped one (similar entities are neighbours), as the section cuts its sorted arrays; without
+ *                pruning it is the entity order
+ *   rel_block    relations per unit
+ *   cursor       host; all zero to start a join.  Units run in the order (relation range, head block, tail block)
+ * Each call runs units from cursor->unit on and appends their triples to out_triples until all are done (KGC_OK,
+ * cursor->unit == cursor->units) or the next unit's triples do not fit what is left of the buffer (KGC_OVERFLOW:
+ * *count triples of COMPLETE units are in the buffer, cursor->unit names the unit that is still to be done and
+ * cursor->need its size; the caller takes the triples away and calls again with the same arguments and cursor).  A
+ * unit larger than the whole buffer returns KGC_OVERFLOW with *count == 0: call again with cap >= cursor->need, or
+ * start over with smaller blocks.  No triple is returned twice, and the union over the calls is the result of kgc_join.
+ * The handle keeps the row order, the summaries and the staged tail operands of the join between the units and the
+ * calls (and the bound test of a relation range between that range's units); any other call on the handle except
+ * kgc_get_stats / kgc_last_error discards them, after which a continued pruned join is refused (KGC_E_INVALID): its
+ * grouped order cannot be made again identically.  They are made anew when the cursor is zero or E, Rvecs, N, d, p or
+ * delta differ; the caller must not change the contents of E or Rvecs between the calls of one join.
+ * Other conventions (dtype, layout, errors) as kgc_join; the relation-factorised form is not available here. */
+int kgc_join_blocks(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                    float delta, int64_t block_rows, int32_t rel_block, kgc_cursor* cursor, kgc_triple* out_triples,
+                    uint64_t cap, uint64_t* count);
+
 /* The structured-embedding instance of the general form (Section 4.3): connector_1(h, r) = W_lhs[r] h and
  * connector_2(t, r) = W_rhs[r] t, joined under ||a - b||_p (the model's own norm is p = 1; p = 2 is accepted).
  *   E       N x d row-major, contiguous, of the handle's dtype                                       (device)

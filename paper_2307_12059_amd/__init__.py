@@ -23,7 +23,7 @@ KGC_PRUNE_AUTO, KGC_PRUNE_OFF, KGC_PRUNE_ON = 0, 1, 2
 KGC_OK, KGC_OVERFLOW = 0, 1
 KGC_E_INVALID, KGC_E_NOMEM, KGC_E_HIP = -1, -2, -3
 
-EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_join_se", "kgc_top1", "kgc_topk", "kgc_topk_range", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
+EXPORTS = ["kgc_create", "kgc_join", "kgc_join_range", "kgc_join_ab", "kgc_join_se", "kgc_join_blocks", "kgc_top1", "kgc_topk", "kgc_topk_range", "kgc_norms", "kgc_get_stats", "kgc_last_error", "kgc_destroy",
            "kgc_version", "kgc_calibrate_mfma", "kgc_join_static"]
 
 
@@ -55,6 +55,11 @@ class kgc_stats(ctypes.Structure):
 _lib = None
 
 
+class kgc_cursor(ctypes.Structure):
+    """Where a join over blocks stands (include/kgc.h); all zero to start."""
+    _fields_ = [("unit", ctypes.c_uint64), ("units", ctypes.c_uint64), ("need", ctypes.c_uint64), ("reserved", ctypes.c_uint64)]
+
+
 def library_path() -> str:
     return _build.LIB
 
@@ -79,6 +84,10 @@ def load_library():
     lib.kgc_join_range.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32,
                                    ctypes.c_float, ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_uint64,
                                    ctypes.POINTER(ctypes.c_uint64)]
+    lib.kgc_join_blocks.restype = ctypes.c_int
+    lib.kgc_join_blocks.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                    ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(kgc_cursor), vp, ctypes.c_uint64,
+                                    ctypes.POINTER(ctypes.c_uint64)]
     lib.kgc_join_se.restype = ctypes.c_int
     lib.kgc_join_se.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                 vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64)]
@@ -173,6 +182,16 @@ def kgc_join_ab(handle, A_ptr: int, B_ptr: int, N: int, d: int, R: int, b_per_re
     rc = load_library().kgc_join_ab(ctypes.c_void_p(handle), ctypes.c_void_p(A_ptr), ctypes.c_void_p(B_ptr), N, d, R,
                                     1 if b_per_relation else 0, p, ctypes.c_float(delta), ctypes.c_void_p(out_ptr), cap,
                                     ctypes.byref(count))
+    return rc, int(count.value)
+
+
+def kgc_join_blocks(handle, E_ptr: int, N: int, d: int, R_ptr: int, R: int, p: int, delta: float, block_rows: int,
+                    rel_block: int, cursor: "kgc_cursor", out_ptr: int, cap: int):
+    """Raw call on device addresses: the join block by block; ``cursor`` is updated in place.  Returns (code, count)."""
+    count = ctypes.c_uint64(0)
+    rc = load_library().kgc_join_blocks(ctypes.c_void_p(handle), ctypes.c_void_p(E_ptr), N, d, ctypes.c_void_p(R_ptr), R, p,
+                                        ctypes.c_float(delta), block_rows, rel_block, ctypes.byref(cursor),
+                                        ctypes.c_void_p(out_ptr), cap, ctypes.byref(count))
     return rc, int(count.value)
 
 
@@ -318,6 +337,24 @@ class Join:
         n = min(count, cap)
         host = out[:n].cpu().numpy()
         return {"code": rc, "count": count, "stats": kgc_get_stats(self.handle), "h": host[:, 0].copy(),
+                "r": host[:, 1].copy(), "t": host[:, 2].copy(), "dist": host[:, 3].copy().view("float32")}
+
+    def join_blocks(self, E, Rv, p: int, delta: float, cap: int, block_rows: int, rel_block: int, cursor=None) -> dict:
+        """One call of the join block by block: runs units from ``cursor`` on until the buffer of ``cap`` records is
+        full or all are done.  Returns the records of the completed units, ``code``, ``count`` and the updated ``cursor``
+        (pass it to the next call while ``code`` is KGC_OVERFLOW)."""
+        torch = self._torch
+        self._check(E, Rv)
+        if cursor is None:
+            cursor = kgc_cursor()
+        N, d = E.shape
+        out = torch.empty((max(cap, 1), 4), dtype=torch.int32, device=E.device)
+        rc, count = kgc_join_blocks(self.handle, E.data_ptr(), N, d, Rv.data_ptr(), Rv.shape[0], p, float(delta), block_rows,
+                                    rel_block, cursor, out.data_ptr(), cap)
+        if rc < 0:
+            raise RuntimeError(f"kgc_join_blocks failed with code {rc}: {kgc_last_error(self.handle)}")
+        host = out[:count].cpu().numpy()
+        return {"code": rc, "count": count, "cursor": cursor, "stats": kgc_get_stats(self.handle), "h": host[:, 0].copy(),
                 "r": host[:, 1].copy(), "t": host[:, 2].copy(), "dist": host[:, 3].copy().view("float32")}
 
     def join_se(self, E, W_lhs, W_rhs, p: int, delta: float, cap: int) -> dict:

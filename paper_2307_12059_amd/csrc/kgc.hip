@@ -56,6 +56,14 @@ struct kgc_handle {
   // every DevBuf member must also be listed in kgc_destroy
   DevBuf top1_buf, top1_state;                 // top-1 search: records of the inner joins, Top1State
   DevBuf unit_first, unit_n, cent_u, rad_u, cnorm_u, gram_u, relu_u, pair_list, pair_count;   // two-level bound test
+  // what the handle's grouping, summaries and staged tail operands were made for (kgc_join_blocks reuses them)
+  struct Prep {
+    bool valid = false;
+    const void* E = nullptr; const void* Rv = nullptr;
+    int64_t N = 0; int d = 0, p = 0, dtype = 0, prune = 0, tile_id = 0; float delta = 0.f, group_radius = 0.f;
+    int64_t Nslots = 0; uint64_t n_groups = 0; UnitTable ut{};
+    bool bitmap_valid = false; int64_t bm_r0 = 0, bm_r1 = 0;     // the bitmap holds the bound test of these relations
+  } prep;
   DevBuf se_a, se_b;                           // connector rows of a relation batch (kgc_join_se)
   DevBuf xlist;                                // accumulator blocks listed for the exact stage (L2 joins)
   unsigned int xcap = kExactListCap;           // its length in entries: grows when a batch wanted to list more
@@ -290,6 +298,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   if (!hd) return KGC_E_INVALID;
   if (!count) return fail(hd, KGC_E_INVALID, "count is NULL");
   *count = 0;
+  hd->prep.valid = false;            // (this call overwrites what a join over blocks keeps in the handle)
   int rc = check_common(hd, A, N, d, B, R);
   if (rc != KGC_OK) return rc;
   if (p != 1 && p != 2) return fail(hd, KGC_E_INVALID, "p must be 1 or 2");
@@ -354,7 +363,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   RecheckCtx cx{};
   cx.E = A; cx.Et = B; cx.hstride = (int64_t)N * d; cx.tstride = b_per_relation ? (int64_t)N * d : 0;
   cx.Rv = hd->zero_row.p; cx.rstride = 0;             // the head rows already are connector_1(h, r)
-  cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p; cx.delta = (double)delta;
+  cx.slot_ent = slot_ent; cx.slot_ent_t = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p; cx.delta = (double)delta;
   cx.out = out_triples; cx.cap = cap; cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates; cx.no_self = 0;
   set_alignment(cx);
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
@@ -754,6 +763,7 @@ int top_bounds(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* 
   // R counts the relations of the search, r_begin .. r_begin + R - 1
   int rc;
   hipStream_t st = hd->stream;
+  hd->prep.valid = false;            // (the search overwrites what a join over blocks keeps in the handle)
   Top1State* ts = (Top1State*)hd->top1_state.p;
   Top1State host{};
   double* dev_samples = nullptr;
@@ -841,7 +851,7 @@ int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
   Top1State* ts = (Top1State*)hd->top1_state.p;
   Top1State host{};
   RecheckCtx cx{};
-  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr; cx.slot_ent_t = nullptr; cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
   set_alignment(cx);
 
   double sample_bound = 0.0, bound = 0.0;
@@ -908,7 +918,7 @@ int kgc_topk_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       (rc = ensure(hd, hd->topk_state, sizeof(TopkState))) || (rc = ensure(hd, hd->counters, sizeof(DevCounters))))
     return rc;
   RecheckCtx cx{};
-  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr;
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = nullptr; cx.slot_ent_t = nullptr;
   cx.dtype = hd->cfg.dtype; cx.d = d; cx.p = p;
   set_alignment(cx);
   const double eligible = (double)N * (double)N * (double)Rn - (exclude_self ? (double)N * (double)Rn : 0.0);
@@ -1025,6 +1035,7 @@ int kgc_norms(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* R
               float* nA) {
   int rc = check_common(hd, E, N, d, Rvecs, R);
   if (rc != KGC_OK) return rc;
+  hd->prep.valid = false;
   hd->err.clear();
   if (N == 0) return KGC_OK;
   hipStream_t st = hd->stream;
@@ -1126,8 +1137,23 @@ int kgc_join_static(kgc_handle* hd, const void* E, int64_t N, int32_t d, const v
   return kgc_join_range(hd, E, N, d, Rvecs, R, p, delta, 0, R, out_triples, cap, count);
 }
 
+// A window of the slot order (multiples of kSlotAlign; the end is clipped to the number of slots): only head rows in
+// [h0, h1) and tail rows in [t0, t1) take part.  kgc_join_blocks walks the join window by window.
+struct JoinWindow { int64_t h0, h1, t0, t1; };
+enum { kPrepFresh = 0,      // grouping, summaries and tail operands are made anew (kgc_join, kgc_join_range)
+       kPrepReuse = 1 };    // ... are taken from the handle when they were made for the same join
+static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                           float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count,
+                           const JoinWindow* win, int prep_mode);
+
 int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
                    float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count) {
+  return join_range_impl(hd, E, N, d, Rvecs, R, p, delta, r_begin, r_end, out_triples, cap, count, nullptr, kPrepFresh);
+}
+
+static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                           float delta, int32_t r_begin, int32_t r_end, kgc_triple* out_triples, uint64_t cap, uint64_t* count,
+                           const JoinWindow* win, int prep_mode) {
   if (!hd) return KGC_E_INVALID;
   if (!count) return fail(hd, KGC_E_INVALID, "count is NULL");
   *count = 0;
@@ -1174,8 +1200,19 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   DevCounters* cnt = (DevCounters*)hd->counters.p;
   JoinParams* prm = (JoinParams*)hd->params.p;
 
+  // what the handle holds from an earlier call of the same logical join may be taken over
+  kgc_handle::Prep& pr = hd->prep;
+  const bool reuse = prep_mode != kPrepFresh && pr.valid && pr.E == E && pr.Rv == Rvecs && pr.N == N && pr.d == d && pr.p == p &&
+                     pr.dtype == dtype && pr.prune == (int)prune && pr.tile_id == tile_id && pr.delta == delta &&
+                     pr.group_radius == hd->cfg.group_radius && !fact;
   KGC_HIP(hd, hipEventRecord(hd->ev[0], st));
-  k_fill_u32<<<grid_for(sizeof(DevCounters) / 4, 256), 256, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
+  if (!reuse) {
+    k_fill_u32<<<grid_for(sizeof(DevCounters) / 4, 256), 256, 0, st>>>((uint32_t*)cnt, sizeof(DevCounters) / 4, 0u);
+  } else {    // (the running maxima of the staged tail rows stay)
+    k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)cnt, 12, 0u);
+    k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 2, 0u);
+  }
+  pr.valid = false;
 
   // ---- row order: identity, or entities grouped around local pivots (pruning) ----
   int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
@@ -1183,7 +1220,9 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   UnitTable ut{};                 // two-level bound test: filled after the layout
   bool use_units = false;
   bool fine_direct = false;       // ... whose micro-tile level then sums centre distances directly (no M x M matrix)
-  if (prune) {
+  if (reuse) {
+    Nslots = pr.Nslots; n_groups = pr.n_groups; ut = pr.ut;
+  } else if (prune) {
     if ((rc = group_rows(hd, E, N, d, p, delta, KS, k16, &Nslots, &n_groups, &ut)) != KGC_OK) return rc;
   } else {
     if ((rc = ensure(hd, hd->slot_ent, Nslots * 4))) return rc;
@@ -1250,13 +1289,13 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   }
 
   RecheckCtx cx;
-  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
+  cx.E = E; cx.Et = E; cx.Rv = Rvecs; cx.rstride = d; cx.hstride = 0; cx.tstride = 0; cx.slot_ent = slot_ent; cx.slot_ent_t = slot_ent; cx.dtype = dtype; cx.d = d; cx.p = p;
   cx.delta = (double)delta; cx.out = out_triples; cx.cap = cap; cx.no_self = hd->no_self;
   cx.hit_counter = &cnt->hits; cx.cand_counter = &cnt->candidates;
   set_alignment(cx);
 
   KGC_HIP(hd, hipEventRecord(hd->ev[3], st));     // end of grouping
-  if (prune) {
+  if (prune && !reuse) {
     if (p == 2) {
       k_micro_summary<2><<<(unsigned)n_micro, 64, 0, st>>>(E, dtype, d, slot_ent, n_micro, (float*)hd->cent.p,
                                                             (float*)hd->rad.p, (float*)hd->cnorm.p);
@@ -1290,7 +1329,9 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     }
   }
   const size_t stage_lds = (size_t)kStageRows * (KS * kSliceK + 8) * 2;
-  if (p == 2) {
+  if (reuse) {
+    // tail operands, summaries and (L1) the join parameters are in place
+  } else if (p == 2) {
     k_stage_operands<false><<<grid_for(Nslots / kStageRows, 1), 256, stage_lds, st>>>(
         E, Rvecs, dtype, d, 0, 1, slot_ent, Nslots, KS, (uint16_t*)hd->opB.p, (float*)hd->normsB.p, cnt->max_b, nullptr, nullptr, 0, kStageRows,
         0, nullptr, fact ? -1.f : delta);      // (the factorised filter has an error analysis of its own: plain norms)
@@ -1304,9 +1345,24 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, 0);
   }
   KGC_HIP(hd, hipEventRecord(hd->ev[1], st));
+  const bool bitmap_ready = reuse && pr.bitmap_valid && pr.bm_r0 == r_begin && pr.bm_r1 == r_end && nbatch == 1;
+  pr.E = E; pr.Rv = Rvecs; pr.N = N; pr.d = d; pr.p = p; pr.dtype = dtype; pr.prune = (int)prune; pr.tile_id = tile_id;
+  pr.delta = delta; pr.group_radius = hd->cfg.group_radius; pr.Nslots = Nslots; pr.n_groups = n_groups; pr.ut = ut;
+  pr.bitmap_valid = false;
+  // the window in join tiles (whole problem without one)
+  int wH0 = 0, wH1 = nH, wT0 = 0, wT1 = nT;
+  if (win) {
+    wH0 = (int)(std::min(win->h0, Nslots) / BM); wH1 = (int)(std::min(win->h1, Nslots) / BM);
+    wT0 = (int)(std::min(win->t0, Nslots) / BN); wT1 = (int)(std::min(win->t1, Nslots) / BN);
+    if ((rc = ensure(hd, hd->active_rows, (size_t)RBmax * (Nslots / kSlotAlign) * 4 + 4))) return rc;
+  }
+  const int nHw = wH1 - wH0, nTw = wT1 - wT0;
+  const bool empty_window = nHw <= 0 || nTw <= 0;
+  RecheckCtx cxw = cx;               // dense launches over a window count their slots from the window's start
+  cxw.slot_ent = slot_ent + (int64_t)wH0 * BM; cxw.slot_ent_t = slot_ent + (int64_t)wT0 * BN;
 
   int b = 0;
-  for (int64_t r0 = r_begin; r0 < r_end; r0 += RBmax, ++b) {
+  for (int64_t r0 = r_begin; r0 < r_end && !empty_window; r0 += RBmax, ++b) {
     const int RB = (int)std::min<int64_t>(RBmax, r_end - r0);
     const uint32_t* row_start = nullptr;
     const uint32_t* row_count = nullptr;
@@ -1316,8 +1372,10 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
     if (prune) {
       // a2: bound test on micro-tile pairs -> bitmap of join tiles -> per-row lists of surviving tail tiles
       const int64_t bm_words = (int64_t)RB * nH * words_per_row;
-      k_fill_u32<<<grid_for(bm_words, 256), 256, 0, st>>>((uint32_t*)hd->bitmap.p, bm_words, 0u);
-      if (delta >= 0.f && p == 2) {
+      if (!bitmap_ready) k_fill_u32<<<grid_for(bm_words, 256), 256, 0, st>>>((uint32_t*)hd->bitmap.p, bm_words, 0u);
+      if (bitmap_ready) {
+        // the bound test of these relations is still in the bitmap (the previous window of the same relation range)
+      } else if (delta >= 0.f && p == 2) {
         // u[rl][m] = r . c_m as a tiled product, ||r||^2 by one wave per relation
         k_rel_centre_dot<<<grid_for((int64_t)RB * 64, 256), 256, 0, st>>>(
             Rvecs, dtype, d, (int)r0, RB, (const float*)hd->cent.p, 0, (float*)hd->relu.p, (float*)hd->reln.p);
@@ -1385,7 +1443,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 256 * kBitmapRowsPerLane - 1) / (256 * kBitmapRowsPerLane)), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p,
-          &cnt->n_active, pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr);
+          &cnt->n_active, pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr, nH, wH0, wH1, wT0, wT1);
       k_batch_tiles<<<1, 64, 0, st>>>(cnt, pairs_ok ? 1 : 0);
       row_start = (const uint32_t*)hd->row_start.p;
       row_count = (const uint32_t*)hd->row_count.p;
@@ -1425,11 +1483,20 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       hipLaunchKernelGGL((k_join_l2_fact<2, 4>), dim3((unsigned)nH, (unsigned)nsplit, 1), dim3(512), dyn_lds, st, fa);
       if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else if (p == 2) {
-      const int stage_grid = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 4096)
-                                   : grid_for((int64_t)RB * (Nslots / kStageRows), 1);
+      int stage_grid = prune ? (int)std::min<int64_t>((int64_t)RB * nH * (BM / kStageRows), 4096)
+                             : grid_for((int64_t)RB * (Nslots / kStageRows), 1);
+      int stage_nh = nH, stage_bm = BM;
+      if (win && !prune) {      // dense join over a window: only its head rows are staged, as a list of 256-row tiles
+        const int n256 = (int)(Nslots / kSlotAlign), w0 = (int)((int64_t)wH0 * BM / kSlotAlign), w1 = (int)((int64_t)wH1 * BM / kSlotAlign);
+        k_window_rows<<<grid_for((int64_t)RB * (w1 - w0), 256), 256, 0, st>>>((uint32_t*)hd->active_rows.p, &cnt->n_active, RB, n256, w0, w1);
+        active_rows = (const uint32_t*)hd->active_rows.p; n_active = &cnt->n_active;
+        stage_nh = n256; stage_bm = (int)kSlotAlign;
+        stage_grid = (int)std::min<int64_t>((int64_t)RB * (w1 - w0) * (kSlotAlign / kStageRows), 16384);
+      }
       k_stage_operands<true><<<stage_grid, 256, stage_lds, st>>>(
           E, Rvecs, dtype, d, (int)r0, RB, slot_ent, Nslots, KS, (uint16_t*)hd->opA.p, (float*)hd->normsA.p,
-          cnt->max_a, active_rows, n_active, nH, BM, 0, nullptr, delta);
+          cnt->max_a, active_rows, n_active, stage_nh, stage_bm, 0, nullptr, delta);
+      if (win && !prune) { active_rows = nullptr; n_active = nullptr; }
       k_join_params<<<1, 64, 0, st>>>(cnt, prm, delta, p, dtype, d, KS * kSliceK);
       if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
       if (tc.stream_kernel) {
@@ -1438,6 +1505,9 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
         sa.KS = KS; sa.k16 = k16; sa.nH = nH; sa.nT = nT; sa.r0 = (int)r0; sa.RB = RB;
         sa.row_start = row_start; sa.row_count = row_count; sa.cols = cols; sa.active_rows = active_rows;
         sa.n_active = n_active; sa.cx = cx;
+        if (!prune) {      // dense: the window by its first tiles (pruned: the tile lists hold only the window's tiles)
+          sa.A += (size_t)wH0 * BM * kSliceK; sa.B += (size_t)wT0 * BN * kSliceK; sa.nH = nHw; sa.nT = nTw; sa.cx = cxw;
+        }
         // Dense: tail tiles are cut into ranges of about kL2RangeBytes of staged B rows and the range is the
         // slowest grid dimension, so that a range stays in the 4 MiB L2 of every XCD while all head tiles of
         // all relations of the batch pass over it (the tail rows then cost almost no HBM traffic; what remains
@@ -1448,9 +1518,9 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
           const int64_t range_bytes = hd->cfg.range_kib > 0 ? (int64_t)hd->cfg.range_kib * 1024
                                       : (tc.head_resident ? kL2RangeBytesResident : kL2RangeBytes);
-          nsplit = (nT * tile_bytes + range_bytes - 1) / range_bytes;
-          nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nH * RB - 1) / ((int64_t)nH * RB));
-          nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nT, 65535)));
+          nsplit = (nTw * tile_bytes + range_bytes - 1) / range_bytes;
+          nsplit = std::max<int64_t>(nsplit, (4096 + (int64_t)nHw * RB - 1) / ((int64_t)nHw * RB));
+          nsplit = std::max<int64_t>(1, std::min<int64_t>(nsplit, std::min<int64_t>(nTw, 65535)));
         }
         void (*kern)(const JoinStreamArgs) = prune ? tc.listed_kernel : tc.stream_kernel;
         if (tile_id == kDenseL2Tile) {
@@ -1469,7 +1539,7 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           }
           KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
         }
-        const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nH, (unsigned)RB, (unsigned)nsplit);
+        const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nHw, (unsigned)RB, (unsigned)nsplit);
         // the head-resident and streaming kernels list the accumulator blocks that hold candidates; a kernel of its own
         // then scores the list (the barrier-free dense kernels re-score in place: their candidates are few per tile)
         const bool lists_blocks = tile_id != kDenseL2Tile && tile_id != kDirectL2Tile && tile_id != kDirectL2Tile + 1 &&
@@ -1486,14 +1556,14 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
           hipLaunchKernelGGL(k_join_l2_pairs, dim3(2048), dim3(256), pair_lds, st, sa);
         }
         if (lists_blocks) {
-          launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, hd->xcap, &cnt->exact_total, &cnt->exact_need, cx);
+          launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, hd->xcap, &cnt->exact_total, &cnt->exact_need, sa.cx);
           k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 1, 0u);
         }
       } else {
         JoinArgs ja{};
-        ja.A = (const uint16_t*)hd->opA.p; ja.B = (const uint16_t*)hd->opB.p; ja.prm = prm;
-        ja.Nslots = Nslots; ja.KS = KS; ja.k16 = k16; ja.nH = nH; ja.nT = nT; ja.r0 = (int)r0; ja.RB = RB; ja.cx = cx;
-        hipLaunchKernelGGL(tc.tile_kernel, dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(tc.threads), 0, st, ja);
+        ja.A = (const uint16_t*)hd->opA.p + (size_t)wH0 * BM * kSliceK; ja.B = (const uint16_t*)hd->opB.p + (size_t)wT0 * BN * kSliceK; ja.prm = prm;
+        ja.Nslots = Nslots; ja.KS = KS; ja.k16 = k16; ja.nH = nHw; ja.nT = nTw; ja.r0 = (int)r0; ja.RB = RB; ja.cx = cxw;
+        hipLaunchKernelGGL(tc.tile_kernel, dim3((unsigned)nTw, (unsigned)nHw, (unsigned)RB), dim3(tc.threads), 0, st, ja);
       }
       if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     } else {
@@ -1501,8 +1571,9 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
       la.prm = prm; la.Nslots = Nslots; la.nH = nH; la.nT = nT; la.r0 = (int)r0; la.RB = RB;
       la.row_start = row_start; la.row_count = row_count; la.cols = cols; la.active_rows = active_rows;
       la.n_active = n_active; la.cx = cx;
+      if (!prune) { la.nH = nHw; la.nT = nTw; la.cx = cxw; }
       if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b], st));
-      hipLaunchKernelGGL(k_join_l1, prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nT, (unsigned)nH, (unsigned)RB), dim3(256), 0,
+      hipLaunchKernelGGL(k_join_l1, prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nTw, (unsigned)nHw, (unsigned)RB), dim3(256), 0,
                          st, la);
       if (timed) KGC_HIP(hd, hipEventRecord(hd->join_ev[2 * b + 1], st));
     }
@@ -1513,12 +1584,15 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
   KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
   KGC_HIP(hd, hipStreamSynchronize(st));
 
+  pr.valid = !fact;                  // what the handle now holds describes this join
+  pr.bitmap_valid = prune && nbatch == 1 && !empty_window; pr.bm_r0 = r_begin; pr.bm_r1 = r_end;
   // A batch that wanted to list more accumulator blocks than the list holds has dropped the rest (and counted
   // them): the list grows to what was asked for and the join runs again from the start.
   if (hd->host_counters->exact_need > hd->xcap) {
     const unsigned long long need = hd->host_counters->exact_need;
     hd->xcap = (unsigned int)std::min<unsigned long long>(need + need / 4 + 1024, 0xffffffffull);
-    return kgc_join_range(hd, E, N, d, Rvecs, R, p, delta, r_begin, r_end, out_triples, cap, count);
+    return join_range_impl(hd, E, N, d, Rvecs, R, p, delta, r_begin, r_end, out_triples, cap, count, win,
+                           prep_mode == kPrepFresh ? kPrepReuse : prep_mode);      // (what was just prepared is still good)
   }
 
   kgc_stats& s = hd->stats;
@@ -1552,6 +1626,80 @@ int kgc_join_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const vo
 
   *count = s.emitted;
   return s.emitted > cap ? KGC_OVERFLOW : KGC_OK;
+}
+
+
+// The join block by block (Section 4.7).  The slot order of the join (the grouped order with pruning on, the entity
+// order otherwise) is cut into blocks of block_rows rows, the relations into ranges of rel_block, and the units
+// (relation range, head block, tail block) are joined one after the other, in that order, each through the kernels
+// of kgc_join over a window.  Grouping, summaries and the staged tail operands are made by the first unit and
+// reused by the others, also across calls; the bound test of a relation range is reused by the units of that range.
+int kgc_join_blocks(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
+                    float delta, int64_t block_rows, int32_t rel_block, kgc_cursor* cursor, kgc_triple* out_triples,
+                    uint64_t cap, uint64_t* count) {
+  if (!hd) return KGC_E_INVALID;
+  if (!count) return fail(hd, KGC_E_INVALID, "count is NULL");
+  *count = 0;
+  if (!cursor) return fail(hd, KGC_E_INVALID, "cursor is NULL");
+  if (block_rows < 1 || rel_block < 1) return fail(hd, KGC_E_INVALID, "block_rows and rel_block must be positive");
+  if (hd->cfg.factorised) return fail(hd, KGC_E_INVALID, "kgc_join_blocks does not take the relation-factorised form");
+  if (hd->static_mode) return fail(hd, KGC_E_INVALID, "kgc_join_blocks allocates: not available inside kgc_join_static");
+  cursor->need = 0;
+  if (N <= 0 || R <= 0) {            // (negative sizes are reported by the checks of the join itself)
+    uint64_t c = 0;
+    const int rc0 = join_range_impl(hd, E, N, d, Rvecs, R, p, delta, 0, R < 0 ? 0 : R, out_triples, cap, &c, nullptr, kPrepFresh);
+    cursor->unit = 0; cursor->units = 0;
+    return rc0;
+  }
+  const int64_t brows = (block_rows + kSlotAlign - 1) / kSlotAlign * kSlotAlign;      // blocks are whole 256-row tiles
+  const bool prune = hd->cfg.prune != KGC_PRUNE_OFF;
+  const int64_t n_rel = ((int64_t)R + rel_block - 1) / rel_block;
+  if (cursor->unit > 0) {
+    // a continued join: the handle must still hold this join's row order (a grouped order cannot be made again the same)
+    const kgc_handle::Prep& pr = hd->prep;
+    const bool same = pr.valid && pr.E == E && pr.Rv == Rvecs && pr.N == N && pr.d == d && pr.p == p && pr.delta == delta;
+    if (prune && !same)
+      return fail(hd, KGC_E_INVALID, "the handle no longer holds this join's row order: start again with a zeroed cursor");
+  }
+  uint64_t written = 0;
+  kgc_stats total{};
+  for (;;) {
+    // blocks per side: known once the row order is (the grouped order pads its groups); the first unit is (0, 0, 0) anyway
+    int64_t Nslots = (N + kSlotAlign - 1) / kSlotAlign * kSlotAlign;
+    if (hd->prep.valid && hd->prep.E == E && hd->prep.N == N) Nslots = hd->prep.Nslots;
+    else if (cursor->unit > 0 && prune) return fail(hd, KGC_E_INVALID, "the handle lost this join's row order");
+    const int64_t nb = (Nslots + brows - 1) / brows;
+    const uint64_t units = (uint64_t)n_rel * (uint64_t)nb * (uint64_t)nb;
+    cursor->units = units;
+    if (cursor->unit >= units) break;
+    const uint64_t u = cursor->unit;
+    const int64_t rr = (int64_t)(u / (uint64_t)(nb * nb)), bh = (int64_t)((u / (uint64_t)nb) % (uint64_t)nb), bt = (int64_t)(u % (uint64_t)nb);
+    const JoinWindow w{bh * brows, (bh + 1) * brows, bt * brows, (bt + 1) * brows};
+    const int32_t r_lo = (int32_t)(rr * rel_block), r_hi = (int32_t)std::min<int64_t>((int64_t)R, (rr + 1) * (int64_t)rel_block);
+    uint64_t c = 0;
+    const int rc = join_range_impl(hd, E, N, d, Rvecs, R, p, delta, r_lo, r_hi, out_triples ? out_triples + written : nullptr,
+                                   cap - written, &c, &w, u == 0 ? kPrepFresh : kPrepReuse);
+    if (rc != KGC_OK && rc != KGC_OVERFLOW) return rc;
+    if (rc == KGC_OVERFLOW) {         // the unit does not fit what is left of the buffer: it stays to be done
+      cursor->need = c;
+      hd->stats = total; hd->stats.emitted = written;
+      *count = written;
+      return KGC_OVERFLOW;
+    }
+    written += c;
+    const kgc_stats& b = hd->stats;
+    total.triples_total += b.triples_total; total.tiles_total += b.tiles_total; total.tiles_evaluated += b.tiles_evaluated;
+    total.tiles_pruned += b.tiles_pruned; total.pairs_evaluated += b.pairs_evaluated; total.candidates += b.candidates;
+    total.join_launches += b.join_launches; total.ms_total += b.ms_total; total.ms_precompute += b.ms_precompute;
+    total.ms_prune += b.ms_prune; total.ms_join += b.ms_join; total.relation_batches += b.relation_batches;
+    total.exact_blocks += b.exact_blocks; total.groups = b.groups; total.tile_m = b.tile_m; total.tile_n = b.tile_n;
+    total.k_padded = b.k_padded; total.join_variant = b.join_variant;
+    cursor->unit = u + 1;
+  }
+  hd->stats = total; hd->stats.emitted = written;
+  hd->stats.triples_total = (uint64_t)N * (uint64_t)N * (uint64_t)R;
+  *count = written;
+  return KGC_OK;
 }
 
 }  // extern "C"

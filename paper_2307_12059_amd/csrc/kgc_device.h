@@ -75,7 +75,8 @@ struct RecheckCtx {
                              // (one entity array), N * d for per-relation connector outputs
   int64_t rstride;           // elements between relation vectors: d, or 0 when every relation reads row 0 of Rv
                              // (the general form, whose head rows already are connector_1(h, r): Rv is a zero row)
-  const int32_t* slot_ent;   // slot -> entity row, -1 for padding
+  const int32_t* slot_ent;   // slot -> entity row, -1 for padding (head side)
+  const int32_t* slot_ent_t; // the same for the tail side (a join over a window of tiles counts its slots from the window's start)
   int dtype;
   int d;
   int p;
@@ -291,7 +292,7 @@ __device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, 
 #pragma unroll
   for (int q = 0; q < 2; ++q) {
     hent[q] = cx.slot_ent[hs0 + 16 * q + rr];
-    tent[q] = cx.slot_ent[ts0 + 16 * q + rr];
+    tent[q] = cx.slot_ent_t[ts0 + 16 * q + rr];
     ho[q] = (int64_t)r * cx.hstride + (int64_t)(hent[q] < 0 ? 0 : hent[q]) * d;
     to[q] = (int64_t)r * cx.tstride + (int64_t)(tent[q] < 0 ? 0 : tent[q]) * d;
   }
@@ -447,7 +448,7 @@ __device__ __forceinline__ void recheck_and_emit(unsigned long long cm, int32_t 
       int64_t hslot, tslot;
       map(e, src, hslot, tslot);
       h = cx.slot_ent[hslot];
-      t = cx.slot_ent[tslot];
+      t = cx.slot_ent_t[tslot];
       if (h >= 0 && t >= 0 && !(cx.no_self && h == t)) {
         const double dist = group16_exact_dist(cx, h, r, t, sub);
         hit = dist <= cx.delta;
@@ -529,7 +530,7 @@ __device__ __forceinline__ void block_recheck(unsigned long long (&cm)[NW], int3
     for (unsigned int i = threadIdx.x; i < qn; i += NWAVES * 64) {
       const unsigned long long ent = q->ent[i];
       q->ent[i] = ((unsigned long long)(uint32_t)cx.slot_ent[(int64_t)(uint32_t)(ent >> 32)] << 32) |
-                  (unsigned long long)(uint32_t)cx.slot_ent[(int64_t)(uint32_t)ent];
+                  (unsigned long long)(uint32_t)cx.slot_ent_t[(int64_t)(uint32_t)ent];
     }
     __syncthreads();
     // 2. all groups drain the queue, kDrain entries per group and step (entry e0 + 4 * wave + group and those

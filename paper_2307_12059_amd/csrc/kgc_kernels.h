@@ -59,6 +59,15 @@ __global__ void k_shift_relation(kgc_triple* rec, uint64_t n, int32_t r0) {
   for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) rec[i].r += r0;
 }
 
+// dense join over a window of head tiles: the (relation, 256-row tile) rows that the operand staging has to fill
+__global__ void k_window_rows(uint32_t* rows, unsigned int* n_rows, int RB, int n_tiles, int w0, int w1) {
+  const int per_rel = w1 - w0;
+  const int64_t total = (int64_t)RB * per_rel;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x)
+    rows[i] = (uint32_t)((i / per_rel) * n_tiles + w0 + i % per_rel);
+  if (blockIdx.x == 0 && threadIdx.x == 0) *n_rows = (unsigned int)total;
+}
+
 // after the tile lists of a pruned batch: the running total of surviving tiles, and which L2 join kernel takes the
 // batch: tile by tile when its rows keep at most kPairModeTilesPerRow tiles on average (and the host allows it)
 constexpr unsigned long long kPairModeTilesPerRow = 3;
@@ -1712,7 +1721,7 @@ __global__ __launch_bounds__(256, 3) void k_join_l1(const JoinL1Args a) {
   for (int ti = t_begin; ti < t_end; ++ti) {
     const int tT = cols ? (int)cols[ti] : ti;
     __syncthreads();                        // previous tile done with tent / As / Bs
-    if (tid >= BM) tent[tid - BM] = a.cx.slot_ent[(int64_t)tT * BN + (tid - BM)];
+    if (tid >= BM) tent[tid - BM] = a.cx.slot_ent_t[(int64_t)tT * BN + (tid - BM)];
     __syncthreads();
     float acc[8][8];
 #pragma unroll

@@ -826,7 +826,18 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
                                                          unsigned long long* __restrict__ total,
                                                          uint32_t* __restrict__ active_rows,
                                                          unsigned int* __restrict__ n_active,
-                                                         uint32_t* __restrict__ tile_rows) {      // may be NULL: the row of every entry of cols
+                                                         uint32_t* __restrict__ tile_rows,        // may be NULL: the row of every entry of cols
+                                                         int nH = 1, int h0 = 0, int h1 = 0x7fffffff,     // window: only head tiles [h0, h1)
+                                                         int t0 = 0, int t1 = 0x7fffffff) {               // ... and tail tiles [t0, t1) count
+  // word i of a row holds tail tiles 32 i .. 32 i + 31: the bits of those inside [t0, t1)
+  auto col_mask = [=](int i) -> uint32_t {
+    const int lo = t0 - 32 * i, hi = t1 - 32 * i;
+    if (hi <= 0 || lo >= 32) return 0u;
+    const uint32_t mlo = lo <= 0 ? 0xffffffffu : 0xffffffffu << lo;
+    const uint32_t mhi = hi >= 32 ? 0xffffffffu : (1u << hi) - 1u;
+    return mlo & mhi;
+  };
+  auto row_in = [=](int64_t row) -> bool { const int tH = (int)(row % nH); return tH >= h0 && tH < h1; };
   const int lane = threadIdx.x & 63;
   const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * (64 * kBitmapRowsPerLane);
   if (row0 >= n_rows) return;                                  // whole waves leave together
@@ -836,17 +847,17 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
     const int64_t base_row = row0 + k * 64;
     cnt[k] = 0;
     if (words_per_row <= 8) {                // short rows: every lane counts its own
-      if (base_row + lane < n_rows) {
+      if (base_row + lane < n_rows && row_in(base_row + lane)) {
         const uint32_t* w = bitmap + (base_row + lane) * words_per_row;
-        for (int i = 0; i < words_per_row; ++i) cnt[k] += __builtin_popcount(w[i]);
+        for (int i = 0; i < words_per_row; ++i) cnt[k] += __builtin_popcount(w[i] & col_mask(i));
       }
     } else {                                 // long rows: the wave counts them one after the other, words over lanes
       for (int rr = 0; rr < 64 && base_row + rr < n_rows; ++rr) {
         const uint32_t* w = bitmap + (base_row + rr) * words_per_row;
         uint32_t c = 0;
-        for (int i = lane; i < words_per_row; i += 64) c += __builtin_popcount(w[i]);
+        for (int i = lane; i < words_per_row; i += 64) c += __builtin_popcount(w[i] & col_mask(i));
         for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
-        if (lane == rr) cnt[k] = c;
+        if (lane == rr && row_in(base_row + rr)) cnt[k] = c;
       }
     }
   }
@@ -901,7 +912,7 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
       uint32_t run = 0;
       for (int i0 = 0; i0 < words_per_row; i0 += 64) {
         const int i = i0 + lane;
-        uint32_t word = i < words_per_row ? w[i] : 0u;
+        uint32_t word = i < words_per_row ? (w[i] & col_mask(i)) : 0u;
         const uint32_t pc = __builtin_popcount(word);
         uint32_t pre = pc;
         for (int off = 1; off < 64; off <<= 1) {

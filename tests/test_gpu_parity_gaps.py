@@ -366,3 +366,94 @@ def test_structured_embedding_join_overflow_and_empty():
         assert none["code"] == 0 and none["count"] == 0
     finally:
         j.close()
+
+
+# ---- the join block by block with a cursor (Section 4.7): a small buffer is drained again and again
+def _drain_blocks(j, Ed, Rd, p, delta, cap, block_rows, rel_block, max_calls=10000):
+    import paper_2307_12059_amd as kgc
+    parts, cursor, calls = [], None, 0
+    while True:
+        got = j.join_blocks(Ed, Rd, p, delta, cap, block_rows, rel_block, cursor)
+        cursor = got["cursor"]
+        calls += 1
+        assert calls <= max_calls
+        if got["code"] == kgc.KGC_OVERFLOW and got["count"] == 0:
+            assert cursor.need > cap          # one unit alone is larger than the buffer: take a larger one for it
+            cap = int(cursor.need)
+            continue
+        parts.append(got)
+        if got["code"] == 0:
+            assert cursor.unit == cursor.units
+            break
+        assert got["code"] == kgc.KGC_OVERFLOW and 0 < cursor.need
+    out = {k: np.concatenate([q[k] for q in parts]) for k in ("h", "r", "t", "dist")}
+    out["count"] = int(out["h"].size)
+    return out, calls, cursor
+
+
+@pytest.mark.parametrize("prune", [PRUNE_OFF, PRUNE_ON])
+@pytest.mark.parametrize("p", [1, 2])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,block_rows,rel_block", [(1100, 256, 2), (700, 300, 5), (1300, 1024, 1)])
+def test_join_blocks_drains_to_the_oracle_set(p, dtype, N, block_rows, rel_block, prune):
+    import paper_2307_12059_amd as kgc
+    g = np.random.default_rng(6000 + N + p)
+    R, d, sig = 5, 64, 0.1
+    E, Rv = _clustered(g, N, R, d, 7, sig)
+    E, Rv = _seen(E, dtype), _seen(Rv, dtype)
+    delta = float(np.float32(sig * np.sqrt(2.0 * d) if p == 2 else sig * np.sqrt(2.0) * d * 0.8))
+    ref = oracle.join(E, Rv, p, delta, mode="abandon")
+    assert ref["count"] > 1000
+    j = kgc.Join(dtype=dtype, prune=prune)
+    try:
+        got, calls, cursor = _drain_blocks(j, _dev(E, dtype), _dev(Rv, dtype), p, delta, max(64, ref["count"] // 7), block_rows, rel_block)
+    finally:
+        j.close()
+    assert calls >= 3, "the buffer was meant to be too small for one call"
+    nb = -(-(-(-N // 256) * 256) // (-(-block_rows // 256) * 256))
+    assert cursor.units >= (-(-R // rel_block)) * nb * nb          # (a grouped order may pad itself into more blocks)
+    parity.compare(got, ref, E, Rv, p, delta, N)                   # set against set, every triple once
+
+
+def test_join_blocks_equals_join_in_one_call_and_survives_other_calls():
+    import paper_2307_12059_amd as kgc
+    g = np.random.default_rng(6100)
+    N, R, d, sig = 900, 4, 37, 0.1
+    E, Rv = _clustered(g, N, R, d, 5, sig)
+    delta = float(np.float32(sig * np.sqrt(2.0 * d)))
+    ref = oracle.join(E, Rv, 2, delta, mode="abandon")
+    Ed, Rd = _dev(E, "f32"), _dev(Rv, "f32")
+    # everything in one call when the buffer is large enough
+    j = kgc.Join(dtype="f32", prune=PRUNE_ON)
+    try:
+        got = j.join_blocks(Ed, Rd, 2, delta, 2 * ref["count"], 512, 2)
+        assert got["code"] == 0 and got["cursor"].unit == got["cursor"].units
+        parity.compare(got, ref, E, Rv, 2, delta, N)
+        # a pruned join that is continued after another call on the handle is refused, not silently wrong
+        first = j.join_blocks(Ed, Rd, 2, delta, max(64, ref["count"] // 5), 512, 2)
+        assert first["code"] == kgc.KGC_OVERFLOW and first["cursor"].unit > 0
+        j.top1(Ed, Rd, 2)
+        with pytest.raises(RuntimeError, match="row order"):
+            j.join_blocks(Ed, Rd, 2, delta, max(64, ref["count"] // 5), 512, 2, first["cursor"])
+    finally:
+        j.close()
+    # a dense join keeps going: its row order is the entity order
+    j = kgc.Join(dtype="f32", prune=PRUNE_OFF)
+    try:
+        cap = max(64, ref["count"] // 5)
+        parts, cursor = [], None
+        for step in range(1000):
+            got = j.join_blocks(Ed, Rd, 2, delta, cap, 512, 2, cursor)
+            cursor = got["cursor"]
+            if got["code"] == kgc.KGC_OVERFLOW and got["count"] == 0:
+                cap = int(cursor.need)
+                continue
+            parts.append(got)
+            if got["code"] == 0:
+                break
+            j.top1(Ed, Rd, 2)               # the handle is used for something else between the calls
+        allp = {k: np.concatenate([q[k] for q in parts]) for k in ("h", "r", "t", "dist")}
+        allp["count"] = int(allp["h"].size)
+        parity.compare(allp, ref, E, Rv, 2, delta, N)
+    finally:
+        j.close()
