@@ -185,6 +185,11 @@ def main():
         roof["kernel"] = ("k_join_l1" if p == 1 else "k_join_l2_fact" if v == 100 else "k_join_l2_dense" if v == 18
                           else "k_join_l2_direct" if v >= 15 else "k_join_l2_ares" if v >= 11
                           else "k_join_l2_stream" if v >= 6 else "k_join_l2")
+        if prune and p == 2 and 6 <= v <= 14:
+            # the pruned join: the tile kernel (128 x 128 tiles: tile by tile or row by row, chosen per batch on the
+            # device) lists the accumulator blocks with candidates, a second kernel scores them in double precision;
+            # ms_join spans both
+            roof["kernel"] = ("k_join_l2_pairs|k_join_l2_ares" if v == 14 else roof["kernel"]) + " + k_exact_blocks"
         roof["tile_cfg"] = v
         roof["launches_per_step"] = launches
         roof["avg_launch_ms"] = ms_join / launches

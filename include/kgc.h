@@ -57,7 +57,8 @@ typedef struct {
     int32_t tile_cfg;         /* 0 = automatic choice of the L2 join kernel; > 0 forces a variant (for measurements):
                                  1-5   one block per tile pair, 128/256-row tiles (dense mode only)
                                  6-10  streaming: a block walks tail tiles, head and tail slices through LDS (any d)
-                                 11-14 head tile resident in LDS, tail slices through LDS (d <= 218; pruned default 12)
+                                 11-14 head tile resident in LDS, tail slices through LDS (d <= 250; pruned defaults:
+                                       14, two 128 x 128 blocks per CU, below 262,144 entities; 12, 256 x 256, from there on)
                                  15-18 head tile resident, tail fragments straight to registers, no barrier in the
                                        loop (dense mode only; 15-16: d <= 282; 17: d <= 602; 18: d <= 282, one
                                        straight-line instantiation per number of K steps, the dense default)
@@ -226,7 +227,8 @@ int kgc_join_se(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void*
 int kgc_top1(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
              int32_t exclude_self, kgc_triple* out);
 
-/* The k triples with the smallest distances (kgc_top1 for k = 1 .. 65536), optionally without self pairs.
+/* The k triples with the smallest distances: the top-k scores the experiments of Section 3.3 rank by (kgc_top1 is
+ * k = 1; k up to 65536), optionally without self pairs.
  *   out_triples  room for k records, 16-byte aligned, in no particular order                 (device)
  *   found        receives min(k, number of eligible triples)                                 (host)
  * Joins with a growing threshold, started just above the top-1 bound of kgc_top1, until one returns at least
@@ -236,7 +238,7 @@ int kgc_topk(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rv
              int32_t exclude_self, uint64_t k, kgc_triple* out_triples, uint64_t* found);
 
 /* kgc_topk over the relations r_begin <= r < r_end only (kgc_topk is the range [0, R)); with a range of one
- * relation, the k best (h, t) pairs of that relation. */
+ * relation, the k best (h, t) pairs of that relation: the per-relation ranking of Section 3.3. */
 int kgc_topk_range(kgc_handle* hd, const void* E, int64_t N, int32_t d, const void* Rvecs, int32_t R, int32_t p,
                    int32_t exclude_self, int32_t r_begin, int32_t r_end, uint64_t k, kgc_triple* out_triples,
                    uint64_t* found);

@@ -65,12 +65,21 @@ def library_path() -> str:
 
 
 def load_library():
-    """Load libkgc.so (building it first only if no built library exists)."""
+    """Load libkgc.so.  It is built first when no built library exists.  A library older than its sources is loaded
+    as it is, with a warning (a rebuild takes minutes and the GPU tests must not spend them): run
+    ``python -m paper_2307_12059_amd.build`` after a change, or set KGC_REBUILD_STALE=1 to have it done here."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build()
+    elif _build.stale():
+        if os.environ.get("KGC_REBUILD_STALE") == "1":
+            _build.build()
+        else:
+            import warnings
+            warnings.warn("libkgc.so is older than its sources: loading it as it is (rebuild with "
+                          "`python -m paper_2307_12059_amd.build`)", RuntimeWarning, stacklevel=2)
     lib = ctypes.CDLL(_build.LIB)
     vp = ctypes.c_void_p
     lib.kgc_create.restype = ctypes.c_int
