@@ -425,7 +425,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       if (p == 2) k_tile_dist<2, kEpiBound><<<g, 256, 0, st>>>(ta);
       else k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
       k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
-      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 256 * kBitmapRowsPerLane - 1) / (256 * kBitmapRowsPerLane)), 256, 0, st>>>(
+      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 256 * bitmap_rows_per_lane(words_per_row) - 1) / (256 * bitmap_rows_per_lane(words_per_row))), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p, &cnt->n_active,
           pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr);
@@ -1440,7 +1440,7 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         }
       }
       k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
-      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 256 * kBitmapRowsPerLane - 1) / (256 * kBitmapRowsPerLane)), 256, 0, st>>>(
+      k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 256 * bitmap_rows_per_lane(words_per_row) - 1) / (256 * bitmap_rows_per_lane(words_per_row))), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p,
           &cnt->n_active, pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr, nH, wH0, wH1, wT0, wT1);

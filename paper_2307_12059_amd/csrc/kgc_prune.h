@@ -820,6 +820,8 @@ __global__ __launch_bounds__(256) void k_bound_refine(const BoundL2Args fine, co
 // whole scan), and the rows that have tiles are then written out by the whole wave, one row after the other, tile
 // numbers ascending.
 constexpr int kBitmapRowsPerLane = 8;
+constexpr int kBitmapShortWords = 64;
+__host__ __device__ inline int bitmap_rows_per_lane(int words_per_row) { return words_per_row <= kBitmapShortWords ? kBitmapRowsPerLane : 1; }
 __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __restrict__ bitmap, int words_per_row,
                                                          int64_t n_rows, uint32_t* __restrict__ row_start,
                                                          uint32_t* __restrict__ row_count, uint32_t* __restrict__ cols,
@@ -839,14 +841,18 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
   };
   auto row_in = [=](int64_t row) -> bool { const int tH = (int)(row % nH); return tH >= h0 && tH < h1; };
   const int lane = threadIdx.x & 63;
-  const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * (64 * kBitmapRowsPerLane);
+  // rows of up to kBitmapShortWords words are counted one per lane, kBitmapRowsPerLane of them; longer rows by the
+  // whole wave, one after the other, 64 per wave
+  const int rpl = bitmap_rows_per_lane(words_per_row);
+  const int64_t row0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * (64 * rpl);
   if (row0 >= n_rows) return;                                  // whole waves leave together
   uint32_t cnt[kBitmapRowsPerLane];
 #pragma unroll
   for (int k = 0; k < kBitmapRowsPerLane; ++k) {
     const int64_t base_row = row0 + k * 64;
     cnt[k] = 0;
-    if (words_per_row <= 8) {                // short rows: every lane counts its own
+    if (k >= rpl) continue;
+    if (words_per_row <= kBitmapShortWords) {   // short rows: every lane counts its own
       if (base_row + lane < n_rows && row_in(base_row + lane)) {
         const uint32_t* w = bitmap + (base_row + lane) * words_per_row;
         for (int i = 0; i < words_per_row; ++i) cnt[k] += __builtin_popcount(w[i] & col_mask(i));
@@ -887,7 +893,7 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
   for (int k = 0; k < kBitmapRowsPerLane; ++k) {
     const int64_t my_row = row0 + k * 64 + lane;
     bases[k] = cnt[k] ? my_base : 0ull;
-    if (my_row < n_rows) {
+    if (k < rpl && my_row < n_rows) {
       row_start[my_row] = (uint32_t)bases[k];
       row_count[my_row] = cnt[k];
       if (cnt[k]) active_rows[my_act++] = (uint32_t)my_row;   // rows that still have work, in any order
@@ -896,7 +902,7 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
   }
   if (!wrows) return;
 #pragma unroll 1
-  for (int k = 0; k < kBitmapRowsPerLane; ++k) {
+  for (int k = 0; k < rpl; ++k) {
     uint32_t c = 0;
     unsigned long long bk = 0;
 #pragma unroll
