@@ -27,6 +27,7 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 namespace {
 
 constexpr int kMaxD = 960;                      // keeps kernel 1's LDS tile under 64 KiB
+constexpr int64_t kFewEntities = 32768;        // grouping: up to here three covering rounds instead of six
 constexpr int64_t kSlotAlign = 256;            // rows are padded to a multiple of the largest tile
 constexpr int64_t kDefaultWorkspace = 16ll << 30;
 constexpr size_t kBoundPairCap = 8u << 20;      // surviving (relation, unit, unit) entries of one batch kept in the list
@@ -679,11 +680,17 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
   unc = (int32_t*)hd->unc_a.p;
   unc_next = (int32_t*)hd->unc_b.p;
   k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
-  for (int round = 0; round < kGroupRounds; ++round) {
-    // sampling density of the pivots among the still uncovered entities: 1/16, 1/16, 1/8, 1/8, 1/4, 1/2
+  // Sampling density of the pivots among the still uncovered entities, round by round: 1/16, 1/16, 1/8, 1/8, 1/4,
+  // 1/2.  With few entities three rounds at 1/4, 1/2 and 1 reach the same cover (their up to 3 x 4,096 pivots are
+  // more than a third of the entities; several pivots in one natural cluster do not split it, the lowest one within
+  // reach wins), and each round is five launches that a small join feels.
+  const bool few = N <= kFewEntities;
+  const int n_rounds = few ? 3 : kGroupRounds;
+  for (int round = 0; round < n_rounds; ++round) {
     static const int kShift[kGroupRounds] = {4, 4, 3, 3, 2, 1};
+    static const int kShiftFew[3] = {2, 1, 0};
     k_round_begin<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->piv_ent.p, (unsigned long long*)hd->best.p,
-                                     kShift[round], mfma_assign ? 1 : 0);
+                                     few ? kShiftFew[round] : kShift[round], mfma_assign ? 1 : 0);
     if (mfma_assign) {
       k_stage_operands<false><<<kPivotsPerRound / kStageRows, 256, asg_lds, st>>>(
           E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->piv_ent.p, kPivotsPerRound, KS, (uint16_t*)hd->asg_b.p, nullptr,
@@ -1413,7 +1420,7 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
           k_bound_l2_units<<<gu, 256, 0, st>>>(bu, ba, ut, bp);
           k_bound_refine<<<dim3(1024, 32, 1), 256, 0, st>>>(ba, ut, bp);
         } else {
-          const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)((n_micro + kHeadChunk - 1) / kHeadChunk),
+          const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)((n_micro + kHeadsFlat - 1) / kHeadsFlat),
                        (unsigned)((RB + kRelChunk - 1) / kRelChunk));
           k_bound_l2<<<g, 256, 0, st>>>(ba);
         }

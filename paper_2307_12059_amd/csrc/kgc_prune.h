@@ -555,28 +555,40 @@ struct BoundL2Args {
   const float* cent; const void* Rv; int dtype; int r0;
 };
 constexpr int kHeadChunk = 16;
+constexpr int kHeadsFlat = 64;       // head micro-tiles per block of the flat test (four groups of kHeadChunk)
 __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
-  // block = 256 tail micro-tiles x kHeadChunk head micro-tiles x kRelChunk relations; the per-(head, relation)
+  // block = 256 tail micro-tiles x kHeadsFlat head micro-tiles x kRelChunk relations; the per-(head, relation)
   // terms sit in LDS, the thread's own per-relation terms in registers, so one test costs one (shared) D load per
-  // kRelChunk relations, one addition and one comparison
-  __shared__ __attribute__((aligned(16))) float aH[kHeadChunk][kRelChunk];   // 2 r.c_H + ||r||^2 - kk ||c_H|| ||r|| per (head micro-tile, relation)
+  // kRelChunk relations, one addition and one comparison -- and most chunks of relations end at one comparison
+  __shared__ __attribute__((aligned(16))) float aH[kHeadsFlat][kRelChunk];   // 2 r.c_H + ||r||^2 - kk ||c_H|| ||r|| per (head micro-tile, relation)
   __shared__ float srnS[kRelChunk];
-  __shared__ float radH[kHeadChunk];
+  __shared__ float radH[kHeadsFlat], aHmin[kHeadsFlat];
   const int tid = threadIdx.x;
   const int64_t mT = (int64_t)blockIdx.x * blockDim.x + tid;
-  const int64_t mH0 = (int64_t)blockIdx.y * kHeadChunk;
+  const int64_t mH0 = (int64_t)blockIdx.y * kHeadsFlat;
   const int rl0 = (int)blockIdx.z * kRelChunk;
   const float kk = 2.f * (float)(a.d + 12) * 6e-8f;
   {
-    const int hq = tid / kRelChunk, q = tid % kRelChunk;        // 256 threads = kHeadChunk x kRelChunk
+    const int q = tid % kRelChunk;                              // 256 threads = 16 heads x kRelChunk relations per pass
     const int rl = rl0 + q;
-    const int64_t mH = mH0 + hq;
     const float rnq = rl < a.RB ? a.rn[rl] : 0.f;
-    const bool in = rl < a.RB && mH < a.n_micro;
-    const float ah = in ? 2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f) : 0.f;
-    aH[hq][q] = in ? ah - (kk * a.cnorm[mH]) * sqrtf(rnq) : 0.f;
-    if (tid < kRelChunk) srnS[tid] = sqrtf((rl0 + tid < a.RB) ? a.rn[rl0 + tid] : 0.f);
-    if (tid < kHeadChunk) {
+    const float srn = sqrtf(rnq);
+#pragma unroll
+    for (int pass = 0; pass < kHeadsFlat / 16; ++pass) {
+      const int hq = pass * 16 + tid / kRelChunk;
+      const int64_t mH = mH0 + hq;
+      const bool in = rl < a.RB && mH < a.n_micro;
+      const float ah = in ? 2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f) : 0.f;
+      const float ahq = in ? ah - (kk * a.cnorm[mH]) * srn : 0.f;
+      aH[hq][q] = ahq;
+      // the smallest left side of the head micro-tile over the chunk's relations (the 16 lanes that hold them are neighbours)
+      float mn = in ? ahq : 3e38f;
+      mn = fminf(mn, __shfl_xor(mn, 8, 16)); mn = fminf(mn, __shfl_xor(mn, 4, 16));
+      mn = fminf(mn, __shfl_xor(mn, 2, 16)); mn = fminf(mn, __shfl_xor(mn, 1, 16));
+      if (q == 0) aHmin[hq] = mn;
+    }
+    if (tid < kRelChunk) srnS[tid] = srn;
+    if (tid < kHeadsFlat) {
       const int64_t m = mH0 + tid;
       radH[tid] = m < a.n_micro ? a.rad[m] : -1.f;
     }
@@ -597,25 +609,35 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
 #pragma unroll
   for (int q = 0; q < kRelChunk; ++q)
     bT[q] = q < nrel ? 2.f * a.u[(int64_t)(rl0 + q) * a.n_micro + mT] + (kk * cT) * srnS[q] : -3e38f;   // past the batch: never passes
+  // One comparison first for the whole chunk: no relation can pass when even the smallest left side exceeds the right
+  // side with the largest per-relation term (float addition is monotonic, so this is the 16 tests' own arithmetic:
+  // nothing is widened).  For TransE data the two sides are 6 sigma apart, so almost every chunk ends here.
+  float bmax = bT[0];
+#pragma unroll
+  for (int q = 1; q < kRelChunk; ++q) bmax = fmaxf(bmax, bT[q]);
   const int tT = (int)(mT / a.micro_per_bn);
   const float dsl = a.delta * (1.f + kBoundSlack);
   const float dk = (float)(a.d + 8) * 6e-8f;
-  // the centre distances of the chunk, all loads in flight together (a head past the end reads row 0; it is skipped below)
+  for (int hg = 0; hg < kHeadsFlat; hg += kHeadChunk) {
+  if (mH0 + hg >= a.n_micro) break;                              // the same for the block
+  // the centre distances of a group of heads, all loads in flight together (a head past the end reads the group's first row; it is skipped below)
   float Dv[kHeadChunk];
   {
-    const float* Dp = a.D + mH0 * a.n_micro + mT;
-    const int nvalid = a.n_micro - mH0 < kHeadChunk ? (int)(a.n_micro - mH0) : kHeadChunk;     // the same for the block
+    const float* Dp = a.D + (mH0 + hg) * a.n_micro + mT;
+    const int nvalid = a.n_micro - (mH0 + hg) < kHeadChunk ? (int)(a.n_micro - (mH0 + hg)) : kHeadChunk;
 #pragma unroll
     for (int hq = 0; hq < kHeadChunk; ++hq) Dv[hq] = Dp[hq < nvalid ? (int64_t)hq * a.n_micro : 0];
   }
 #pragma unroll
-  for (int hq = 0; hq < kHeadChunk; ++hq) {
+  for (int hl = 0; hl < kHeadChunk; ++hl) {
+    const int hq = hg + hl;
     const float rH = radH[hq];
     if (rH < 0.f) continue;                                      // empty or past the end
     const int64_t mH = mH0 + hq;
-    const float D = Dv[hq];
+    const float D = Dv[hl];
     const float reach = dsl + rH + rT;
     const float rhs = reach * reach * (1.f + kBoundSlack) + D * dk - D;
+    if (__builtin_amdgcn_ballot_w64(aHmin[hq] <= rhs + bmax) == 0ull) continue;
     bool any = false;
 #pragma unroll
     for (int q = 0; q < kRelChunk; ++q) any |= aH[hq][q] <= rhs + bT[q];
@@ -630,6 +652,7 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
       atomicOr(&a.bitmap[((int64_t)(rl0 + q) * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
     }
   }
+  }   // groups of heads
 }
 
 // ---------------------------------------------------------------------------------------------
