@@ -309,7 +309,7 @@ __device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, 
   // to four successive steps (step e of the group multiplies dimensions 16 g + 4 slot + e, slot = 0 .. 3).
   // The rows are walked in chunks of kGroups groups: ALL loads of a chunk are issued before any is used, so a chunk
   // costs one memory round trip.  Elements past d count as zero.
-  constexpr int kGroups = 8;
+  constexpr int kGroups = 4;
   for (int k0 = 0; k0 < d; k0 += 16 * kGroups) {
     f32x4_t hv[2][kGroups], tv[2][kGroups], rv[kGroups];
 #pragma unroll

@@ -527,7 +527,7 @@ __device__ __forceinline__ void list_block(const JoinStreamArgs& a, int32_t r, i
 // The exact stage of the L2 joins that list blocks: one wave per listed block (exact_block_l2), the grid strides over
 // the list.
 template <bool BF16, bool VEC>
-__global__ __launch_bounds__(256, 2) void k_exact_blocks(const ExactEntry* __restrict__ list, const unsigned int* __restrict__ count,
+__global__ __launch_bounds__(256, 3) void k_exact_blocks(const ExactEntry* __restrict__ list, const unsigned int* __restrict__ count,
                                                       unsigned int cap, unsigned long long* __restrict__ total,
                                                       unsigned int* __restrict__ need, const RecheckCtx cx) {
   const unsigned int n = *count < cap ? *count : cap;
