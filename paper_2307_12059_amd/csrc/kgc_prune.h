@@ -476,28 +476,29 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
 
 // The same MATRIX results for small operands (a few hundred to a few thousand rows and columns: micro-tile centres,
 // relation vectors), where the 128 x 128 tiles above leave most of the chip idle: 32 x 32 results per block of 256
-// threads, K through LDS 32 dimensions at a time, four rows x one column per thread.  out[i][j] = ||x_i - y_j||^2
+// threads, K through LDS 128 dimensions at a time, four rows x one column per thread.  out[i][j] = ||x_i - y_j||^2
 // (P = 2) or x_i . y_j (P = 0), row-major n_rows x n_cols; X rows of the given type, Y rows float32.
 template <int P>
 __global__ __launch_bounds__(256) void k_small_matrix(const void* __restrict__ X, int dtypeX, int64_t n_rows,
                                                       const float* __restrict__ Y, int64_t n_cols, int d,
                                                       float* __restrict__ out) {
-  __shared__ float xs[32][33], ys[32][33];
+  constexpr int KC = 128;                                 // dimensions per pass through LDS (d <= 128: one pass, two barriers)
+  __shared__ float xs[32][KC + 1], ys[32][KC + 1];
   const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
   const int64_t row0 = (int64_t)blockIdx.y * 32, col0 = (int64_t)blockIdx.x * 32;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int k0 = 0; k0 < d; k0 += 32) {
+  for (int k0 = 0; k0 < d; k0 += KC) {
+    const int kn = d - k0 < KC ? d - k0 : KC;
     __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int rw = ty + 8 * q, k = k0 + tx;
-      const bool in = k < d;
-      xs[rw][tx] = (in && row0 + rw < n_rows) ? ld_elem(X, (row0 + rw) * d + k, dtypeX) : 0.f;
-      ys[rw][tx] = (in && col0 + rw < n_cols) ? Y[(col0 + rw) * d + k] : 0.f;
+    // 32 rows x kn dimensions of each operand, consecutive threads on consecutive dimensions of a row
+    for (int e = tid; e < 32 * KC; e += 256) {
+      const int rw = e / KC, k = e - rw * KC;
+      const bool in = k < kn;
+      xs[rw][k] = (in && row0 + rw < n_rows) ? ld_elem(X, (row0 + rw) * d + k0 + k, dtypeX) : 0.f;
+      ys[rw][k] = (in && col0 + rw < n_cols) ? Y[(col0 + rw) * d + k0 + k] : 0.f;
     }
     __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 32; ++k) {
+    for (int k = 0; k < kn; ++k) {
       const float b = ys[tx][k];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
