@@ -457,3 +457,48 @@ def test_join_blocks_equals_join_in_one_call_and_survives_other_calls():
         parity.compare(allp, ref, E, Rv, 2, delta, N)
     finally:
         j.close()
+
+
+def test_join_blocks_edge_cases():
+    import paper_2307_12059_amd as kgc
+    import torch
+    g = np.random.default_rng(6200)
+    N, R, d, sig = 500, 3, 32, 0.1
+    E, Rv = _clustered(g, N, R, d, 4, sig)
+    delta = float(np.float32(sig * np.sqrt(2.0 * d)))
+    ref = oracle.join(E, Rv, 2, delta, mode="abandon")
+    Ed, Rd = _dev(E, "f32"), _dev(Rv, "f32")
+    for prune in (PRUNE_OFF, PRUNE_ON):
+        j = kgc.Join(dtype="f32", prune=prune)
+        try:
+            # one block, one relation range: a single unit, the same as kgc_join
+            one = j.join_blocks(Ed, Rd, 2, delta, 2 * ref["count"], 1 << 20, 1000)
+            assert one["code"] == 0 and one["cursor"].units == 1 and one["cursor"].unit == 1
+            parity.compare(one, ref, E, Rv, 2, delta, N)
+            # no room at all: nothing is returned, the cursor stops at the first unit that has triples and says how many
+            none = j.join_blocks(Ed, Rd, 2, delta, 0, 256, 1)
+            assert none["code"] == kgc.KGC_OVERFLOW and none["count"] == 0 and none["cursor"].need > 0
+            assert none["cursor"].unit < none["cursor"].units
+            # a finished cursor: nothing more to do
+            done = j.join_blocks(Ed, Rd, 2, delta, 16, 1 << 20, 1000, one["cursor"])
+            assert done["code"] == 0 and done["count"] == 0
+            # empty inputs
+            empty = j.join_blocks(Ed, torch.empty((0, d), device="cuda"), 2, delta, 16, 256, 1)
+            assert empty["code"] == 0 and empty["count"] == 0
+            empty = j.join_blocks(torch.empty((0, d), device="cuda"), Rd, 2, delta, 16, 256, 1)
+            assert empty["code"] == 0 and empty["count"] == 0
+            # a negative threshold has no hits in any unit
+            neg = j.join_blocks(Ed, Rd, 2, -1.0, 16, 256, 1)
+            assert neg["code"] == 0 and neg["count"] == 0 and neg["cursor"].unit == neg["cursor"].units
+            with pytest.raises(RuntimeError):
+                j.join_blocks(Ed, Rd, 2, delta, 16, 0, 1)
+            with pytest.raises(RuntimeError):
+                j.join_blocks(Ed, Rd, 2, delta, 16, 256, 0)
+        finally:
+            j.close()
+    j = kgc.Join(dtype="f32", prune=PRUNE_OFF, factorised=True)
+    try:
+        with pytest.raises(RuntimeError, match="factorised"):
+            j.join_blocks(Ed, Rd, 2, delta, 16, 256, 1)
+    finally:
+        j.close()
