@@ -1185,8 +1185,8 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
   const int KS = (d + kNormCols + kSliceK - 1) / kSliceK;
   const int k16 = (d + kNormCols + 15) / 16;
   // automatic choice.  Dense: the barrier-free head-resident kernel while the head tile fits in LDS with
-  // some room to spare (256 rows for KS <= 9, d <= 282; 128 rows for KS <= 19, d <= 602).  Pruned: the head-resident kernel with its candidate queue
-  // (KS <= 8, d <= 250).  Otherwise the streaming kernel.
+  // some room to spare (256 rows for KS <= 9, d <= 282; 128 rows for KS <= 19, d <= 602).  Pruned: the head-resident list-walking kernels
+  // (KS <= 8, d <= 250; pruned_l2_tile).  Otherwise the streaming kernel.
   // the relation-factorised form (optional, dense L2 only, head tile in LDS) has one tile shape of its own
   const bool fact = hd->cfg.factorised != 0 && p == 2 && !prune && KS <= kDirectMaxKS;
   int tile_id = kDefaultL2Tile;

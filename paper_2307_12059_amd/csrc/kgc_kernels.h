@@ -50,10 +50,6 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
-__global__ void k_add_u64(unsigned long long* dst, const unsigned long long* src) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *dst += *src;
-}
-
 // relation numbers of a batch's records become numbers of the whole join (kgc_join_se)
 __global__ void k_shift_relation(kgc_triple* rec, uint64_t n, int32_t r0) {
   for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) rec[i].r += r0;
@@ -495,16 +491,16 @@ struct JoinStreamArgs {
   const uint32_t* active_rows;   // pruned mode: the rows with row_count > 0 ...
   const unsigned int* n_active;  // ... and how many there are; the grid strides over them
   RecheckCtx cx;
-  // Group assignment (k_join_l2_direct<.., kEpiAssignMin>): heads are all entities in identity order, tails
-  // the pivots of a covering round, staged in an array of their own with tail_slots rows.
-  ExactEntry* xlist;                  // pruned mode: where the kernel lists the accumulator blocks that hold candidates,
-  unsigned int* xcount;               // how many it has listed, and how many the list holds; a block that finds the
-  unsigned int xcap;                  // list full is re-scored on the spot, candidate by candidate
+  ExactEntry* xlist;                  // where the kernel lists the accumulator blocks that hold candidates (k_exact_blocks
+  unsigned int* xcount;               // scores them), how many it has listed, and how many the list holds; a block that
+  unsigned int xcap;                  // finds the list full is counted, not stored (the host enlarges the list and reruns)
   const uint32_t* tile_rows;          // pruned mode, tile-at-a-time kernel: the row of every entry of cols ...
   const unsigned long long* tile_total;   // ... how many entries there are ...
   const unsigned int* pair_mode;      // ... and whether that kernel (1) or the row-walking one (0) takes this batch
   int cols_lds;                       // head-resident listed kernel: entries of LDS reserved for a row's tile list
   int b_per_rel;                      // 1: the tail operands are staged per relation, [RB][KS][Nslots][32] like A
+  // Group assignment (k_join_l2_direct<.., kEpiAssignMin>): heads are all entities in identity order, tails
+  // the pivots of a covering round, staged in an array of their own with tail_slots rows.
   int64_t tail_slots;                 // rows per K slice of B when it differs from Nslots (0: the same)
   const int32_t* tail_rows_dev;       // device count of valid tail rows (tail tiles past it are skipped); may be NULL
   float thr_value;                    // filter threshold on the squared distance when prm == NULL
