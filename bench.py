@@ -92,6 +92,13 @@ def main():
     ap.add_argument("--general-form", type=int, default=0, metavar="STEPS",
                     help="also time kgc_join_ab (connector outputs supplied by the caller, pruned and dense) on the TransE connectors "
                          "A[r][h] = E[h] + Rv[r], B = E of the workload; needs R * N * d elements of extra memory")
+    ap.add_argument("--se-form", type=int, default=0, metavar="STEPS",
+                    help="also time kgc_join_se (structured embedding: connectors W_r e formed on the device) on the "
+                         "workload's entities with seeded near-identity maps, L1, pruned and dense; R is cut to --se-relations")
+    ap.add_argument("--se-relations", type=int, default=64)
+    ap.add_argument("--blocks", type=int, default=0, metavar="STEPS",
+                    help="also time kgc_join_blocks: the workload drained through a buffer of a quarter of its result, "
+                         "4 x 4 entity blocks and 4 relation ranges")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--calibrate-mfma", type=int, default=0, metavar="MS",
@@ -296,6 +303,66 @@ def main():
                 "tiles_pruned_frac": st["tiles_pruned"] / max(1, st["tiles_total"]),
                 "achieved": 2.0 * d * st["pairs_evaluated"] / (st["ms_join"] * 1e-3) / 1e12,
                 "unit": "TFLOP/s" if p == 2 else "Tlane-op/s (join, staging and bound test together)"}
+    if args.se_form > 0:
+        # the structured-embedding instance of Section 4.3: a = W1_r h, b = W2_r t under the L1 norm; the maps are
+        # seeded perturbations of the identity, so that the clusters of the workload survive and hits exist
+        Rs = min(R, args.se_relations)
+        gen = torch.Generator(device="cpu").manual_seed(4242)
+        eye = torch.eye(d).unsqueeze(0)
+        W1 = (eye + 0.03 / d ** 0.5 * torch.randn((Rs, d, d), generator=gen)).to(E.dtype).cuda().contiguous()
+        W2 = (eye + 0.03 / d ** 0.5 * torch.randn((Rs, d, d), generator=gen)).to(E.dtype).cuda().contiguous()
+        # threshold: 2.5 standard deviations below the mean L1 distance of two members of a cluster of the workload
+        # (per-coordinate difference N(0, 2 sigma^2): mean |x| = 0.798 sqrt(2) sigma, standard deviation 0.603 sqrt(2) sigma)
+        sig = {"c1_tiny_l2": 0.1, "c2_mid_l2": 0.15, "c3_l1": 0.1, "c4_large_l2": 0.1, "c5_scale_l2": 0.05}.get(spec.name, 0.1)
+        delta_se = 1.4142 * sig * (0.798 * d - 2.5 * 0.603 * d ** 0.5)
+        cap_se = 1 << 24
+        line["se_form"] = {"relations": Rs, "p": 1, "delta": delta_se,
+                           "connector_flop": 2.0 * 2.0 * Rs * N * d * d}
+        for label, mode in (("pruned", kgc.KGC_PRUNE_ON), ("dense", kgc.KGC_PRUNE_OFF)):
+            j = kgc.Join(dtype=spec.storage, prune=mode)
+            res = j.join_se(E, W1, W2, 1, delta_se, cap_se, fetch=False)   # warm-up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.se_form):
+                res = j.join_se(E, W1, W2, 1, delta_se, cap_se, fetch=False)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.se_form
+            j.close()
+            line["se_form"][label] = {"ms_per_step": ms, "value": N * N * Rs / (ms * 1e-3), "hits": res["count"],
+                                      "code": res["code"], "relation_batches": res["stats"]["relation_batches"],
+                                      "ms_join_ab_total": res["stats"]["ms_total"]}
+    if args.blocks > 0:
+        # the join unit by unit (Section 4.7): 4 x 4 blocks of the row order, 4 relation ranges, a buffer of a quarter of
+        # the result; every call's records are fetched to the host as a caller draining the buffer would
+        hits = main_run["count"]
+        cap_b = max(1024, hits // 4)
+        block_rows = (N // 4 + 255) // 256 * 256
+        rel_block = (R + 3) // 4
+        line["blocks"] = {"cap": cap_b, "block_rows": block_rows, "rel_block": rel_block}
+        for label, mode in (("pruned", kgc.KGC_PRUNE_ON), ("dense", kgc.KGC_PRUNE_OFF)):
+            if mode == kgc.KGC_PRUNE_OFF and est_dense_s * 16 > 30.0:
+                continue          # (every unit of a dense join stages and joins its window: only for small workloads)
+            j = kgc.Join(dtype=spec.storage, prune=mode)
+            ms_all, calls, total, units = 0.0, 0, 0, 0
+            for it in range(args.blocks + 1):
+                cursor, calls, total, cap_now = None, 0, 0, cap_b
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                while True:
+                    got = j.join_blocks(E, Rv, p, wl.delta, cap_now, block_rows, rel_block, cursor)
+                    cursor = got["cursor"]
+                    calls += 1
+                    total += got["count"]
+                    if got["code"] == kgc.KGC_OVERFLOW and got["count"] == 0:
+                        cap_now = int(cursor.need)
+                    if got["code"] == 0:
+                        break
+                if it > 0:
+                    ms_all += (time.perf_counter() - t0) * 1e3
+                units = int(cursor.units)
+            j.close()
+            assert total == hits, "the drained join and the main run disagree on the number of hits"
+            line["blocks"][label] = {"ms_per_join": ms_all / args.blocks, "calls": calls, "units": units, "hits": total}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(line))

@@ -366,8 +366,9 @@ class Join:
         return {"code": rc, "count": count, "cursor": cursor, "stats": kgc_get_stats(self.handle), "h": host[:, 0].copy(),
                 "r": host[:, 1].copy(), "t": host[:, 2].copy(), "dist": host[:, 3].copy().view("float32")}
 
-    def join_se(self, E, W_lhs, W_rhs, p: int, delta: float, cap: int) -> dict:
-        """The structured-embedding join: ``E`` is N x d, ``W_lhs`` and ``W_rhs`` are R x d x d."""
+    def join_se(self, E, W_lhs, W_rhs, p: int, delta: float, cap: int, fetch: bool = True) -> dict:
+        """The structured-embedding join: ``E`` is N x d, ``W_lhs`` and ``W_rhs`` are R x d x d.  ``fetch=False`` leaves
+        the records on the device (``out``) and returns counts and stats only."""
         torch = self._torch
         want = torch.float32 if self.dtype == "f32" else torch.bfloat16
         for x in (E, W_lhs, W_rhs):
@@ -382,6 +383,8 @@ class Join:
                                 out.data_ptr(), cap)
         if rc < 0:
             raise RuntimeError(f"kgc_join_se failed with code {rc}: {kgc_last_error(self.handle)}")
+        if not fetch:
+            return {"code": rc, "count": count, "stats": kgc_get_stats(self.handle), "out": out}
         n = min(count, cap)
         host = out[:n].cpu().numpy()
         return {"code": rc, "count": count, "stats": kgc_get_stats(self.handle), "h": host[:, 0].copy(),
