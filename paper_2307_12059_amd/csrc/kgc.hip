@@ -223,6 +223,17 @@ void launch_exact_blocks(hipStream_t st, const ExactEntry* list, const unsigned 
 // Blocks for `items` work items, `per_block` each.  A launch may hold fewer than 2^32 threads per grid dimension, so
 // the count stops at 2^24 - 1 blocks (of at most 256 threads): enough for every per-row or per-slot kernel here
 // (N < 2^31); kernels that can be asked for more (k_fill_u32, the staging kernels) stride over their items.
+// Wait for an event that is usually a fraction of a millisecond away: polling it saves the wake-up of a blocking
+// wait (tens of microseconds, twice per pruned join of half a millisecond); a join that takes longer falls back to
+// the blocking wait and leaves the core alone.
+hipError_t wait_event(hipEvent_t ev) {
+  for (int i = 0; i < 4000; ++i) {
+    const hipError_t q = hipEventQuery(ev);
+    if (q != hipErrorNotReady) return q;
+  }
+  return hipEventSynchronize(ev);
+}
+
 int grid_for(int64_t items, int per_block) {
   return (int)std::min<int64_t>((items + per_block - 1) / per_block, (1 << 24) - 1);
 }
@@ -520,7 +531,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
   KGC_HIP(hd, hipGetLastError());
   KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 48, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
-  KGC_HIP(hd, hipStreamSynchronize(st));
+  KGC_HIP(hd, wait_event(hd->ev[2]));
 
   // A batch that wanted to list more accumulator blocks than the list holds has dropped the rest (and counted
   // them): the list grows to what was asked for and the join runs again from the start.
@@ -733,7 +744,8 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
   KGC_HIP(hd, hipGetLastError());
   // the layout decides the number of rows, which sizes every later launch: one small read-back
   KGC_HIP(hd, hipMemcpyAsync(hd->host_gstate, gs, sizeof(GroupState), hipMemcpyDeviceToHost, st));
-  KGC_HIP(hd, hipStreamSynchronize(st));
+  KGC_HIP(hd, hipEventRecord(hd->ev[3], st));
+  KGC_HIP(hd, wait_event(hd->ev[3]));
   if (attempt >= 3 || !(tau > 0.f) || (int64_t)hd->host_gstate->tail_fill * 2 <= N) break;
   tau *= 4.f;
   }   // attempts
@@ -1589,7 +1601,7 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
   KGC_HIP(hd, hipGetLastError());
   KGC_HIP(hd, hipMemcpyAsync(hd->host_counters, cnt, 48, hipMemcpyDeviceToHost, st));
   KGC_HIP(hd, hipEventRecord(hd->ev[2], st));
-  KGC_HIP(hd, hipStreamSynchronize(st));
+  KGC_HIP(hd, wait_event(hd->ev[2]));
 
   pr.valid = !fact;                  // what the handle now holds describes this join
   pr.bitmap_valid = prune && nbatch == 1 && !empty_window; pr.bm_r0 = r_begin; pr.bm_r1 = r_end;
