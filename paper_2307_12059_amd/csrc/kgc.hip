@@ -441,7 +441,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p, &cnt->n_active,
           pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr);
-      k_batch_tiles<<<1, 64, 0, st>>>(cnt, pairs_ok ? 1 : 0);
+      k_batch_tiles<<<1, 64, 0, st>>>(cnt, pairs_ok ? 1 : 0, 0, 0ull, 0ull);
       active_rows = (const uint32_t*)hd->active_rows.p;
       n_active = &cnt->n_active;
     }
@@ -1392,6 +1392,11 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
       // a2: bound test on micro-tile pairs -> bitmap of join tiles -> per-row lists of surviving tail tiles
       const int64_t bm_words = (int64_t)RB * nH * words_per_row;
       if (!bitmap_ready) k_fill_u32<<<grid_for(bm_words, 256), 256, 0, st>>>((uint32_t*)hd->bitmap.p, bm_words, 0u);
+      // The flat bound test can list the surviving tiles itself; when they are few, that list serves the tile-at-a-time
+      // join kernel and the pass over the bitmap is skipped (the device decides, k_batch_tiles).  Not with a window:
+      // the list would hold the tiles outside it too.
+      const bool direct_lists = pairs_ok && !use_units && !win && !bitmap_ready && delta >= 0.f && p == 2;
+      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
       if (bitmap_ready) {
         // the bound test of these relations is still in the bitmap (the previous window of the same relation range)
       } else if (delta >= 0.f && p == 2) {
@@ -1415,6 +1420,11 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         ba.rad = (const float*)hd->rad.p; ba.cnorm = (const float*)hd->cnorm.p; ba.n_micro = n_micro; ba.RB = RB;
         ba.d = d; ba.delta = delta; ba.bitmap = (uint32_t*)hd->bitmap.p; ba.nH = nH; ba.words_per_row = words_per_row;
         ba.micro_per_bm = BM / kMicro; ba.micro_per_bn = BN / kMicro;
+        if (direct_lists) {
+          ba.list_cols = (uint32_t*)hd->cols.p; ba.list_rows = (uint32_t*)hd->tile_rows.p; ba.list_active = (uint32_t*)hd->active_rows.p;
+          ba.list_count = &cnt->tile_cursor;
+          ba.list_cap = (unsigned long long)std::min<int64_t>((int64_t)RB * nH, (int64_t)RB * tiles_per_rel);   // what all three arrays hold
+        }
         if (use_units) {
           // unit level first (same arithmetic on unit summaries), then the micro-tile pairs of the survivors
           TileDistArgs tu{};
@@ -1458,12 +1468,15 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
           k_tile_dist<1, kEpiBound><<<g, 256, 0, st>>>(ta);
         }
       }
-      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
+      if (direct_lists)
+        k_batch_tiles<<<1, 64, 0, st>>>(cnt, 1, 1, (unsigned long long)RB * nH,
+                                        (unsigned long long)std::min<int64_t>((int64_t)RB * nH, (int64_t)RB * tiles_per_rel));
       k_rows_from_bitmap<<<(unsigned)(((int64_t)RB * nH + 256 * bitmap_rows_per_lane(words_per_row) - 1) / (256 * bitmap_rows_per_lane(words_per_row))), 256, 0, st>>>(
           (const uint32_t*)hd->bitmap.p, words_per_row, (int64_t)RB * nH, (uint32_t*)hd->row_start.p,
           (uint32_t*)hd->row_count.p, (uint32_t*)hd->cols.p, &cnt->tile_cursor, (uint32_t*)hd->active_rows.p,
-          &cnt->n_active, pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr, nH, wH0, wH1, wT0, wT1);
-      k_batch_tiles<<<1, 64, 0, st>>>(cnt, pairs_ok ? 1 : 0);
+          &cnt->n_active, pairs_ok ? (uint32_t*)hd->tile_rows.p : nullptr, nH, wH0, wH1, wT0, wT1,
+          direct_lists ? &cnt->pair_mode : nullptr, direct_lists ? &cnt->tiles : nullptr);
+      if (!direct_lists) k_batch_tiles<<<1, 64, 0, st>>>(cnt, pairs_ok ? 1 : 0, 0, 0ull, 0ull);
       row_start = (const uint32_t*)hd->row_start.p;
       row_count = (const uint32_t*)hd->row_count.p;
       cols = (const uint32_t*)hd->cols.p;

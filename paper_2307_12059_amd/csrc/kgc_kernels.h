@@ -64,13 +64,27 @@ __global__ void k_window_rows(uint32_t* rows, unsigned int* n_rows, int RB, int 
   if (blockIdx.x == 0 && threadIdx.x == 0) *n_rows = (unsigned int)total;
 }
 
-// after the tile lists of a pruned batch: the running total of surviving tiles, and which L2 join kernel takes the
-// batch: tile by tile when its rows keep at most kPairModeTilesPerRow tiles on average (and the host allows it)
+// Around the tile lists of a pruned batch: the running total of surviving tiles, and which L2 join kernel takes the
+// batch (when the host allows the choice): tile by tile when its rows keep few tiles.
+//   phase 0, after k_rows_from_bitmap: at most kPairModeTilesPerRow tiles per active row on average.
+//   phase 1, after a bound test that listed the new tiles itself (BoundL2Args::list_*) and before k_rows_from_bitmap:
+//            the flat list is the batch's list when it is short against the number of rows (and fits); the rows then
+//            count once per tile.  Otherwise the cursors start over and k_rows_from_bitmap builds the lists per row.
 constexpr unsigned long long kPairModeTilesPerRow = 3;
-__global__ void k_batch_tiles(DevCounters* c, int allow_pairs) {
+__global__ void k_batch_tiles(DevCounters* c, int allow_pairs, int phase, unsigned long long n_rows, unsigned long long list_cap) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
-    c->tiles += c->tile_cursor;
-    c->pair_mode = (allow_pairs && c->tile_cursor <= kPairModeTilesPerRow * c->n_active && c->tile_cursor < 0xffffffffull) ? 1u : 0u;
+    if (phase == 0) {
+      c->tiles += c->tile_cursor;
+      c->pair_mode = (allow_pairs && c->tile_cursor <= kPairModeTilesPerRow * c->n_active && c->tile_cursor < 0xffffffffull) ? 1u : 0u;
+    } else {
+      const unsigned long long n = c->tile_cursor;
+      const unsigned long long few = n_rows / 8 > 4096 ? n_rows / 8 : 4096;
+      if (allow_pairs && n <= few && n <= list_cap && n < 0xffffffffull) {
+        c->tiles += n; c->n_active = (unsigned int)n; c->pair_mode = 1u;
+      } else {
+        c->tile_cursor = 0; c->n_active = 0; c->pair_mode = 0u;
+      }
+    }
   }
 }
 

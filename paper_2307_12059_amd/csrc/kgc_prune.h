@@ -554,6 +554,10 @@ struct BoundL2Args {
   // micro-tile level of the two-level test without the D and u matrices (D == NULL): centre distances are then
   // summed directly from the centres and the relation vector
   const float* cent; const void* Rv; int dtype; int r0;
+  // k_bound_l2 only, optional (NULL: off): every tile whose bit is set for the first time is also appended to a flat
+  // list -- its tail tile to list_cols, its row (relation, head tile) to list_rows and to list_active -- so that a
+  // batch with few surviving tiles needs no pass over the bitmap (see k_batch_tiles)
+  uint32_t* list_cols; uint32_t* list_rows; uint32_t* list_active; unsigned long long* list_count; unsigned long long list_cap;
 };
 constexpr int kHeadChunk = 16;
 constexpr int kHeadsFlat = 64;       // head micro-tiles per block of the flat test (four groups of kHeadChunk)
@@ -650,7 +654,13 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
     while (keep) {
       const int q = __builtin_ctz(keep);
       keep &= keep - 1u;
-      atomicOr(&a.bitmap[((int64_t)(rl0 + q) * a.nH + tH) * a.words_per_row + (tT >> 5)], 1u << (tT & 31));
+      const int64_t row = (int64_t)(rl0 + q) * a.nH + tH;
+      const uint32_t bit = 1u << (tT & 31);
+      const uint32_t old = atomicOr(&a.bitmap[row * a.words_per_row + (tT >> 5)], bit);
+      if (a.list_count && !(old & bit)) {                        // the tile is new: also onto the flat list
+        const unsigned long long idx = atomicAdd(a.list_count, 1ull);
+        if (idx < a.list_cap) { a.list_cols[idx] = (uint32_t)tT; a.list_rows[idx] = (uint32_t)row; a.list_active[idx] = (uint32_t)row; }
+      }
     }
   }
   }   // groups of heads
@@ -854,7 +864,10 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
                                                          unsigned int* __restrict__ n_active,
                                                          uint32_t* __restrict__ tile_rows,        // may be NULL: the row of every entry of cols
                                                          int nH = 1, int h0 = 0, int h1 = 0x7fffffff,     // window: only head tiles [h0, h1)
-                                                         int t0 = 0, int t1 = 0x7fffffff) {               // ... and tail tiles [t0, t1) count
+                                                         int t0 = 0, int t1 = 0x7fffffff,                 // ... and tail tiles [t0, t1) count
+                                                         const unsigned int* skip = nullptr,              // non-zero: the lists exist already, nothing to do
+                                                         unsigned long long* tiles_total = nullptr) {     // running total of listed tiles (with skip)
+  if (skip && *skip) return;
   // word i of a row holds tail tiles 32 i .. 32 i + 31: the bits of those inside [t0, t1)
   auto col_mask = [=](int i) -> uint32_t {
     const int lo = t0 - 32 * i, hi = t1 - 32 * i;
@@ -906,6 +919,7 @@ __global__ __launch_bounds__(256) void k_rows_from_bitmap(const uint32_t* __rest
   if (lane == 0 && wrows) {
     wbase = atomicAdd(total, (unsigned long long)wtiles);
     abase = atomicAdd(n_active, wrows);
+    if (tiles_total) atomicAdd(tiles_total, (unsigned long long)wtiles);
   }
   wbase = ((unsigned long long)(uint32_t)__shfl((int)(uint32_t)(wbase >> 32), 0, 64) << 32) |
           (uint32_t)__shfl((int)(uint32_t)(wbase & 0xffffffffull), 0, 64);

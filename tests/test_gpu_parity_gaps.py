@@ -502,3 +502,19 @@ def test_join_blocks_edge_cases():
             j.join_blocks(Ed, Rd, 2, delta, 16, 256, 1)
     finally:
         j.close()
+
+
+def test_many_surviving_tiles_fall_back_to_row_lists():
+    """The flat bound test lists the surviving tiles itself when they are few; here nothing can be pruned (no cluster
+    structure, 9,000 entities), more than 4,096 tiles survive, and the lists must come from the pass over the bitmap."""
+    g = np.random.default_rng(7000)
+    N, R, d = 9000, 2, 16
+    E = g.standard_normal((N, d)).astype(np.float32)
+    Rv = (0.3 * g.standard_normal((R, d))).astype(np.float32)
+    h, t, r = g.integers(0, N, 300000), g.integers(0, N, 300000), g.integers(0, R, 300000)
+    x = E[h].astype(np.float64) + Rv[r] - E[t]
+    dist = np.sqrt((x * x).sum(-1))
+    delta = float(np.float32(np.quantile(dist[h != t], 1e-4)))
+    got, ref, rep = _join_and_compare(E, Rv, 2, delta, "f32", prune=PRUNE_ON)
+    assert ref["count"] > 1000
+    assert got["stats"]["tiles_evaluated"] > 4096 and got["stats"]["join_variant"] == 14
