@@ -674,11 +674,10 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
     if ((rc = ensure(hd, hd->asg_a, (size_t)KS * Npad * kSliceK * 2)) ||
         (rc = ensure(hd, hd->asg_b, (size_t)KS * kPivotsPerRound * kSliceK * 2)))
       return rc;
-    // slot_ent is free until the layout fills it: identity order for the staging of the heads
-    k_identity_slots<<<grid_for(Npad, 256), 256, 0, st>>>((int32_t*)hd->slot_ent.p, N, Npad);
+    // the heads in identity order
     k_stage_operands<true><<<grid_for(Npad / kStageRows, 1), 256, asg_lds, st>>>(
-        E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->slot_ent.p, Npad, KS, (uint16_t*)hd->asg_a.p, nullptr, nullptr,
-        nullptr, nullptr, 0, kStageRows);
+        E, nullptr, dtype, d, 0, 1, nullptr, Npad, KS, (uint16_t*)hd->asg_a.p, nullptr, nullptr,
+        nullptr, nullptr, 0, kStageRows, 0, nullptr, -1.f, N);
     KGC_HIP(hd, hipFuncSetAttribute((const void*)assign_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)((size_t)KS * abm * kSliceK * 2)));
   }
@@ -690,7 +689,6 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
   const float tau_l2 = (p == 2) ? tau : tau / (0.79788456f * std::sqrt((float)d));
   unc = (int32_t*)hd->unc_a.p;
   unc_next = (int32_t*)hd->unc_b.p;
-  k_group_init<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->group_of.p, N);
   // Sampling density of the pivots among the still uncovered entities, round by round: 1/16, 1/16, 1/8, 1/8, 1/4,
   // 1/2.  With few entities three rounds at 1/4, 1/2 and 1 reach the same cover (their up to 3 x 4,096 pivots are
   // more than a third of the entities; several pivots in one natural cluster do not split it, the lowest one within
@@ -701,7 +699,8 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
     static const int kShift[kGroupRounds] = {4, 4, 3, 3, 2, 1};
     static const int kShiftFew[3] = {2, 1, 0};
     k_round_begin<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->piv_ent.p, (unsigned long long*)hd->best.p,
-                                     few ? kShiftFew[round] : kShift[round], mfma_assign ? 1 : 0);
+                                     few ? kShiftFew[round] : kShift[round], mfma_assign ? 1 : 0, round == 0 ? N : 0,
+                                     (int32_t*)hd->group_of.p);
     if (mfma_assign) {
       k_stage_operands<false><<<kPivotsPerRound / kStageRows, 256, asg_lds, st>>>(
           E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->piv_ent.p, kPivotsPerRound, KS, (uint16_t*)hd->asg_b.p, nullptr,
@@ -733,9 +732,8 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
     k_round_end<<<1, 64, 0, st>>>(gs);
     std::swap(unc, unc_next);
   }
-  k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gsize.p, kMaxGroups, 0u);
-  k_fill_u32<<<grid_for(kMaxGroups, 256), 256, 0, st>>>((uint32_t*)hd->gfill.p, kMaxGroups, 0u);
-  k_fill_u32<<<grid_for(slots_cap, 256), 256, 0, st>>>((uint32_t*)hd->slot_ent.p, slots_cap, 0xffffffffu);
+  k_group_clear<<<grid_for(std::max<int64_t>(kMaxGroups, slots_cap), 256), 256, 0, st>>>(
+      (int32_t*)hd->gsize.p, (int32_t*)hd->gfill.p, kMaxGroups, (int32_t*)hd->slot_ent.p, slots_cap);
   k_group_hist<<<gN, 256, 0, st>>>((const int32_t*)hd->group_of.p, N, (int32_t*)hd->gsize.p);
   k_group_layout<<<1, 1024, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign,
                                      (int32_t*)hd->unit_first.p, (int32_t*)hd->unit_n.p);

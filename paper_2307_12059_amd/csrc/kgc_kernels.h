@@ -175,7 +175,8 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
                                                         const uint32_t* __restrict__ active_rows,
                                                         const unsigned int* __restrict__ n_active, int nH, int bm,
                                                         int64_t rel_stride = 0, const int32_t* __restrict__ n_rows_dev = nullptr,
-                                                        float slack_delta = -1.f) {
+                                                        float slack_delta = -1.f,
+                                                        int64_t n_identity = 0) {      // slot_ent == NULL: slot s holds entity s, s < n_identity
   extern __shared__ __attribute__((aligned(16))) uint16_t tile_all[];   // [4 waves][16 rows][KS * 32 + 8]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, l32 = lane & 31;
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__
     // n_rows_dev: only the first *n_rows_dev slots (rounded up to a 256-row tile) hold rows this time
     if (n_rows_dev && slot0 >= ((int64_t)*n_rows_dev + 255) / 256 * 256) continue;
     slot0 += wave * kStageWaveRows;
-    const int ent_l = lane < kStageWaveRows ? slot_ent[slot0 + lane] : -1;
+    const int ent_l = lane >= kStageWaveRows ? -1 : slot_ent ? slot_ent[slot0 + lane] : (slot0 + lane < n_identity ? (int)(slot0 + lane) : -1);
     const int64_t ro = (int64_t)(r0 + rl) * d;
     const int64_t eo = (int64_t)(r0 + rl) * rel_stride;       // per-relation source rows (0: one array for all)
     float sq[8], er[8];

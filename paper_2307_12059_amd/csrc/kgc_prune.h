@@ -33,29 +33,29 @@ struct GroupState {
   int32_t n_big;        // groups of at least kSmallGroup rows: each is one unit of the two-level bound test
 };
 
-__global__ void k_group_init(GroupState* gs, int32_t* unc, int32_t* group_of, int64_t N) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i == 0) {
-    gs->n_unc = (int32_t)N; gs->n_unc_next = 0; gs->n_piv = 0; gs->n_groups = 0;
-    gs->n_slots = 0; gs->tail_base = 0; gs->tail_fill = 0; gs->n_big = 0;
-  }
-  if (i < N) { unc[i] = (int32_t)i; group_of[i] = -1; }
-}
-
 // Start of a round: pivots are an even-stride sample (one in 2^shift, at most kPivotsPerRound) of the
 // uncovered list; nearest-pivot records are reset.
 // `best` is indexed by the position in the uncovered list, or (by_entity) by the entity itself; the pivot
 // list is padded with -1 up to kPivotsPerRound (the grid covers max(N, kPivotsPerRound) threads).
-__global__ void k_round_begin(GroupState* gs, const int32_t* unc, int32_t* piv_ent, unsigned long long* best,
-                              int shift, int by_entity) {
-  const int n_unc = gs->n_unc;
+// The first round (init_N > 0) also sets up the state: every entity uncovered and in no group.
+__global__ void k_round_begin(GroupState* gs, int32_t* unc, int32_t* piv_ent, unsigned long long* best,
+                              int shift, int by_entity, int64_t init_N, int32_t* group_of) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool first = init_N > 0;
+  const int n_unc = first ? (int)init_N : gs->n_unc;
   int n_piv = n_unc >> shift;
   n_piv = n_piv < 1 ? (n_unc > 0 ? 1 : 0) : n_piv;
   n_piv = n_piv < kPivotsPerRound ? n_piv : kPivotsPerRound;
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < kPivotsPerRound) piv_ent[i] = i < n_piv ? unc[(int64_t)i * n_unc / n_piv] : -1;   // n_piv > 0 where read
-  if (i < n_unc) best[by_entity ? unc[i] : i] = ~0ull;
-  if (i == 0) { gs->n_piv = n_piv; gs->n_unc_next = 0; }
+  if (first && i < n_unc) { unc[i] = (int32_t)i; group_of[i] = -1; }
+  if (i < kPivotsPerRound) {
+    const int64_t pos = i < n_piv ? (int64_t)i * n_unc / n_piv : -1;   // n_piv > 0 where read
+    piv_ent[i] = pos < 0 ? -1 : (first ? (int32_t)pos : unc[pos]);
+  }
+  if (i < n_unc) best[by_entity ? (first ? (int32_t)i : unc[i]) : i] = ~0ull;
+  if (i == 0) {
+    if (first) { gs->n_unc = n_unc; gs->n_groups = 0; gs->n_slots = 0; gs->tail_base = 0; gs->tail_fill = 0; gs->n_big = 0; }
+    gs->n_piv = n_piv; gs->n_unc_next = 0;
+  }
 }
 
 // End of a round: an uncovered entity joins the group of the pivot the assignment found within tau, if any.
@@ -75,6 +75,13 @@ __global__ void k_round_end(GroupState* gs) {
     gs->n_unc = gs->n_unc_next;
     gs->n_piv = 0;
   }
+}
+
+// before the layout: group sizes and fill counts to zero, every slot to "padding"
+__global__ void k_group_clear(int32_t* gsize, int32_t* gfill, int n_groups_max, int32_t* slot_ent, int64_t n_slots) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_groups_max) { gsize[i] = 0; gfill[i] = 0; }
+  if (i < n_slots) slot_ent[i] = -1;
 }
 
 __global__ void k_group_hist(const int32_t* group_of, int64_t N, int32_t* gsize) {
