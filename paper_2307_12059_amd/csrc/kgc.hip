@@ -1394,7 +1394,7 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
       // join kernel and the pass over the bitmap is skipped (the device decides, k_batch_tiles).  Not with a window:
       // the list would hold the tiles outside it too.
       const bool direct_lists = pairs_ok && !use_units && !win && !bitmap_ready && delta >= 0.f && p == 2;
-      k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active
+      if (b > 0) k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active (zero at the start of a call)
       if (bitmap_ready) {
         // the bound test of these relations is still in the bitmap (the previous window of the same relation range)
       } else if (delta >= 0.f && p == 2) {
@@ -1587,7 +1587,7 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         }
         if (lists_blocks) {
           launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, hd->xcap, &cnt->exact_total, &cnt->exact_need, sa.cx);
-          k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 1, 0u);
+          if (r0 + RBmax < r_end) k_fill_u32<<<1, 64, 0, st>>>(&cnt->n_exact, 1, 0u);      // an empty list for the next batch
         }
       } else {
         JoinArgs ja{};
