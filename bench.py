@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--blocks", type=int, default=0, metavar="STEPS",
                     help="also time kgc_join_blocks: the workload drained through a buffer of a quarter of its result, "
                          "4 x 4 entity blocks and 4 relation ranges")
+    ap.add_argument("--topk", type=int, default=0, metavar="STEPS",
+                    help="also time kgc_top1 and kgc_topk (k = 1000 over all relations, k = 100 for one relation) on the workload")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--calibrate-mfma", type=int, default=0, metavar="MS",
@@ -363,6 +365,23 @@ def main():
             j.close()
             assert total == hits, "the drained join and the main run disagree on the number of hits"
             line["blocks"][label] = {"ms_per_join": ms_all / args.blocks, "calls": calls, "units": units, "hits": total}
+    if args.topk > 0:
+        # the smallest distances instead of a threshold (the Top-1 score of Section 3.3 and its k-best form)
+        j = kgc.Join(dtype=spec.storage, prune=kgc.KGC_PRUNE_ON)
+        line["topk"] = {}
+        for label, fn in (("top1", lambda: j.top1(E, Rv, p)),
+                          ("top1000", lambda: j.topk(E, Rv, p, 1000)),
+                          ("top100_of_relation_0", lambda: j.topk(E, Rv, p, 100, r_range=(0, 1)))):
+            res = fn()                                                 # warm-up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.topk):
+                res = fn()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.topk
+            line["topk"][label] = {"ms_per_call": ms, "smallest_dist": float(res["dist"] if label == "top1" else res["dist"][0]),
+                                   "found": 1 if label == "top1" else int(res["count"])}
+        j.close()
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(line))

@@ -225,7 +225,7 @@ void launch_exact_blocks(hipStream_t st, const ExactEntry* list, const unsigned 
   const bool bf = cx.dtype == KGC_BF16, vec = cx.vec_ok != 0;
   auto kern = bf ? (vec ? k_exact_blocks<true, true> : k_exact_blocks<true, false>)
                  : (vec ? k_exact_blocks<false, true> : k_exact_blocks<false, false>);
-  hipLaunchKernelGGL(kern, dim3(1024), dim3(256), 0, st, list, count, cap, total, need, cx);
+  hipLaunchKernelGGL(kern, dim3(256), dim3(kExactWaves * 64), 0, st, list, count, cap, total, need, cx);      // one workgroup per compute unit
 }
 
 // Blocks for `items` work items, `per_block` each.  A launch may hold fewer than 2^32 threads per grid dimension, so

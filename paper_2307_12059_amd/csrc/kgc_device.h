@@ -244,8 +244,8 @@ __device__ __forceinline__ void group16_exact_dist_multi(const RecheckCtx& cx, c
 // by more than this error, not a hit when it is above by more than it, and in the (practically empty) band between,
 // or when a hit's value is tiny against the norms, the lane falls back to the definition: x_k = (E[h][k] + Rv[r][k]) - Et[t][k] in double, summed over k ascending,
 // sqrt, <= delta.  Every true hit of the block passed the low-precision filter, so testing all pairs of the block
-// gives exactly the hits among its candidates.  Hits leave with ONE atomic per block (a wave prefix sum over the
-// lanes' hit counts).
+// gives exactly the hits among its candidates.  Hits leave with one reservation per block (a wave prefix sum over the
+// lanes' hit counts), which the caller may share between waves.
 //   hs0  slot of the block's first head row;  ts0  slot of its first tail column.   All 64 lanes call this together.
 // Operand layout of the instruction: A[i][k] in lane 16 k + i, B[k][j] in lane 16 k + j, D[i][j] in element i / 4 of
 // lane 16 (i % 4) + j (for double precision the four elements of a lane are four rows apart, not adjacent).
@@ -282,8 +282,10 @@ __device__ __forceinline__ f32x4_t exact_ld4(const void* base, int64_t off, int 
 }
 // BF16: the storage type of the rows; VEC: rows may be read four elements at a time (template parameters, so that
 // the loads below are straight-line code)
-template <bool BF16, bool VEC>
-__device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, int64_t hs0, int64_t ts0) {
+// reserve(total): called once by all lanes of the wave, returns the output position of the wave's first hit; the caller
+// decides how waves share the atomic on the hit counter (thousands of atomics on one address cost more than the scoring).
+template <bool BF16, bool VEC, typename Reserve>
+__device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, int64_t hs0, int64_t ts0, Reserve reserve) {
   const int lane = lane_id_here();
   const int rr = lane & 15, kk = lane >> 4;         // operand row (or column), and which of a step's four operand slots
   const int d = cx.d, dtype = cx.dtype;
@@ -309,7 +311,7 @@ __device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, 
   // to four successive steps (step e of the group multiplies dimensions 16 g + 4 slot + e, slot = 0 .. 3).
   // The rows are walked in chunks of kGroups groups: ALL loads of a chunk are issued before any is used, so a chunk
   // costs one memory round trip.  Elements past d count as zero.
-  constexpr int kGroups = 4;
+  constexpr int kGroups = 2;
   for (int k0 = 0; k0 < d; k0 += 16 * kGroups) {
     f32x4_t hv[2][kGroups], tv[2][kGroups], rv[kGroups];
 #pragma unroll
@@ -398,12 +400,9 @@ __device__ __forceinline__ void exact_block_l2(int32_t r, const RecheckCtx& cx, 
     if (lane >= off) incl += o;
   }
   const int total = __shfl(incl, 63, 64);
+  const unsigned long long base = reserve(total);
   if (total > 0) {
-    unsigned long long base = 0ull;
-    if (lane == 63) base = atomicAdd(cx.hit_counter, (unsigned long long)total);
-    const uint32_t blo = (uint32_t)__shfl((int)(uint32_t)(base & 0xffffffffull), 63, 64);
-    const uint32_t bhi = (uint32_t)__shfl((int)(uint32_t)(base >> 32), 63, 64);
-    unsigned long long pos = (((unsigned long long)bhi << 32) | blo) + (unsigned long long)(incl - nh);
+    unsigned long long pos = base + (unsigned long long)(incl - nh);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       if (!((hit >> e) & 1u)) continue;

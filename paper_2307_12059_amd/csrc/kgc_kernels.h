@@ -536,20 +536,48 @@ __device__ __forceinline__ void list_block(const JoinStreamArgs& a, int32_t r, i
 }
 
 // The exact stage of the L2 joins that list blocks: one wave per listed block (exact_block_l2), the grid strides over
-// the list.
+// the list.  Workgroups of kExactWaves waves: the waves of a workgroup score their blocks side by side and reserve
+// their output records with ONE atomic on the hit counter between them (two barriers per round; the sums of a round
+// sit in the LDS buffer of the round's parity, so a wave that is already in the next round does not overwrite what a
+// slower one still reads).  One atomic per block was measured at 18 of the kernel's 46 microseconds on a list of
+// 2,400 blocks: atomics on one address are served one after the other, 8 ns each.
+constexpr int kExactWaves = 16;
 template <bool BF16, bool VEC>
-__global__ __launch_bounds__(256, 3) void k_exact_blocks(const ExactEntry* __restrict__ list, const unsigned int* __restrict__ count,
+__global__ __launch_bounds__(kExactWaves * 64, 1) void k_exact_blocks(const ExactEntry* __restrict__ list, const unsigned int* __restrict__ count,
                                                       unsigned int cap, unsigned long long* __restrict__ total,
                                                       unsigned int* __restrict__ need, const RecheckCtx cx) {
+  __shared__ unsigned int wave_hits[2][kExactWaves];
+  __shared__ unsigned long long wave_base[2][kExactWaves];
   const unsigned int n = *count < cap ? *count : cap;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     *total += n;
     if (*count > *need) *need = *count;
   }
-  const unsigned int w0 = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
-  for (unsigned int e = w0; e < n; e += nw) {
-    const ExactEntry x = list[e];
-    exact_block_l2<BF16, VEC>(x.r, cx, (int64_t)x.hs0, (int64_t)x.ts0);
+  // entry e goes to wave e / gridDim.x of workgroup e % gridDim.x: a short list is spread over all workgroups (and with
+  // them over all compute units), not over the waves of the first few
+  const unsigned int wv = (unsigned int)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), per_round = gridDim.x * kExactWaves;
+  int round = 0;
+  for (unsigned int e0 = 0; e0 < n; e0 += per_round, ++round) {          // the same number of rounds for the whole workgroup
+    const int par = round & 1;
+    auto reserve = [&](int hits) -> unsigned long long {
+      if ((threadIdx.x & 63) == 0) wave_hits[par][wv] = (unsigned int)hits;
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        unsigned int sum = 0u;
+        for (int w = 0; w < kExactWaves; ++w) sum += wave_hits[par][w];
+        unsigned long long base = sum ? atomicAdd(cx.hit_counter, (unsigned long long)sum) : 0ull;
+        for (int w = 0; w < kExactWaves; ++w) { wave_base[par][w] = base; base += wave_hits[par][w]; }
+      }
+      __syncthreads();
+      return wave_base[par][wv];
+    };
+    const unsigned int e = e0 + blockIdx.x + gridDim.x * wv;
+    if (e < n) {                                                         // (the same for the whole wave)
+      const ExactEntry x = list[e];
+      exact_block_l2<BF16, VEC>(x.r, cx, (int64_t)x.hs0, (int64_t)x.ts0, reserve);
+    } else {
+      (void)reserve(0);
+    }
   }
 }
 
