@@ -1414,9 +1414,14 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
           td.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); td.dtypeX = dtype; td.n_rows = RB;
           td.Y = hd->cent.p; td.dtypeY = KGC_F32; td.n_cols = n_micro; td.shift = nullptr; td.dtype_shift = KGC_F32;
           td.d = d; td.matrix = (float*)hd->relu.p;
-          if (n_micro <= 4096 && RB <= 4096)
-            k_small_matrix<0><<<dim3((unsigned)((n_micro + 31) / 32), (unsigned)((RB + 31) / 32), 1), 256, 0, st>>>(
-                td.X, dtype, RB, (const float*)hd->cent.p, n_micro, d, (float*)hd->relu.p);
+          if (n_micro <= 4096 && RB <= 4096) {
+            const bool bf = dtype == KGC_BF16;
+            const bool vec = d % 4 == 0 && (uintptr_t)td.X % (bf ? 8 : 16) == 0 && (uintptr_t)hd->cent.p % 16 == 0;
+            auto kern = bf ? (vec ? k_small_dot<true, true> : k_small_dot<true, false>)
+                           : (vec ? k_small_dot<false, true> : k_small_dot<false, false>);
+            hipLaunchKernelGGL(kern, dim3((unsigned)((n_micro + 31) / 32), (unsigned)((RB + 31) / 32), 1), dim3(64), 0, st,
+                               td.X, (int64_t)RB, (const float*)hd->cent.p, (int64_t)n_micro, d, (float*)hd->relu.p);
+          }
           else
             k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((n_micro + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(td);
         }

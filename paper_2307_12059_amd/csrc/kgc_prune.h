@@ -522,6 +522,50 @@ __global__ __launch_bounds__(256) void k_small_matrix(const void* __restrict__ X
   }
 }
 
+// out[i][j] = x_i . y_j for small operands, on the float32 matrix pipes: one wave per 32 x 32 results, no LDS and no
+// barrier.  v_mfma_f32_32x32x2_f32 takes A[i][k] from lane 32 k + i and B[k][j] from lane 32 k + j (k = 0, 1); a dot
+// product does not care in which order its dimensions are taken as long as both operands agree, so lane (row, half)
+// reads the four consecutive elements 8 g + 4 half .. + 3 of its row in one load and feeds them to four successive
+// steps.  All loads of up to 128 dimensions are issued before the first is used: a chunk costs one memory round trip.
+// Products and sums are float32 (the bound test charges (d + 8) 2^-24 ||x|| ||y|| for them, which holds for any order
+// of a float32 sum of d products).  X rows of the given storage type, Y rows float32; VEC: rows may be read four
+// elements at a time (both bases on 16-byte boundaries -- 8 for bf16 rows -- and d a multiple of four).
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(64) void k_small_dot(const void* __restrict__ X, int64_t n_rows, const float* __restrict__ Y,
+                                                  int64_t n_cols, int d, float* __restrict__ out) {
+  const int lane = threadIdx.x, row = lane & 31, half = lane >> 5;
+  const int64_t row0 = (int64_t)blockIdx.y * 32, col0 = (int64_t)blockIdx.x * 32;
+  const int64_t xr = row0 + row < n_rows ? row0 + row : n_rows - 1;      // (past the end: a valid row, the results are dropped)
+  const int64_t yc = col0 + row < n_cols ? col0 + row : n_cols - 1;
+  const int64_t xo = xr * d, yo = yc * d;
+  f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  constexpr int kG = 16;                                                  // groups of 8 dimensions per chunk (d <= 128: one chunk)
+  for (int k0 = 0; k0 < d; k0 += 8 * kG) {
+    f32x4_t xv[kG], yv[kG];
+#pragma unroll
+    for (int g = 0; g < kG; ++g) {
+      const int k = k0 + 8 * g + 4 * half;
+      xv[g] = exact_ld4<BF16, VEC>(X, xo, k, d);
+      yv[g] = exact_ld4<false, VEC>(Y, yo, k, d);
+    }
+    __builtin_amdgcn_sched_barrier(0);                                    // (the loads stay together, ahead of the arithmetic)
+#pragma unroll
+    for (int g = 0; g < kG; ++g) {
+      if (k0 + 8 * g >= d) break;                                         // the same for the whole wave
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xv[g][e], yv[g][e], acc, 0, 0, 0);
+    }
+  }
+  // register v of lane l holds row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32
+  if (col0 + row < n_cols) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int64_t i = row0 + 8 * (v >> 2) + 4 * half + (v & 3);
+      if (i < n_rows) out[i * n_cols + col0 + row] = acc[v];
+    }
+  }
+}
+
 // L2 only.  u[rl][m] = r . c_m and rn[rl] = ||r||^2 for the relations of a batch: one wave per (rl, m).
 __global__ __launch_bounds__(256) void k_rel_centre_dot(const void* __restrict__ Rv, int dtype, int d, int r0, int RB,
                                                         const float* __restrict__ cent, int64_t n_micro,
