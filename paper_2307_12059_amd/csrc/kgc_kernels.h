@@ -167,7 +167,7 @@ __device__ __forceinline__ float stage_reduce8(const float v[8], int lane) {
 }
 
 template <bool IS_A>
-__global__ __launch_bounds__(256) void k_stage_operands(const void* __restrict__ E, const void* __restrict__ Rv,
+__global__ __launch_bounds__(256, 4) void k_stage_operands(const void* __restrict__ E, const void* __restrict__ Rv,
                                                         int dtype, int d, int r0, int RB,
                                                         const int32_t* __restrict__ slot_ent, int64_t Nslots, int KS,
                                                         uint16_t* __restrict__ out, float* __restrict__ norms,
