@@ -1330,9 +1330,10 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.n_rows = n_micro; ta.Y = hd->cent.p; ta.dtypeY = KGC_F32;
         ta.n_cols = n_micro; ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.d = d; ta.matrix = (float*)hd->gram.p;
         const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), 1);
-        if (n_micro <= 4096)      // few centres: small tiles, so that the launch fills the chip
+        if (n_micro <= 4096)      // few centres: small tiles, so that the launch fills the chip; the flat test takes its pair terms ready made
           k_small_matrix<2><<<dim3((unsigned)((n_micro + 31) / 32), (unsigned)((n_micro + 31) / 32), 1), 256, 0, st>>>(
-              hd->cent.p, KGC_F32, n_micro, (const float*)hd->cent.p, n_micro, d, (float*)hd->gram.p);
+              hd->cent.p, KGC_F32, n_micro, (const float*)hd->cent.p, n_micro, d, (float*)hd->gram.p,
+              (!use_units && delta >= 0.f) ? (const float*)hd->rad.p : nullptr, delta);
         else
           k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
       }
@@ -1455,7 +1456,8 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         } else {
           const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)((n_micro + kHeadsFlat - 1) / kHeadsFlat),
                        (unsigned)((RB + kRelChunk - 1) / kRelChunk));
-          k_bound_l2<<<g, 256, 0, st>>>(ba);
+          if (n_micro <= 4096) k_bound_l2<true><<<g, 256, 0, st>>>(ba);       // (the matrix came from k_small_matrix with radii)
+          else k_bound_l2<false><<<g, 256, 0, st>>>(ba);
         }
       } else if (delta >= 0.f) {
         TileDistArgs ta{};

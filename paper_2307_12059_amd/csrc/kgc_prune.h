@@ -485,10 +485,15 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
 // relation vectors), where the 128 x 128 tiles above leave most of the chip idle: 32 x 32 results per block of 256
 // threads, K through LDS 128 dimensions at a time, four rows x one column per thread.  out[i][j] = ||x_i - y_j||^2
 // (P = 2) or x_i . y_j (P = 0), row-major n_rows x n_cols; X rows of the given type, Y rows float32.
+// With `rad` set (P = 2, X = Y = the micro-tile centres) the result is not the squared centre distance D itself but
+// the part of the flat bound test that depends on the pair alone, reach^2 (1 + slack) + D (d + 8) 2^-24 - D with
+// reach = delta (1 + slack) + rad_i + rad_j (see k_bound_l2), so that the test does not form it again for every
+// group of relations; a pair with an empty micro-tile (rad < 0) gets -3e38 and never passes.
 template <int P>
 __global__ __launch_bounds__(256) void k_small_matrix(const void* __restrict__ X, int dtypeX, int64_t n_rows,
                                                       const float* __restrict__ Y, int64_t n_cols, int d,
-                                                      float* __restrict__ out) {
+                                                      float* __restrict__ out, const float* __restrict__ rad = nullptr,
+                                                      float delta = 0.f) {
   constexpr int KC = 128;                                 // dimensions per pass through LDS (d <= 128: one pass, two barriers)
   __shared__ float xs[32][KC + 1], ys[32][KC + 1];
   const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
@@ -516,9 +521,19 @@ __global__ __launch_bounds__(256) void k_small_matrix(const void* __restrict__ X
     }
   }
   if (col0 + tx < n_cols) {
+    const float rT = rad ? rad[col0 + tx] : 0.f;
+    const float dsl = delta * (1.f + kBoundSlack), dk = (float)(d + 8) * 6e-8f;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      if (row0 + ty + 8 * q < n_rows) out[(row0 + ty + 8 * q) * n_cols + col0 + tx] = acc[q];
+      if (row0 + ty + 8 * q < n_rows) {
+        float v = acc[q];
+        if (rad) {
+          const float rH = rad[row0 + ty + 8 * q];
+          const float reach = dsl + rH + rT;
+          v = (rH < 0.f || rT < 0.f) ? -3e38f : reach * reach * (1.f + kBoundSlack) + v * dk - v;
+        }
+        out[(row0 + ty + 8 * q) * n_cols + col0 + tx] = v;
+      }
   }
 }
 
@@ -612,6 +627,9 @@ struct BoundL2Args {
 };
 constexpr int kHeadChunk = 16;
 constexpr int kHeadsFlat = 64;       // head micro-tiles per block of the flat test (four groups of kHeadChunk)
+// PAIR_READY: a.D holds the pair's part of the right side, ready made (k_small_matrix with radii), not the plain
+// squared centre distance: a test then costs one load, one addition and one comparison.
+template <bool PAIR_READY>
 __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
   // block = 256 tail micro-tiles x kHeadsFlat head micro-tiles x kRelChunk relations; the per-(head, relation)
   // terms sit in LDS, the thread's own per-relation terms in registers, so one test costs one (shared) D load per
@@ -625,35 +643,46 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
   const int rl0 = (int)blockIdx.z * kRelChunk;
   const float kk = 2.f * (float)(a.d + 12) * 6e-8f;
   {
-    const int q = tid % kRelChunk;                              // 256 threads = 16 heads x kRelChunk relations per pass
+    // 256 threads = kRelChunk relations x 16 neighbouring heads per pass: a row of u is read 64 bytes at a time (one
+    // thread per relation and sixteenth of the heads would pull a whole cache line per value: 64 lines per load
+    // instruction, 0.4 GB through the vector caches per launch for a matrix of 4 MB)
+    const int q = tid >> 4, j = tid & 15;
     const int rl = rl0 + q;
     const float rnq = rl < a.RB ? a.rn[rl] : 0.f;
     const float srn = sqrtf(rnq);
 #pragma unroll
     for (int pass = 0; pass < kHeadsFlat / 16; ++pass) {
-      const int hq = pass * 16 + tid / kRelChunk;
+      const int hq = pass * 16 + j;
       const int64_t mH = mH0 + hq;
       const bool in = rl < a.RB && mH < a.n_micro;
       const float ah = in ? 2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f) : 0.f;
-      const float ahq = in ? ah - (kk * a.cnorm[mH]) * srn : 0.f;
-      aH[hq][q] = ahq;
-      // the smallest left side of the head micro-tile over the chunk's relations (the 16 lanes that hold them are neighbours)
-      float mn = in ? ahq : 3e38f;
-      mn = fminf(mn, __shfl_xor(mn, 8, 16)); mn = fminf(mn, __shfl_xor(mn, 4, 16));
-      mn = fminf(mn, __shfl_xor(mn, 2, 16)); mn = fminf(mn, __shfl_xor(mn, 1, 16));
-      if (q == 0) aHmin[hq] = mn;
+      aH[hq][q] = in ? ah - (kk * a.cnorm[mH]) * srn : 0.f;
     }
-    if (tid < kRelChunk) srnS[tid] = srn;
+    if (tid < kRelChunk) srnS[tid] = sqrtf(rl0 + tid < a.RB ? a.rn[rl0 + tid] : 0.f);
     if (tid < kHeadsFlat) {
       const int64_t m = mH0 + tid;
       radH[tid] = m < a.n_micro ? a.rad[m] : -1.f;
     }
   }
   __syncthreads();
+  {
+    // the smallest left side of every head micro-tile over the chunk's relations: four threads per head
+    const int hq = tid >> 2, part = tid & 3;
+    float mn = 3e38f;
+    if (mH0 + hq < a.n_micro) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mn = rl0 + part * 4 + i < a.RB ? fminf(mn, aH[hq][part * 4 + i]) : mn;
+    }
+    mn = fminf(mn, __shfl_xor(mn, 1, 64));
+    mn = fminf(mn, __shfl_xor(mn, 2, 64));
+    if (part == 0) aHmin[hq] = mn;
+  }
+  __syncthreads();
   if (mT >= a.n_micro) return;
   const float rT = a.rad[mT];
   if (rT < 0.f) return;                                          // empty micro-tile
   const float cT = a.cnorm[mT];
+  const int heads_here = a.n_micro - mH0 < kHeadsFlat ? (int)(a.n_micro - mH0) : kHeadsFlat;
   // dist^2 <= lim + ek sqrt(rn), ek = kk (||c_H|| + ||c_T||)
   //   <=>   (2 u_H + rn) - kk ||c_H|| sqrt(rn)  <=  (lim - D) + (2 u_T + kk ||c_T|| sqrt(rn)):
   // the left side is formed once per (head micro-tile, relation) and block, the last term once per (thread, relation),
@@ -687,12 +716,18 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
 #pragma unroll
   for (int hl = 0; hl < kHeadChunk; ++hl) {
     const int hq = hg + hl;
-    const float rH = radH[hq];
-    if (rH < 0.f) continue;                                      // empty or past the end
+    float rhs;
+    if (PAIR_READY) {
+      if (hq >= heads_here) break;                               // past the end (the same for the block)
+      rhs = Dv[hl];                                              // (-3e38 for an empty micro-tile)
+    } else {
+      const float rH = radH[hq];
+      if (rH < 0.f) continue;                                    // empty or past the end
+      const float D = Dv[hl];
+      const float reach = dsl + rH + rT;
+      rhs = reach * reach * (1.f + kBoundSlack) + D * dk - D;
+    }
     const int64_t mH = mH0 + hq;
-    const float D = Dv[hl];
-    const float reach = dsl + rH + rT;
-    const float rhs = reach * reach * (1.f + kBoundSlack) + D * dk - D;
     if (__builtin_amdgcn_ballot_w64(aHmin[hq] <= rhs + bmax) == 0ull) continue;
     bool any = false;
 #pragma unroll
