@@ -501,7 +501,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
         if (pairs_ok) {
           const size_t pair_lds = (size_t)2 * KS * 128 * kSliceK * 2;
           KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_pairs, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pair_lds));
-          hipLaunchKernelGGL(k_join_l2_pairs, dim3(2048), dim3(256), pair_lds, st, sa);
+          hipLaunchKernelGGL(k_join_l2_pairs, dim3(512), dim3(256), pair_lds, st, sa);      // two resident blocks per compute unit, each walks its tiles
         }
       } else {
         const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
@@ -1598,7 +1598,7 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         if (pairs_ok) {          // the same batch tile by tile, when the device chose that (the other kernel then returned at once)
           const size_t pair_lds = (size_t)2 * KS * 128 * kSliceK * 2;
           KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_pairs, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pair_lds));
-          hipLaunchKernelGGL(k_join_l2_pairs, dim3(2048), dim3(256), pair_lds, st, sa);
+          hipLaunchKernelGGL(k_join_l2_pairs, dim3(512), dim3(256), pair_lds, st, sa);      // two resident blocks per compute unit, each walks its tiles
         }
         if (lists_blocks) {
           launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, hd->xcap, &cnt->exact_total, &cnt->exact_need, sa.cx);

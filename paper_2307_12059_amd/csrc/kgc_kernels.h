@@ -1023,35 +1023,86 @@ __global__ __launch_bounds__(256, 2) void k_join_l2_pairs(const JoinStreamArgs a
   const float thr = a.prm->thr;
   const bool last_two = (a.k16 - (KS - 1) * 2) >= 2;
   int ncand_lane = 0;
-  for (unsigned int e = blockIdx.x; e < total; e += gridDim.x) {
-    const uint32_t row = a.tile_rows[e], tcol = a.cols[e];
+  // A block walks its tiles (entries blockIdx.x, + gridDim.x, ... of the list) in batches of up to kPairsBatch: the
+  // batch's list entries are read into the LDS first, so that no load of the list sits among the tile loads (loads
+  // return in order: waiting for a list entry would wait for every tile load asked for before it).  The first four K
+  // slices of the NEXT tile are asked for as soon as the current tile is in the LDS, so that their memory round trip
+  // runs beside the current tile's arithmetic.  Which of a tile's 32 x 32 blocks hold candidates is noted per wave,
+  // and the batch's blocks are listed for the exact kernel at its end with ONE atomic on the list's length for the
+  // whole workgroup (atomics on one address are served one after the other, and their round trip would sit in
+  // every tile's path).
+  constexpr int kPairsBatch = 32;
+  __shared__ uint32_t my_row[kPairsBatch], my_col[kPairsBatch];
+  __shared__ uint8_t my_has[kPairsBatch][4];
+  __shared__ unsigned int list_n[4];
+  __shared__ unsigned int list_base;
+  typedef uint32_t regt_t __attribute__((ext_vector_type(16 * LA)));   // 4 slices x LA chunks x 4 registers: vectors, so
+  regt_t ta, tb;                                                       // that they are plain SSA values for the compiler
+#define KGC_PAIRS_ASK(ROW, TCOL)                                                                              \
+  do {                                                                                                       \
+    const int rl_ = (int)((ROW) / (uint32_t)a.nH), tH_ = (int)((ROW) - (uint32_t)rl_ * (uint32_t)a.nH);      \
+    const char* Ab_ = (const char*)a.A + ((int64_t)rl_ * KS * a.Nslots + (int64_t)tH_ * BM) * (kSliceK * 2); \
+    const char* Bb_ = (const char*)a.B + (a.b_per_rel ? (int64_t)rl_ * KS * a.Nslots * (kSliceK * 2) : 0) +  \
+                      (int64_t)(TCOL) * BN * (kSliceK * 2);                                                  \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                          \
+      const int ks = j < KS ? j : KS - 1; /* past the last slice the loads repeat it and nothing is stored */ \
+      _Pragma("unroll") for (int i = 0; i < LA; ++i) {                                                       \
+        const uint4 x_ = *(const uint4*)(Ab_ + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));  \
+        const uint4 y_ = *(const uint4*)(Bb_ + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));  \
+        ta[4 * (j * LA + i)] = x_.x; ta[4 * (j * LA + i) + 1] = x_.y; ta[4 * (j * LA + i) + 2] = x_.z; ta[4 * (j * LA + i) + 3] = x_.w; \
+        tb[4 * (j * LA + i)] = y_.x; tb[4 * (j * LA + i) + 1] = y_.y; tb[4 * (j * LA + i) + 2] = y_.z; tb[4 * (j * LA + i) + 3] = y_.w; \
+      }                                                                                                      \
+    }                                                                                                        \
+  } while (0)
+  for (unsigned int e0 = blockIdx.x; e0 < total; e0 += kPairsBatch * gridDim.x) {      // (the same for the whole block)
+    // the batch's entries e0, e0 + gridDim.x, ...
+    const unsigned int left = (total - e0 + gridDim.x - 1) / gridDim.x;
+    const int nb = left < (unsigned int)kPairsBatch ? (int)left : kPairsBatch;
+    __syncthreads();                                         // the previous batch is listed
+    if (tid < nb) { my_row[tid] = a.tile_rows[e0 + (unsigned int)tid * gridDim.x]; my_col[tid] = a.cols[e0 + (unsigned int)tid * gridDim.x]; }
+    __syncthreads();
+    KGC_PAIRS_ASK(my_row[0], my_col[0]);
+    for (int it = 0; it < nb; ++it) {
+    const uint32_t row = my_row[it], tcol_now = my_col[it];
     const int rl = (int)(row / (uint32_t)a.nH), tH = (int)(row - (uint32_t)rl * (uint32_t)a.nH);
-    const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * (kSliceK * 2);
-    const char* Bbase = (const char*)a.B + (a.b_per_rel ? (int64_t)rl * KS * a.Nslots * (kSliceK * 2) : 0) +
-                        (int64_t)tcol * BN * (kSliceK * 2);
     __syncthreads();                                         // the previous tile is done with the LDS
-    for (int ks0 = 0; ks0 < KS; ks0 += 4) {                  // (past the last slice the loads repeat it and nothing is stored)
-      uint4 ta[4][LA], tb[4][LA];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int ks = ks0 + j < KS ? ks0 + j : KS - 1;
+    for (int j = 0; j < 4; ++j)
+      if (j < KS) {
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
-          ta[j][i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
-          tb[j][i] = *(const uint4*)(Bbase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+          *(uint4*)(&As[j * ASZ + st0 + i * st_step]) = make_uint4(ta[4 * (j * LA + i)], ta[4 * (j * LA + i) + 1], ta[4 * (j * LA + i) + 2], ta[4 * (j * LA + i) + 3]);
+          *(uint4*)(&Bs[j * ASZ + st0 + i * st_step]) = make_uint4(tb[4 * (j * LA + i)], tb[4 * (j * LA + i) + 1], tb[4 * (j * LA + i) + 2], tb[4 * (j * LA + i) + 3]);
         }
       }
+    if (KS > 4) {                                            // the slices after the fourth: loaded now (d > 122)
+      const char* Abase = (const char*)a.A + ((int64_t)rl * KS * a.Nslots + (int64_t)tH * BM) * (kSliceK * 2);
+      const char* Bbase = (const char*)a.B + (a.b_per_rel ? (int64_t)rl * KS * a.Nslots * (kSliceK * 2) : 0) +
+                          (int64_t)tcol_now * BN * (kSliceK * 2);
+      for (int ks0 = 4; ks0 < KS; ks0 += 4) {
+        uint4 ua[4][LA], ub[4][LA];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (ks0 + j < KS) {
+        for (int j = 0; j < 4; ++j) {
+          const int ks = ks0 + j < KS ? ks0 + j : KS - 1;
 #pragma unroll
           for (int i = 0; i < LA; ++i) {
-            *(uint4*)(&As[(ks0 + j) * ASZ + st0 + i * st_step]) = ta[j][i];
-            *(uint4*)(&Bs[(ks0 + j) * ASZ + st0 + i * st_step]) = tb[j][i];
+            ua[j][i] = *(const uint4*)(Abase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
+            ub[j][i] = *(const uint4*)(Bbase + (int64_t)ks * slice_bytes + voff + (uint32_t)(i * NT * 16));
           }
         }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (ks0 + j < KS) {
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+              *(uint4*)(&As[(ks0 + j) * ASZ + st0 + i * st_step]) = ua[j][i];
+              *(uint4*)(&Bs[(ks0 + j) * ASZ + st0 + i * st_step]) = ub[j][i];
+            }
+          }
+      }
     }
     __syncthreads();
+    if (it + 1 < nb) KGC_PAIRS_ASK(my_row[it + 1], my_col[it + 1]);      // the next tile's loads
     f32x16_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -1075,31 +1126,53 @@ __global__ __launch_bounds__(256, 2) void k_join_l2_pairs(const JoinStreamArgs a
           for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
       }
     }
-    // the filter on the squared distance; blocks that hold candidates are listed for the exact kernel
-    float mn = acc[0][0][0];
+    // the filter on the squared distance: which of the wave's blocks hold candidates
+    unsigned int has = 0u;                                   // bit i * TN + j: block (i, j)
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j) {
+        int n = 0;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mn = fminf(mn, acc[i][j][v]);
-    if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {
-      const int64_t hbase = (int64_t)tH * BM + wm * WTM;
-      const int64_t tbase = (int64_t)tcol * BN + wn * WTN;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          int n = 0;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) n += (acc[i][j][v] <= thr) ? 1 : 0;
-          if (__builtin_amdgcn_ballot_w64(n != 0) != 0ull) {
-            ncand_lane += n;
-            list_block(a, a.r0 + rl, hbase + i * 32, tbase + j * 32);
-          }
-        }
+        for (int v = 0; v < 16; ++v) n += (acc[i][j][v] <= thr) ? 1 : 0;
+        ncand_lane += n;
+        if (__builtin_amdgcn_ballot_w64(n != 0) != 0ull) has |= 1u << (i * TN + j);
+      }
+    if (lane == 0) my_has[it][wave] = (uint8_t)has;
+    }   // tiles of the batch
+    // the batch's blocks with candidates onto the list: wave w takes the notes of all four waves for tiles w, w + 4, ...
+    __syncthreads();
+    unsigned int mine = 0u;
+    for (int it = wave; it < nb; it += 4)
+      mine += (unsigned int)__builtin_popcount((unsigned int)my_has[it][0] | ((unsigned int)my_has[it][1] << 8) |
+                                               ((unsigned int)my_has[it][2] << 16) | ((unsigned int)my_has[it][3] << 24));
+    if (lane == 0) list_n[wave] = mine;
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned int sum = list_n[0] + list_n[1] + list_n[2] + list_n[3];
+      list_base = sum ? atomicAdd(a.xcount, sum) : 0u;
     }
-  }
+    __syncthreads();
+    if (lane == 0 && mine) {
+      unsigned int idx = list_base;
+      for (int w = 0; w < wave; ++w) idx += list_n[w];
+      for (int it = wave; it < nb; it += 4) {
+        const uint32_t row = my_row[it];
+        const int rl = (int)(row / (uint32_t)a.nH), tH = (int)(row - (uint32_t)rl * (uint32_t)a.nH);
+        for (int w = 0; w < 4; ++w) {
+          const unsigned int has = my_has[it][w];
+          const int64_t hbase = (int64_t)tH * BM + (w / WGN) * WTM;
+          const int64_t tbase = (int64_t)my_col[it] * BN + (w % WGN) * WTN;
+          for (int b = 0; b < TM * TN; ++b)
+            if ((has >> b) & 1u) {
+              if (idx < a.xcap) a.xlist[idx] = ExactEntry{a.r0 + rl, (int32_t)(hbase + (b / TN) * 32), (int32_t)(tbase + (b % TN) * 32), 0};
+              ++idx;
+            }
+        }
+      }
+    }
+  }   // batches
+#undef KGC_PAIRS_ASK
   for (int off = 32; off > 0; off >>= 1) ncand_lane += __shfl_xor(ncand_lane, off, 64);
   if (lane == 0 && ncand_lane) atomicAdd(a.cx.cand_counter, (unsigned long long)ncand_lane);
 }
