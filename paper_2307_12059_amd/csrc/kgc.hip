@@ -228,6 +228,17 @@ void launch_exact_blocks(hipStream_t st, const ExactEntry* list, const unsigned 
   hipLaunchKernelGGL(kern, dim3(256), dim3(kExactWaves * 64), 0, st, list, count, cap, total, need, cx);      // one workgroup per compute unit
 }
 
+// out[i][j] = x_i . y_j, one wave per 32 x 32 results on the float32 matrix pipes (k_small_dot): X rows of the storage
+// type, Y rows float32
+void launch_small_dot(hipStream_t st, const void* X, int dtype, int64_t n_rows, const float* Y, int64_t n_cols, int d, float* out) {
+  const bool bf = dtype == KGC_BF16;
+  const bool vec = d % 4 == 0 && (uintptr_t)X % (bf ? 8 : 16) == 0 && (uintptr_t)Y % 16 == 0;
+  auto kern = bf ? (vec ? k_small_dot<true, true> : k_small_dot<true, false>)
+                 : (vec ? k_small_dot<false, true> : k_small_dot<false, false>);
+  hipLaunchKernelGGL(kern, dim3((unsigned)((n_cols + 31) / 32), (unsigned)((n_rows + 31) / 32), 1), dim3(64), 0, st,
+                     X, n_rows, Y, n_cols, d, out);
+}
+
 // Blocks for `items` work items, `per_block` each.  A launch may hold fewer than 2^32 threads per grid dimension, so
 // the count stops at 2^24 - 1 blocks (of at most 256 threads): enough for every per-row or per-slot kernel here
 // (N < 2^31); kernels that can be asked for more (k_fill_u32, the staging kernels) stride over their items.
@@ -1415,14 +1426,8 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
           td.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); td.dtypeX = dtype; td.n_rows = RB;
           td.Y = hd->cent.p; td.dtypeY = KGC_F32; td.n_cols = n_micro; td.shift = nullptr; td.dtype_shift = KGC_F32;
           td.d = d; td.matrix = (float*)hd->relu.p;
-          if (n_micro <= 4096 && RB <= 4096) {
-            const bool bf = dtype == KGC_BF16;
-            const bool vec = d % 4 == 0 && (uintptr_t)td.X % (bf ? 8 : 16) == 0 && (uintptr_t)hd->cent.p % 16 == 0;
-            auto kern = bf ? (vec ? k_small_dot<true, true> : k_small_dot<true, false>)
-                           : (vec ? k_small_dot<false, true> : k_small_dot<false, false>);
-            hipLaunchKernelGGL(kern, dim3((unsigned)((n_micro + 31) / 32), (unsigned)((RB + 31) / 32), 1), dim3(64), 0, st,
-                               td.X, (int64_t)RB, (const float*)hd->cent.p, (int64_t)n_micro, d, (float*)hd->relu.p);
-          }
+          if (n_micro <= 4096 && RB <= 4096)
+            launch_small_dot(st, td.X, dtype, RB, (const float*)hd->cent.p, n_micro, d, (float*)hd->relu.p);
           else
             k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((n_micro + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(td);
         }
@@ -1443,7 +1448,10 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
           tu.X = (const char*)Rvecs + (size_t)r0 * d * (dtype == KGC_BF16 ? 2 : 4); tu.dtypeX = dtype; tu.n_rows = RB;
           tu.Y = hd->cent_u.p; tu.dtypeY = KGC_F32; tu.n_cols = ut.n_units; tu.shift = nullptr; tu.dtype_shift = KGC_F32;
           tu.d = d; tu.matrix = (float*)hd->relu_u.p;
-          k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((ut.n_units + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(tu);
+          if (ut.n_units <= 8192 && RB <= 4096)      // a thin product: 128 x 128 tiles would leave most of the chip idle
+            launch_small_dot(st, tu.X, dtype, RB, (const float*)hd->cent_u.p, ut.n_units, d, (float*)hd->relu_u.p);
+          else
+            k_tile_dist<0, kEpiMatrix><<<dim3((unsigned)((ut.n_units + 127) / 128), (unsigned)((RB + 127) / 128), 1), 256, 0, st>>>(tu);
           k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)hd->pair_count.p, 2, 0u);
           BoundL2Args bu = ba;
           bu.D = (const float*)hd->gram_u.p; bu.u = (const float*)hd->relu_u.p; bu.rad = (const float*)hd->rad_u.p;

@@ -858,7 +858,7 @@ __global__ __launch_bounds__(256) void k_bound_l2_units(const BoundL2Args a, con
   const int64_t mH0 = (int64_t)blockIdx.y * kHeadChunk;
   const int rl0 = (int)blockIdx.z * kRelChunk;
   {
-    const int hq = tid / kRelChunk, q = tid % kRelChunk;
+    const int q = tid / kHeadChunk, hq = tid % kHeadChunk;      // neighbouring threads on neighbouring heads: 64 bytes of a row of u
     const int rl = rl0 + q;
     const int64_t mH = mH0 + hq;
     const float rnq = rl < a.RB ? a.rn[rl] : 0.f;
