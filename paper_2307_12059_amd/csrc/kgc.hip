@@ -1339,12 +1339,12 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         // squared distances between all micro-tile centres, once: the part of the bound that no relation changes
         TileDistArgs ta{};
         ta.X = hd->cent.p; ta.dtypeX = KGC_F32; ta.n_rows = n_micro; ta.Y = hd->cent.p; ta.dtypeY = KGC_F32;
-        ta.n_cols = n_micro; ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.d = d; ta.matrix = (float*)hd->gram.p;
+        ta.n_cols = n_micro; ta.shift = nullptr; ta.dtype_shift = KGC_F32; ta.d = d; ta.matrix = (float*)hd->gram.p; ta.symmetric = 1;
         const dim3 g((unsigned)((n_micro + 127) / 128), (unsigned)((n_micro + 127) / 128), 1);
         if (n_micro <= 4096)      // few centres: small tiles, so that the launch fills the chip; the flat test takes its pair terms ready made
           k_small_matrix<2><<<dim3((unsigned)((n_micro + 31) / 32), (unsigned)((n_micro + 31) / 32), 1), 256, 0, st>>>(
               hd->cent.p, KGC_F32, n_micro, (const float*)hd->cent.p, n_micro, d, (float*)hd->gram.p,
-              (!use_units && delta >= 0.f) ? (const float*)hd->rad.p : nullptr, delta);
+              (!use_units && delta >= 0.f) ? (const float*)hd->rad.p : nullptr, delta, 1);
         else
           k_tile_dist<2, kEpiMatrix><<<g, 256, 0, st>>>(ta);
       }
@@ -1353,7 +1353,7 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
                                                             (float*)hd->cent_u.p, (float*)hd->rad_u.p, (float*)hd->cnorm_u.p);
         TileDistArgs tu{};
         tu.X = hd->cent_u.p; tu.dtypeX = KGC_F32; tu.n_rows = ut.n_units; tu.Y = hd->cent_u.p; tu.dtypeY = KGC_F32;
-        tu.n_cols = ut.n_units; tu.shift = nullptr; tu.dtype_shift = KGC_F32; tu.d = d; tu.matrix = (float*)hd->gram_u.p;
+        tu.n_cols = ut.n_units; tu.shift = nullptr; tu.dtype_shift = KGC_F32; tu.d = d; tu.matrix = (float*)hd->gram_u.p; tu.symmetric = 1;
         const dim3 gu((unsigned)((ut.n_units + 127) / 128), (unsigned)((ut.n_units + 127) / 128), 1);
         k_tile_dist<2, kEpiMatrix><<<gu, 256, 0, st>>>(tu);
       }

@@ -277,6 +277,7 @@ struct TileDistArgs {
   unsigned long long* best;                        // ASSIGN
   float* matrix;                                   // MATRIX
   int64_t matrix_rel_stride;                       // MATRIX: relation blockIdx.z writes its n_rows x n_cols block this many floats further on
+  int symmetric;                                   // MATRIX with X == Y and no shift: only the blocks on and above the diagonal work, and write both halves
   const float* rad; float delta; uint32_t* bitmap; // BOUND
   int nH, words_per_row, micro_per_bm, micro_per_bn;
   // BOUND with per-relation summaries (the general form): relation blockIdx.z reads rows z * x_rel_rows + i of X and
@@ -323,6 +324,7 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
   const int64_t n_cols = a.n_cols_dev ? (int64_t)*a.n_cols_dev : a.n_cols;
   const int64_t row0 = (int64_t)blockIdx.y * BM, col0 = (int64_t)blockIdx.x * BN;
   if (row0 >= n_rows || col0 >= n_cols) return;
+  if (EPI == kEpiMatrix && a.symmetric && blockIdx.y > blockIdx.x) return;      // the mirror block writes this one
   if (tid < BM) {
     const int64_t r = row0 + tid;
     rid[tid] = r < n_rows ? (a.row_ids ? a.row_ids[r] : (int32_t)r) : -1;
@@ -423,6 +425,11 @@ __global__ __launch_bounds__(256) void k_tile_dist(const TileDistArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           if (cid[lc + j] >= 0) o[j] = acc[i][jg * 4 + j];
+        if (a.symmetric && blockIdx.y != blockIdx.x) {       // sum of (x_i - x_j)^2 = sum of (x_j - x_i)^2, term by term
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (cid[lc + j] >= 0) a.matrix[(int64_t)blockIdx.z * a.matrix_rel_stride + (col0 + lc + j) * n_cols + row0 + lr] = acc[i][jg * 4 + j];
+        }
       }
     }
   } else if (EPI == kEpiBoundUnits) {
@@ -493,11 +500,12 @@ template <int P>
 __global__ __launch_bounds__(256) void k_small_matrix(const void* __restrict__ X, int dtypeX, int64_t n_rows,
                                                       const float* __restrict__ Y, int64_t n_cols, int d,
                                                       float* __restrict__ out, const float* __restrict__ rad = nullptr,
-                                                      float delta = 0.f) {
+                                                      float delta = 0.f, int symmetric = 0) {      // symmetric (X == Y): blocks above the diagonal write both halves
   constexpr int KC = 128;                                 // dimensions per pass through LDS (d <= 128: one pass, two barriers)
   __shared__ float xs[32][KC + 1], ys[32][KC + 1];
   const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
   const int64_t row0 = (int64_t)blockIdx.y * 32, col0 = (int64_t)blockIdx.x * 32;
+  if (symmetric && blockIdx.y > blockIdx.x) return;        // the mirror block writes this one
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int k0 = 0; k0 < d; k0 += KC) {
     const int kn = d - k0 < KC ? d - k0 : KC;
@@ -529,10 +537,11 @@ __global__ __launch_bounds__(256) void k_small_matrix(const void* __restrict__ X
         float v = acc[q];
         if (rad) {
           const float rH = rad[row0 + ty + 8 * q];
-          const float reach = dsl + rH + rT;
+          const float reach = dsl + (rH + rT);                 // (the same for both orders of the pair)
           v = (rH < 0.f || rT < 0.f) ? -3e38f : reach * reach * (1.f + kBoundSlack) + v * dk - v;
         }
         out[(row0 + ty + 8 * q) * n_cols + col0 + tx] = v;
+        if (symmetric && blockIdx.y != blockIdx.x) out[(col0 + tx) * n_cols + row0 + ty + 8 * q] = v;   // (sum of (x_i - x_j)^2 = sum of (x_j - x_i)^2 term by term, and the pair term is symmetric too)
       }
   }
 }
