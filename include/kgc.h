@@ -57,11 +57,12 @@ typedef struct {
     int32_t tile_cfg;         /* 0 = automatic choice of the L2 join kernel; > 0 forces a variant (for measurements):
                                  1-5   one block per tile pair, 128/256-row tiles (dense mode only)
                                  6-10  streaming: a block walks tail tiles, head and tail slices through LDS (any d)
-                                 11-14 head tile resident in LDS, tail slices through LDS (d <= 250; pruned defaults:
-                                       14, two 128 x 128 blocks per CU, below 262,144 entities; 12, 256 x 256, from there on)
+                                 11-14 head tile resident in LDS, tail slices through LDS (d <= 250; 14, two 128 x 128
+                                       blocks per CU, is the pruned default below 262,144 entities)
                                  15-18 head tile resident, tail fragments straight to registers, no barrier in the
-                                       loop (dense mode only; 15-16: d <= 282; 17: d <= 602; 18: d <= 282, one
-                                       straight-line instantiation per number of K steps, the dense default)
+                                       loop (15-16: d <= 282; 17: d <= 602; 18: d <= 282, one straight-line
+                                       instantiation per number of K steps, the dense default).  Dense mode, and 15
+                                       also pruned, walking tile lists: the pruned default from 262,144 entities on
                                  A variant that cannot run the request (pruned mode, d) fails with KGC_E_INVALID. */
     int64_t workspace_bytes;  /* cap on scratch held for staged operands; 0 = 16 GiB.  Larger joins run in relation batches */
     void*   stream;           /* hipStream_t to enqueue on; NULL = the default stream */

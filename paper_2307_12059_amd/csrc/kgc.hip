@@ -76,6 +76,7 @@ struct kgc_handle {
   DevBuf se_a, se_b;                           // connector rows of a relation batch (kgc_join_se)
   DevBuf xlist;                                // accumulator blocks listed for the exact stage (L2 joins)
   unsigned int xcap = kExactListCap;           // its length in entries: grows when a batch wanted to list more
+  int list_seg_cap = 0;                        // > 0: the pruned barrier-free kernel keeps at most this many entries of a row's tile list in the LDS (tests)
   DevBuf zero_row, cent_a, rad_a;              // kgc_join_ab: the zero relation row; micro-tile summaries of A[r]
   DevBuf top1_a, top1_b, top1_pick, top_samples, topk_state;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
@@ -171,7 +172,7 @@ const TileCfg kL2Tiles[] = {
     {256, 256, 512, nullptr, k_join_l2_ares<256, 256, 2, 4, 1, 512, false>, k_join_l2_ares<256, 256, 2, 4, 1, 512, true>, true, 0, 1, 2},
     {256, 128, 512, nullptr, k_join_l2_ares<256, 128, 4, 2, 1, 512, false>, k_join_l2_ares<256, 128, 4, 2, 1, 512, true>, true, 0, 1, 2},
     {128, 128, 256, nullptr, k_join_l2_ares<128, 128, 2, 2, 2, 256, false>, k_join_l2_ares<128, 128, 2, 2, 2, 256, true>, true, 0, 2, 2},
-    {256, 256, 512, nullptr, k_join_l2_direct<256, 2, 4, kEpiJoin>, nullptr, true, 0, 1, 0},
+    {256, 256, 512, nullptr, k_join_l2_direct<256, 2, 4, kEpiJoin>, k_join_l2_direct<256, 2, 4, kEpiJoin, true>, true, 0, 1, 0},
     {256, 256, 512, nullptr, k_join_l2_direct<256, 1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
     {128, 256, 512, nullptr, k_join_l2_direct<128, 1, 8, kEpiJoin>, nullptr, true, 0, 1, 0},
     {256, 256, 512, nullptr, k_join_l2_dense<1>, nullptr, true, 0, 1, 0},      // placeholder: see dense_kernel_for
@@ -183,11 +184,15 @@ constexpr int64_t kResidentLargeN = 1 << 18;      // ... from this many on: rows
                                                   // larger wave tile (half the LDS reads per MFMA) pays; below, the finer
                                                   // tiles follow the surviving patches more closely and balance better
 // the pruned default for N entities and KS slices (both head-resident shapes need KS <= 8 to fit their LDS)
+constexpr int kDirectL2Tile = 14;                 // head-resident and barrier-free, 8 waves (2 x 4): dense joins, and pruned joins over many entities
 inline int pruned_l2_tile(int64_t N, int KS, int fallback) {
   if (((size_t)KS * 128 + 2 * 128) * kSliceK * 2 * 2 > kMaxLds) return fallback;
-  return N >= kResidentLargeN ? kResidentLargeL2Tile : kResidentL2Tile;
+  if (N < kResidentLargeN) return kResidentL2Tile;
+  // many entities: the barrier-free form walking the row's tile list, which sits in the LDS behind the head slices
+  // (measured on the 10^6-entity workload: 610 ms of join per step against 647 ms)
+  if ((size_t)KS * 256 * kSliceK * 2 + 16384 <= kMaxLds) return kDirectL2Tile;      // (room for 4,096 tiles of a row's list at a time)
+  return kResidentLargeL2Tile;
 }
-constexpr int kDirectL2Tile = 14;                 // head-resident and barrier-free (dense mode only), 8 waves (2 x 4)
 constexpr int kDenseL2Tile = 17;                  // the same with a straight-line tile body per number of K steps (dense default)
 constexpr int kDirectMaxKS = 9;                   // its head tile then takes 144 of the 160 KiB of LDS
 constexpr int kDirectHalfL2Tile = 16;             // the same with a 128-row head tile (wave tile 128 x 32), for larger d
@@ -290,6 +295,7 @@ int kgc_create(const kgc_config* cfg, kgc_handle** out) {
   h->err.reserve(256);          // later error messages fit without a host allocation
   // the first length of the exact stage's block list (it grows by itself; tests set it small to see it grow)
   if (const char* e = std::getenv("KGC_EXACT_LIST_CAP")) h->xcap = (unsigned int)std::max(1L, std::atol(e));
+  if (const char* e = std::getenv("KGC_TILE_LIST_SEGMENT")) h->list_seg_cap = (int)std::max(1L, std::atol(e));
   if (hipHostMalloc((void**)&h->host_counters, sizeof(DevCounters), hipHostMallocDefault) != hipSuccess) {
     delete h;
     return KGC_E_NOMEM;
@@ -491,6 +497,12 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
       size_t dyn_lds = 0;
       if (tc.head_resident) {
         dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
+        if (prune && tc.tail_buffers == 0) {      // the barrier-free form keeps a row's tile list behind the head slices, in segments if need be
+          if (dyn_lds + 1024 > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the pruned barrier-free tile variant");
+          sa.cols_lds = (int)std::min<size_t>((kMaxLds - dyn_lds) / 4, (size_t)nT);
+          if (hd->list_seg_cap > 0) sa.cols_lds = std::min(sa.cols_lds, hd->list_seg_cap);
+          dyn_lds += (size_t)sa.cols_lds * 4;
+        }
         if (prune && tc.tail_buffers > 0) {
           const size_t spare = kMaxLds / tc.blocks_per_cu - (dyn_lds + tc.static_lds);
           sa.cols_lds = (int)std::min<size_t>(spare / 4, (size_t)nT);
@@ -1584,6 +1596,12 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         if (tc.head_resident) {
           dyn_lds = ((size_t)KS * BM + (size_t)tc.tail_buffers * BN) * kSliceK * 2;
           if ((dyn_lds + tc.static_lds) * tc.blocks_per_cu > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the head-resident tile variant");
+          if (prune && tc.tail_buffers == 0) {    // the barrier-free form keeps a row's tile list behind the head slices, in segments if need be
+            if (dyn_lds + 1024 > kMaxLds) return fail(hd, KGC_E_INVALID, "d too large for the pruned barrier-free tile variant");
+            sa.cols_lds = (int)std::min<size_t>((kMaxLds - dyn_lds) / 4, (size_t)nT);
+            if (hd->list_seg_cap > 0) sa.cols_lds = std::min(sa.cols_lds, hd->list_seg_cap);
+            dyn_lds += (size_t)sa.cols_lds * 4;
+          }
           if (prune && tc.tail_buffers > 0) {     // room for a row's tile list behind the tail buffers, if the LDS has it
             const size_t spare = kMaxLds / tc.blocks_per_cu - (dyn_lds + tc.static_lds);
             sa.cols_lds = (int)std::min<size_t>(spare / 4, (size_t)nT);

@@ -1189,7 +1189,10 @@ __global__ __launch_bounds__(256, 2) void k_join_l2_pairs(const JoinStreamArgs a
 // LDS: KS * BM * 64 bytes: BM = 256 up to KS = 9 (d <= 282), BM = 128 up to KS = 19 (d <= 602).  In the join
 // form (EPI = kEpiJoin) candidates are re-scored by the owning wave; kEpiAssignMin is the epilogue of the
 // group assignment (see JoinStreamArgs).
-template <int BM, int WGM, int WGN, int EPI>
+// LISTED (pruned joins over many entities, kEpiJoin): the grid strides over the active rows, and a row's tile list
+// sits in the LDS behind the head slices (a.cols_lds entries), so that the tile loop holds no load of the list among
+// its prefetches.
+template <int BM, int WGM, int WGN, int EPI, bool LISTED = false>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinStreamArgs a) {
   constexpr int BN = 256;
   constexpr int NT = WGM * WGN * 64;
@@ -1205,16 +1208,27 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  const int tH = (int)blockIdx.x, rl = (int)blockIdx.y;
-  int nT = a.nT;
-  if (EPI == kEpiAssignMin && a.tail_rows_dev) {          // only the tail tiles that hold pivots of this round
-    const int used = (*a.tail_rows_dev + BN - 1) / BN;
-    nT = used < nT ? used : nT;
+  for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
+  int tH, rl, t_begin, ntiles;
+  const uint32_t* tlist = nullptr;                         // LISTED: the row's tile list in the LDS
+  if constexpr (LISTED) {
+    if (row_i >= *a.n_active) break;
+    // (the same for the whole block: kept in scalar registers)
+    const int64_t row = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)a.active_rows[row_i]);
+    rl = (int)(row / a.nH); tH = (int)(row - (int64_t)rl * a.nH);
+    t_begin = __builtin_amdgcn_readfirstlane((int)a.row_start[row]); ntiles = __builtin_amdgcn_readfirstlane((int)a.row_count[row]);
+    __syncthreads();                                       // the previous row is done with the LDS
+  } else {
+    tH = (int)blockIdx.x; rl = (int)blockIdx.y;
+    int nT = a.nT;
+    if (EPI == kEpiAssignMin && a.tail_rows_dev) {        // only the tail tiles that hold pivots of this round
+      const int used = (*a.tail_rows_dev + BN - 1) / BN;
+      nT = used < nT ? used : nT;
+    }
+    t_begin = (int)(((int64_t)nT * blockIdx.z) / gridDim.z);
+    ntiles = (int)(((int64_t)nT * (blockIdx.z + 1)) / gridDim.z) - t_begin;
   }
-  const int t_begin = (int)(((int64_t)nT * blockIdx.z) / gridDim.z);
-  const int t_end = (int)(((int64_t)nT * (blockIdx.z + 1)) / gridDim.z);
-  const int ntiles = t_end - t_begin;
-  if (ntiles <= 0) return;
+  if (ntiles <= 0) break;                                  // (an active row has tiles; the same for the whole block)
   const int64_t slice_bytes_a = a.Nslots * ROWB;
   const int64_t slice_bytes = (a.tail_slots ? a.tail_slots : a.Nslots) * ROWB;
 
@@ -1232,16 +1246,28 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
       for (int i = 0; i < LA; ++i) *(uint4*)(&lds[ks * ASZ + st0 + i * st_step]) = t[i];
     }
   }
-  __syncthreads();          // the only barrier: the head tile is complete
+  // LISTED: the row's tiles in segments of what the LDS holds of the list (a.cols_lds entries; nearly always one segment)
+  const int row_tiles = ntiles;
+  for (int seg0 = 0; seg0 < (LISTED ? row_tiles : 1); seg0 += (LISTED ? a.cols_lds : 1)) {
+  if constexpr (LISTED) {
+    if (seg0 > 0) __syncthreads();                         // the previous segment's list is no longer read
+    ntiles = row_tiles - seg0 < a.cols_lds ? row_tiles - seg0 : a.cols_lds;
+    uint32_t* l = (uint32_t*)(lds + KS * ASZ);
+    for (int t = tid; t < ntiles; t += NT) l[t] = a.cols[t_begin + seg0 + t];
+    tlist = l;
+  }
+  __syncthreads();          // the head tile (and the tile list) is complete: no barrier in the tile loop
 
   const int rsw = lds_swizzle(lane & 31);
   const int rd_a = (wm * WTM + (lane & 31)) * kSliceK + (((lane >> 5) ^ rsw) * 8);
   const int rd_step = (((lane >> 5) ^ rsw) & 2) ? -16 : 16;
 
   // tail fragments of this lane: row (lane % 32) of each 32-row group of the wave's columns
-  const char* Bw = (const char*)a.B + (a.b_per_rel ? (int64_t)rl * KS * a.Nslots * ROWB : 0) +
-                   ((int64_t)wn * WTN + (lane & 31)) * ROWB + (lane >> 5) * 16;
-  const char* pB = Bw + (int64_t)t_begin * BN * ROWB;
+  // (LISTED: the tile part of the address is the same for the whole wave and stays in scalar registers, the lane's
+  // part is a 32-bit offset: the kernel has no register to spare)
+  const uint32_t boff = (uint32_t)((wn * WTN + (lane & 31)) * ROWB + (lane >> 5) * 16);
+  const char* Bw = (const char*)a.B + (a.b_per_rel ? (int64_t)rl * KS * a.Nslots * ROWB : 0) + (LISTED ? 0u : boff);
+  const char* pB = Bw + (int64_t)(LISTED ? __builtin_amdgcn_readfirstlane((int)tlist[0]) : t_begin) * BN * ROWB;
   const int total = ntiles * KS;
   int pf_k = 0, pf_t = 0, pf_i = 0;
 
@@ -1250,8 +1276,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
 #define KGC_GLOAD(Q)                                                                              \
   do {                                                                                            \
     _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                              \
-      const uint4 t0 = *(const uint4*)(pB + j * 32 * ROWB);                                       \
-      const uint4 t1 = *(const uint4*)(pB + j * 32 * ROWB + 32);                                  \
+      const uint4 t0 = *(const uint4*)(pB + ((LISTED ? boff : 0u) + (uint32_t)(j * 32 * ROWB)));  \
+      const uint4 t1 = *(const uint4*)(pB + ((LISTED ? boff : 0u) + (uint32_t)(j * 32 * ROWB + 32))); \
       Q[8 * j] = t0.x; Q[8 * j + 1] = t0.y; Q[8 * j + 2] = t0.z; Q[8 * j + 3] = t0.w;             \
       Q[8 * j + 4] = t1.x; Q[8 * j + 5] = t1.y; Q[8 * j + 6] = t1.z; Q[8 * j + 7] = t1.w;         \
     }                                                                                             \
@@ -1260,7 +1286,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
       if (++pf_k == KS) {                                                                         \
         pf_k = 0;                                                                                 \
         ++pf_t;                                                                                   \
-        pB = Bw + (int64_t)(t_begin + pf_t) * BN * ROWB;                                          \
+        pB = Bw + (int64_t)(LISTED ? __builtin_amdgcn_readfirstlane((int)tlist[pf_t]) : t_begin + pf_t) * BN * ROWB; \
       } else {                                                                                    \
         pB += slice_bytes;                                                                        \
       }                                                                                           \
@@ -1317,7 +1343,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
         run_min = fminf(run_min, mn);        /* only the smallest squared distance is wanted */    \
       } else if (__builtin_amdgcn_ballot_w64(mn <= thr) != 0ull) {                                \
         const int64_t hbase = (int64_t)tH * BM + wm * WTM;                                        \
-        const int64_t tbase = (int64_t)(t_begin + ct) * BN + wn * WTN;                            \
+        const int64_t tbase = (int64_t)(LISTED ? __builtin_amdgcn_readfirstlane((int)tlist[ct]) : t_begin + ct) * BN + wn * WTN; \
         constexpr int NW = (TM * TN + 3) / 4;                                                     \
         _Pragma("unroll") for (int w = 0; w < NW; ++w) {                                          \
           unsigned long long cm = 0ull;                                                           \
@@ -1373,10 +1399,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
 #undef KGC_GLOAD
 #undef KGC_FRAG
 #undef KGC_COMPUTE
-  if (EPI == kEpiMinDist) {
+  if (!LISTED && EPI == kEpiMinDist) {                     // (not listed: a single pass)
     for (int off = 32; off > 0; off >>= 1) run_min = fminf(run_min, __shfl_xor(run_min, off, 64));
     if (lane == 0) atomicMin(a.best, (unsigned long long)__float_as_uint(fmaxf(run_min, 0.f)));   // non-negative floats order like their bits
   }
+  }   // segments of the row's tile list
+  if (!LISTED) break;
+  }   // rows
 }
 
 // ---------------------------------------------------------------------------------------------

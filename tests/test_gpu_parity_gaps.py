@@ -215,6 +215,26 @@ def test_exact_block_list_grows(prune):
         assert small["stats"]["exact_blocks"] > 3
 
 
+# ---- the barrier-free kernel walking tile lists (the pruned default for many entities, here chosen by hand): whole
+# ---- lists in the LDS, and lists cut into segments of two entries
+@pytest.mark.parametrize("segment", [0, 2])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pruned_barrier_free_kernel_walks_tile_lists(segment, dtype):
+    g = np.random.default_rng(515 + segment)
+    N, R, d, sig = 3000, 5, 64, 0.1
+    E, Rv = _clustered(g, N, R, d, 4, sig)               # four clusters of 750: rows with several surviving 256 x 256 tiles
+    E, Rv = _seen(E, dtype), _seen(Rv, dtype)
+    delta = float(np.float32(sig * np.sqrt(2.0 * d) * 0.9))
+    if segment:
+        os.environ["KGC_TILE_LIST_SEGMENT"] = str(segment)
+    try:
+        got, ref, _ = _join_and_compare(E, Rv, 2, delta, dtype, prune=PRUNE_ON, tile_cfg=15)
+    finally:
+        os.environ.pop("KGC_TILE_LIST_SEGMENT", None)
+    assert got["stats"]["join_variant"] == 15
+    assert ref["count"] > 0
+
+
 # ---- seeded sweep: random shapes (ragged in N and d, through every kernel family's range of d), cluster widths,
 # ---- norms, storage types, thresholds and modes; bounded so that the oracle side stays within a minute
 def _fuzz_cases(seed, n):
