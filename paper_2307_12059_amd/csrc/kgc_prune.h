@@ -638,8 +638,51 @@ constexpr int kHeadChunk = 16;
 constexpr int kHeadsFlat = 64;       // head micro-tiles per block of the flat test (four groups of kHeadChunk)
 // PAIR_READY: a.D holds the pair's part of the right side, ready made (k_small_matrix with radii), not the plain
 // squared centre distance: a test then costs one load, one addition and one comparison.
-template <bool PAIR_READY>
-__global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
+// UNITS: the unit level of the two-level test (see below): `a` describes UNITS, and a surviving (relation, unit pair)
+// is appended to the list `bp` -- or refined on the spot on the micro-tile arrays `fine` when the pair is small or
+// the list is full -- instead of setting bits.
+__device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const UnitTable& ut, int rl, int uH, int uT, int lane0,
+                                                 int lane_count);
+// The surviving (relation rl0 + q, unit pair) of a wave: bit q of `keep` per lane (head unit mH the same for the wave,
+// tail unit mT the lane's).  A pair of small units (in the packed tail region both are single micro-tiles) is
+// finished on the spot; pairs with many micro-tile pairs go through the list, whose length is advanced ONCE per
+// relation for all lanes of the wave that append (atomics on one address are served one after the other: with one
+// per entry the unit level of a join with many survivors spent most of its time there).  Called by all active lanes.
+__device__ __forceinline__ void unit_pairs_out(uint32_t keep, int rl0, int mH, int mT, const BoundL2Args& fine,
+                                               const UnitTable& ut, const BoundPairs& bp) {
+  if (__builtin_amdgcn_ballot_w64(keep != 0u) == 0ull) return;
+  int fH, nHm, fT, nTm;
+  unit_range(ut, mH, fH, nHm);
+  unit_range(ut, mT, fT, nTm);
+  // (without the matrices a micro-tile pair costs a loop over d: then every pair but a single one is listed)
+  const bool big = (int64_t)nHm * nTm > (fine.D ? kInlineMicroPairs : 1);
+  const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+#pragma unroll 1
+  for (int q = 0; q < kRelChunk; ++q) {
+    const bool k = (keep >> q) & 1u;
+    if (__builtin_amdgcn_ballot_w64(k) == 0ull) continue;
+    const unsigned long long ml = __builtin_amdgcn_ballot_w64(k && big);
+    unsigned long long pos = bp.cap;
+    if (ml) {
+      const int leader = (int)__builtin_ctzll(ml);
+      unsigned long long base = 0ull;
+      if (lane == leader) base = atomicAdd(bp.count, (unsigned long long)__builtin_popcountll(ml));
+      const uint32_t blo = (uint32_t)__shfl((int)(uint32_t)(base & 0xffffffffull), leader, 64);
+      const uint32_t bhi = (uint32_t)__shfl((int)(uint32_t)(base >> 32), leader, 64);
+      if (k && big) pos = (((unsigned long long)bhi << 32) | blo) + (unsigned long long)__builtin_popcountll(ml & ((1ull << lane) - 1ull));
+    }
+    if (k) {
+      if (pos < bp.cap)
+        bp.list[pos] = ((unsigned long long)(uint32_t)(rl0 + q) << 48) | ((unsigned long long)(uint32_t)mH << 24) |
+                       (unsigned long long)(uint32_t)mT;
+      else
+        refine_unit_pair(fine, ut, rl0 + q, mH, mT, 0, 1);
+    }
+  }
+}
+template <bool PAIR_READY, bool UNITS>
+__global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a, const BoundL2Args fine, const UnitTable ut,
+                                                  const BoundPairs bp) {
   // block = 256 tail micro-tiles x kHeadsFlat head micro-tiles x kRelChunk relations; the per-(head, relation)
   // terms sit in LDS, the thread's own per-relation terms in registers, so one test costs one (shared) D load per
   // kRelChunk relations, one addition and one comparison -- and most chunks of relations end at one comparison
@@ -709,7 +752,7 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
   float bmax = bT[0];
 #pragma unroll
   for (int q = 1; q < kRelChunk; ++q) bmax = fmaxf(bmax, bT[q]);
-  const int tT = (int)(mT / a.micro_per_bn);
+  const int tT = UNITS ? 0 : (int)(mT / a.micro_per_bn);
   const float dsl = a.delta * (1.f + kBoundSlack);
   const float dk = (float)(a.d + 8) * 6e-8f;
   for (int hg = 0; hg < kHeadsFlat; hg += kHeadChunk) {
@@ -745,6 +788,10 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a) {
     uint32_t keep = 0u;
 #pragma unroll
     for (int q = 0; q < kRelChunk; ++q) keep |= (aH[hq][q] <= rhs + bT[q]) ? (1u << q) : 0u;
+    if constexpr (UNITS) {
+      unit_pairs_out(keep, rl0, (int)mH, (int)mT, fine, ut, bp);
+      continue;
+    }
     const int tH = (int)(mH / a.micro_per_bm);
     while (keep) {
       const int q = __builtin_ctz(keep);
@@ -890,34 +937,27 @@ __global__ __launch_bounds__(256) void k_bound_l2_units(const BoundL2Args a, con
   for (int q = 0; q < kRelChunk; ++q) bT[q] = q < nrel ? 2.f * a.u[(int64_t)(rl0 + q) * a.n_micro + mT] : -3e38f;
   const float dsl = a.delta * (1.f + kBoundSlack);
   const float kk = 2.f * (float)(a.d + 12) * 6e-8f;
+  // the centre distances of the block's heads, all loads in flight together (a head past the end reads the first row; it is skipped below)
+  float Dv[kHeadChunk];
+  {
+    const float* Dp = a.D + mH0 * a.n_micro + mT;
+    const int nvalid = a.n_micro - mH0 < kHeadChunk ? (int)(a.n_micro - mH0) : kHeadChunk;
+#pragma unroll
+    for (int hq = 0; hq < kHeadChunk; ++hq) Dv[hq] = Dp[hq < nvalid ? (int64_t)hq * a.n_micro : 0];
+  }
+#pragma unroll
   for (int hq = 0; hq < kHeadChunk; ++hq) {
     const float rH = radH[hq];
     if (rH < 0.f) continue;
     const int64_t mH = mH0 + hq;
-    const float D = a.D[mH * a.n_micro + mT];
+    const float D = Dv[hq];
     const float reach = dsl + rH + rT;
     const float rhs = reach * reach * (1.f + kBoundSlack) + D * ((float)(a.d + 8) * 6e-8f) - D;
     const float ek = kk * (cnH[hq] + cT);
     uint32_t keep = 0u;
 #pragma unroll
     for (int q = 0; q < kRelChunk; ++q) keep |= (aH[hq][q] - bT[q] - ek * srnS[q] <= rhs) ? (1u << q) : 0u;
-    while (keep) {
-      const int q = __builtin_ctz(keep);
-      keep &= keep - 1u;
-      // a pair of small units (in the packed tail region both are single micro-tiles) is finished here;
-      // only pairs with many micro-tile pairs go through the list
-      int fH, nHm, fT, nTm;
-      unit_range(ut, (int)mH, fH, nHm);
-      unit_range(ut, (int)mT, fT, nTm);
-      unsigned long long pos = bp.cap;
-      // (without the matrices a micro-tile pair costs a loop over d: then every pair but a single one is listed)
-      if ((int64_t)nHm * nTm > (fine.D ? kInlineMicroPairs : 1)) pos = atomicAdd(bp.count, 1ull);
-      if (pos < bp.cap)
-        bp.list[pos] = ((unsigned long long)(uint32_t)(rl0 + q) << 48) | ((unsigned long long)(uint32_t)mH << 24) |
-                       (unsigned long long)(uint32_t)mT;
-      else
-        refine_unit_pair(fine, ut, rl0 + q, (int)mH, (int)mT, 0, 1);
-    }
+    unit_pairs_out(keep, rl0, (int)mH, (int)mT, fine, ut, bp);
   }
 }
 
