@@ -1422,10 +1422,10 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
       // a2: bound test on micro-tile pairs -> bitmap of join tiles -> per-row lists of surviving tail tiles
       const int64_t bm_words = (int64_t)RB * nH * words_per_row;
       if (!bitmap_ready) k_fill_u32<<<grid_for(bm_words, 256), 256, 0, st>>>((uint32_t*)hd->bitmap.p, bm_words, 0u);
-      // The flat bound test can list the surviving tiles itself; when they are few, that list serves the tile-at-a-time
+      // The bound test (flat, or the micro-tile level of the two-level one) can list the surviving tiles itself; when they are few, that list serves the tile-at-a-time
       // join kernel and the pass over the bitmap is skipped (the device decides, k_batch_tiles).  Not with a window:
       // the list would hold the tiles outside it too.
-      const bool direct_lists = pairs_ok && !use_units && !win && !bitmap_ready && delta >= 0.f && p == 2;
+      const bool direct_lists = pairs_ok && !win && !bitmap_ready && delta >= 0.f && p == 2;
       if (b > 0) k_fill_u32<<<1, 64, 0, st>>>((uint32_t*)&cnt->tile_cursor, 3, 0u);      // cursor and n_active (zero at the start of a call)
       if (bitmap_ready) {
         // the bound test of these relations is still in the bitmap (the previous window of the same relation range)

@@ -858,6 +858,19 @@ __global__ __launch_bounds__(64) void k_unit_summary(const float* __restrict__ c
 
 // the micro-tile level of the test for one surviving unit pair and relation; `lane_count` lanes starting at
 // `lane0` share the micro-tile pairs (1 lane = on the spot in the unit-level kernel, a block in k_bound_refine)
+// a surviving join tile: its bit in the bitmap, and -- the first time, when the kernel keeps a flat list (a.list_count) -- its
+// entry on the list (see k_batch_tiles)
+__device__ __forceinline__ void keep_tile(const BoundL2Args& a, int rl, int tH, int tT) {
+  const int64_t row = (int64_t)rl * a.nH + tH;
+  uint32_t* w = &a.bitmap[row * a.words_per_row + (tT >> 5)];
+  const uint32_t bit = 1u << (tT & 31);
+  if (*w & bit) return;                                          // (most micro-tile pairs of a tile find it set)
+  const uint32_t old = atomicOr(w, bit);
+  if (a.list_count && !(old & bit)) {
+    const unsigned long long idx = atomicAdd(a.list_count, 1ull);
+    if (idx < a.list_cap) { a.list_cols[idx] = (uint32_t)tT; a.list_rows[idx] = (uint32_t)row; a.list_active[idx] = (uint32_t)row; }
+  }
+}
 __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const UnitTable& ut, int rl, int uH, int uT, int lane0,
                                                  int lane_count) {
   int fH, nHm, fT, nTm;
@@ -880,11 +893,7 @@ __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const Uni
         const float x = cH[k] + ld_elem(a.Rv, so + k, a.dtype) - cT[k];
         sq += x * x;
       }
-      if (sqrtf(sq) * (1.f - kBoundSlack) - rH - rT <= dsl) {
-        const int tH = (int)(mH / a.micro_per_bm), tT = (int)(mT / a.micro_per_bn);
-        uint32_t* w = &a.bitmap[((int64_t)rl * a.nH + tH) * a.words_per_row + (tT >> 5)];
-        if (!(*w & (1u << (tT & 31)))) atomicOr(w, 1u << (tT & 31));
-      }
+      if (sqrtf(sq) * (1.f - kBoundSlack) - rH - rT <= dsl) keep_tile(a, rl, (int)(mH / a.micro_per_bm), (int)(mT / a.micro_per_bn));
       continue;
     }
     const float D = a.D[mH * a.n_micro + mT];
@@ -893,11 +902,7 @@ __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const Uni
     const float ek = kk * (a.cnorm[mH] + a.cnorm[mT]);
     const float lhs = (2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f)) - 2.f * a.u[(int64_t)rl * a.n_micro + mT] -
                       ek * srn;
-    if (lhs <= rhs) {
-      const int tH = (int)(mH / a.micro_per_bm), tT = (int)(mT / a.micro_per_bn);
-      uint32_t* w = &a.bitmap[((int64_t)rl * a.nH + tH) * a.words_per_row + (tT >> 5)];
-      if (!(*w & (1u << (tT & 31)))) atomicOr(w, 1u << (tT & 31));
-    }
+    if (lhs <= rhs) keep_tile(a, rl, (int)(mH / a.micro_per_bm), (int)(mT / a.micro_per_bn));
   }
 }
 
