@@ -731,7 +731,7 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
     static const int kShiftFew[3] = {2, 1, 0};
     k_round_begin<<<gN, 256, 0, st>>>(gs, unc, (int32_t*)hd->piv_ent.p, (unsigned long long*)hd->best.p,
                                      few ? kShiftFew[round] : kShift[round], mfma_assign ? 1 : 0, round == 0 ? N : 0,
-                                     (int32_t*)hd->group_of.p);
+                                     (int32_t*)hd->group_of.p, round);
     if (mfma_assign) {
       k_stage_operands<false><<<kPivotsPerRound / kStageRows, 256, asg_lds, st>>>(
           E, nullptr, dtype, d, 0, 1, (const int32_t*)hd->piv_ent.p, kPivotsPerRound, KS, (uint16_t*)hd->asg_b.p, nullptr,
@@ -759,12 +759,11 @@ int group_rows(kgc_handle* hd, const void* E, int64_t N, int32_t d, int32_t p, f
       else k_tile_dist<1, kEpiAssign><<<g, 256, 0, st>>>(ta);
     }
     k_round_commit<<<gN, 256, 0, st>>>(gs, unc, (const unsigned long long*)hd->best.p, (int32_t*)hd->group_of.p,
-                                      unc_next, mfma_assign ? 1 : 0);
-    k_round_end<<<1, 64, 0, st>>>(gs);
-    std::swap(unc, unc_next);
+                                      unc_next, mfma_assign ? 1 : 0, round);
+    std::swap(unc, unc_next);      // (the next round's start, or k_group_clear after the last, closes this round)
   }
   k_group_clear<<<grid_for(std::max<int64_t>(kMaxGroups, slots_cap), 256), 256, 0, st>>>(
-      (int32_t*)hd->gsize.p, (int32_t*)hd->gfill.p, kMaxGroups, (int32_t*)hd->slot_ent.p, slots_cap);
+      (int32_t*)hd->gsize.p, (int32_t*)hd->gfill.p, kMaxGroups, (int32_t*)hd->slot_ent.p, slots_cap, gs, n_rounds - 1);
   k_group_hist<<<gN, 256, 0, st>>>((const int32_t*)hd->group_of.p, N, (int32_t*)hd->gsize.p);
   k_group_layout<<<1, 1024, 0, st>>>(gs, (const int32_t*)hd->gsize.p, (int32_t*)hd->goff.p, N, (int)kSlotAlign,
                                      (int32_t*)hd->unit_first.p, (int32_t*)hd->unit_n.p);

@@ -24,7 +24,8 @@ constexpr float kBoundSlack = 2e-4f;       // relative widening of float32 dista
 
 struct GroupState {
   int32_t n_unc;        // uncovered entities in the current list
-  int32_t n_unc_next;   // ... appended to the next list
+  int32_t n_unc_next[2]; // ... appended to the next list, by the round's parity (a round's start reads the count the
+                        // round before left and clears its own)
   int32_t n_piv;        // pivots of the current round
   int32_t n_groups;     // groups formed so far
   int32_t n_slots;      // rows after layout, multiple of the slot alignment
@@ -37,12 +38,14 @@ struct GroupState {
 // uncovered list; nearest-pivot records are reset.
 // `best` is indexed by the position in the uncovered list, or (by_entity) by the entity itself; the pivot
 // list is padded with -1 up to kPivotsPerRound (the grid covers max(N, kPivotsPerRound) threads).
-// The first round (init_N > 0) also sets up the state: every entity uncovered and in no group.
+// The first round (init_N > 0) also sets up the state: every entity uncovered and in no group.  A later round first
+// closes the one before it (its pivots become groups, the entities it left uncovered are this round's list): what
+// the threads read of the state is not what thread 0 writes.
 __global__ void k_round_begin(GroupState* gs, int32_t* unc, int32_t* piv_ent, unsigned long long* best,
-                              int shift, int by_entity, int64_t init_N, int32_t* group_of) {
+                              int shift, int by_entity, int64_t init_N, int32_t* group_of, int round) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const bool first = init_N > 0;
-  const int n_unc = first ? (int)init_N : gs->n_unc;
+  const int n_unc = first ? (int)init_N : gs->n_unc_next[(round & 1) ^ 1];
   int n_piv = n_unc >> shift;
   n_piv = n_piv < 1 ? (n_unc > 0 ? 1 : 0) : n_piv;
   n_piv = n_piv < kPivotsPerRound ? n_piv : kPivotsPerRound;
@@ -53,33 +56,33 @@ __global__ void k_round_begin(GroupState* gs, int32_t* unc, int32_t* piv_ent, un
   }
   if (i < n_unc) best[by_entity ? (first ? (int32_t)i : unc[i]) : i] = ~0ull;
   if (i == 0) {
-    if (first) { gs->n_unc = n_unc; gs->n_groups = 0; gs->n_slots = 0; gs->tail_base = 0; gs->tail_fill = 0; gs->n_big = 0; }
-    gs->n_piv = n_piv; gs->n_unc_next = 0;
+    if (first) { gs->n_groups = 0; gs->n_slots = 0; gs->tail_base = 0; gs->tail_fill = 0; gs->n_big = 0; }
+    else gs->n_groups += gs->n_piv;                        // the round before
+    gs->n_unc = n_unc; gs->n_piv = n_piv; gs->n_unc_next[round & 1] = 0;
   }
 }
 
 // End of a round: an uncovered entity joins the group of the pivot the assignment found within tau, if any.
 __global__ void k_round_commit(GroupState* gs, const int32_t* unc, const unsigned long long* best,
-                               int32_t* group_of, int32_t* unc_next, int by_entity) {
+                               int32_t* group_of, int32_t* unc_next, int by_entity, int round) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= gs->n_unc) return;
   const int ent = unc[i];
   const unsigned long long b = best[by_entity ? ent : i];
   if (b != ~0ull) group_of[ent] = gs->n_groups + (int)(uint32_t)(b >> 32);
-  else unc_next[atomicAdd(&gs->n_unc_next, 1)] = ent;
+  else unc_next[atomicAdd(&gs->n_unc_next[round & 1], 1)] = ent;
 }
 
-__global__ void k_round_end(GroupState* gs) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
+// before the layout: group sizes and fill counts to zero, every slot to "padding"; the last round (number last_round)
+// is closed
+__global__ void k_group_clear(int32_t* gsize, int32_t* gfill, int n_groups_max, int32_t* slot_ent, int64_t n_slots,
+                              GroupState* gs, int last_round) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) {
     gs->n_groups += gs->n_piv;
-    gs->n_unc = gs->n_unc_next;
+    gs->n_unc = gs->n_unc_next[last_round & 1];
     gs->n_piv = 0;
   }
-}
-
-// before the layout: group sizes and fill counts to zero, every slot to "padding"
-__global__ void k_group_clear(int32_t* gsize, int32_t* gfill, int n_groups_max, int32_t* slot_ent, int64_t n_slots) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n_groups_max) { gsize[i] = 0; gfill[i] = 0; }
   if (i < n_slots) slot_ent[i] = -1;
 }
