@@ -520,7 +520,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
         sa.row_start = (const uint32_t*)hd->row_start.p; sa.row_count = (const uint32_t*)hd->row_count.p;
         sa.cols = (const uint32_t*)hd->cols.p; sa.active_rows = active_rows; sa.n_active = n_active;
         if (pairs_ok) { sa.tile_rows = (const uint32_t*)hd->tile_rows.p; sa.tile_total = &cnt->tile_cursor; sa.pair_mode = &cnt->pair_mode; }
-        hipLaunchKernelGGL(kern, dim3(row_grid, 1, 1), dim3(tc.threads), dyn_lds, st, sa);
+        hipLaunchKernelGGL(kern, dim3(tile_id == kDirectL2Tile ? (row_grid + 255u) & ~255u : row_grid, 1, 1), dim3(tc.threads), dyn_lds, st, sa);
         if (pairs_ok) {
           const size_t pair_lds = (size_t)2 * KS * 128 * kSliceK * 2;
           KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_pairs, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pair_lds));
@@ -1473,13 +1473,16 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
             // chunk, loads in groups -- 137 -> 59 us on the N = 100,000 workload
             const dim3 gu((unsigned)((ut.n_units + 255) / 256), (unsigned)((ut.n_units + kHeadsFlat - 1) / kHeadsFlat),
                           (unsigned)((RB + kRelChunk - 1) / kRelChunk));
-            k_bound_l2<false, true><<<gu, 256, 0, st>>>(bu, ba, ut, bp);
+            if (direct_lists) k_bound_l2<false, true, true><<<gu, 256, 0, st>>>(bu, ba, ut, bp);
+            else k_bound_l2<false, true, false><<<gu, 256, 0, st>>>(bu, ba, ut, bp);
           } else {                       // large units (many pairs survive, the first comparison rarely ends a chunk): the plain form (2.4 against 3.2 ms per batch on the N = 1,000,000 workload)
             const dim3 gu((unsigned)((ut.n_units + 255) / 256), (unsigned)((ut.n_units + kHeadChunk - 1) / kHeadChunk),
                           (unsigned)((RB + kRelChunk - 1) / kRelChunk));
-            k_bound_l2_units<<<gu, 256, 0, st>>>(bu, ba, ut, bp);
+            if (direct_lists) k_bound_l2_units<true><<<gu, 256, 0, st>>>(bu, ba, ut, bp);
+            else k_bound_l2_units<false><<<gu, 256, 0, st>>>(bu, ba, ut, bp);
           }
-          k_bound_refine<<<dim3(1024, 32, 1), 256, 0, st>>>(ba, ut, bp);
+          if (direct_lists) k_bound_refine<true><<<dim3(1024, 32, 1), 256, 0, st>>>(ba, ut, bp);
+          else k_bound_refine<false><<<dim3(1024, 32, 1), 256, 0, st>>>(ba, ut, bp);
         } else {
           const dim3 g((unsigned)((n_micro + 255) / 256), (unsigned)((n_micro + kHeadsFlat - 1) / kHeadsFlat),
                        (unsigned)((RB + kRelChunk - 1) / kRelChunk));
@@ -1617,7 +1620,9 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
           }
           KGC_HIP(hd, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds));
         }
-        const dim3 grid = prune ? dim3(row_grid, 1, 1) : dim3((unsigned)nHw, (unsigned)RB, (unsigned)nsplit);
+        // (the barrier-free kernel deals rows to workgroups in sets of 256: its grid is a whole number of sets)
+        const dim3 grid = prune ? dim3(tile_id == kDirectL2Tile ? (row_grid + 255u) & ~255u : row_grid, 1, 1)
+                                : dim3((unsigned)nHw, (unsigned)RB, (unsigned)nsplit);
         // the head-resident and streaming kernels list the accumulator blocks that hold candidates; a kernel of its own
         // then scores the list (the barrier-free dense kernels re-score in place: their candidates are few per tile)
         const bool lists_blocks = tile_id != kDenseL2Tile && tile_id != kDirectL2Tile && tile_id != kDirectL2Tile + 1 &&

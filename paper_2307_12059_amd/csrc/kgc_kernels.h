@@ -1208,11 +1208,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void k_join_l2_direct(const JoinS
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  for (unsigned int row_i = blockIdx.x;; row_i += gridDim.x) {
+  for (unsigned int blk_i = blockIdx.x;; blk_i += gridDim.x) {
+  unsigned int row_i = blk_i;
   int tH, rl, t_begin, ntiles;
   const uint32_t* tlist = nullptr;                         // LISTED: the row's tile list in the LDS
   if constexpr (LISTED) {
-    if (row_i >= *a.n_active) break;
+    // Workgroups go to the eight XCDs in turn, and neighbouring active rows (one relation, neighbouring head tiles)
+    // meet the same tail tiles: within every 256 consecutive workgroups, those of one XCD take 32 neighbouring rows,
+    // so that a tail tile is fetched into one L2, not into all eight.
+    const unsigned int n_act = *a.n_active;
+    if ((blk_i & ~255u) >= n_act) break;                   // (the same for the whole block)
+    row_i = (blk_i & ~255u) + (blk_i & 7u) * 32u + ((blk_i >> 3) & 31u);
+    if (row_i >= n_act) continue;                          // (a hole of the last, partial set of 256)
     // (the same for the whole block: kept in scalar registers)
     const int64_t row = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)a.active_rows[row_i]);
     rl = (int)(row / a.nH); tH = (int)(row - (int64_t)rl * a.nH);

@@ -644,6 +644,7 @@ constexpr int kHeadsFlat = 64;       // head micro-tiles per block of the flat t
 // UNITS: the unit level of the two-level test (see below): `a` describes UNITS, and a surviving (relation, unit pair)
 // is appended to the list `bp` -- or refined on the spot on the micro-tile arrays `fine` when the pair is small or
 // the list is full -- instead of setting bits.
+template <bool LIST>
 __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const UnitTable& ut, int rl, int uH, int uT, int lane0,
                                                  int lane_count);
 // The surviving (relation rl0 + q, unit pair) of a wave: bit q of `keep` per lane (head unit mH the same for the wave,
@@ -651,6 +652,7 @@ __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const Uni
 // finished on the spot; pairs with many micro-tile pairs go through the list, whose length is advanced ONCE per
 // relation for all lanes of the wave that append (atomics on one address are served one after the other: with one
 // per entry the unit level of a join with many survivors spent most of its time there).  Called by all active lanes.
+template <bool LIST>
 __device__ __forceinline__ void unit_pairs_out(uint32_t keep, int rl0, int mH, int mT, const BoundL2Args& fine,
                                                const UnitTable& ut, const BoundPairs& bp) {
   if (__builtin_amdgcn_ballot_w64(keep != 0u) == 0ull) return;
@@ -679,11 +681,12 @@ __device__ __forceinline__ void unit_pairs_out(uint32_t keep, int rl0, int mH, i
         bp.list[pos] = ((unsigned long long)(uint32_t)(rl0 + q) << 48) | ((unsigned long long)(uint32_t)mH << 24) |
                        (unsigned long long)(uint32_t)mT;
       else
-        refine_unit_pair(fine, ut, rl0 + q, mH, mT, 0, 1);
+        refine_unit_pair<LIST>(fine, ut, rl0 + q, mH, mT, 0, 1);
     }
   }
 }
-template <bool PAIR_READY, bool UNITS>
+// LIST (UNITS only): the micro-tile level also lists the tiles it keeps (see keep_tile)
+template <bool PAIR_READY, bool UNITS, bool LIST = false>
 __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a, const BoundL2Args fine, const UnitTable ut,
                                                   const BoundPairs bp) {
   // block = 256 tail micro-tiles x kHeadsFlat head micro-tiles x kRelChunk relations; the per-(head, relation)
@@ -792,7 +795,7 @@ __global__ __launch_bounds__(256) void k_bound_l2(const BoundL2Args a, const Bou
 #pragma unroll
     for (int q = 0; q < kRelChunk; ++q) keep |= (aH[hq][q] <= rhs + bT[q]) ? (1u << q) : 0u;
     if constexpr (UNITS) {
-      unit_pairs_out(keep, rl0, (int)mH, (int)mT, fine, ut, bp);
+      unit_pairs_out<LIST>(keep, rl0, (int)mH, (int)mT, fine, ut, bp);
       continue;
     }
     const int tH = (int)(mH / a.micro_per_bm);
@@ -861,19 +864,27 @@ __global__ __launch_bounds__(64) void k_unit_summary(const float* __restrict__ c
 
 // the micro-tile level of the test for one surviving unit pair and relation; `lane_count` lanes starting at
 // `lane0` share the micro-tile pairs (1 lane = on the spot in the unit-level kernel, a block in k_bound_refine)
-// a surviving join tile: its bit in the bitmap, and -- the first time, when the kernel keeps a flat list (a.list_count) -- its
-// entry on the list (see k_batch_tiles)
+// a surviving join tile: its bit in the bitmap, and -- LIST: the first time -- its entry on the flat list (see
+// k_batch_tiles).  A template parameter and not a test of a.list_count: with both forms in one kernel the atomic of the
+// plain form became a returning one too, and a join with many surviving tiles (N = 1,000,000) lost a third of its
+// bound test's speed.
+template <bool LIST>
 __device__ __forceinline__ void keep_tile(const BoundL2Args& a, int rl, int tH, int tT) {
   const int64_t row = (int64_t)rl * a.nH + tH;
   uint32_t* w = &a.bitmap[row * a.words_per_row + (tT >> 5)];
   const uint32_t bit = 1u << (tT & 31);
   if (*w & bit) return;                                          // (most micro-tile pairs of a tile find it set)
-  const uint32_t old = atomicOr(w, bit);
-  if (a.list_count && !(old & bit)) {
-    const unsigned long long idx = atomicAdd(a.list_count, 1ull);
-    if (idx < a.list_cap) { a.list_cols[idx] = (uint32_t)tT; a.list_rows[idx] = (uint32_t)row; a.list_active[idx] = (uint32_t)row; }
+  if constexpr (!LIST) {
+    atomicOr(w, bit);
+  } else {
+    const uint32_t old = atomicOr(w, bit);
+    if (!(old & bit)) {
+      const unsigned long long idx = atomicAdd(a.list_count, 1ull);
+      if (idx < a.list_cap) { a.list_cols[idx] = (uint32_t)tT; a.list_rows[idx] = (uint32_t)row; a.list_active[idx] = (uint32_t)row; }
+    }
   }
 }
+template <bool LIST>
 __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const UnitTable& ut, int rl, int uH, int uT, int lane0,
                                                  int lane_count) {
   int fH, nHm, fT, nTm;
@@ -896,7 +907,7 @@ __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const Uni
         const float x = cH[k] + ld_elem(a.Rv, so + k, a.dtype) - cT[k];
         sq += x * x;
       }
-      if (sqrtf(sq) * (1.f - kBoundSlack) - rH - rT <= dsl) keep_tile(a, rl, (int)(mH / a.micro_per_bm), (int)(mT / a.micro_per_bn));
+      if (sqrtf(sq) * (1.f - kBoundSlack) - rH - rT <= dsl) keep_tile<LIST>(a, rl, (int)(mH / a.micro_per_bm), (int)(mT / a.micro_per_bn));
       continue;
     }
     const float D = a.D[mH * a.n_micro + mT];
@@ -905,13 +916,14 @@ __device__ __forceinline__ void refine_unit_pair(const BoundL2Args& a, const Uni
     const float ek = kk * (a.cnorm[mH] + a.cnorm[mT]);
     const float lhs = (2.f * a.u[(int64_t)rl * a.n_micro + mH] + rnq * (1.f - 2.4e-7f)) - 2.f * a.u[(int64_t)rl * a.n_micro + mT] -
                       ek * srn;
-    if (lhs <= rhs) keep_tile(a, rl, (int)(mH / a.micro_per_bm), (int)(mT / a.micro_per_bn));
+    if (lhs <= rhs) keep_tile<LIST>(a, rl, (int)(mH / a.micro_per_bm), (int)(mT / a.micro_per_bn));
   }
 }
 
 // Unit level: the flat kernel's arithmetic on unit summaries (a.D, a.u, a.rad, a.cnorm and a.n_micro then
 // describe UNITS); survivors are appended to the list, or refined on the spot when the list is full.
 // `fine` holds the micro-tile level arrays for that case.
+template <bool LIST>
 __global__ __launch_bounds__(256) void k_bound_l2_units(const BoundL2Args a, const BoundL2Args fine, const UnitTable ut,
                                                         const BoundPairs bp) {
   __shared__ float aH[kHeadChunk][kRelChunk];
@@ -965,7 +977,7 @@ __global__ __launch_bounds__(256) void k_bound_l2_units(const BoundL2Args a, con
     uint32_t keep = 0u;
 #pragma unroll
     for (int q = 0; q < kRelChunk; ++q) keep |= (aH[hq][q] - bT[q] - ek * srnS[q] <= rhs) ? (1u << q) : 0u;
-    unit_pairs_out(keep, rl0, (int)mH, (int)mT, fine, ut, bp);
+    unit_pairs_out<LIST>(keep, rl0, (int)mH, (int)mT, fine, ut, bp);
   }
 }
 
@@ -982,11 +994,12 @@ __global__ __launch_bounds__(256) void k_bound_refine_l1(const TileDistArgs a) {
 // Micro-tile level for the listed unit pairs.  The grid strides over the list in x; the gridDim.y blocks of
 // one x share the micro-tile pairs of an entry, so that a pair of large groups (millions of micro-tile pairs
 // in one entry) does not hang on a single block.
+template <bool LIST>
 __global__ __launch_bounds__(256) void k_bound_refine(const BoundL2Args fine, const UnitTable ut, const BoundPairs bp) {
   const unsigned long long n = *bp.count < bp.cap ? *bp.count : bp.cap;
   for (unsigned long long e = blockIdx.x; e < n; e += gridDim.x) {
     const unsigned long long v = bp.list[e];
-    refine_unit_pair(fine, ut, (int)(v >> 48), (int)((v >> 24) & 0xffffffull), (int)(v & 0xffffffull),
+    refine_unit_pair<LIST>(fine, ut, (int)(v >> 48), (int)((v >> 24) & 0xffffffull), (int)(v & 0xffffffull),
                      (int)(blockIdx.y * blockDim.x + threadIdx.x), (int)(gridDim.y * blockDim.x));
   }
 }
