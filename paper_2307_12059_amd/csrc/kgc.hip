@@ -77,6 +77,7 @@ struct kgc_handle {
   DevBuf xlist;                                // accumulator blocks listed for the exact stage (L2 joins)
   unsigned int xcap = kExactListCap;           // its length in entries: grows when a batch wanted to list more
   int list_seg_cap = 0;                        // > 0: the pruned barrier-free kernel keeps at most this many entries of a row's tile list in the LDS (tests)
+  unsigned pairs_grid = 512;                   // workgroups of the tile-at-a-time kernel: two per compute unit (tests set fewer, so that a workgroup walks several batches of tiles)
   DevBuf zero_row, cent_a, rad_a;              // kgc_join_ab: the zero relation row; micro-tile summaries of A[r]
   DevBuf top1_a, top1_b, top1_pick, top_samples, topk_state;            // ... and the operands / entity samples of its sub-sampled dense pass
   int no_self = 0;                             // set by kgc_top1 around its inner joins: drop h == t
@@ -296,6 +297,7 @@ int kgc_create(const kgc_config* cfg, kgc_handle** out) {
   // the first length of the exact stage's block list (it grows by itself; tests set it small to see it grow)
   if (const char* e = std::getenv("KGC_EXACT_LIST_CAP")) h->xcap = (unsigned int)std::max(1L, std::atol(e));
   if (const char* e = std::getenv("KGC_TILE_LIST_SEGMENT")) h->list_seg_cap = (int)std::max(1L, std::atol(e));
+  if (const char* e = std::getenv("KGC_PAIRS_GRID")) h->pairs_grid = (unsigned)std::min(512L, std::max(1L, std::atol(e)));
   if (hipHostMalloc((void**)&h->host_counters, sizeof(DevCounters), hipHostMallocDefault) != hipSuccess) {
     delete h;
     return KGC_E_NOMEM;
@@ -524,7 +526,7 @@ int kgc_join_ab(kgc_handle* hd, const void* A, const void* B, int64_t N, int32_t
         if (pairs_ok) {
           const size_t pair_lds = (size_t)2 * KS * 128 * kSliceK * 2;
           KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_pairs, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pair_lds));
-          hipLaunchKernelGGL(k_join_l2_pairs, dim3(512), dim3(256), pair_lds, st, sa);      // two resident blocks per compute unit, each walks its tiles
+          hipLaunchKernelGGL(k_join_l2_pairs, dim3(hd->pairs_grid), dim3(256), pair_lds, st, sa);      // two resident blocks per compute unit, each walks its tiles
         }
       } else {
         const int64_t tile_bytes = (int64_t)BN * KS * kSliceK * 2;
@@ -1636,7 +1638,7 @@ static int join_range_impl(kgc_handle* hd, const void* E, int64_t N, int32_t d, 
         if (pairs_ok) {          // the same batch tile by tile, when the device chose that (the other kernel then returned at once)
           const size_t pair_lds = (size_t)2 * KS * 128 * kSliceK * 2;
           KGC_HIP(hd, hipFuncSetAttribute((const void*)k_join_l2_pairs, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pair_lds));
-          hipLaunchKernelGGL(k_join_l2_pairs, dim3(512), dim3(256), pair_lds, st, sa);      // two resident blocks per compute unit, each walks its tiles
+          hipLaunchKernelGGL(k_join_l2_pairs, dim3(hd->pairs_grid), dim3(256), pair_lds, st, sa);      // two resident blocks per compute unit, each walks its tiles
         }
         if (lists_blocks) {
           launch_exact_blocks(st, (const ExactEntry*)hd->xlist.p, &cnt->n_exact, hd->xcap, &cnt->exact_total, &cnt->exact_need, sa.cx);

@@ -235,6 +235,24 @@ def test_pruned_barrier_free_kernel_walks_tile_lists(segment, dtype):
     assert ref["count"] > 0
 
 
+# ---- the tile-at-a-time kernel with so few workgroups that each walks several batches of tiles (its list entries are
+# ---- staged per batch of 32 tiles, the flagged blocks listed per batch)
+def test_tile_at_a_time_kernel_walks_several_batches():
+    g = np.random.default_rng(616)
+    N, R, d, sig = 2600, 24, 64, 0.1
+    E, Rv = _clustered(g, N, R, d, 40, sig)              # 40 clusters of 65: a surviving tile or two per (relation, head tile)
+    delta = float(np.float32(sig * np.sqrt(2.0 * d) * 0.8))
+    normal, ref, _ = _join_and_compare(E, Rv, 2, delta, "f32", prune=PRUNE_ON)
+    os.environ["KGC_PAIRS_GRID"] = "2"
+    try:
+        few, _, _ = _join_and_compare(E, Rv, 2, delta, "f32", prune=PRUNE_ON)
+    finally:
+        del os.environ["KGC_PAIRS_GRID"]
+    tiles = normal["stats"]["tiles_total"] - normal["stats"]["tiles_pruned"]
+    assert tiles > 2 * 32 * 2, f"vacuous: {tiles} surviving tiles do not make two batches for each of two workgroups"
+    assert few["count"] == normal["count"] == ref["count"] > 0
+
+
 # ---- seeded sweep: random shapes (ragged in N and d, through every kernel family's range of d), cluster widths,
 # ---- norms, storage types, thresholds and modes; bounded so that the oracle side stays within a minute
 def _fuzz_cases(seed, n):
